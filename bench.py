@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the PowerSGD step on one MI355X.
+
+A "step" is one psgd_step over one batch of synthetic gradients: error-feedback
+add, P = M Q, orthogonalisation, Q = M^T P_hat, decompression and the new error
+memory for every matrix of the model (plus the uncompressed vector tensors),
+for W simulated workers.  Inputs are generated on the GPU before the timed
+region (planted low rank + Gaussian noise in the model's tensor shapes) and a
+ring of several gradient buffers is cycled so that the gradient is not simply
+re-read from cache.
+
+Prints ONE JSON line: gradient GB/s for the whole job, the HBM roofline of the
+dominant kernel (duration measured here with HIP events on the library's
+stream) and the CPU oracle's throughput on the host cores as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+# HBM bytes per launch of a kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
+# copy kernel of known size (see profiles/); keyed by (workload, rank, workers, kernel).  None = not
+# measured for that configuration.
+MEASURED_TRAFFIC = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="resnet18", choices=["tiny", "resnet18", "lstm"])
+    ap.add_argument("--rank", type=int, default=None)
+    ap.add_argument("--workers", type=int, default=1)
+    ap.add_argument("--grad-buffers", type=int, default=4, help="distinct gradient batches cycled through")
+    ap.add_argument("--profile-steps", type=int, default=50, help="steps of the per-kernel HIP-event pass")
+    ap.add_argument("--cold-steps", type=int, default=20,
+                    help="steps of the cold-cache pass (caches flushed before each step, outside the timing)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing")
+    ap.add_argument("--tune", action="append", default=[], help="key=value planner tuning (experiments)")
+    return ap.parse_args()
+
+
+def device_gradients(wl, lay, plan, workers, seed, torch, dev):
+    """One flat [W][grad_stride] gradient batch generated on the GPU: planted low rank + noise."""
+    s = plan.sizes
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    grad = torch.zeros(workers * s.grad_stride, dtype=torch.float32, device=dev)
+    fac_gen = torch.Generator(device=dev)
+    fac_gen.manual_seed(12345)
+    sv = torch.tensor(np.asarray(wl.singular_values), dtype=torch.float32, device=dev)
+    for t, shape in enumerate(wl.shapes):
+        off = lay.flat_off[t]
+        if len(shape) == 1:
+            for w in range(workers):
+                grad[w * s.grad_stride + off: w * s.grad_stride + off + shape[0]] = \
+                    wl.sigma * torch.randn(shape[0], generator=gen, device=dev)
+            continue
+        n, m = shape
+        k = min(wl.planted_rank, n, m)
+        U, _ = torch.linalg.qr(torch.randn(n, k, generator=fac_gen, device=dev))
+        V, _ = torch.linalg.qr(torch.randn(m, k, generator=fac_gen, device=dev))
+        base = (U * sv[:k]) @ V.T
+        dens = wl.row_density.get(t)
+        mask = None
+        if dens is not None:
+            mask = (torch.rand(n, 1, generator=gen, device=dev) < dens).to(torch.float32)
+        for w in range(workers):
+            g = base + wl.sigma * torch.randn(n, m, generator=gen, device=dev)
+            if mask is not None:
+                g = g * mask
+            grad[w * s.grad_stride + off: w * s.grad_stride + off + n * m] = g.reshape(-1)
+    return grad
+
+
+def cpu_baseline(wl, rank, workers, budget_s):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
+    from oracle import powersgd_oracle as O
+    from paper_1905_13727_amd import workloads as WL
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    factors = WL.planted_factors(wl, 0)
+    q = [None if x is None else x.astype(np.float64) for x in WL.initial_q(wl, rank, 0)]
+    errs = [[None if len(s) == 1 else np.zeros(s) for s in wl.shapes] for _ in range(workers)]
+    grads = [WL.gradients(wl, factors, 0, 0, w) for w in range(workers)]
+    n_elems = sum(int(np.prod(s)) for s in wl.shapes)
+    steps, spent = 0, 0.0
+    while True:
+        t0 = time.perf_counter()
+        res = O.powersgd_step(grads, errs, q, rank)
+        spent += time.perf_counter() - t0
+        q, errs = res["Q"], res["err"]
+        steps += 1
+        if spent >= budget_s or steps >= 50:
+            break
+    gbs = workers * n_elems * 4 / (spent / steps) / 1e9
+    return {"value": round(gbs, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "ms_per_step": round(1e3 * spent / steps, 3),
+            "sample": "%d full steps of the %s workload (W=%d, r=%d), numpy fp64, same gradient each step"
+                      % (steps, wl.name, workers, rank)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (W simulated workers share it); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        return 2
+    import torch
+    from paper_1905_13727_amd import binding as B
+    from paper_1905_13727_amd import workloads as WL
+    from paper_1905_13727_amd.flat import FlatLayout
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    wl = WL.by_name(args.workload)
+    rank = args.rank if args.rank is not None else (4 if args.workload == "lstm" else 2)
+    W = args.workers
+    plan = B.Plan(wl.shapes, rank, W)
+    for kv in args.tune:
+        k, v = kv.split("=")
+        plan.set_tuning(k, int(v))
+    lay = FlatLayout(plan, wl.shapes)
+    s = plan.sizes
+
+    grads = [device_gradients(wl, lay, plan, W, 100 + i, torch, dev) for i in range(args.grad_buffers)]
+    err = torch.zeros(W * s.err_stride, dtype=torch.float32, device=dev)
+    q0 = WL.initial_q(wl, rank, 0)
+    q = torch.from_numpy(lay.pack_q(q0)).to(dev)
+    p = torch.zeros(s.p_elems, dtype=torch.float32, device=dev)
+    out = torch.zeros(s.out_elems, dtype=torch.float32, device=dev)
+    ws = torch.empty(s.workspace_bytes // 4 + 64, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream(dev)
+    sh = stream.cuda_stream
+
+    def step(i):
+        plan.step(grads[i % len(grads)], err, q, p, out, ws, sh)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize(dev)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize(dev)
+    wall = time.perf_counter() - t0
+    ms_per_step = 1e3 * wall / args.steps
+
+    # per-kernel durations: HIP events recorded by the library on its own stream
+    plan.set_profiling(True)
+    for i in range(args.profile_steps):
+        step(i)
+    kms, ksteps = plan.kernel_times()
+    plan.set_profiling(False)
+    kavg = {k: v / max(1, ksteps) for k, v in kms.items()}
+
+    # cold-cache pass: a 1 GiB fill between steps evicts L2 and the memory-side cache
+    cold_ms = None
+    if args.cold_steps > 0:
+        flush = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device=dev)
+        ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.cold_steps)]
+        ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.cold_steps)]
+        for i in range(args.cold_steps):
+            flush.fill_(float(i))
+            ev0[i].record(stream)
+            step(i)
+            ev1[i].record(stream)
+        torch.cuda.synchronize(dev)
+        ts = sorted(a.elapsed_time(b) for a, b in zip(ev0, ev1))
+        cold_ms = {"median": round(ts[len(ts) // 2], 4), "min": round(ts[0], 4)}
+        del flush
+
+    payload_mat = s.payload_elems - s.n_vec_elems
+    L = s.n_vec_elems
+    kernel_bytes = {
+        "k_ef_right": payload_mat * W * 12,                       # read g, read e, write M
+        "k_left": payload_mat * W * 4,                            # read M
+        "k_decomp": payload_mat * (W * 8 + 4) + L * (W * 4 + 4),  # read M, write e', write Delta' once
+    }
+    dom = max(kernel_bytes, key=lambda k: kavg.get(k, 0.0))
+    achieved = kernel_bytes[dom] / (kavg[dom] * 1e-3) / 1e9 if kavg[dom] > 0 else 0.0
+    grad_bytes = W * (payload_mat + L) * 4
+    value = grad_bytes / (ms_per_step * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC.get((wl.name, rank, W, dom))
+
+    rec = {
+        "metric": "PowerSGD step gradient GB/s + % HBM peak, ResNet18 shapes r=2",
+        "value": round(value, 3),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s-shaped gradient set, W=%d simulated worker(s), rank %d, fp32" % (wl.name, W, rank),
+                   "matrices": int(s.n_matrices), "matrix_elems": int(payload_mat), "vector_elems": int(L),
+                   "grad_buffers": len(grads)},
+        "stream_model": {"bytes_per_step": int(s.bytes_stream),
+                         "GBps": round(s.bytes_stream / (ms_per_step * 1e-3) / 1e9, 2),
+                         "frac_of_hbm_peak": round(s.bytes_stream / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "min_model": {"bytes_per_step": int(s.bytes_min),
+                      "GBps": round(s.bytes_min / (ms_per_step * 1e-3) / 1e9, 2),
+                      "frac_of_hbm_peak": round(s.bytes_min / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "cold_ms_per_step": cold_ms,
+        "kernel_ms": {k: round(v, 5) for k, v in kavg.items()},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "algorithmic_bytes_per_launch": int(kernel_bytes[dom]),
+                     "avg_launch_ms": round(kavg[dom], 5)},
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(wl, rank, W, args.cpu_seconds)
+    print(json.dumps(rec), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

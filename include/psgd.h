@@ -1,0 +1,178 @@
+/*
+ * psgd.h - C ABI of the MI355X (gfx950) PowerSGD step library.
+ *
+ * The library runs, for every gradient matrix of a model and for W simulated
+ * workers resident on one GPU, one step of the rank-r PowerSGD compressor with
+ * error feedback (Vogels, Karimireddy, Jaggi, "PowerSGD", arXiv 1905.13727):
+ *
+ *   Algorithm 2, "Delta_w <- g_w + e_w"            error-feedback add
+ *   Algorithm 1, compress+aggregate                P <- M Q ; mean over workers ;
+ *                                                  P_hat <- orthogonalize(P) ;
+ *                                                  Q <- M^T P_hat ; mean over workers
+ *   Algorithm 1, decompress                        Delta' <- P_hat Q^T
+ *   Algorithm 2 / eq. (ef-sgd), last line          e_w <- Delta_w - Delta'
+ *   Algorithm 1 line 1, Section 3                  tensors with >= 2 dims are seen as
+ *                                                  matrices d0 x prod(d1..); vector-shaped
+ *                                                  tensors are aggregated uncompressed
+ *   Section 3, "warm start"                        the Q written by one step is the
+ *                                                  starting Q of the next
+ *
+ * All data buffers are DEVICE pointers owned by the caller (allocate them with
+ * any allocator; the tests use PyTorch).  The library owns only the plan and
+ * its small device-side descriptor tables.  No entry point throws or aborts;
+ * every failure is a psgd_status.
+ *
+ * Flat layout (all offsets in elements, reported by psgd_plan_sizes /
+ * psgd_plan_offsets):
+ *   matrix region   [0, N): the matrices in the order given to
+ *                   psgd_plan_create, each row-major n x m, each starting at a
+ *                   multiple of 64 elements (padding elements are never read or
+ *                   written);
+ *   vector region   [N, N+L): the 1-D tensors back to back, same order.
+ *   grad   [W][grad_stride]  gradients g_w, dtype grad_dtype, grad_stride >= N+L
+ *   err    [W][N]            error memory e_w, float
+ *   out    [N+L]             Delta' (matrices) and the worker mean (vectors), out_dtype
+ *   p      [p_elems]         per matrix n x r_i row-major, float
+ *   q      [q_elems]         per matrix m x r_i row-major, float
+ *   r_i = min(rank, n, m) is the effective rank of matrix i.
+ */
+#ifndef PSGD_H
+#define PSGD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PSGD_API __attribute__((visibility("default")))
+
+typedef struct psgd_plan psgd_plan; /* opaque, library-owned */
+
+typedef enum {
+    PSGD_OK = 0,
+    PSGD_EINVAL = 1,       /* bad argument (null pointer, non-positive size, ...) */
+    PSGD_ENOMEM = 2,       /* host or device allocation failed */
+    PSGD_EHIP = 3,         /* a HIP runtime call or kernel launch failed */
+    PSGD_EUNSUPPORTED = 4  /* valid request the library does not implement */
+} psgd_status;
+
+typedef enum { PSGD_F32 = 0, PSGD_BF16 = 1 } psgd_dtype;
+
+/* One tensor of the model as the compressor sees it (Algorithm 1 line 1).
+ * cols >= 2: a rows x cols matrix (conv kernels o,i,k,k are passed as rows=o,
+ * cols=i*k*k).  cols == 1: a vector-shaped tensor of `rows` elements, not
+ * compressed. */
+typedef struct {
+    int64_t rows;
+    int64_t cols;
+} psgd_shape;
+
+typedef struct {
+    int64_t n_mat_elems;     /* N, including alignment padding */
+    int64_t n_vec_elems;     /* L */
+    int64_t grad_stride;     /* elements between consecutive workers in grad */
+    int64_t err_stride;      /* elements between consecutive workers in err (= N) */
+    int64_t out_elems;       /* N + L */
+    int64_t p_elems;         /* sum n_i r_i */
+    int64_t q_elems;         /* sum m_i r_i */
+    int64_t workspace_bytes; /* scratch the caller must provide to compress/decompress/step */
+    int64_t n_matrices;
+    int64_t n_vectors;
+    int64_t payload_elems;   /* sum of n_i*m_i + L without padding: what SGD would exchange */
+    int64_t compressed_elems;/* sum r_i (n_i + m_i) + L: what PowerSGD exchanges (Appendix F tables) */
+    int64_t bytes_min;       /* algorithmic HBM bytes per step if every M element moved once:
+                                read g, read e, write e' per worker, write Delta' once */
+    int64_t bytes_stream;    /* same with the two extra reads of M forced by the two global
+                                reductions (after P, after Q) */
+} psgd_sizes;
+
+/* Build a plan.  Host only: makes no HIP call, so it works without a GPU.
+ *   shapes[n_tensors]  tensors in model order (see psgd_shape)
+ *   rank               r >= 1; clipped per matrix to min(r, n, m)
+ *   workers            W >= 1 simulated workers whose P and Q are averaged
+ *                      (the two "all reduce mean" lines of Algorithm 1)
+ *   grad_dtype         PSGD_F32, or PSGD_BF16 (upcast exactly; error memory,
+ *                      P and Q stay float)
+ *   out_dtype          dtype of `out`
+ * Errors: PSGD_EINVAL for null pointers, n_tensors < 1, rank < 1, workers < 1,
+ * a non-positive dimension; PSGD_EUNSUPPORTED for rank > PSGD_MAX_RANK or a
+ * dtype pair that is not implemented; PSGD_ENOMEM. */
+#define PSGD_MAX_RANK 64
+PSGD_API psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_t rank,
+                             int32_t workers, psgd_dtype grad_dtype, psgd_dtype out_dtype,
+                             psgd_plan** out_plan);
+
+/* Frees the plan and its device tables (if any were uploaded).  NULL is allowed. */
+PSGD_API void psgd_plan_destroy(psgd_plan* plan);
+
+/* Sizes of every buffer of the flat layout, and the traffic model. */
+PSGD_API psgd_status psgd_plan_sizes(const psgd_plan* plan, psgd_sizes* out_sizes);
+
+/* Placement of tensor `tensor` (index into the shapes array).
+ *   flat_off   offset in the flat [N+L] layout (matrix region or vector region)
+ *   p_off, q_off, eff_rank   for matrices; -1, -1, 0 for vectors
+ * Any output pointer may be NULL. */
+PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, int64_t* flat_off,
+                              int64_t* p_off, int64_t* q_off, int32_t* eff_rank);
+
+/* Tuning knob for experiments; must be called before the plan's first GPU call.
+ * Unknown keys give PSGD_EINVAL.  Keys are documented in the design notes. */
+PSGD_API psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value);
+
+/* Algorithm 2 "Delta_w <- g_w + e_w" followed by Algorithm 1 compress+aggregate.
+ *   grad (device, const)  g_w                          [W][grad_stride] grad_dtype
+ *   err  (device, in/out) in: e_w ; out: M_w = g_w+e_w [W][N] float
+ *   q    (device, in/out) in: previous Q (warm start; iid N(0,1) before the
+ *                         first step) ; out: Q = mean_w M_w^T P_hat
+ *   p    (device, out)    P_hat (orthonormal columns)
+ *   workspace (device)    workspace_bytes of scratch, 256-byte aligned, contents
+ *                         ignored on entry and undefined on exit
+ *   hip_stream            a hipStream_t (NULL = the default stream)
+ * Everything is enqueued on hip_stream; the call does not synchronise, allocate
+ * or read back, except that a plan's first GPU call allocates and uploads its
+ * descriptor tables (one hipMalloc, one synchronous copy).
+ * Vector-shaped tensors are not touched by this call. */
+PSGD_API psgd_status psgd_compress(psgd_plan* plan, const void* grad, float* err, float* q, float* p,
+                          void* workspace, void* hip_stream);
+
+/* Algorithm 1 decompress and the error-memory update of Algorithm 2.
+ *   p, q (device, const)  the pair produced by psgd_compress
+ *   err  (device, in/out) in: M_w as left by psgd_compress ; out: e_w = M_w - P_hat Q^T
+ *   grad (device, const)  read only for the vector-shaped tensors
+ *   out  (device, out)    [N+L] out_dtype: Delta' = P_hat Q^T for matrices, the
+ *                         mean over workers of g_w for vectors
+ * Same stream / workspace rules as psgd_compress. */
+PSGD_API psgd_status psgd_decompress(psgd_plan* plan, const float* p, const float* q, float* err,
+                            const void* grad, void* out, void* workspace, void* hip_stream);
+
+/* One whole step = psgd_compress followed by psgd_decompress, bit-identical to
+ * calling the two in sequence. */
+PSGD_API psgd_status psgd_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p,
+                      void* out, void* workspace, void* hip_stream);
+
+/* Per-kernel timing for benchmarks.  With profiling enabled, psgd_compress and
+ * psgd_decompress record HIP events on the caller's stream around each of their
+ * kernels, and psgd_decompress (hence psgd_step) WAITS for the stream at its
+ * end to accumulate the elapsed times: use it for measurement runs only.
+ * psgd_plan_kernel_times copies the accumulated milliseconds per kernel (array
+ * of PSGD_N_KERNELS doubles, order given by psgd_kernel_name) and the number of
+ * accumulated steps, then clears the accumulators. */
+#define PSGD_N_KERNELS 5
+PSGD_API psgd_status psgd_plan_set_profiling(psgd_plan* plan, int32_t enable);
+PSGD_API psgd_status psgd_plan_kernel_times(psgd_plan* plan, double* ms_sum, int64_t* steps);
+/* Name of kernel `index` in [0, PSGD_N_KERNELS) as it appears in a profiler's
+ * kernel trace (prefix of the symbol); NULL if out of range. */
+PSGD_API const char* psgd_kernel_name(int32_t index);
+
+/* Static, never NULL. */
+PSGD_API const char* psgd_status_string(psgd_status status);
+
+/* Text of the last HIP error seen by this plan ("" if none).  The pointer is
+ * valid until the next failing call on the plan or its destruction. */
+PSGD_API const char* psgd_plan_last_error(const psgd_plan* plan);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSGD_H */

@@ -1,0 +1,112 @@
+// Internal tables shared by the host planner and the device kernels.
+// Plain structs only: they are copied byte-for-byte to the GPU.
+#ifndef PSGD_INTERNAL_H
+#define PSGD_INTERNAL_H
+
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "psgd.h"
+
+namespace psgd {
+
+constexpr int kWave = 64;          // gfx950 wavefront
+constexpr int kBlock = 256;        // threads per workgroup in the streaming kernels (4 waves)
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kAlignElems = 64;    // every matrix starts on a multiple of this many elements
+constexpr int kMaxVecPerLaneK1 = 4;  // column vectors a lane owns per row in the P = M Q kernel
+constexpr int kMaxVecPerLaneK3 = 2;  // column vectors a lane owns in the Q = M^T P and decompress kernels
+constexpr int kOrthoBlock = 256;   // threads of the single-workgroup Gram-Schmidt kernel
+constexpr int kValuMaxRank = 8;    // ranks up to this run on the vector-ALU kernels
+
+// One matrix of the model.
+struct MatDesc {
+    int64_t off;        // element offset in the matrix region
+    int64_t p_off;      // float offset in packed P
+    int64_t q_off;      // float offset in packed Q
+    int64_t ppart_off;  // float offset in the workspace: partial P, [n_cchunk][n][r]
+    int64_t qpart_off;  // float offset in the workspace: partial Q, [n_rblock][m][r]
+    int32_t n, m, r;    // rows, columns, effective rank
+    int32_t vec;        // elements per vector access along a row (4, 2 or 1)
+    int32_t n_cchunk;   // column chunks of the P = M Q kernel (partials to sum)
+    int32_t n_rblock;   // row blocks of the Q = M^T P kernel (partials to sum)
+    int32_t tensor;     // index in the caller's shape list
+    int32_t pad_;
+};
+
+// One workgroup's share of a streaming kernel.
+struct Tile {
+    int32_t mat;    // matrix index; -1: a slice of the vector region
+    int32_t row0;   // first row (vector tiles: unused)
+    int32_t nrows;  // rows
+    int32_t vec0;   // first column vector (units of MatDesc::vec elements);
+                    // vector tiles: first element / 4 is not assumed, see elem0 below
+    int32_t nvec;   // column vectors
+    int32_t part;   // which partial buffer slice this tile writes
+    int64_t elem0;  // vector tiles and Q-reduce tiles: first element
+    int64_t nelem;  // vector tiles and Q-reduce tiles: element count
+};
+
+struct Tuning {
+    int64_t k1_rows = 32;   // rows per workgroup tile, P = M Q
+    int64_t k1_nv = 4;      // column vectors per lane (<= kMaxVecPerLaneK1)
+    int64_t k3_rows = 128;  // rows per workgroup tile, Q = M^T P
+    int64_t k3_nv = 1;      // column vectors per lane (<= kMaxVecPerLaneK3)
+    int64_t k4_rows = 64;   // rows per workgroup tile, decompress + residual
+    int64_t k4_nv = 1;
+    int64_t q_reduce_elems = 1024;  // elements per workgroup in the Q reduction
+};
+
+struct DeviceTables {
+    MatDesc* mats = nullptr;
+    Tile* tiles1 = nullptr;
+    Tile* tiles3 = nullptr;
+    Tile* tiles4 = nullptr;
+    Tile* tilesq = nullptr;
+    void* base = nullptr;   // the one allocation holding all of the above
+};
+
+}  // namespace psgd
+
+struct psgd_plan {
+    int32_t rank = 0;
+    int32_t workers = 0;
+    psgd_dtype grad_dtype = PSGD_F32;
+    psgd_dtype out_dtype = PSGD_F32;
+    psgd_sizes sizes{};
+    std::vector<psgd_shape> shapes;
+    std::vector<int64_t> tensor_flat_off;   // per tensor
+    std::vector<int32_t> tensor_mat;        // per tensor: matrix index or -1
+    std::vector<psgd::MatDesc> mats;
+    std::vector<psgd::Tile> tiles1, tiles3, tiles4, tilesq;
+    int32_t max_n = 0;
+    int64_t ws_ppart_floats = 0;            // workspace: partial P region (floats)
+    int64_t ws_qpart_floats = 0;            // workspace: partial Q region, starts after partial P
+    psgd::Tuning tuning;
+    bool tables_built = false;
+    bool uploaded = false;
+    int device = -1;
+    psgd::DeviceTables dev;
+    std::string last_error;
+    // per-kernel timing (benchmarks only)
+    bool profiling = false;
+    void* events[PSGD_N_KERNELS + 2] = {};   // hipEvent_t: before/after each kernel
+    double kernel_ms[PSGD_N_KERNELS] = {};
+    int64_t profiled_steps = 0;
+};
+
+namespace psgd {
+// host planner (psgd_plan.cpp)
+psgd_status build_tables(psgd_plan* plan);
+// device side (psgd_kernels.hip)
+psgd_status upload_tables(psgd_plan* plan);
+void free_tables(psgd_plan* plan);
+psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float* q, float* p,
+                            void* workspace, void* stream);
+psgd_status launch_decompress(psgd_plan* plan, const float* p, const float* q, float* err,
+                              const void* grad, void* out, void* workspace, void* stream);
+psgd_status set_profiling(psgd_plan* plan, bool enable);
+}  // namespace psgd
+
+#endif

@@ -1,0 +1,732 @@
+// HIP kernels for gfx950 (MI355X) and their launchers.
+//
+// One PowerSGD step (arXiv 1905.13727, Algorithm 1 inside the error-feedback
+// loop of Algorithm 2) is five grouped launches over work-lists built by the
+// planner; every launch covers all matrices of the model and all W workers:
+//
+//   k_ef_right    M_w = g_w + e_w (stored in e_w's place) fused with the row dot
+//                 products of P_w = M_w Q               (Alg. 2 "Delta_w", Alg. 1 "P <- M Q")
+//   k_ortho       mean over workers / column chunks, then Gram-Schmidt
+//                                                       (Alg. 1 "all reduce mean", "orthogonalize")
+//   k_left        column sums of Q_w = M_w^T P_hat      (Alg. 1 "Q <- M^T P_hat")
+//   k_q_reduce    mean over workers / row blocks        (Alg. 1 second "all reduce mean")
+//   k_decomp      Delta' = P_hat Q^T fused with e_w = M_w - Delta' and with the
+//                 mean of the vector-shaped tensors     (Alg. 1 "decompress", Alg. 2 error memory)
+//
+// All reductions run in a fixed order (no float atomics): results are
+// bit-reproducible from run to run.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+
+#include "psgd_internal.h"
+
+namespace psgd {
+
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+// ---- V-wide row accesses -----------------------------------------------------------------------
+
+template <int V>
+__device__ __forceinline__ void ldv(const float* p, float (&x)[V]);
+template <>
+__device__ __forceinline__ void ldv<1>(const float* p, float (&x)[1]) { x[0] = *p; }
+template <>
+__device__ __forceinline__ void ldv<2>(const float* p, float (&x)[2]) {
+    f2 t = *reinterpret_cast<const f2*>(p);
+    x[0] = t.x; x[1] = t.y;
+}
+template <>
+__device__ __forceinline__ void ldv<4>(const float* p, float (&x)[4]) {
+    f4 t = *reinterpret_cast<const f4*>(p);
+    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+}
+
+// streamed-once data (the gradient): non-temporal so that it does not evict M from the caches
+template <int V>
+__device__ __forceinline__ void ldv_stream(const float* p, float (&x)[V]);
+template <>
+__device__ __forceinline__ void ldv_stream<1>(const float* p, float (&x)[1]) { x[0] = __builtin_nontemporal_load(p); }
+template <>
+__device__ __forceinline__ void ldv_stream<2>(const float* p, float (&x)[2]) {
+    f2 t = __builtin_nontemporal_load(reinterpret_cast<const f2*>(p));
+    x[0] = t.x; x[1] = t.y;
+}
+template <>
+__device__ __forceinline__ void ldv_stream<4>(const float* p, float (&x)[4]) {
+    f4 t = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
+    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+}
+
+template <int V>
+__device__ __forceinline__ void stv(float* p, const float (&x)[V]);
+template <>
+__device__ __forceinline__ void stv<1>(float* p, const float (&x)[1]) { *p = x[0]; }
+template <>
+__device__ __forceinline__ void stv<2>(float* p, const float (&x)[2]) {
+    f2 t; t.x = x[0]; t.y = x[1];
+    *reinterpret_cast<f2*>(p) = t;
+}
+template <>
+__device__ __forceinline__ void stv<4>(float* p, const float (&x)[4]) {
+    f4 t; t.x = x[0]; t.y = x[1]; t.z = x[2]; t.w = x[3];
+    *reinterpret_cast<f4*>(p) = t;
+}
+
+// ---- wavefront helpers ---------------------------------------------------------------------------
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, kWave);
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, kWave);
+    return v;
+}
+
+__device__ __forceinline__ float lane_bcast(float v, int src_lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
+}
+
+// rows [*begin, *begin + *count) of a tile's `total` rows that wavefront `wave` of 4 handles
+__device__ __forceinline__ void wave_rows(int total, int wave, int* begin, int* count) {
+    const int base = total / kWavesPerBlock, rem = total % kWavesPerBlock;
+    *begin = wave * base + (wave < rem ? wave : rem);
+    *count = base + (wave < rem ? 1 : 0);
+}
+
+// ---- k_ef_right: M = g + e, P_w[i,:] = sum_j M[i,j] Q[j,:] ---------------------------------------
+//
+// A wavefront owns a strip of rows and a chunk of at most 64*NV*V columns.  Each lane keeps
+// the Q rows of its columns in registers for the whole strip, streams g and e with V-wide
+// loads, writes M over e, and the wavefront reduces R dot products per row.  Partial sums
+// of different column chunks / workers go to separate slices of the workspace.
+
+template <int R, int V>
+__device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, const float* __restrict__ g,
+                                              float* __restrict__ e, const float* __restrict__ q,
+                                              float* __restrict__ ppart) {
+    constexpr int NV = kMaxVecPerLaneK1;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int ri = d.r;
+
+    float qr[NV][V][R];
+    bool valid[NV];
+    int col[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int jv = lane + kWave * v;
+        valid[v] = jv < t.nvec;
+        col[v] = (t.vec0 + jv) * V;
+#pragma unroll
+        for (int x = 0; x < V; ++x)
+#pragma unroll
+            for (int k = 0; k < R; ++k)
+                qr[v][x][k] = (valid[v] && k < ri) ? q[d.q_off + (int64_t)(col[v] + x) * ri + k] : 0.f;
+    }
+
+    int rb, rn;
+    wave_rows(t.nrows, wave, &rb, &rn);
+    const int i_begin = t.row0 + rb, i_end = i_begin + rn;
+    for (int i = i_begin; i < i_end; i += 2) {
+        const bool two = (i + 1) < i_end;
+        const int64_t row_a = d.off + (int64_t)i * d.m;
+        const int64_t row_b = row_a + d.m;
+        float ga[NV][V], ea[NV][V], gb[NV][V], eb[NV][V];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            if (valid[v]) {
+                ldv_stream<V>(g + row_a + col[v], ga[v]);
+                ldv<V>(e + row_a + col[v], ea[v]);
+                if (two) {
+                    ldv_stream<V>(g + row_b + col[v], gb[v]);
+                    ldv<V>(e + row_b + col[v], eb[v]);
+                }
+            }
+        }
+        float acc_a[R], acc_b[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k) acc_a[k] = acc_b[k] = 0.f;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            if (valid[v]) {
+                float ma[V];
+#pragma unroll
+                for (int x = 0; x < V; ++x) {
+                    ma[x] = ga[v][x] + ea[v][x];
+#pragma unroll
+                    for (int k = 0; k < R; ++k) acc_a[k] = fmaf(ma[x], qr[v][x][k], acc_a[k]);
+                }
+                stv<V>(e + row_a + col[v], ma);
+                if (two) {
+                    float mb[V];
+#pragma unroll
+                    for (int x = 0; x < V; ++x) {
+                        mb[x] = gb[v][x] + eb[v][x];
+#pragma unroll
+                        for (int k = 0; k < R; ++k) acc_b[k] = fmaf(mb[x], qr[v][x][k], acc_b[k]);
+                    }
+                    stv<V>(e + row_b + col[v], mb);
+                }
+            }
+        }
+        float out_a = 0.f, out_b = 0.f;
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+            const float sa = wave_sum(acc_a[k]);
+            const float sb = wave_sum(acc_b[k]);
+            if (lane == k) { out_a = sa; out_b = sb; }
+        }
+        if (lane < ri) {
+            float* dst = ppart + d.ppart_off + ((int64_t)t.part * d.n + i) * ri + lane;
+            dst[0] = out_a;
+            if (two) dst[ri] = out_b;
+        }
+    }
+}
+
+template <int R>
+__global__ __launch_bounds__(kBlock) void k_ef_right(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
+                                                     const float* __restrict__ grad, float* __restrict__ err,
+                                                     const float* __restrict__ q, float* __restrict__ ws,
+                                                     int64_t gstride, int64_t estride, int64_t ppart_wstride) {
+    const Tile t = tiles[blockIdx.x];
+    const MatDesc d = mats[t.mat];
+    const int w = blockIdx.y;
+    const float* g = grad + (int64_t)w * gstride;
+    float* e = err + (int64_t)w * estride;
+    float* pp = ws + (int64_t)w * ppart_wstride;
+    if (d.vec == 4) ef_right_tile<R, 4>(t, d, g, e, q, pp);
+    else if (d.vec == 2) ef_right_tile<R, 2>(t, d, g, e, q, pp);
+    else ef_right_tile<R, 1>(t, d, g, e, q, pp);
+}
+
+// ---- k_ortho: P_bar = mean of the partials, then modified Gram-Schmidt ----------------------------
+//
+// One workgroup per matrix.  The n x r panel lives in LDS when it fits, else in the P
+// buffer itself.  Round j reduces, over all rows, the squared norm of column j and its dot
+// products with the columns to its right (fp64 accumulation of fp32 data, wavefront
+// reduction then a fixed-order sum over the 4 wavefronts), then normalises column j and
+// removes its component from the others.  A column whose squared norm is <= 1e-30 when its
+// turn comes is set to zero.
+
+constexpr int kPanelFloats = 12288;  // 48 KB of LDS
+
+__global__ __launch_bounds__(kOrthoBlock) void k_ortho(const MatDesc* __restrict__ mats, const float* __restrict__ ws,
+                                                       float* __restrict__ p, int workers, int64_t ppart_wstride) {
+    __shared__ float panel[kPanelFloats];
+    __shared__ double red[kOrthoBlock / kWave][kValuMaxRank];
+    const MatDesc d = mats[blockIdx.x];
+    const int n = d.n, r = d.r;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int64_t nr = (int64_t)n * r;
+    const bool in_lds = nr <= kPanelFloats;
+    float* P = in_lds ? panel : (p + d.p_off);
+    const float inv_w = 1.0f / (float)workers;
+
+    for (int64_t idx = tid; idx < nr; idx += kOrthoBlock) {
+        float s = 0.f;
+        for (int w = 0; w < workers; ++w) {
+            const float* src = ws + (int64_t)w * ppart_wstride + d.ppart_off + idx;
+            for (int c = 0; c < d.n_cchunk; ++c) s += src[(int64_t)c * nr];
+        }
+        P[idx] = s * inv_w;
+    }
+    __syncthreads();
+
+    for (int j = 0; j < r; ++j) {
+        double s[kValuMaxRank];
+#pragma unroll
+        for (int k = 0; k < kValuMaxRank; ++k) s[k] = 0.0;
+        for (int i = tid; i < n; i += kOrthoBlock) {
+            const float* row = P + (int64_t)i * r;
+            const double pj = (double)row[j];
+#pragma unroll
+            for (int k = 0; k < kValuMaxRank; ++k)
+                if (k >= j && k < r) s[k] += pj * (double)row[k];
+        }
+#pragma unroll
+        for (int k = 0; k < kValuMaxRank; ++k) {
+            if (k >= j && k < r) {
+                const double v = wave_sum(s[k]);
+                if (lane == 0) red[wave][k] = v;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kValuMaxRank; ++k) {
+            if (k >= j && k < r) {
+                double v = 0.0;
+                for (int wv = 0; wv < kOrthoBlock / kWave; ++wv) v += red[wv][k];
+                s[k] = v;
+            }
+        }
+        double sjj = 0.0;
+#pragma unroll
+        for (int k = 0; k < kValuMaxRank; ++k)
+            if (k == j) sjj = s[k];
+        if (sjj <= 1e-30) {
+            for (int i = tid; i < n; i += kOrthoBlock) P[(int64_t)i * r + j] = 0.f;
+        } else {
+            const double inv = 1.0 / sqrt(sjj);
+            double c[kValuMaxRank];
+#pragma unroll
+            for (int k = 0; k < kValuMaxRank; ++k) c[k] = s[k] / sjj;
+            for (int i = tid; i < n; i += kOrthoBlock) {
+                float* row = P + (int64_t)i * r;
+                const double pj = (double)row[j];
+                row[j] = (float)(pj * inv);
+#pragma unroll
+                for (int k = 0; k < kValuMaxRank; ++k)
+                    if (k > j && k < r) row[k] = (float)((double)row[k] - c[k] * pj);
+            }
+        }
+        __syncthreads();
+    }
+    if (in_lds) {
+        float* dst = p + d.p_off;
+        for (int64_t idx = tid; idx < nr; idx += kOrthoBlock) dst[idx] = panel[idx];
+    }
+}
+
+// ---- k_left: Q_w[j,:] = sum_i M[i,j] P_hat[i,:] ---------------------------------------------------
+//
+// A lane owns NV column vectors and keeps their V*R running sums in registers while its
+// wavefront walks down a strip of rows.  The P_hat rows of a 64-row group are loaded one
+// row per lane and broadcast with readlane.  The four wavefronts of a workgroup walk four
+// strips of the same columns; their sums are added in LDS in a fixed order and written as
+// one partial per (row block, worker).
+
+template <int R, int V, int NV>
+__device__ __forceinline__ void left_tile(const Tile& t, const MatDesc& d, const float* __restrict__ e,
+                                          const float* __restrict__ p, float* __restrict__ qpart, float* lds) {
+    constexpr int RU = 8;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int ri = d.r;
+    float acc[NV][V][R];
+    bool valid[NV];
+    int col[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int jv = lane + kWave * v;
+        valid[v] = jv < t.nvec;
+        col[v] = (t.vec0 + jv) * V;
+#pragma unroll
+        for (int x = 0; x < V; ++x)
+#pragma unroll
+            for (int k = 0; k < R; ++k) acc[v][x][k] = 0.f;
+    }
+    int rb, rn;
+    wave_rows(t.nrows, wave, &rb, &rn);
+    for (int g0 = 0; g0 < rn; g0 += kWave) {
+        const int gr = min(kWave, rn - g0);
+        const int i0 = t.row0 + rb + g0;
+        float pr[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k)
+            pr[k] = (lane < gr && k < ri) ? p[d.p_off + (int64_t)(i0 + lane) * ri + k] : 0.f;
+        for (int ii = 0; ii < gr; ii += RU) {
+            float x[RU][NV][V];
+#pragma unroll
+            for (int u = 0; u < RU; ++u) {
+                if (ii + u < gr) {
+                    const int64_t row = d.off + (int64_t)(i0 + ii + u) * d.m;
+#pragma unroll
+                    for (int v = 0; v < NV; ++v)
+                        if (valid[v]) ldv<V>(e + row + col[v], x[u][v]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < RU; ++u) {
+                if (ii + u < gr) {
+                    float pk[R];
+#pragma unroll
+                    for (int k = 0; k < R; ++k) pk[k] = lane_bcast(pr[k], ii + u);
+#pragma unroll
+                    for (int v = 0; v < NV; ++v)
+                        if (valid[v]) {
+#pragma unroll
+                            for (int xx = 0; xx < V; ++xx)
+#pragma unroll
+                                for (int k = 0; k < R; ++k)
+                                    acc[v][xx][k] = fmaf(x[u][v][xx], pk[k], acc[v][xx][k]);
+                        }
+                }
+            }
+        }
+    }
+    // fixed-order sum over the 4 wavefronts: 1, 2, 3 deposit, 0 adds them in that order
+    constexpr int PER_LANE = NV * V * R;
+    if (wave > 0) {
+        float* dst = lds + ((wave - 1) * kWave + lane) * PER_LANE;
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+#pragma unroll
+            for (int x = 0; x < V; ++x)
+#pragma unroll
+                for (int k = 0; k < R; ++k) dst[(v * V + x) * R + k] = acc[v][x][k];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        for (int wv = 0; wv < kWavesPerBlock - 1; ++wv) {
+            const float* src = lds + (wv * kWave + lane) * PER_LANE;
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+#pragma unroll
+                for (int x = 0; x < V; ++x)
+#pragma unroll
+                    for (int k = 0; k < R; ++k) acc[v][x][k] += src[(v * V + x) * R + k];
+        }
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            if (valid[v]) {
+                float* dst = qpart + d.qpart_off + ((int64_t)t.part * d.m + col[v]) * ri;
+#pragma unroll
+                for (int x = 0; x < V; ++x)
+#pragma unroll
+                    for (int k = 0; k < R; ++k)
+                        if (k < ri) dst[x * ri + k] = acc[v][x][k];
+            }
+        }
+    }
+}
+
+template <int R, int NV>
+__global__ __launch_bounds__(kBlock) void k_left(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
+                                                 const float* __restrict__ err, const float* __restrict__ p,
+                                                 float* __restrict__ ws, int64_t estride, int64_t qpart_wstride) {
+    __shared__ float lds[(kWavesPerBlock - 1) * kWave * NV * 4 * R];
+    const Tile t = tiles[blockIdx.x];
+    const MatDesc d = mats[t.mat];
+    const int w = blockIdx.y;
+    const float* e = err + (int64_t)w * estride;
+    float* qp = ws + (int64_t)w * qpart_wstride;
+    if (d.vec == 4) left_tile<R, 4, NV>(t, d, e, p, qp, lds);
+    else if (d.vec == 2) left_tile<R, 2, NV>(t, d, e, p, qp, lds);
+    else left_tile<R, 1, NV>(t, d, e, p, qp, lds);
+}
+
+// ---- k_q_reduce: Q = (1/W) sum over workers and row blocks of the partials ------------------------
+
+__global__ __launch_bounds__(kBlock) void k_q_reduce(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
+                                                     const float* __restrict__ ws, float* __restrict__ q, int workers,
+                                                     int64_t qpart_wstride) {
+    const Tile t = tiles[blockIdx.x];
+    const MatDesc d = mats[t.mat];
+    const int64_t mr = (int64_t)d.m * d.r;
+    const float inv_w = 1.0f / (float)workers;
+    for (int64_t idx = t.elem0 + threadIdx.x; idx < t.elem0 + t.nelem; idx += kBlock) {
+        float s = 0.f;
+        for (int w = 0; w < workers; ++w) {
+            const float* src = ws + (int64_t)w * qpart_wstride + d.qpart_off + idx;
+            for (int b = 0; b < d.n_rblock; ++b) s += src[(int64_t)b * mr];
+        }
+        q[d.q_off + idx] = s * inv_w;
+    }
+}
+
+// ---- k_decomp: Delta' = P_hat Q^T, e_w = M_w - Delta', vectors averaged ---------------------------
+
+template <int R, int V, int NV>
+__device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, float* __restrict__ e,
+                                            const float* __restrict__ p, const float* __restrict__ q,
+                                            float* __restrict__ out, bool write_out) {
+    constexpr int RU = 8;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int ri = d.r;
+    float qr[NV][V][R];
+    bool valid[NV];
+    int col[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int jv = lane + kWave * v;
+        valid[v] = jv < t.nvec;
+        col[v] = (t.vec0 + jv) * V;
+#pragma unroll
+        for (int x = 0; x < V; ++x)
+#pragma unroll
+            for (int k = 0; k < R; ++k)
+                qr[v][x][k] = (valid[v] && k < ri) ? q[d.q_off + (int64_t)(col[v] + x) * ri + k] : 0.f;
+    }
+    int rb, rn;
+    wave_rows(t.nrows, wave, &rb, &rn);
+    for (int g0 = 0; g0 < rn; g0 += kWave) {
+        const int gr = min(kWave, rn - g0);
+        const int i0 = t.row0 + rb + g0;
+        float pr[R];
+#pragma unroll
+        for (int k = 0; k < R; ++k)
+            pr[k] = (lane < gr && k < ri) ? p[d.p_off + (int64_t)(i0 + lane) * ri + k] : 0.f;
+        for (int ii = 0; ii < gr; ii += RU) {
+            float x[RU][NV][V];
+#pragma unroll
+            for (int u = 0; u < RU; ++u) {
+                if (ii + u < gr) {
+                    const int64_t row = d.off + (int64_t)(i0 + ii + u) * d.m;
+#pragma unroll
+                    for (int v = 0; v < NV; ++v)
+                        if (valid[v]) ldv<V>(e + row + col[v], x[u][v]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < RU; ++u) {
+                if (ii + u < gr) {
+                    const int64_t row = d.off + (int64_t)(i0 + ii + u) * d.m;
+                    float pk[R];
+#pragma unroll
+                    for (int k = 0; k < R; ++k) pk[k] = lane_bcast(pr[k], ii + u);
+#pragma unroll
+                    for (int v = 0; v < NV; ++v)
+                        if (valid[v]) {
+                            float dl[V], en[V];
+#pragma unroll
+                            for (int xx = 0; xx < V; ++xx) {
+                                float s = 0.f;
+#pragma unroll
+                                for (int k = 0; k < R; ++k) s = fmaf(pk[k], qr[v][xx][k], s);
+                                dl[xx] = s;
+                                en[xx] = x[u][v][xx] - s;
+                            }
+                            stv<V>(e + row + col[v], en);
+                            if (write_out) stv<V>(out + row + col[v], dl);
+                        }
+                }
+            }
+        }
+    }
+}
+
+template <int R, int NV>
+__global__ __launch_bounds__(kBlock) void k_decomp(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
+                                                   float* __restrict__ err, const float* __restrict__ p,
+                                                   const float* __restrict__ q, const float* __restrict__ grad,
+                                                   float* __restrict__ out, int workers, int64_t gstride,
+                                                   int64_t estride, int64_t n_mat_elems) {
+    const Tile t = tiles[blockIdx.x];
+    const int w = blockIdx.y;
+    if (t.mat < 0) {
+        if (w != 0) return;
+        const float inv_w = 1.0f / (float)workers;
+        for (int64_t idx = t.elem0 + threadIdx.x; idx < t.elem0 + t.nelem; idx += kBlock) {
+            float s = 0.f;
+            for (int ww = 0; ww < workers; ++ww) s += grad[(int64_t)ww * gstride + n_mat_elems + idx];
+            out[n_mat_elems + idx] = s * inv_w;
+        }
+        return;
+    }
+    const MatDesc d = mats[t.mat];
+    float* e = err + (int64_t)w * estride;
+    if (d.vec == 4) decomp_tile<R, 4, NV>(t, d, e, p, q, out, w == 0);
+    else if (d.vec == 2) decomp_tile<R, 2, NV>(t, d, e, p, q, out, w == 0);
+    else decomp_tile<R, 1, NV>(t, d, e, p, q, out, w == 0);
+}
+
+// ---- host side ------------------------------------------------------------------------------------
+
+static psgd_status hip_fail(psgd_plan* plan, hipError_t err, const char* what) {
+    plan->last_error = std::string(what) + ": " + hipGetErrorString(err);
+    return err == hipErrorOutOfMemory ? PSGD_ENOMEM : PSGD_EHIP;
+}
+
+#define PSGD_HIP(call, what)                                   \
+    do {                                                       \
+        hipError_t e_ = (call);                                \
+        if (e_ != hipSuccess) return hip_fail(plan, e_, what); \
+    } while (0)
+
+psgd_status set_profiling(psgd_plan* plan, bool enable) {
+    if (enable == plan->profiling) return PSGD_OK;
+    if (enable) {
+        for (auto& ev : plan->events) {
+            hipEvent_t e = nullptr;
+            PSGD_HIP(hipEventCreate(&e), "hipEventCreate");
+            ev = e;
+        }
+    } else {
+        for (auto& ev : plan->events) {
+            if (ev) (void)hipEventDestroy(static_cast<hipEvent_t>(ev));
+            ev = nullptr;
+        }
+    }
+    plan->profiling = enable;
+    return PSGD_OK;
+}
+
+#define PSGD_MARK(i)                                                                                \
+    do {                                                                                            \
+        if (plan->profiling) PSGD_HIP(hipEventRecord(static_cast<hipEvent_t>(plan->events[i]), s), "hipEventRecord"); \
+    } while (0)
+
+void free_tables(psgd_plan* plan) {
+    (void)set_profiling(plan, false);
+    if (plan->dev.base) {
+        (void)hipFree(plan->dev.base);
+        plan->dev = DeviceTables();
+    }
+    plan->uploaded = false;
+}
+
+psgd_status upload_tables(psgd_plan* plan) {
+    if (plan->uploaded) return PSGD_OK;
+    auto bytes_of = [](size_t n, size_t sz) { return (n * sz + 255) / 256 * 256; };
+    const size_t b_m = bytes_of(plan->mats.size(), sizeof(MatDesc));
+    const size_t b_1 = bytes_of(plan->tiles1.size(), sizeof(Tile));
+    const size_t b_3 = bytes_of(plan->tiles3.size(), sizeof(Tile));
+    const size_t b_4 = bytes_of(plan->tiles4.size(), sizeof(Tile));
+    const size_t b_q = bytes_of(plan->tilesq.size(), sizeof(Tile));
+    const size_t total = b_m + b_1 + b_3 + b_4 + b_q + 256;
+    std::vector<char> host(total, 0);
+    size_t o = 0;
+    auto put = [&](const void* src, size_t n, size_t padded) {
+        if (n) std::memcpy(host.data() + o, src, n);
+        size_t at = o;
+        o += padded;
+        return at;
+    };
+    const size_t o_m = put(plan->mats.data(), plan->mats.size() * sizeof(MatDesc), b_m);
+    const size_t o_1 = put(plan->tiles1.data(), plan->tiles1.size() * sizeof(Tile), b_1);
+    const size_t o_3 = put(plan->tiles3.data(), plan->tiles3.size() * sizeof(Tile), b_3);
+    const size_t o_4 = put(plan->tiles4.data(), plan->tiles4.size() * sizeof(Tile), b_4);
+    const size_t o_q = put(plan->tilesq.data(), plan->tilesq.size() * sizeof(Tile), b_q);
+    PSGD_HIP(hipGetDevice(&plan->device), "hipGetDevice");
+    void* base = nullptr;
+    PSGD_HIP(hipMalloc(&base, total), "hipMalloc(descriptor tables)");
+    hipError_t ce = hipMemcpy(base, host.data(), total, hipMemcpyHostToDevice);
+    if (ce != hipSuccess) {
+        (void)hipFree(base);
+        return hip_fail(plan, ce, "hipMemcpy(descriptor tables)");
+    }
+    char* b = static_cast<char*>(base);
+    plan->dev.base = base;
+    plan->dev.mats = reinterpret_cast<MatDesc*>(b + o_m);
+    plan->dev.tiles1 = reinterpret_cast<Tile*>(b + o_1);
+    plan->dev.tiles3 = reinterpret_cast<Tile*>(b + o_3);
+    plan->dev.tiles4 = reinterpret_cast<Tile*>(b + o_4);
+    plan->dev.tilesq = reinterpret_cast<Tile*>(b + o_q);
+    plan->uploaded = true;
+    return PSGD_OK;
+}
+
+template <int R>
+static void launch_ef_right(psgd_plan* plan, const float* grad, float* err, const float* q, float* ws,
+                            hipStream_t s) {
+    dim3 grid((unsigned)plan->tiles1.size(), (unsigned)plan->workers);
+    hipLaunchKernelGGL((k_ef_right<R>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles1, grad, err, q, ws,
+                       plan->sizes.grad_stride, plan->sizes.err_stride, plan->ws_ppart_floats);
+}
+
+template <int R>
+static void launch_left(psgd_plan* plan, const float* err, const float* p, float* ws, hipStream_t s) {
+    dim3 grid((unsigned)plan->tiles3.size(), (unsigned)plan->workers);
+    float* qpart = ws + (int64_t)plan->workers * plan->ws_ppart_floats;  // after all workers' partial P
+    if (plan->tuning.k3_nv == 1)
+        hipLaunchKernelGGL((k_left<R, 1>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles3, err, p, qpart,
+                           plan->sizes.err_stride, plan->ws_qpart_floats);
+    else
+        hipLaunchKernelGGL((k_left<R, 2>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles3, err, p, qpart,
+                           plan->sizes.err_stride, plan->ws_qpart_floats);
+}
+
+template <int R>
+static void launch_decomp(psgd_plan* plan, float* err, const float* p, const float* q, const float* grad, float* out,
+                          hipStream_t s) {
+    dim3 grid((unsigned)plan->tiles4.size(), (unsigned)plan->workers);
+    if (plan->tuning.k4_nv == 1)
+        hipLaunchKernelGGL((k_decomp<R, 1>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles4, err, p, q,
+                           grad, out, plan->workers, plan->sizes.grad_stride, plan->sizes.err_stride,
+                           plan->sizes.n_mat_elems);
+    else
+        hipLaunchKernelGGL((k_decomp<R, 2>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles4, err, p, q,
+                           grad, out, plan->workers, plan->sizes.grad_stride, plan->sizes.err_stride,
+                           plan->sizes.n_mat_elems);
+}
+
+#define PSGD_RANK_SWITCH(fn, ...)                       \
+    switch (plan->rank) {                               \
+        case 1: fn<1>(__VA_ARGS__); break;              \
+        case 2: fn<2>(__VA_ARGS__); break;              \
+        case 3: fn<3>(__VA_ARGS__); break;              \
+        case 4: fn<4>(__VA_ARGS__); break;              \
+        case 5: fn<5>(__VA_ARGS__); break;              \
+        case 6: fn<6>(__VA_ARGS__); break;              \
+        case 7: fn<7>(__VA_ARGS__); break;              \
+        case 8: fn<8>(__VA_ARGS__); break;              \
+        default: return PSGD_EUNSUPPORTED;              \
+    }
+
+static psgd_status check_ready(psgd_plan* plan) {
+    if (plan->grad_dtype != PSGD_F32 || plan->out_dtype != PSGD_F32) return PSGD_EUNSUPPORTED;
+    if (!plan->uploaded) {
+        psgd_status st = upload_tables(plan);
+        if (st != PSGD_OK) return st;
+    }
+    return PSGD_OK;
+}
+
+psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* workspace,
+                            void* stream) {
+    psgd_status st = check_ready(plan);
+    if (st != PSGD_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* ws = static_cast<float*>(workspace);
+    const float* g = static_cast<const float*>(grad);
+    if (plan->mats.empty()) return PSGD_OK;
+
+    PSGD_MARK(0);
+    PSGD_RANK_SWITCH(launch_ef_right, plan, g, err, q, ws, s);
+    PSGD_HIP(hipGetLastError(), "launch k_ef_right");
+    PSGD_MARK(1);
+
+    hipLaunchKernelGGL(k_ortho, dim3((unsigned)plan->mats.size()), dim3(kOrthoBlock), 0, s, plan->dev.mats, ws, p,
+                       plan->workers, plan->ws_ppart_floats);
+    PSGD_HIP(hipGetLastError(), "launch k_ortho");
+    PSGD_MARK(2);
+
+    PSGD_RANK_SWITCH(launch_left, plan, err, p, ws, s);
+    PSGD_HIP(hipGetLastError(), "launch k_left");
+    PSGD_MARK(3);
+
+    float* qpart = ws + (int64_t)plan->workers * plan->ws_ppart_floats;
+    hipLaunchKernelGGL(k_q_reduce, dim3((unsigned)plan->tilesq.size()), dim3(kBlock), 0, s, plan->dev.mats,
+                       plan->dev.tilesq, qpart, q, plan->workers, plan->ws_qpart_floats);
+    PSGD_HIP(hipGetLastError(), "launch k_q_reduce");
+    PSGD_MARK(4);
+    return PSGD_OK;
+}
+
+psgd_status launch_decompress(psgd_plan* plan, const float* p, const float* q, float* err, const void* grad, void* out,
+                              void* workspace, void* stream) {
+    (void)workspace;
+    psgd_status st = check_ready(plan);
+    if (st != PSGD_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (plan->tiles4.empty()) return PSGD_OK;
+    PSGD_MARK(5);
+    PSGD_RANK_SWITCH(launch_decomp, plan, err, p, q, static_cast<const float*>(grad), static_cast<float*>(out), s);
+    PSGD_HIP(hipGetLastError(), "launch k_decomp");
+    PSGD_MARK(6);
+    if (plan->profiling) {
+        // measurement mode: wait, then add this step's per-kernel times (compress must have run first)
+        PSGD_HIP(hipEventSynchronize(static_cast<hipEvent_t>(plan->events[6])), "hipEventSynchronize");
+        static const int first[PSGD_N_KERNELS] = {0, 1, 2, 3, 5};
+        for (int k = 0; k < PSGD_N_KERNELS; ++k) {
+            float ms = 0.f;
+            hipError_t e = hipEventElapsedTime(&ms, static_cast<hipEvent_t>(plan->events[first[k]]),
+                                               static_cast<hipEvent_t>(plan->events[first[k] + 1]));
+            if (e != hipSuccess) return hip_fail(plan, e, "hipEventElapsedTime");
+            plan->kernel_ms[k] += ms;
+        }
+        ++plan->profiled_steps;
+    }
+    return PSGD_OK;
+}
+
+}  // namespace psgd

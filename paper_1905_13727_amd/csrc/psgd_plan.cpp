@@ -1,0 +1,330 @@
+// Host side of the library: plan construction (flat layout, effective ranks,
+// tile work-lists, workspace layout, traffic model) and the C ABI entry points.
+// No HIP call is made in this file.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "psgd_internal.h"
+
+namespace psgd {
+
+static int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+static int64_t ceil_div(int64_t x, int64_t a) { return (x + a - 1) / a; }
+
+// Split `total` items into `parts` consecutive ranges whose sizes differ by at most one.
+static void even_split(int64_t total, int64_t parts, int64_t idx, int64_t* begin, int64_t* count) {
+    const int64_t base = total / parts, rem = total % parts;
+    *begin = idx * base + std::min(idx, rem);
+    *count = base + (idx < rem ? 1 : 0);
+}
+
+// Column chunks of a row of `nvec` vectors when one wavefront lane owns at most
+// `nv` vectors: chunks are whole multiples of 64 vectors except the last.
+static int64_t col_chunks(int64_t nvec, int64_t nv) { return ceil_div(nvec, (int64_t)kWave * nv); }
+
+static void col_chunk_range(int64_t nvec, int64_t nchunk, int64_t c, int32_t* vec0, int32_t* cnt) {
+    const int64_t units = ceil_div(nvec, kWave);
+    int64_t u0, un;
+    even_split(units, nchunk, c, &u0, &un);
+    const int64_t v0 = u0 * kWave;
+    const int64_t v1 = std::min(nvec, (u0 + un) * kWave);
+    *vec0 = (int32_t)v0;
+    *cnt = (int32_t)(v1 - v0);
+}
+
+static void streaming_tiles(const psgd_plan* plan, int64_t rows_per_tile, int64_t nv, bool by_col_part,
+                            std::vector<Tile>* out, std::vector<int32_t>* n_rblock,
+                            std::vector<int32_t>* n_cchunk) {
+    out->clear();
+    for (size_t i = 0; i < plan->mats.size(); ++i) {
+        const MatDesc& d = plan->mats[i];
+        const int64_t nvec = d.m / d.vec;
+        const int64_t ncc = col_chunks(nvec, nv);
+        const int64_t nrb = ceil_div(d.n, rows_per_tile);
+        if (n_rblock) (*n_rblock)[i] = (int32_t)nrb;
+        if (n_cchunk) (*n_cchunk)[i] = (int32_t)ncc;
+        for (int64_t b = 0; b < nrb; ++b) {
+            int64_t r0, rn;
+            even_split(d.n, nrb, b, &r0, &rn);
+            for (int64_t c = 0; c < ncc; ++c) {
+                Tile t{};
+                t.mat = (int32_t)i;
+                t.row0 = (int32_t)r0;
+                t.nrows = (int32_t)rn;
+                col_chunk_range(nvec, ncc, c, &t.vec0, &t.nvec);
+                t.part = (int32_t)(by_col_part ? c : b);
+                out->push_back(t);
+            }
+        }
+    }
+}
+
+psgd_status build_tables(psgd_plan* plan) {
+    const Tuning& tu = plan->tuning;
+    if (tu.k1_rows < 1 || tu.k3_rows < 1 || tu.k4_rows < 1 || tu.k1_nv < 1 ||
+        tu.k1_nv > kMaxVecPerLaneK1 || tu.k3_nv < 1 || tu.k3_nv > kMaxVecPerLaneK3 || tu.k4_nv < 1 ||
+        tu.k4_nv > kMaxVecPerLaneK3 || tu.q_reduce_elems < 1)
+        return PSGD_EINVAL;
+    const size_t nm = plan->mats.size();
+    std::vector<int32_t> nrb(nm, 0), ncc(nm, 0);
+    streaming_tiles(plan, tu.k1_rows, tu.k1_nv, true, &plan->tiles1, nullptr, &ncc);
+    streaming_tiles(plan, tu.k3_rows, tu.k3_nv, false, &plan->tiles3, &nrb, nullptr);
+    streaming_tiles(plan, tu.k4_rows, tu.k4_nv, false, &plan->tiles4, nullptr, nullptr);
+
+    // vector region: slices appended to the decompress work-list
+    const int64_t L = plan->sizes.n_vec_elems;
+    const int64_t vec_slice = (int64_t)kBlock * 4 * 4;
+    for (int64_t e = 0; e < L; e += vec_slice) {
+        Tile t{};
+        t.mat = -1;
+        t.elem0 = e;
+        t.nelem = std::min(vec_slice, L - e);
+        plan->tiles4.push_back(t);
+    }
+
+    // workspace: [W][partial P], then [W][partial Q]; offsets are within one worker's slice
+    int64_t pp = 0, qp = 0;
+    for (size_t i = 0; i < nm; ++i) {
+        MatDesc& d = plan->mats[i];
+        d.n_cchunk = ncc[i];
+        d.n_rblock = nrb[i];
+        d.ppart_off = pp;
+        pp += round_up((int64_t)d.n_cchunk * d.n * d.r, kAlignElems);
+    }
+    for (size_t i = 0; i < nm; ++i) {
+        MatDesc& d = plan->mats[i];
+        d.qpart_off = qp;
+        qp += round_up((int64_t)d.n_rblock * d.m * d.r, kAlignElems);
+    }
+    plan->ws_ppart_floats = pp;
+    plan->ws_qpart_floats = qp;
+    plan->sizes.workspace_bytes = std::max<int64_t>(256, (int64_t)plan->workers * (pp + qp) * (int64_t)sizeof(float));
+
+    // Q reduction: slices of each matrix's m x r panel
+    plan->tilesq.clear();
+    for (size_t i = 0; i < nm; ++i) {
+        const MatDesc& d = plan->mats[i];
+        const int64_t total = (int64_t)d.m * d.r;
+        for (int64_t e = 0; e < total; e += tu.q_reduce_elems) {
+            Tile t{};
+            t.mat = (int32_t)i;
+            t.elem0 = e;
+            t.nelem = std::min<int64_t>(tu.q_reduce_elems, total - e);
+            plan->tilesq.push_back(t);
+        }
+    }
+    plan->tables_built = true;
+    return PSGD_OK;
+}
+
+}  // namespace psgd
+
+using namespace psgd;
+
+extern "C" {
+
+psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_t rank, int32_t workers,
+                             psgd_dtype grad_dtype, psgd_dtype out_dtype, psgd_plan** out_plan) {
+    if (!out_plan) return PSGD_EINVAL;
+    *out_plan = nullptr;
+    if (!shapes || n_tensors < 1 || rank < 1 || workers < 1) return PSGD_EINVAL;
+    if ((grad_dtype != PSGD_F32 && grad_dtype != PSGD_BF16) ||
+        (out_dtype != PSGD_F32 && out_dtype != PSGD_BF16))
+        return PSGD_EINVAL;
+    for (int32_t t = 0; t < n_tensors; ++t) {
+        if (shapes[t].rows < 1 || shapes[t].cols < 1) return PSGD_EINVAL;
+        if (shapes[t].rows > INT32_MAX || shapes[t].cols > INT32_MAX) return PSGD_EUNSUPPORTED;
+    }
+    if (rank > PSGD_MAX_RANK) return PSGD_EUNSUPPORTED;
+    if (rank > kValuMaxRank) return PSGD_EUNSUPPORTED;            // matrix-core path: not built yet
+    if (grad_dtype != PSGD_F32 || out_dtype != PSGD_F32) return PSGD_EUNSUPPORTED;
+
+    psgd_plan* plan = new (std::nothrow) psgd_plan();
+    if (!plan) return PSGD_ENOMEM;
+    try {
+        plan->rank = rank;
+        plan->workers = workers;
+        plan->grad_dtype = grad_dtype;
+        plan->out_dtype = out_dtype;
+        plan->shapes.assign(shapes, shapes + n_tensors);
+        plan->tensor_flat_off.assign(n_tensors, 0);
+        plan->tensor_mat.assign(n_tensors, -1);
+
+        const int64_t gsz = grad_dtype == PSGD_BF16 ? 2 : 4;
+        const int64_t osz = out_dtype == PSGD_BF16 ? 2 : 4;
+        int64_t N = 0, P = 0, Q = 0, payload = 0, compressed = 0;
+        // matrices first
+        for (int32_t t = 0; t < n_tensors; ++t) {
+            if (shapes[t].cols == 1) continue;
+            MatDesc d{};
+            d.n = (int32_t)shapes[t].rows;
+            d.m = (int32_t)shapes[t].cols;
+            d.r = std::min<int32_t>(rank, std::min(d.n, d.m));
+            d.vec = (d.m % 4 == 0) ? 4 : (d.m % 2 == 0 ? 2 : 1);
+            d.off = N;
+            d.p_off = P;
+            d.q_off = Q;
+            d.tensor = t;
+            plan->tensor_flat_off[t] = N;
+            plan->tensor_mat[t] = (int32_t)plan->mats.size();
+            plan->mats.push_back(d);
+            plan->max_n = std::max(plan->max_n, d.n);
+            const int64_t elems = (int64_t)d.n * d.m;
+            N += round_up(elems, kAlignElems);
+            P += (int64_t)d.n * d.r;
+            Q += (int64_t)d.m * d.r;
+            payload += elems;
+            compressed += (int64_t)d.r * ((int64_t)d.n + d.m);
+        }
+        int64_t L = 0;
+        int64_t nvec_t = 0;
+        for (int32_t t = 0; t < n_tensors; ++t) {
+            if (shapes[t].cols != 1) continue;
+            plan->tensor_flat_off[t] = N + L;
+            L += shapes[t].rows;
+            ++nvec_t;
+        }
+        psgd_sizes& s = plan->sizes;
+        s.n_mat_elems = N;
+        s.n_vec_elems = L;
+        s.grad_stride = round_up(N + L, kAlignElems);
+        s.err_stride = N;
+        s.out_elems = N + L;
+        s.p_elems = P;
+        s.q_elems = Q;
+        s.n_matrices = (int64_t)plan->mats.size();
+        s.n_vectors = nvec_t;
+        s.payload_elems = payload + L;
+        s.compressed_elems = compressed + L;
+        const int64_t W = workers;
+        s.bytes_min = payload * (W * (gsz + 4 + 4) + osz) + L * (W * gsz + osz);
+        s.bytes_stream = s.bytes_min + payload * W * 12;
+        psgd_status st = build_tables(plan);
+        if (st != PSGD_OK) {
+            delete plan;
+            return st;
+        }
+    } catch (const std::bad_alloc&) {
+        delete plan;
+        return PSGD_ENOMEM;
+    }
+    *out_plan = plan;
+    return PSGD_OK;
+}
+
+void psgd_plan_destroy(psgd_plan* plan) {
+    if (!plan) return;
+    free_tables(plan);
+    delete plan;
+}
+
+psgd_status psgd_plan_sizes(const psgd_plan* plan, psgd_sizes* out_sizes) {
+    if (!plan || !out_sizes) return PSGD_EINVAL;
+    *out_sizes = plan->sizes;
+    return PSGD_OK;
+}
+
+psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, int64_t* flat_off, int64_t* p_off,
+                              int64_t* q_off, int32_t* eff_rank) {
+    if (!plan || tensor < 0 || tensor >= (int32_t)plan->shapes.size()) return PSGD_EINVAL;
+    if (flat_off) *flat_off = plan->tensor_flat_off[tensor];
+    const int32_t mi = plan->tensor_mat[tensor];
+    if (mi < 0) {
+        if (p_off) *p_off = -1;
+        if (q_off) *q_off = -1;
+        if (eff_rank) *eff_rank = 0;
+    } else {
+        const MatDesc& d = plan->mats[mi];
+        if (p_off) *p_off = d.p_off;
+        if (q_off) *q_off = d.q_off;
+        if (eff_rank) *eff_rank = d.r;
+    }
+    return PSGD_OK;
+}
+
+psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value) {
+    if (!plan || !key) return PSGD_EINVAL;
+    if (plan->uploaded) return PSGD_EINVAL;
+    Tuning tu = plan->tuning;
+    if (!strcmp(key, "k1_rows")) tu.k1_rows = value;
+    else if (!strcmp(key, "k1_nv")) tu.k1_nv = value;
+    else if (!strcmp(key, "k3_rows")) tu.k3_rows = value;
+    else if (!strcmp(key, "k3_nv")) tu.k3_nv = value;
+    else if (!strcmp(key, "k4_rows")) tu.k4_rows = value;
+    else if (!strcmp(key, "k4_nv")) tu.k4_nv = value;
+    else if (!strcmp(key, "q_reduce_elems")) tu.q_reduce_elems = value;
+    else return PSGD_EINVAL;
+    Tuning old = plan->tuning;
+    plan->tuning = tu;
+    try {
+        psgd_status st = build_tables(plan);
+        if (st != PSGD_OK) {
+            plan->tuning = old;
+            build_tables(plan);
+        }
+        return st;
+    } catch (const std::bad_alloc&) {
+        return PSGD_ENOMEM;
+    }
+}
+
+static bool bad_ptrs(const void* a, const void* b, const void* c, const void* d, const void* e) {
+    return !a || !b || !c || !d || !e;
+}
+
+psgd_status psgd_compress(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* workspace,
+                          void* hip_stream) {
+    if (!plan || bad_ptrs(grad, err, q, p, workspace)) return PSGD_EINVAL;
+    return launch_compress(plan, grad, err, q, p, workspace, hip_stream);
+}
+
+psgd_status psgd_decompress(psgd_plan* plan, const float* p, const float* q, float* err, const void* grad,
+                            void* out, void* workspace, void* hip_stream) {
+    if (!plan || bad_ptrs(p, q, err, out, workspace) || !grad) return PSGD_EINVAL;
+    return launch_decompress(plan, p, q, err, grad, out, workspace, hip_stream);
+}
+
+psgd_status psgd_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,
+                      void* workspace, void* hip_stream) {
+    if (!plan || bad_ptrs(grad, err, q, p, workspace) || !out) return PSGD_EINVAL;
+    psgd_status st = launch_compress(plan, grad, err, q, p, workspace, hip_stream);
+    if (st != PSGD_OK) return st;
+    return launch_decompress(plan, p, q, err, grad, out, workspace, hip_stream);
+}
+
+psgd_status psgd_plan_set_profiling(psgd_plan* plan, int32_t enable) {
+    if (!plan) return PSGD_EINVAL;
+    return set_profiling(plan, enable != 0);
+}
+
+psgd_status psgd_plan_kernel_times(psgd_plan* plan, double* ms_sum, int64_t* steps) {
+    if (!plan || !ms_sum || !steps) return PSGD_EINVAL;
+    for (int i = 0; i < PSGD_N_KERNELS; ++i) {
+        ms_sum[i] = plan->kernel_ms[i];
+        plan->kernel_ms[i] = 0.0;
+    }
+    *steps = plan->profiled_steps;
+    plan->profiled_steps = 0;
+    return PSGD_OK;
+}
+
+const char* psgd_kernel_name(int32_t index) {
+    static const char* const names[PSGD_N_KERNELS] = {"k_ef_right", "k_ortho", "k_left", "k_q_reduce", "k_decomp"};
+    return (index >= 0 && index < PSGD_N_KERNELS) ? names[index] : nullptr;
+}
+
+const char* psgd_status_string(psgd_status status) {
+    switch (status) {
+        case PSGD_OK: return "ok";
+        case PSGD_EINVAL: return "invalid argument";
+        case PSGD_ENOMEM: return "out of memory";
+        case PSGD_EHIP: return "HIP runtime error";
+        case PSGD_EUNSUPPORTED: return "unsupported";
+    }
+    return "unknown status";
+}
+
+const char* psgd_plan_last_error(const psgd_plan* plan) { return plan ? plan->last_error.c_str() : ""; }
+
+}  // extern "C"

@@ -1,0 +1,122 @@
+// Host-only check of the planner's work-lists, built with g++ and the sanitizers by
+// tests/test_host_planner.py.  For a set of shape lists and tunings it verifies that the
+// tiles of every streaming kernel cover every matrix element exactly once, stay inside the
+// row, respect the per-lane vector limit, and that every partial-sum slice lies inside the
+// workspace the plan asks for: the bounds the kernels rely on.
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+#include "psgd_internal.h"
+
+namespace psgd {
+void free_tables(psgd_plan*) {}
+psgd_status set_profiling(psgd_plan*, bool) { return PSGD_EHIP; }
+psgd_status launch_compress(psgd_plan*, const void*, float*, float*, float*, void*, void*) { return PSGD_EHIP; }
+psgd_status launch_decompress(psgd_plan*, const float*, const float*, float*, const void*, void*, void*, void*) {
+    return PSGD_EHIP;
+}
+}  // namespace psgd
+
+#define CHECK(c)                                                        \
+    do {                                                                \
+        if (!(c)) {                                                     \
+            std::printf("FAIL %s:%d %s\n", __FILE__, __LINE__, #c);     \
+            std::exit(1);                                               \
+        }                                                               \
+    } while (0)
+
+using namespace psgd;
+
+// parts: 1 = column-chunk partials (P = M Q), 2 = row-block partials (Q = M^T P), 0 = the kernel writes no partials
+static void check_cover(const psgd_plan* plan, const std::vector<Tile>& tiles, int nv_cap, int parts) {
+    std::vector<std::vector<unsigned char>> seen(plan->mats.size());
+    for (size_t i = 0; i < plan->mats.size(); ++i) seen[i].assign((size_t)plan->mats[i].n * plan->mats[i].m, 0);
+    int64_t vec_seen = 0;
+    for (const Tile& t : tiles) {
+        if (t.mat < 0) {
+            CHECK(t.elem0 == vec_seen && t.nelem > 0);
+            vec_seen += t.nelem;
+            continue;
+        }
+        CHECK(t.mat < (int)plan->mats.size());
+        const MatDesc& d = plan->mats[t.mat];
+        CHECK(d.m % d.vec == 0);
+        CHECK(t.nrows > 0 && t.row0 >= 0 && t.row0 + t.nrows <= d.n);
+        CHECK(t.nvec > 0 && t.vec0 >= 0 && (int64_t)(t.vec0 + t.nvec) * d.vec <= d.m);
+        CHECK(t.nvec <= kWave * nv_cap);
+        if (parts) CHECK(t.part >= 0 && t.part < (parts == 1 ? d.n_cchunk : d.n_rblock));
+        for (int i = t.row0; i < t.row0 + t.nrows; ++i)
+            for (int j = t.vec0 * d.vec; j < (t.vec0 + t.nvec) * d.vec; ++j) {
+                unsigned char& s = seen[t.mat][(size_t)i * d.m + j];
+                CHECK(s == 0);
+                s = 1;
+            }
+    }
+    for (auto& v : seen)
+        for (unsigned char s : v) CHECK(s == 1);
+    if (vec_seen) CHECK(vec_seen == plan->sizes.n_vec_elems);
+}
+
+static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int workers, const Tuning* tu) {
+    psgd_plan* plan = nullptr;
+    CHECK(psgd_plan_create(shapes.data(), (int)shapes.size(), rank, workers, PSGD_F32, PSGD_F32, &plan) == PSGD_OK);
+    if (tu) {
+        CHECK(psgd_plan_set_tuning(plan, "k1_rows", tu->k1_rows) == PSGD_OK);
+        CHECK(psgd_plan_set_tuning(plan, "k1_nv", tu->k1_nv) == PSGD_OK);
+        CHECK(psgd_plan_set_tuning(plan, "k3_rows", tu->k3_rows) == PSGD_OK);
+        CHECK(psgd_plan_set_tuning(plan, "k3_nv", tu->k3_nv) == PSGD_OK);
+        CHECK(psgd_plan_set_tuning(plan, "k4_rows", tu->k4_rows) == PSGD_OK);
+        CHECK(psgd_plan_set_tuning(plan, "k4_nv", tu->k4_nv) == PSGD_OK);
+        CHECK(psgd_plan_set_tuning(plan, "q_reduce_elems", tu->q_reduce_elems) == PSGD_OK);
+    }
+    check_cover(plan, plan->tiles1, (int)plan->tuning.k1_nv, 1);
+    check_cover(plan, plan->tiles3, (int)plan->tuning.k3_nv, 2);
+    check_cover(plan, plan->tiles4, (int)plan->tuning.k4_nv, 0);
+    // flat layout: matrices do not overlap, stay inside N, are 64-aligned
+    int64_t prev_end = 0;
+    for (const MatDesc& d : plan->mats) {
+        CHECK(d.off % kAlignElems == 0 && d.off >= prev_end);
+        prev_end = d.off + (int64_t)d.n * d.m;
+        CHECK(prev_end <= plan->sizes.n_mat_elems);
+        CHECK(d.r >= 1 && d.r <= rank && d.r <= d.n && d.r <= d.m);
+        CHECK(d.p_off + (int64_t)d.n * d.r <= plan->sizes.p_elems);
+        CHECK(d.q_off + (int64_t)d.m * d.r <= plan->sizes.q_elems);
+        CHECK(d.ppart_off + (int64_t)d.n_cchunk * d.n * d.r <= plan->ws_ppart_floats);
+        CHECK(d.qpart_off + (int64_t)d.n_rblock * d.m * d.r <= plan->ws_qpart_floats);
+    }
+    CHECK((int64_t)workers * (plan->ws_ppart_floats + plan->ws_qpart_floats) * 4 <= plan->sizes.workspace_bytes);
+    CHECK(plan->sizes.grad_stride >= plan->sizes.n_mat_elems + plan->sizes.n_vec_elems);
+    // Q-reduction slices cover each m x r panel exactly once
+    std::vector<int64_t> covered(plan->mats.size(), 0);
+    for (const Tile& t : plan->tilesq) {
+        CHECK(t.mat >= 0 && t.elem0 == covered[t.mat] && t.nelem > 0);
+        covered[t.mat] += t.nelem;
+    }
+    for (size_t i = 0; i < plan->mats.size(); ++i) CHECK(covered[i] == (int64_t)plan->mats[i].m * plan->mats[i].r);
+    psgd_plan_destroy(plan);
+}
+
+int main() {
+    std::vector<std::vector<psgd_shape>> sets = {
+        {{64, 27}, {64, 576}, {64, 576}},
+        {{37, 91}, {7, 1}, {50, 650}, {130, 1028}, {5, 3}, {300, 2}, {1, 40}, {1031, 1}, {3, 4700}, {257, 260}},
+        {{512, 4608}, {10, 512}, {128, 64}, {9610, 1}},
+        {{2600, 650}, {3328, 650}},
+        {{1, 2}, {2, 1}},
+    };
+    Tuning small;
+    small.k1_rows = 8; small.k1_nv = 1; small.k3_rows = 16; small.k3_nv = 1; small.k4_rows = 8; small.k4_nv = 1;
+    small.q_reduce_elems = 256;
+    Tuning big;
+    big.k1_rows = 64; big.k1_nv = 2; big.k3_rows = 300; big.k3_nv = 2; big.k4_rows = 300; big.k4_nv = 2;
+    for (auto& s : sets)
+        for (int rank : {1, 2, 4, 8})
+            for (int W : {1, 3}) {
+                check_plan(s, rank, W, nullptr);
+                check_plan(s, rank, W, &small);
+                check_plan(s, rank, W, &big);
+            }
+    std::printf("OK\n");
+    return 0;
+}

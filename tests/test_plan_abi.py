@@ -1,0 +1,112 @@
+"""CPU-only checks of the host side of the library: it loads, exports every
+symbol the header declares, validates arguments, and its layout / byte
+accounting agrees with the paper's tables."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1905_13727_amd import binding as B
+from paper_1905_13727_amd import workloads as WL
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load_library()
+    hdr = open(os.path.join(ROOT, "include", "psgd.h")).read()
+    names = re.findall(r"PSGD_API\s+[\w\s\*]+?\b(psgd_\w+)\s*\(", hdr)
+    assert len(names) >= 10
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    assert B.status_string(B.PSGD_OK) == "ok"
+    assert "invalid" in B.status_string(B.PSGD_EINVAL)
+    assert B.status_string(77) == "unknown status"
+
+
+@pytest.mark.parametrize("kwargs,status", [
+    (dict(shapes=[(4, 4)], rank=0), B.PSGD_EINVAL),
+    (dict(shapes=[(4, 4)], rank=2, workers=0), B.PSGD_EINVAL),
+    (dict(shapes=[(0, 4)], rank=2), B.PSGD_EINVAL),
+    (dict(shapes=[(4, -1)], rank=2), B.PSGD_EINVAL),
+    (dict(shapes=[], rank=2), B.PSGD_EINVAL),
+    (dict(shapes=[(4, 4)], rank=B.PSGD_MAX_RANK + 1), B.PSGD_EUNSUPPORTED),
+    (dict(shapes=[(4, 4)], rank=2, grad_dtype=7), B.PSGD_EINVAL),
+])
+def test_invalid_plans(kwargs, status):
+    with pytest.raises(B.PsgdError) as ei:
+        B.Plan(**kwargs)
+    assert ei.value.status == status
+
+
+def test_null_pointers_are_rejected_without_a_gpu():
+    lib = B.load_library()
+    assert lib.psgd_plan_create(None, 1, 1, 1, 0, 0, None) == B.PSGD_EINVAL
+    h = C.c_void_p()
+    assert lib.psgd_plan_create(None, 1, 1, 1, 0, 0, C.byref(h)) == B.PSGD_EINVAL
+    plan = B.Plan([(8, 8)], 2)
+    assert lib.psgd_step(plan._h, None, None, None, None, None, None, None) == B.PSGD_EINVAL
+    assert lib.psgd_compress(None, 1, 1, 1, 1, 1, None) == B.PSGD_EINVAL
+    assert lib.psgd_decompress(plan._h, 1, 1, None, 1, 1, 1, None) == B.PSGD_EINVAL
+    assert lib.psgd_plan_sizes(plan._h, None) == B.PSGD_EINVAL
+    assert lib.psgd_plan_offsets(plan._h, 5, None, None, None, None) == B.PSGD_EINVAL
+    lib.psgd_plan_destroy(None)
+    with pytest.raises(B.PsgdError):
+        plan.set_tuning("no_such_key", 1)
+    with pytest.raises(B.PsgdError):
+        plan.set_tuning("k1_nv", 99)
+    plan.set_tuning("k1_rows", 16)
+
+
+def test_layout_resnet18():
+    shapes = WL.resnet18_shapes()
+    plan = B.Plan(shapes, 2, 1)
+    s = plan.sizes
+    assert s.n_matrices == 21 and s.n_vec_elems == 9610
+    assert s.payload_elems == 11164352 + 9610
+    assert s.n_mat_elems == 11164352          # every ResNet18 matrix is a multiple of 64 elements
+    assert s.p_elems == 2 * 4810 and s.q_elems == 2 * 31515
+    # traffic model per matrix element: 12 + 4/W compulsory, 24 + 4/W streaming
+    assert s.bytes_min == 11164352 * 16 + 9610 * 8
+    assert s.bytes_stream == 11164352 * 28 + 9610 * 8
+    # offsets: matrices in order, aligned, then vectors in order
+    prev_end = 0
+    voff = s.n_mat_elems
+    for t, sh in enumerate(shapes):
+        f, p, q, r = plan.offsets(t)
+        if len(sh) == 1:
+            assert (f, p, q, r) == (voff, -1, -1, 0)
+            voff += sh[0]
+        else:
+            assert f % 64 == 0 and f >= prev_end and r == 2
+            prev_end = f + sh[0] * sh[1]
+    assert voff == s.out_elems
+
+
+def test_effective_rank_and_padding():
+    shapes = [(5, 3), (7,), (37, 91), (2, 100)]
+    plan = B.Plan(shapes, 4, 3)
+    assert [plan.offsets(t)[3] for t in range(4)] == [3, 0, 4, 2]
+    assert plan.offsets(0)[0] == 0 and plan.offsets(2)[0] == 64 and plan.offsets(3)[0] == 64 + 3392
+    s = plan.sizes
+    assert s.n_mat_elems == 64 + 3392 + 256 and s.n_vec_elems == 7
+    assert s.grad_stride % 64 == 0 and s.grad_stride >= s.n_mat_elems + 7
+    assert s.p_elems == 5 * 3 + 37 * 4 + 2 * 2 and s.q_elems == 3 * 3 + 91 * 4 + 100 * 2
+    assert s.workspace_bytes > 0
+
+
+def test_compression_ratios_match_the_paper():
+    """Appendix F / Table 3: 243x, 136x, 72x for ResNet18; 310x, 203x, 120x for the LSTM."""
+    from oracle import powersgd_oracle as O
+    for shapes, want in ((WL.resnet18_shapes(), {1: 243, 2: 136, 4: 72}),
+                         (WL.lstm_shapes(vocab=28869), {1: 310, 2: 203, 4: 120})):
+        for r, ratio in want.items():
+            s = B.Plan(shapes, r, 1).sizes
+            got = s.payload_elems / s.compressed_elems
+            assert abs(got - ratio) <= 0.5
+            assert s.compressed_elems == O.compressed_floats(shapes, r)
