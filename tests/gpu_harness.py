@@ -52,6 +52,9 @@ class GpuRun:
             host[w] = self.lay.pack_flat(errs[w], matrices_only=True)
         self.err.copy_(torch.from_numpy(host.reshape(-1)))
 
+    def set_q(self, qs):
+        self.q.copy_(torch.from_numpy(self.lay.pack_q(qs)))
+
     def step(self, grads=None, split=False):
         if grads is not None:
             self.upload(grads)
@@ -87,6 +90,13 @@ class OracleRun:
         self.Qs = [None if q is None else np.asarray(q, dtype=np.float64) for q in q0]
         self.errs = [[None if len(s) == 1 else np.zeros(O.matrix_view(s)) for s in self.shapes]
                      for _ in range(workers)]
+
+    def round_state_to_fp32(self):
+        """The method's state is fp32 (the paper's precision): round the carried error memories and
+        warm-start Q to fp32 so that the GPU can be restarted from bit-identical values."""
+        self.Qs = [None if q is None else q.astype(np.float32).astype(np.float64) for q in self.Qs]
+        self.errs = [[None if e is None else e.astype(np.float32).astype(np.float64) for e in ew]
+                     for ew in self.errs]
 
     def step(self, grads):
         res = O.powersgd_step(grads, self.errs, self.Qs, self.rank)
