@@ -146,8 +146,17 @@ PSGD_API psgd_status psgd_compress(psgd_plan* plan, const void* grad, float* err
 PSGD_API psgd_status psgd_decompress(psgd_plan* plan, const float* p, const float* q, float* err,
                             const void* grad, void* out, void* workspace, void* hip_stream);
 
-/* One whole step = psgd_compress followed by psgd_decompress, bit-identical to
- * calling the two in sequence. */
+/* One whole step: the same quantities as psgd_compress followed by
+ * psgd_decompress.  For W = 1, rank <= 4 and a model whose matrices fit the
+ * register files of the chip (every matrix at most 512 rows, about 16 M
+ * elements in total) the plan runs in RESIDENT mode: one kernel keeps
+ * M = g + e on chip for the whole step, so each element is read and written
+ * once.  Its sums run in another (fixed) order than the split calls, so the
+ * two agree to rounding, not bit for bit; each is reproducible from run to
+ * run.  Otherwise psgd_step is exactly the two calls in sequence.  Resident
+ * mode keeps barrier words in plan-owned device memory: do not run two steps
+ * of the same plan concurrently on different streams.
+ * psgd_plan_check (below) reports whether a resident step ever timed out. */
 PSGD_API psgd_status psgd_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p,
                       void* out, void* workspace, void* hip_stream);
 
@@ -157,13 +166,28 @@ PSGD_API psgd_status psgd_step(psgd_plan* plan, const void* grad, float* err, fl
  * end to accumulate the elapsed times: use it for measurement runs only.
  * psgd_plan_kernel_times copies the accumulated milliseconds per kernel (array
  * of PSGD_N_KERNELS doubles, order given by psgd_kernel_name) and the number of
- * accumulated steps, then clears the accumulators. */
-#define PSGD_N_KERNELS 5
+ * accumulated steps, then clears the accumulators.  A plan in resident mode
+ * (see psgd_step) runs one kernel per step, index PSGD_KERNEL_RESIDENT. */
+#define PSGD_N_KERNELS 6
+#define PSGD_KERNEL_RESIDENT 5
 PSGD_API psgd_status psgd_plan_set_profiling(psgd_plan* plan, int32_t enable);
 PSGD_API psgd_status psgd_plan_kernel_times(psgd_plan* plan, double* ms_sum, int64_t* steps);
 /* Name of kernel `index` in [0, PSGD_N_KERNELS) as it appears in a profiler's
  * kernel trace (prefix of the symbol); NULL if out of range. */
 PSGD_API const char* psgd_kernel_name(int32_t index);
+
+/* Waits for hip_stream, then returns PSGD_EHIP if a resident-mode kernel of this
+ * plan gave up waiting at a grid barrier since the last check (its outputs are
+ * then invalid; the plan's barrier words are reset), PSGD_OK otherwise.
+ * is_resident (may be NULL) receives 1 if psgd_step runs in resident mode. */
+PSGD_API psgd_status psgd_plan_check(psgd_plan* plan, void* hip_stream, int32_t* is_resident);
+
+/* Diagnostic.  After psgd_plan_set_tuning(plan, "res_trace", 1), every resident
+ * step records 8 device timestamps (100 MHz clock) per workgroup: start, partial
+ * P written, before / after the first grid barrier, before / after the second,
+ * end (the 8th is unused).  Synchronises the device and copies at most
+ * `capacity` values of the last step to `out` (host); *n_written = count. */
+PSGD_API psgd_status psgd_plan_read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t* n_written);
 
 /* Static, never NULL. */
 PSGD_API const char* psgd_status_string(psgd_status status);

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(HERE, "libpsgd.so")
 PSGD_OK, PSGD_EINVAL, PSGD_ENOMEM, PSGD_EHIP, PSGD_EUNSUPPORTED = range(5)
 PSGD_F32, PSGD_BF16 = 0, 1
 PSGD_MAX_RANK = 64
-PSGD_N_KERNELS = 5
+PSGD_N_KERNELS = 6
 
 
 class psgd_shape(C.Structure):
@@ -73,6 +73,10 @@ def load_library(path: Optional[str] = None):
     lib.psgd_plan_kernel_times.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.psgd_kernel_name.restype = C.c_char_p
     lib.psgd_kernel_name.argtypes = [i32]
+    lib.psgd_plan_check.restype = C.c_int
+    lib.psgd_plan_check.argtypes = [vp, vp, C.POINTER(i32)]
+    lib.psgd_plan_read_trace.restype = C.c_int
+    lib.psgd_plan_read_trace.argtypes = [vp, C.POINTER(C.c_uint64), i64, C.POINTER(i64)]
     lib.psgd_status_string.restype = C.c_char_p
     lib.psgd_status_string.argtypes = [C.c_int]
     lib.psgd_plan_last_error.restype = C.c_char_p
@@ -172,6 +176,21 @@ class Plan:
         self._check(self._lib.psgd_plan_kernel_times(self._h, ms, C.byref(steps)), "psgd_plan_kernel_times")
         names = [self._lib.psgd_kernel_name(i).decode() for i in range(PSGD_N_KERNELS)]
         return dict(zip(names, list(ms))), steps.value
+
+    def check(self, stream=None) -> bool:
+        """Synchronises the stream, raises if a resident step timed out; returns True if the plan's
+        psgd_step runs in resident mode."""
+        r = C.c_int32()
+        self._check(self._lib.psgd_plan_check(self._h, _ptr(stream), C.byref(r)), "psgd_plan_check")
+        return bool(r.value)
+
+    def read_trace(self, capacity=1 << 16):
+        """Diagnostic timestamps of the last resident step: list of per-workgroup lists (see psgd.h)."""
+        buf = (C.c_uint64 * capacity)()
+        n = C.c_int64()
+        self._check(self._lib.psgd_plan_read_trace(self._h, buf, capacity, C.byref(n)), "psgd_plan_read_trace")
+        vals = list(buf[: n.value])
+        return [vals[i: i + 8] for i in range(0, len(vals), 8)]
 
     def last_error(self) -> str:
         return self._lib.psgd_plan_last_error(self._h).decode()

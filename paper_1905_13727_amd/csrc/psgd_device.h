@@ -1,0 +1,148 @@
+// Device-side helpers shared by the streaming kernels and the resident kernel (gfx950).
+#ifndef PSGD_DEVICE_H
+#define PSGD_DEVICE_H
+
+#include <hip/hip_runtime.h>
+
+#include "psgd_internal.h"
+
+namespace psgd {
+
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+// ---- V-wide row accesses -----------------------------------------------------------------------
+
+template <int V>
+__device__ __forceinline__ void ldv(const float* p, float (&x)[V]);
+template <>
+__device__ __forceinline__ void ldv<1>(const float* p, float (&x)[1]) { x[0] = *p; }
+template <>
+__device__ __forceinline__ void ldv<2>(const float* p, float (&x)[2]) {
+    f2 t = *reinterpret_cast<const f2*>(p);
+    x[0] = t.x; x[1] = t.y;
+}
+template <>
+__device__ __forceinline__ void ldv<4>(const float* p, float (&x)[4]) {
+    f4 t = *reinterpret_cast<const f4*>(p);
+    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+}
+
+// streamed-once data (the gradient): non-temporal so that it does not evict M from the caches
+template <int V>
+__device__ __forceinline__ void ldv_stream(const float* p, float (&x)[V]);
+template <>
+__device__ __forceinline__ void ldv_stream<1>(const float* p, float (&x)[1]) { x[0] = __builtin_nontemporal_load(p); }
+template <>
+__device__ __forceinline__ void ldv_stream<2>(const float* p, float (&x)[2]) {
+    f2 t = __builtin_nontemporal_load(reinterpret_cast<const f2*>(p));
+    x[0] = t.x; x[1] = t.y;
+}
+template <>
+__device__ __forceinline__ void ldv_stream<4>(const float* p, float (&x)[4]) {
+    f4 t = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
+    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+}
+
+template <int V>
+__device__ __forceinline__ void stv(float* p, const float (&x)[V]);
+template <>
+__device__ __forceinline__ void stv<1>(float* p, const float (&x)[1]) { *p = x[0]; }
+template <>
+__device__ __forceinline__ void stv<2>(float* p, const float (&x)[2]) {
+    f2 t; t.x = x[0]; t.y = x[1];
+    *reinterpret_cast<f2*>(p) = t;
+}
+template <>
+__device__ __forceinline__ void stv<4>(float* p, const float (&x)[4]) {
+    f4 t; t.x = x[0]; t.y = x[1]; t.z = x[2]; t.w = x[3];
+    *reinterpret_cast<f4*>(p) = t;
+}
+
+// ---- wavefront helpers ---------------------------------------------------------------------------
+
+__device__ __forceinline__ float lane_bcast(float v, int src_lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the 64 lanes, same value returned in every lane, fixed order: data-parallel-primitive
+// adds inside each row of 16 lanes (lane^1, lane^2, mirrored 8, mirrored 16), then the four row
+// sums are read out and added as (row0 + row1) + (row2 + row3).
+__device__ __forceinline__ float wave_sum(float v) {
+    v += dpp_mov<0xB1>(v);   // quad_perm [1,0,3,2]
+    v += dpp_mov<0x4E>(v);   // quad_perm [2,3,0,1]
+    v += dpp_mov<0x141>(v);  // row_half_mirror
+    v += dpp_mov<0x140>(v);  // row_mirror
+    const float s0 = lane_bcast(v, 0), s1 = lane_bcast(v, 16), s2 = lane_bcast(v, 32), s3 = lane_bcast(v, 48);
+    return (s0 + s1) + (s2 + s3);
+}
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_mov(double v) {
+    const long long b = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffLL), CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xf, 0xf, true);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
+__device__ __forceinline__ double lane_bcast(double v, int src_lane) {
+    const long long b = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_readlane((int)(b & 0xffffffffLL), src_lane);
+    const int hi = __builtin_amdgcn_readlane((int)(b >> 32), src_lane);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+    v += dpp_mov<0xB1>(v);
+    v += dpp_mov<0x4E>(v);
+    v += dpp_mov<0x141>(v);
+    v += dpp_mov<0x140>(v);
+    const double s0 = lane_bcast(v, 0), s1 = lane_bcast(v, 16), s2 = lane_bcast(v, 32), s3 = lane_bcast(v, 48);
+    return (s0 + s1) + (s2 + s3);
+}
+
+// rows [*begin, *begin + *count) of a tile's `total` rows that wavefront `wave` of 4 handles
+__device__ __forceinline__ void wave_rows(int total, int wave, int* begin, int* count) {
+    const int base = total / kWavesPerBlock, rem = total % kWavesPerBlock;
+    *begin = wave * base + (wave < rem ? wave : rem);
+    *count = base + (wave < rem ? 1 : 0);
+}
+
+// ---- accesses that are coherent across the whole GPU inside one kernel ----------------------------
+//
+// The eight accelerator dies have one L2 each.  Data that one workgroup writes and another reads
+// within the same kernel goes through device-scope relaxed atomics: the store is written through
+// to memory and the load is served from there, so no cache-wide write-back or invalidate is needed.
+
+__device__ __forceinline__ float ld_dev(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned ld_dev(const unsigned* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(unsigned* p, unsigned v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned add_dev(unsigned* p, unsigned v) {
+    return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Wait until every memory operation this wavefront has issued is complete (loads returned, stores
+// acknowledged), and keep the compiler from moving memory operations across this point.
+__device__ __forceinline__ void wave_mem_done() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+}  // namespace psgd
+
+#endif

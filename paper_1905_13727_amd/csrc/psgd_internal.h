@@ -48,6 +48,33 @@ struct Tile {
     int64_t nelem;  // vector tiles and Q-reduce tiles: element count
 };
 
+// Resident path: one wavefront keeps one tile of M in registers through the whole step.
+constexpr int kResRows = 32;         // most rows of a resident tile (registers: kResRows * vec floats per lane)
+constexpr int kResMinRows = 8;       // strips are not made thinner than this
+constexpr int kResMaxN = 512;        // tallest matrix the single-wavefront Gram-Schmidt handles (8 rows per lane)
+constexpr int kResMaxRank = 4;
+constexpr int kResCUs = 256;         // MI355X compute units
+constexpr int kResBlocksPerCU = 2;   // 256-thread workgroups per compute unit (8 wavefronts, 2 per SIMD)
+constexpr int kResBarrierFanIn = 32; // workgroups per first-level arrival counter
+constexpr int kResFlagCopies = 8;    // copies of each readiness flag, one 256-byte line each
+constexpr int kResTracePoints = 8;   // diagnostic timestamps per workgroup of the resident kernel
+
+// One wavefront's share of the resident kernel.
+struct RTile {
+    int32_t mat;         // matrix index; -1: slice of the vector region; -2: idle slot
+    int32_t row0, nrows; // strip of rows (nrows <= kResRows)
+    int32_t vec0, nvec;  // column vectors (nvec <= 64)
+    int32_t ppart;       // column-chunk index = slice of partial P this tile writes
+    int32_t nstrips_mat; // strips of this matrix (strip arrivals before its P is complete)
+    int32_t qrun_len;    // > 0: first of a run of consecutive wavefronts of the workgroup that hold strips of
+                         // the same column chunk; it adds the run's sums in LDS and writes one partial Q
+    int32_t qpart;       // slot of that partial
+    int32_t nqparts;     // partial-Q slots of this column chunk (arrivals before its Q is complete)
+    int32_t cntq;        // index of this column chunk's arrival counter
+    int32_t cnts;        // index of this strip's arrival counter (column chunks arrive)
+    int64_t elem0, nelem;  // vector tiles: slice of the vector region
+};
+
 struct Tuning {
     int64_t k1_rows = 32;   // rows per workgroup tile, P = M Q
     int64_t k1_nv = 4;      // column vectors per lane (<= kMaxVecPerLaneK1)
@@ -56,6 +83,9 @@ struct Tuning {
     int64_t k4_rows = 64;   // rows per workgroup tile, decompress + residual
     int64_t k4_nv = 1;
     int64_t q_reduce_elems = 1024;  // elements per workgroup in the Q reduction
+    int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream
+    int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height
+    int64_t res_trace = 0;  // 1: the resident kernel records phase timestamps (diagnostic)
 };
 
 struct DeviceTables {
@@ -64,6 +94,10 @@ struct DeviceTables {
     Tile* tiles3 = nullptr;
     Tile* tiles4 = nullptr;
     Tile* tilesq = nullptr;
+    MatDesc* res_mats = nullptr;
+    RTile* res_tiles = nullptr;
+    unsigned* res_sync = nullptr;  // barrier lines, arrival counters, error flag (zero between steps)
+    unsigned long long* res_trace = nullptr;  // only with tuning res_trace = 1
     void* base = nullptr;   // the one allocation holding all of the above
 };
 
@@ -84,6 +118,18 @@ struct psgd_plan {
     int64_t ws_ppart_floats = 0;            // workspace: partial P region (floats)
     int64_t ws_qpart_floats = 0;            // workspace: partial Q region, starts after partial P
     psgd::Tuning tuning;
+    // resident path
+    bool resident_ok = false;               // planner found a tiling that fits the chip
+    int32_t res_strip_rows = 0;
+    int32_t res_blocks = 0;
+    int32_t res_vec_class = 0;
+    std::vector<psgd::MatDesc> res_mats;    // same matrices, partial-sum layout of the resident tiling
+    std::vector<psgd::RTile> res_tiles;     // res_blocks * 4 entries
+    int32_t res_n_cntq = 0;                 // column-chunk arrival counters
+    int32_t res_n_cnts = 0;                 // strip arrival counters
+    int64_t res_ws_floats = 0;
+    int64_t res_sync_words = 0;
+    int64_t res_flags_at = 0;               // word offset of the readiness flags inside the sync words
     bool tables_built = false;
     bool uploaded = false;
     int device = -1;
@@ -107,6 +153,19 @@ psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float
 psgd_status launch_decompress(psgd_plan* plan, const float* p, const float* q, float* err,
                               const void* grad, void* out, void* workspace, void* stream);
 psgd_status set_profiling(psgd_plan* plan, bool enable);
+psgd_status check_plan(psgd_plan* plan, void* stream);
+psgd_status read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t* n_written);
+psgd_status resident_check_device(psgd_plan* plan);
+psgd_status launch_resident_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,
+                                 void* workspace, void* stream);
+// layout of the resident kernel's synchronisation words (units of unsigned); every barrier word has a
+// 256-byte line of its own
+constexpr int kSyncLineWords = 64;
+constexpr int64_t res_sync_top() { return 0; }
+constexpr int64_t res_sync_err() { return kSyncLineWords; }
+constexpr int64_t res_sync_gcount(int g) { return (int64_t)(2 + g) * kSyncLineWords; }
+constexpr int64_t res_sync_ggen(int ngroups, int g) { return (int64_t)(2 + ngroups + g) * kSyncLineWords; }
+constexpr int64_t res_sync_cntp(int ngroups) { return (int64_t)(2 + 2 * ngroups) * kSyncLineWords; }
 }  // namespace psgd
 
 #endif

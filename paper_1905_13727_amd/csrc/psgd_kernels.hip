@@ -17,88 +17,14 @@
 // bit-reproducible from run to run.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 
+#include "psgd_device.h"
 #include "psgd_internal.h"
 
 namespace psgd {
-
-typedef float f2 __attribute__((ext_vector_type(2)));
-typedef float f4 __attribute__((ext_vector_type(4)));
-
-// ---- V-wide row accesses -----------------------------------------------------------------------
-
-template <int V>
-__device__ __forceinline__ void ldv(const float* p, float (&x)[V]);
-template <>
-__device__ __forceinline__ void ldv<1>(const float* p, float (&x)[1]) { x[0] = *p; }
-template <>
-__device__ __forceinline__ void ldv<2>(const float* p, float (&x)[2]) {
-    f2 t = *reinterpret_cast<const f2*>(p);
-    x[0] = t.x; x[1] = t.y;
-}
-template <>
-__device__ __forceinline__ void ldv<4>(const float* p, float (&x)[4]) {
-    f4 t = *reinterpret_cast<const f4*>(p);
-    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
-}
-
-// streamed-once data (the gradient): non-temporal so that it does not evict M from the caches
-template <int V>
-__device__ __forceinline__ void ldv_stream(const float* p, float (&x)[V]);
-template <>
-__device__ __forceinline__ void ldv_stream<1>(const float* p, float (&x)[1]) { x[0] = __builtin_nontemporal_load(p); }
-template <>
-__device__ __forceinline__ void ldv_stream<2>(const float* p, float (&x)[2]) {
-    f2 t = __builtin_nontemporal_load(reinterpret_cast<const f2*>(p));
-    x[0] = t.x; x[1] = t.y;
-}
-template <>
-__device__ __forceinline__ void ldv_stream<4>(const float* p, float (&x)[4]) {
-    f4 t = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
-    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
-}
-
-template <int V>
-__device__ __forceinline__ void stv(float* p, const float (&x)[V]);
-template <>
-__device__ __forceinline__ void stv<1>(float* p, const float (&x)[1]) { *p = x[0]; }
-template <>
-__device__ __forceinline__ void stv<2>(float* p, const float (&x)[2]) {
-    f2 t; t.x = x[0]; t.y = x[1];
-    *reinterpret_cast<f2*>(p) = t;
-}
-template <>
-__device__ __forceinline__ void stv<4>(float* p, const float (&x)[4]) {
-    f4 t; t.x = x[0]; t.y = x[1]; t.z = x[2]; t.w = x[3];
-    *reinterpret_cast<f4*>(p) = t;
-}
-
-// ---- wavefront helpers ---------------------------------------------------------------------------
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, kWave);
-    return v;
-}
-
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, kWave);
-    return v;
-}
-
-__device__ __forceinline__ float lane_bcast(float v, int src_lane) {
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
-}
-
-// rows [*begin, *begin + *count) of a tile's `total` rows that wavefront `wave` of 4 handles
-__device__ __forceinline__ void wave_rows(int total, int wave, int* begin, int* count) {
-    const int base = total / kWavesPerBlock, rem = total % kWavesPerBlock;
-    *begin = wave * base + (wave < rem ? wave : rem);
-    *count = base + (wave < rem ? 1 : 0);
-}
 
 // ---- k_ef_right: M = g + e, P_w[i,:] = sum_j M[i,j] Q[j,:] ---------------------------------------
 //
@@ -576,27 +502,32 @@ void free_tables(psgd_plan* plan) {
 
 psgd_status upload_tables(psgd_plan* plan) {
     if (plan->uploaded) return PSGD_OK;
-    auto bytes_of = [](size_t n, size_t sz) { return (n * sz + 255) / 256 * 256; };
-    const size_t b_m = bytes_of(plan->mats.size(), sizeof(MatDesc));
-    const size_t b_1 = bytes_of(plan->tiles1.size(), sizeof(Tile));
-    const size_t b_3 = bytes_of(plan->tiles3.size(), sizeof(Tile));
-    const size_t b_4 = bytes_of(plan->tiles4.size(), sizeof(Tile));
-    const size_t b_q = bytes_of(plan->tilesq.size(), sizeof(Tile));
-    const size_t total = b_m + b_1 + b_3 + b_4 + b_q + 256;
-    std::vector<char> host(total, 0);
-    size_t o = 0;
-    auto put = [&](const void* src, size_t n, size_t padded) {
-        if (n) std::memcpy(host.data() + o, src, n);
-        size_t at = o;
-        o += padded;
-        return at;
-    };
-    const size_t o_m = put(plan->mats.data(), plan->mats.size() * sizeof(MatDesc), b_m);
-    const size_t o_1 = put(plan->tiles1.data(), plan->tiles1.size() * sizeof(Tile), b_1);
-    const size_t o_3 = put(plan->tiles3.data(), plan->tiles3.size() * sizeof(Tile), b_3);
-    const size_t o_4 = put(plan->tiles4.data(), plan->tiles4.size() * sizeof(Tile), b_4);
-    const size_t o_q = put(plan->tilesq.data(), plan->tilesq.size() * sizeof(Tile), b_q);
     PSGD_HIP(hipGetDevice(&plan->device), "hipGetDevice");
+    if (plan->resident_ok) {
+        psgd_status st = resident_check_device(plan);
+        if (st != PSGD_OK) return st;
+    }
+    struct Piece { const void* src; size_t bytes; size_t at; };
+    Piece pieces[9] = {
+        {plan->mats.data(), plan->mats.size() * sizeof(MatDesc), 0},
+        {plan->tiles1.data(), plan->tiles1.size() * sizeof(Tile), 0},
+        {plan->tiles3.data(), plan->tiles3.size() * sizeof(Tile), 0},
+        {plan->tiles4.data(), plan->tiles4.size() * sizeof(Tile), 0},
+        {plan->tilesq.data(), plan->tilesq.size() * sizeof(Tile), 0},
+        {plan->res_mats.data(), plan->res_mats.size() * sizeof(MatDesc), 0},
+        {plan->res_tiles.data(), plan->res_tiles.size() * sizeof(RTile), 0},
+        {nullptr, (size_t)plan->res_sync_words * sizeof(unsigned), 0},   // zero-filled
+        {nullptr, plan->tuning.res_trace ? (size_t)plan->res_blocks * kResTracePoints * sizeof(unsigned long long) : 0, 0},
+    };
+    size_t total = 0;
+    for (Piece& pc : pieces) {
+        pc.at = total;
+        total += (pc.bytes + 255) / 256 * 256;
+    }
+    total += 256;
+    std::vector<char> host(total, 0);
+    for (const Piece& pc : pieces)
+        if (pc.src && pc.bytes) std::memcpy(host.data() + pc.at, pc.src, pc.bytes);
     void* base = nullptr;
     PSGD_HIP(hipMalloc(&base, total), "hipMalloc(descriptor tables)");
     hipError_t ce = hipMemcpy(base, host.data(), total, hipMemcpyHostToDevice);
@@ -606,12 +537,43 @@ psgd_status upload_tables(psgd_plan* plan) {
     }
     char* b = static_cast<char*>(base);
     plan->dev.base = base;
-    plan->dev.mats = reinterpret_cast<MatDesc*>(b + o_m);
-    plan->dev.tiles1 = reinterpret_cast<Tile*>(b + o_1);
-    plan->dev.tiles3 = reinterpret_cast<Tile*>(b + o_3);
-    plan->dev.tiles4 = reinterpret_cast<Tile*>(b + o_4);
-    plan->dev.tilesq = reinterpret_cast<Tile*>(b + o_q);
+    plan->dev.mats = reinterpret_cast<MatDesc*>(b + pieces[0].at);
+    plan->dev.tiles1 = reinterpret_cast<Tile*>(b + pieces[1].at);
+    plan->dev.tiles3 = reinterpret_cast<Tile*>(b + pieces[2].at);
+    plan->dev.tiles4 = reinterpret_cast<Tile*>(b + pieces[3].at);
+    plan->dev.tilesq = reinterpret_cast<Tile*>(b + pieces[4].at);
+    plan->dev.res_mats = reinterpret_cast<MatDesc*>(b + pieces[5].at);
+    plan->dev.res_tiles = reinterpret_cast<RTile*>(b + pieces[6].at);
+    plan->dev.res_sync = reinterpret_cast<unsigned*>(b + pieces[7].at);
+    plan->dev.res_trace = pieces[8].bytes ? reinterpret_cast<unsigned long long*>(b + pieces[8].at) : nullptr;
     plan->uploaded = true;
+    return PSGD_OK;
+}
+
+psgd_status read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t* n_written) {
+    *n_written = 0;
+    if (!plan->uploaded || !plan->dev.res_trace) return PSGD_OK;
+    const int64_t n = std::min<int64_t>(capacity, (int64_t)plan->res_blocks * kResTracePoints);
+    PSGD_HIP(hipDeviceSynchronize(), "hipDeviceSynchronize");
+    PSGD_HIP(hipMemcpy(out, plan->dev.res_trace, (size_t)n * sizeof(uint64_t), hipMemcpyDeviceToHost), "hipMemcpy(trace)");
+    *n_written = n;
+    return PSGD_OK;
+}
+
+// Waits for the stream; reports and clears a barrier time-out of the resident kernel.
+psgd_status check_plan(psgd_plan* plan, void* stream) {
+    if (!plan->uploaded) return PSGD_OK;
+    PSGD_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)), "hipStreamSynchronize");
+    if (!plan->resident_ok || !plan->res_sync_words) return PSGD_OK;
+    unsigned flag = 0;
+    PSGD_HIP(hipMemcpy(&flag, plan->dev.res_sync + res_sync_err(), sizeof(flag), hipMemcpyDeviceToHost),
+             "hipMemcpy(barrier error word)");
+    if (flag) {
+        PSGD_HIP(hipMemset(plan->dev.res_sync, 0, (size_t)plan->res_sync_words * sizeof(unsigned)),
+                 "hipMemset(barrier words)");
+        plan->last_error = "resident kernel: a grid barrier timed out (grid not co-resident?)";
+        return PSGD_EHIP;
+    }
     return PSGD_OK;
 }
 

@@ -60,11 +60,13 @@ static void streaming_tiles(const psgd_plan* plan, int64_t rows_per_tile, int64_
     }
 }
 
+void build_resident(psgd_plan* plan);
+
 psgd_status build_tables(psgd_plan* plan) {
     const Tuning& tu = plan->tuning;
     if (tu.k1_rows < 1 || tu.k3_rows < 1 || tu.k4_rows < 1 || tu.k1_nv < 1 ||
         tu.k1_nv > kMaxVecPerLaneK1 || tu.k3_nv < 1 || tu.k3_nv > kMaxVecPerLaneK3 || tu.k4_nv < 1 ||
-        tu.k4_nv > kMaxVecPerLaneK3 || tu.q_reduce_elems < 1)
+        tu.k4_nv > kMaxVecPerLaneK3 || tu.q_reduce_elems < 1 || tu.res_rows < 0 || tu.res_rows > kResRows)
         return PSGD_EINVAL;
     const size_t nm = plan->mats.size();
     std::vector<int32_t> nrb(nm, 0), ncc(nm, 0);
@@ -114,8 +116,155 @@ psgd_status build_tables(psgd_plan* plan) {
             plan->tilesq.push_back(t);
         }
     }
+    build_resident(plan);
+    plan->sizes.workspace_bytes =
+        std::max<int64_t>(plan->sizes.workspace_bytes, plan->res_ws_floats * (int64_t)sizeof(float));
     plan->tables_built = true;
     return PSGD_OK;
+}
+
+// Resident tiling: every matrix is cut into strips of at most `h` rows and chunks of 64 column
+// vectors; one wavefront keeps one (strip, chunk) tile in registers for the whole step.  The model
+// qualifies when all tiles fit the wavefront slots of one co-resident grid.
+static int64_t resident_tiles_for(const psgd_plan* plan, int h) {
+    int64_t total = 0;
+    for (const MatDesc& d : plan->mats) total += ceil_div(d.n, h) * ceil_div(d.m / d.vec, kWave);
+    return total;
+}
+
+void build_resident(psgd_plan* plan) {
+    plan->resident_ok = false;
+    plan->res_tiles.clear();
+    plan->res_mats.clear();
+    plan->res_ws_floats = 0;
+    plan->res_blocks = 0;
+    const Tuning& tu = plan->tuning;
+    if (!tu.resident || plan->workers != 1 || plan->rank > kResMaxRank || plan->mats.empty()) return;
+    if (plan->grad_dtype != PSGD_F32 || plan->out_dtype != PSGD_F32) return;
+    for (const MatDesc& d : plan->mats)
+        if (d.n > kResMaxN) return;
+    const int64_t max_blocks = (int64_t)kResCUs * kResBlocksPerCU;
+    const int64_t L = plan->sizes.n_vec_elems;
+    const int64_t vec_slice = (int64_t)kWave * 4 * 8;   // elements of the vector region per wavefront
+    const int64_t vec_tiles = ceil_div(L, vec_slice);
+
+    auto layout = [&](int h, std::vector<RTile>* tiles, std::vector<MatDesc>* mats, int32_t* n_cntq,
+                      int32_t* n_cnts) -> int64_t {
+        // returns the number of workgroups, fills the tables when tiles != nullptr
+        int64_t slots = 0;            // wavefront slots used so far (multiple of 4 at block boundaries)
+        int32_t cntq = 0, cnts = 0;
+        int cur_vec = 0;
+        auto pad_block = [&]() {
+            while (slots % kWavesPerBlock) {
+                if (tiles) { RTile t{}; t.mat = -2; tiles->push_back(t); }
+                ++slots;
+            }
+        };
+        for (size_t i = 0; i < plan->mats.size(); ++i) {
+            const MatDesc& d0 = plan->mats[i];
+            if (d0.vec != cur_vec) { pad_block(); cur_vec = d0.vec; }
+            const int64_t nvec = d0.m / d0.vec;
+            const int64_t nchunk = ceil_div(nvec, kWave);
+            const int64_t nstrip = ceil_div(d0.n, h);
+            int32_t max_runs = 0;
+            const size_t first_tile = tiles ? tiles->size() : 0;
+            for (int64_t c = 0; c < nchunk; ++c) {
+                int32_t runs = 0;
+                size_t run_leader = 0;
+                const size_t chunk_first = tiles ? tiles->size() : 0;
+                for (int64_t sidx = 0; sidx < nstrip; ++sidx) {
+                    int64_t r0, rn;
+                    even_split(d0.n, nstrip, sidx, &r0, &rn);
+                    const bool new_run = (sidx == 0) || (slots % kWavesPerBlock == 0);
+                    if (tiles) {
+                        RTile t{};
+                        t.mat = (int32_t)i;
+                        t.row0 = (int32_t)r0;
+                        t.nrows = (int32_t)rn;
+                        t.vec0 = (int32_t)(c * kWave);
+                        t.nvec = (int32_t)std::min<int64_t>(kWave, nvec - c * kWave);
+                        t.ppart = (int32_t)c;
+                        t.cntq = cntq;
+                        t.cnts = cnts + (int32_t)sidx;
+                        if (new_run) {
+                            run_leader = tiles->size();
+                            t.qrun_len = 1;
+                            t.qpart = runs;
+                        } else {
+                            (*tiles)[run_leader].qrun_len += 1;
+                        }
+                        tiles->push_back(t);
+                    }
+                    if (new_run) ++runs;
+                    ++slots;
+                }
+                if (tiles)
+                    for (size_t k = chunk_first; k < tiles->size(); ++k) (*tiles)[k].nqparts = runs;
+                max_runs = std::max(max_runs, runs);
+                ++cntq;
+            }
+            if (tiles) {
+                for (size_t k = first_tile; k < tiles->size(); ++k)
+                    if ((*tiles)[k].mat == (int32_t)i) (*tiles)[k].nstrips_mat = (int32_t)nstrip;
+                MatDesc d = d0;
+                d.n_cchunk = (int32_t)nchunk;
+                d.n_rblock = max_runs;
+                mats->push_back(d);
+            }
+            cnts += (int32_t)nstrip;
+        }
+        if (vec_tiles) {
+            pad_block();
+            for (int64_t v = 0; v < vec_tiles; ++v) {
+                if (tiles) {
+                    RTile t{};
+                    t.mat = -1;
+                    t.elem0 = v * vec_slice;
+                    t.nelem = std::min(vec_slice, L - v * vec_slice);
+                    tiles->push_back(t);
+                }
+                ++slots;
+            }
+        }
+        pad_block();
+        if (n_cntq) *n_cntq = cntq;
+        if (n_cnts) *n_cnts = cnts;
+        return slots / kWavesPerBlock;
+    };
+
+    int h = 0;
+    if (tu.res_rows > 0) {
+        if (tu.res_rows > kResRows) return;
+        h = (int)tu.res_rows;
+        if (layout(h, nullptr, nullptr, nullptr, nullptr) > max_blocks) return;
+    } else {
+        for (int cand = kResMinRows; cand <= kResRows; ++cand) {
+            if (layout(cand, nullptr, nullptr, nullptr, nullptr) <= max_blocks) { h = cand; break; }
+        }
+        if (!h) return;
+    }
+    int32_t n_cntq = 0, n_cnts = 0;
+    const int64_t blocks = layout(h, &plan->res_tiles, &plan->res_mats, &n_cntq, &n_cnts);
+    plan->res_strip_rows = h;
+    plan->res_blocks = (int32_t)blocks;
+    plan->res_n_cntq = n_cntq;
+    plan->res_n_cnts = n_cnts;
+    // workspace of the resident kernel: partial P then partial Q, offsets stored in res_mats
+    int64_t off = 0;
+    for (MatDesc& d : plan->res_mats) {
+        d.ppart_off = off;
+        off += round_up((int64_t)d.n_cchunk * d.n * d.r, kAlignElems);
+    }
+    for (MatDesc& d : plan->res_mats) {
+        d.qpart_off = off;
+        off += round_up((int64_t)d.n_rblock * d.m * d.r, kAlignElems);
+    }
+    plan->res_ws_floats = off;
+    const int ngroups = (int)ceil_div(blocks, kResBarrierFanIn);
+    plan->res_flags_at = res_sync_cntp(ngroups) + round_up((int64_t)plan->mats.size() + n_cntq + n_cnts, kSyncLineWords);
+    plan->res_sync_words =
+        plan->res_flags_at + ((int64_t)plan->mats.size() + n_cntq) * kResFlagCopies * kSyncLineWords;
+    plan->resident_ok = true;
 }
 
 }  // namespace psgd
@@ -254,6 +403,9 @@ psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value
     else if (!strcmp(key, "k4_rows")) tu.k4_rows = value;
     else if (!strcmp(key, "k4_nv")) tu.k4_nv = value;
     else if (!strcmp(key, "q_reduce_elems")) tu.q_reduce_elems = value;
+    else if (!strcmp(key, "resident")) tu.resident = value;
+    else if (!strcmp(key, "res_rows")) tu.res_rows = value;
+    else if (!strcmp(key, "res_trace")) tu.res_trace = value;
     else return PSGD_EINVAL;
     Tuning old = plan->tuning;
     plan->tuning = tu;
@@ -288,6 +440,7 @@ psgd_status psgd_decompress(psgd_plan* plan, const float* p, const float* q, flo
 psgd_status psgd_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,
                       void* workspace, void* hip_stream) {
     if (!plan || bad_ptrs(grad, err, q, p, workspace) || !out) return PSGD_EINVAL;
+    if (plan->resident_ok) return launch_resident_step(plan, grad, err, q, p, out, workspace, hip_stream);
     psgd_status st = launch_compress(plan, grad, err, q, p, workspace, hip_stream);
     if (st != PSGD_OK) return st;
     return launch_decompress(plan, p, q, err, grad, out, workspace, hip_stream);
@@ -310,8 +463,20 @@ psgd_status psgd_plan_kernel_times(psgd_plan* plan, double* ms_sum, int64_t* ste
 }
 
 const char* psgd_kernel_name(int32_t index) {
-    static const char* const names[PSGD_N_KERNELS] = {"k_ef_right", "k_ortho", "k_left", "k_q_reduce", "k_decomp"};
+    static const char* const names[PSGD_N_KERNELS] = {"k_ef_right", "k_ortho",  "k_left",
+                                                      "k_q_reduce", "k_decomp", "k_resident"};
     return (index >= 0 && index < PSGD_N_KERNELS) ? names[index] : nullptr;
+}
+
+psgd_status psgd_plan_check(psgd_plan* plan, void* hip_stream, int32_t* is_resident) {
+    if (!plan) return PSGD_EINVAL;
+    if (is_resident) *is_resident = plan->resident_ok ? 1 : 0;
+    return check_plan(plan, hip_stream);
+}
+
+psgd_status psgd_plan_read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t* n_written) {
+    if (!plan || !out || !n_written || capacity < 0) return PSGD_EINVAL;
+    return read_trace(plan, out, capacity, n_written);
 }
 
 const char* psgd_status_string(psgd_status status) {

@@ -64,6 +64,7 @@ class GpuRun:
             self.plan.decompress(self.p, self.q, self.err, self.grad, self.out, self.ws, stream)
         else:
             self.plan.step(self.grad, self.err, self.q, self.p, self.out, self.ws, stream)
+        self.resident = self.plan.check(stream)   # synchronises; raises if a resident step timed out
         torch.cuda.synchronize(self.dev)
         return self.download()
 

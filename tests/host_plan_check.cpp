@@ -12,6 +12,9 @@
 namespace psgd {
 void free_tables(psgd_plan*) {}
 psgd_status set_profiling(psgd_plan*, bool) { return PSGD_EHIP; }
+psgd_status check_plan(psgd_plan*, void*) { return PSGD_EHIP; }
+psgd_status read_trace(psgd_plan*, uint64_t*, int64_t, int64_t*) { return PSGD_EHIP; }
+psgd_status launch_resident_step(psgd_plan*, const void*, float*, float*, float*, void*, void*, void*) { return PSGD_EHIP; }
 psgd_status launch_compress(psgd_plan*, const void*, float*, float*, float*, void*, void*) { return PSGD_EHIP; }
 psgd_status launch_decompress(psgd_plan*, const float*, const float*, float*, const void*, void*, void*, void*) {
     return PSGD_EHIP;
@@ -58,6 +61,92 @@ static void check_cover(const psgd_plan* plan, const std::vector<Tile>& tiles, i
     if (vec_seen) CHECK(vec_seen == plan->sizes.n_vec_elems);
 }
 
+// Resident tiling: what the resident kernel relies on.
+static void check_resident(const psgd_plan* plan) {
+    if (!plan->resident_ok) return;
+    CHECK(plan->workers == 1 && plan->rank <= kResMaxRank);
+    CHECK(plan->res_blocks > 0 && plan->res_blocks <= kResCUs * kResBlocksPerCU);
+    CHECK((int64_t)plan->res_tiles.size() == (int64_t)plan->res_blocks * kWavesPerBlock);
+    CHECK(plan->res_mats.size() == plan->mats.size());
+    std::vector<std::vector<unsigned char>> seen(plan->mats.size());
+    std::vector<int> tiles_of(plan->mats.size(), 0);
+    for (size_t i = 0; i < plan->mats.size(); ++i) seen[i].assign((size_t)plan->mats[i].n * plan->mats[i].m, 0);
+    std::vector<int> q_leaders(plan->res_n_cntq, 0), q_expect(plan->res_n_cntq, -1);
+    int64_t vec_seen = 0;
+    for (int b = 0; b < plan->res_blocks; ++b) {
+        const RTile* blk = &plan->res_tiles[(size_t)b * kWavesPerBlock];
+        CHECK(blk[0].mat != -2);   // the first slot of a workgroup is never idle
+        int vec = 0;
+        for (int w = 0; w < kWavesPerBlock; ++w) {
+            const RTile& t = blk[w];
+            if (t.mat == -2) { CHECK(t.qrun_len == 0); continue; }
+            if (t.mat == -1) {
+                CHECK(t.elem0 == vec_seen && t.nelem > 0 && t.qrun_len == 0);
+                vec_seen += t.nelem;
+                continue;
+            }
+            CHECK(t.mat >= 0 && t.mat < (int)plan->mats.size());
+            const MatDesc& d = plan->res_mats[t.mat];
+            CHECK(d.n <= kResMaxN);
+            if (!vec) vec = d.vec;
+            CHECK(vec == d.vec);   // one access width per workgroup
+            CHECK(t.nrows > 0 && t.nrows <= kResRows && t.row0 >= 0 && t.row0 + t.nrows <= d.n);
+            CHECK(t.nvec > 0 && t.nvec <= kWave && t.vec0 >= 0 && (int64_t)(t.vec0 + t.nvec) * d.vec <= d.m);
+            CHECK(t.ppart >= 0 && t.ppart < d.n_cchunk);
+            CHECK(t.cntq >= 0 && t.cntq < plan->res_n_cntq);
+            CHECK(t.nqparts >= 1 && t.nqparts <= d.n_rblock);
+            if (q_expect[t.cntq] < 0) q_expect[t.cntq] = t.nqparts;
+            CHECK(q_expect[t.cntq] == t.nqparts);
+            if (t.qrun_len > 0) {
+                CHECK(w + t.qrun_len <= kWavesPerBlock);
+                CHECK(t.qpart >= 0 && t.qpart < t.nqparts);
+                for (int k = 1; k < t.qrun_len; ++k) {
+                    const RTile& f = blk[w + k];   // followers: same matrix, same column chunk, no run of their own
+                    CHECK(f.mat == t.mat && f.vec0 == t.vec0 && f.nvec == t.nvec && f.qrun_len == 0 && f.cntq == t.cntq);
+                }
+                q_leaders[t.cntq] += 1;
+            } else {
+                CHECK(w > 0);
+            }
+            tiles_of[t.mat] += 1;
+            for (int i = t.row0; i < t.row0 + t.nrows; ++i)
+                for (int j = t.vec0 * d.vec; j < (t.vec0 + t.nvec) * d.vec; ++j) {
+                    unsigned char& sflag = seen[t.mat][(size_t)i * d.m + j];
+                    CHECK(sflag == 0);
+                    sflag = 1;
+                }
+        }
+    }
+    for (auto& v : seen)
+        for (unsigned char sflag : v) CHECK(sflag == 1);
+    CHECK(vec_seen == plan->sizes.n_vec_elems);
+    for (int c = 0; c < plan->res_n_cntq; ++c) CHECK(q_leaders[c] == q_expect[c]);   // every slot is written once
+    for (const RTile& t : plan->res_tiles)
+        if (t.mat >= 0) {
+            const MatDesc& d = plan->res_mats[t.mat];
+            CHECK(t.nstrips_mat * d.n_cchunk == tiles_of[t.mat]);
+            CHECK(t.cnts >= 0 && t.cnts < plan->res_n_cnts);
+            CHECK(t.nrows * d.r <= 2 * kWave);
+        }
+    for (const MatDesc& d : plan->res_mats) {
+        CHECK(d.ppart_off >= 0 && d.ppart_off + (int64_t)d.n_cchunk * d.n * d.r <= plan->res_ws_floats);
+        CHECK(d.qpart_off >= 0 && d.qpart_off + (int64_t)d.n_rblock * d.m * d.r <= plan->res_ws_floats);
+    }
+    CHECK(plan->res_ws_floats * 4 <= plan->sizes.workspace_bytes);
+    const int ngroups = (plan->res_blocks + kResBarrierFanIn - 1) / kResBarrierFanIn;
+    CHECK(res_sync_cntp(ngroups) + (int64_t)plan->mats.size() + plan->res_n_cntq + plan->res_n_cnts <= plan->res_flags_at);
+    CHECK(plan->res_flags_at % kSyncLineWords == 0);
+    CHECK(plan->res_flags_at + ((int64_t)plan->mats.size() + plan->res_n_cntq) * kResFlagCopies * kSyncLineWords <= plan->res_sync_words);
+    // every strip counter is shared by exactly the column chunks of one strip
+    {
+        std::vector<int> per_strip(plan->res_n_cnts, 0);
+        for (const RTile& t : plan->res_tiles)
+            if (t.mat >= 0) per_strip[t.cnts] += 1;
+        for (const RTile& t : plan->res_tiles)
+            if (t.mat >= 0) CHECK(per_strip[t.cnts] == plan->res_mats[t.mat].n_cchunk);
+    }
+}
+
 static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int workers, const Tuning* tu) {
     psgd_plan* plan = nullptr;
     CHECK(psgd_plan_create(shapes.data(), (int)shapes.size(), rank, workers, PSGD_F32, PSGD_F32, &plan) == PSGD_OK);
@@ -70,6 +159,12 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
         CHECK(psgd_plan_set_tuning(plan, "k4_nv", tu->k4_nv) == PSGD_OK);
         CHECK(psgd_plan_set_tuning(plan, "q_reduce_elems", tu->q_reduce_elems) == PSGD_OK);
     }
+    check_resident(plan);
+    for (int64_t rr : {5, 8, 13, 32}) {
+        CHECK(psgd_plan_set_tuning(plan, "res_rows", rr) == PSGD_OK);
+        check_resident(plan);
+    }
+    CHECK(psgd_plan_set_tuning(plan, "res_rows", 0) == PSGD_OK);
     check_cover(plan, plan->tiles1, (int)plan->tuning.k1_nv, 1);
     check_cover(plan, plan->tiles3, (int)plan->tuning.k3_nv, 2);
     check_cover(plan, plan->tiles4, (int)plan->tuning.k4_nv, 0);
@@ -104,6 +199,11 @@ int main() {
         {{512, 4608}, {10, 512}, {128, 64}, {9610, 1}},
         {{2600, 650}, {3328, 650}},
         {{1, 2}, {2, 1}},
+        {{37, 91}, {7, 1}, {50, 650}, {130, 1028}, {5, 3}, {300, 2}, {1, 40}, {1031, 1}, {3, 4700}, {257, 260},
+         {512, 36}, {64, 27}},
+        {{64, 27}, {64, 576}, {64, 576}, {64, 576}, {64, 576}, {128, 576}, {128, 1152}, {128, 1152}, {128, 1152},
+         {128, 64}, {256, 1152}, {256, 2304}, {256, 2304}, {256, 2304}, {256, 128}, {512, 2304}, {512, 4608},
+         {512, 4608}, {512, 4608}, {512, 256}, {10, 512}, {9610, 1}},
     };
     Tuning small;
     small.k1_rows = 8; small.k1_nv = 1; small.k3_rows = 16; small.k3_nv = 1; small.k4_rows = 8; small.k4_nv = 1;

@@ -37,7 +37,8 @@ def _need_gpu():
         pytest.skip("no GPU")
 
 
-def _run(wl, rank, workers, steps, seed=0, tuning=None, split=False, verbose=True, resync=None):
+def _run(wl, rank, workers, steps, seed=0, tuning=None, split=False, verbose=True, resync=None,
+         expect_resident=None):
     from paper_1905_13727_amd import workloads as WL
     from gpu_harness import GpuRun, OracleRun, compare
     factors = WL.planted_factors(wl, seed)
@@ -60,8 +61,10 @@ def _run(wl, rank, workers, steps, seed=0, tuning=None, split=False, verbose=Tru
         assert worst["P_hat"] <= TOL and worst["Q"] <= TOL and worst["err"] <= TOL and worst["out"] <= TOL, \
             (wl.name, rank, workers, t, worst)
     if verbose:
-        print("\n[parity] %s r=%d W=%d steps=%d resync=%s worst %s" % (wl.name, rank, workers, steps, resync, worst_all),
-              flush=True)
+        print("\n[parity] %s r=%d W=%d steps=%d resync=%s resident=%s worst %s"
+              % (wl.name, rank, workers, steps, resync, gpu.resident, worst_all), flush=True)
+    if expect_resident is not None:
+        assert gpu.resident == expect_resident
     return worst_all
 
 
@@ -71,9 +74,36 @@ def _workload(shapes, planted_rank=4, sigma=0.01, name="custom"):
 
 
 def test_tiny_config_10_steps():
+    """The Tiny configuration, free-running for all 10 steps, on the resident kernel (the mode
+    psgd_step picks for it) and on the streaming kernels."""
     _need_gpu()
     from paper_1905_13727_amd import workloads as WL
-    _run(WL.tiny(), rank=2, workers=1, steps=10, seed=0)
+    _run(WL.tiny(), rank=2, workers=1, steps=10, seed=0, expect_resident=True)
+    _run(WL.tiny(), rank=2, workers=1, steps=10, seed=0, tuning={"resident": 0}, expect_resident=False)
+
+
+RAGGED_1W = [(37, 91), (7,), (50, 650), (130, 1028), (5, 3), (300, 2), (1, 40), (1031,), (3, 4700), (257, 260),
+             (512, 36), (64, 27)]
+
+
+@pytest.mark.parametrize("rank", [1, 2, 3, 4])
+def test_resident_ragged_shapes(rank):
+    """Resident kernel on shapes with scalar, 2-wide and 4-wide row access in one model, strips with
+    a ragged last strip, column chunks with a ragged tail, clipped ranks, vectors; default strip
+    height, the thinnest and the tallest strips."""
+    _need_gpu()
+    wl = _workload(RAGGED_1W)
+    _run(wl, rank=rank, workers=1, steps=4, seed=10 + rank, expect_resident=True)
+    _run(wl, rank=rank, workers=1, steps=3, seed=20 + rank, tuning={"res_rows": 32}, expect_resident=True)
+    _run(wl, rank=rank, workers=1, steps=3, seed=30 + rank, tuning={"res_rows": 5}, expect_resident=True)
+
+
+def test_resident_falls_back_when_the_model_does_not_fit():
+    _need_gpu()
+    # a 600-row matrix is taller than the resident Gram-Schmidt handles; W = 2 is not resident either
+    _run(_workload([(600, 64), (64, 64)]), rank=2, workers=1, steps=2, seed=3, expect_resident=False)
+    _run(_workload([(64, 64)]), rank=2, workers=2, steps=2, seed=4, expect_resident=False)
+    _run(_workload([(64, 64)]), rank=5, workers=1, steps=2, seed=5, expect_resident=False)
 
 
 @pytest.mark.parametrize("rank", [1, 2, 3, 4, 8])
@@ -144,23 +174,28 @@ def test_zero_gradient_and_reproducibility():
     from gpu_harness import GpuRun
     wl = WL.tiny()
     q0 = WL.initial_q(wl, 2, 0)
-    g = GpuRun(wl.shapes, 2, 1, q0)
-    zero = [[np.zeros(s, dtype=np.float32) for s in wl.shapes]]
-    r = g.step(zero)
-    for t in range(len(wl.shapes)):
-        assert not np.isnan(r["P_hat"][t]).any()
-        assert np.abs(r["P_hat"][t]).max() == 0 and np.abs(r["Q"][t]).max() == 0
-        assert np.abs(r["out"][t]).max() == 0 and np.abs(r["err"][0][t]).max() == 0
-    # same inputs twice on fresh state: bit-identical
+    for tuning in ({}, {"resident": 0}):
+        g = GpuRun(wl.shapes, 2, 1, q0, tuning)
+        zero = [[np.zeros(s, dtype=np.float32) for s in wl.shapes]]
+        r = g.step(zero)
+        for t in range(len(wl.shapes)):
+            assert not np.isnan(r["P_hat"][t]).any()
+            assert np.abs(r["P_hat"][t]).max() == 0 and np.abs(r["Q"][t]).max() == 0
+            assert np.abs(r["out"][t]).max() == 0 and np.abs(r["err"][0][t]).max() == 0
+    # same inputs twice on fresh state: bit-identical (streaming W = 2, resident W = 1)
     factors = WL.planted_factors(wl, 3)
-    runs = []
-    for _ in range(2):
-        h = GpuRun(wl.shapes, 2, 2, q0)
-        for t in range(3):
-            res = h.step([WL.gradients(wl, factors, 3, t, w) for w in range(2)])
-        runs.append(res)
-    for key in ("P_hat", "Q", "out"):
-        for x, y in zip(runs[0][key], runs[1][key]):
+    for workers in (2, 1):
+        runs = []
+        for _ in range(2):
+            h = GpuRun(wl.shapes, 2, workers, q0)
+            for t in range(3):
+                res = h.step([WL.gradients(wl, factors, 3, t, w) for w in range(workers)])
+            assert h.resident == (workers == 1)
+            runs.append(res)
+        for key in ("P_hat", "Q", "out"):
+            for x, y in zip(runs[0][key], runs[1][key]):
+                assert np.array_equal(x, y)
+        for x, y in zip(runs[0]["err"][0], runs[1]["err"][0]):
             assert np.array_equal(x, y)
 
 
@@ -192,7 +227,14 @@ def test_orthonormality_and_conservation_invariants():
 def test_resnet18_r2_100_steps():
     _need_gpu()
     from paper_1905_13727_amd import workloads as WL
-    _run(WL.resnet18(), rank=2, workers=1, steps=100, seed=0, resync=RESYNC)
+    _run(WL.resnet18(), rank=2, workers=1, steps=100, seed=0, resync=RESYNC, expect_resident=True)
+
+
+def test_resnet18_r2_streaming_kernels_20_steps():
+    _need_gpu()
+    from paper_1905_13727_amd import workloads as WL
+    _run(WL.resnet18(), rank=2, workers=1, steps=20, seed=0, resync=RESYNC, tuning={"resident": 0},
+         expect_resident=False)
 
 
 def test_resnet18_r2_100_steps_never_resynchronised():
