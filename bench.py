@@ -155,6 +155,7 @@ def main():
 
     for i in range(args.warmup):
         step(i)
+    resident = plan.check(sh)     # synchronises; raises if a resident step ever timed out
     torch.cuda.synchronize(dev)
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -162,6 +163,7 @@ def main():
     torch.cuda.synchronize(dev)
     wall = time.perf_counter() - t0
     ms_per_step = 1e3 * wall / args.steps
+    plan.check(sh)
 
     # per-kernel durations: HIP events recorded by the library on its own stream
     plan.set_profiling(True)
@@ -189,10 +191,12 @@ def main():
 
     payload_mat = s.payload_elems - s.n_vec_elems
     L = s.n_vec_elems
+    # algorithmic bytes per launch of each kernel (fp32): what the kernel itself has to move
     kernel_bytes = {
         "k_ef_right": payload_mat * W * 12,                       # read g, read e, write M
         "k_left": payload_mat * W * 4,                            # read M
         "k_decomp": payload_mat * (W * 8 + 4) + L * (W * 4 + 4),  # read M, write e', write Delta' once
+        "k_resident": int(s.bytes_min),                           # read g, e; write e', Delta': each once
     }
     dom = max(kernel_bytes, key=lambda k: kavg.get(k, 0.0))
     achieved = kernel_bytes[dom] / (kavg[dom] * 1e-3) / 1e9 if kavg[dom] > 0 else 0.0
@@ -214,6 +218,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": "%s-shaped gradient set, W=%d simulated worker(s), rank %d, fp32" % (wl.name, W, rank),
+                   "mode": "resident (one kernel, M kept in registers)" if resident else "streaming (five kernels)",
                    "matrices": int(s.n_matrices), "matrix_elems": int(payload_mat), "vector_elems": int(L),
                    "grad_buffers": len(grads)},
         "stream_model": {"bytes_per_step": int(s.bytes_stream),

@@ -183,9 +183,11 @@ PSGD_API const char* psgd_kernel_name(int32_t index);
 PSGD_API psgd_status psgd_plan_check(psgd_plan* plan, void* hip_stream, int32_t* is_resident);
 
 /* Diagnostic.  After psgd_plan_set_tuning(plan, "res_trace", 1), every resident
- * step records 8 device timestamps (100 MHz clock) per workgroup: start, partial
- * P written, before / after the first grid barrier, before / after the second,
- * end (the 8th is unused).  Synchronises the device and copies at most
+ * step records 16 device timestamps (100 MHz clock) per wavefront: start, partial
+ * P posted, reducer work done, P_hat received, partial Q posted, Q received, end;
+ * 7..11 are written by a wavefront that orthogonalises (own partial posted,
+ * strip sum posted, mean P received, Gram-Schmidt done, P_hat posted); the rest
+ * is unused.  Synchronises the device and copies at most
  * `capacity` values of the last step to `out` (host); *n_written = count. */
 PSGD_API psgd_status psgd_plan_read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t* n_written);
 

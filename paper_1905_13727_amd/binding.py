@@ -184,13 +184,13 @@ class Plan:
         self._check(self._lib.psgd_plan_check(self._h, _ptr(stream), C.byref(r)), "psgd_plan_check")
         return bool(r.value)
 
-    def read_trace(self, capacity=1 << 16):
+    def read_trace(self, capacity=1 << 18):
         """Diagnostic timestamps of the last resident step: list of per-workgroup lists (see psgd.h)."""
         buf = (C.c_uint64 * capacity)()
         n = C.c_int64()
         self._check(self._lib.psgd_plan_read_trace(self._h, buf, capacity, C.byref(n)), "psgd_plan_read_trace")
         vals = list(buf[: n.value])
-        return [vals[i: i + 8] for i in range(0, len(vals), 8)]
+        return [vals[i: i + 16] for i in range(0, len(vals), 16)]
 
     def last_error(self) -> str:
         return self._lib.psgd_plan_last_error(self._h).decode()

@@ -55,23 +55,23 @@ constexpr int kResMaxN = 512;        // tallest matrix the single-wavefront Gram
 constexpr int kResMaxRank = 4;
 constexpr int kResCUs = 256;         // MI355X compute units
 constexpr int kResBlocksPerCU = 2;   // 256-thread workgroups per compute unit (8 wavefronts, 2 per SIMD)
-constexpr int kResBarrierFanIn = 32; // workgroups per first-level arrival counter
-constexpr int kResFlagCopies = 8;    // copies of each readiness flag, one 256-byte line each
-constexpr int kResTracePoints = 8;   // diagnostic timestamps per workgroup of the resident kernel
+constexpr int kResTracePoints = 16;  // diagnostic timestamps per workgroup of the resident kernel
 
 // One wavefront's share of the resident kernel.
 struct RTile {
     int32_t mat;         // matrix index; -1: slice of the vector region; -2: idle slot
     int32_t row0, nrows; // strip of rows (nrows <= kResRows)
     int32_t vec0, nvec;  // column vectors (nvec <= 64)
-    int32_t ppart;       // column-chunk index = slice of partial P this tile writes
-    int32_t nstrips_mat; // strips of this matrix (strip arrivals before its P is complete)
+    int32_t ppart;       // column-chunk index = slice of partial P this tile writes; the wavefront with
+                         // ppart == 0 adds the chunks of its strip, the one that also has row0 == 0
+                         // orthogonalises the matrix
+    int32_t nstrips_mat; // strips of this matrix
     int32_t qrun_len;    // > 0: first of a run of consecutive wavefronts of the workgroup that hold strips of
                          // the same column chunk; it adds the run's sums in LDS and writes one partial Q
-    int32_t qpart;       // slot of that partial
-    int32_t nqparts;     // partial-Q slots of this column chunk (arrivals before its Q is complete)
-    int32_t cntq;        // index of this column chunk's arrival counter
-    int32_t cnts;        // index of this strip's arrival counter (column chunks arrive)
+    int32_t qpart;       // slot of that partial; the run with qpart == 0 adds the chunk's partials
+    int32_t nqparts;     // partial-Q slots of this column chunk
+    int32_t cntq;        // running index of this column chunk over the model
+    int32_t cnts;        // running index of this strip over the model
     int64_t elem0, nelem;  // vector tiles: slice of the vector region
 };
 
@@ -96,7 +96,8 @@ struct DeviceTables {
     Tile* tilesq = nullptr;
     MatDesc* res_mats = nullptr;
     RTile* res_tiles = nullptr;
-    unsigned* res_sync = nullptr;  // barrier lines, arrival counters, error flag (zero between steps)
+    unsigned* res_sync = nullptr;  // error word, epoch, finished-workgroup count
+    unsigned long long* res_mail = nullptr;  // mailbox of {value, epoch} slots
     unsigned long long* res_trace = nullptr;  // only with tuning res_trace = 1
     void* base = nullptr;   // the one allocation holding all of the above
 };
@@ -129,7 +130,7 @@ struct psgd_plan {
     int32_t res_n_cnts = 0;                 // strip arrival counters
     int64_t res_ws_floats = 0;
     int64_t res_sync_words = 0;
-    int64_t res_flags_at = 0;               // word offset of the readiness flags inside the sync words
+    int64_t res_mail_slots = 0;             // 64-bit mailbox slots (plan-owned device memory)
     bool tables_built = false;
     bool uploaded = false;
     int device = -1;
@@ -158,14 +159,13 @@ psgd_status read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t
 psgd_status resident_check_device(psgd_plan* plan);
 psgd_status launch_resident_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,
                                  void* workspace, void* stream);
-// layout of the resident kernel's synchronisation words (units of unsigned); every barrier word has a
-// 256-byte line of its own
+// The resident kernel's synchronisation words (units of unsigned), one 256-byte line each: an error word
+// (a wait gave up), the epoch that tags this step's mailbox slots, the count of finished workgroups.
 constexpr int kSyncLineWords = 64;
-constexpr int64_t res_sync_top() { return 0; }
-constexpr int64_t res_sync_err() { return kSyncLineWords; }
-constexpr int64_t res_sync_gcount(int g) { return (int64_t)(2 + g) * kSyncLineWords; }
-constexpr int64_t res_sync_ggen(int ngroups, int g) { return (int64_t)(2 + ngroups + g) * kSyncLineWords; }
-constexpr int64_t res_sync_cntp(int ngroups) { return (int64_t)(2 + 2 * ngroups) * kSyncLineWords; }
+constexpr int64_t res_sync_err() { return 1 * kSyncLineWords; }
+constexpr int64_t res_sync_epoch() { return 2 * kSyncLineWords; }
+constexpr int64_t res_sync_done() { return 3 * kSyncLineWords; }
+constexpr int64_t kResSyncWords = 4 * kSyncLineWords;
 }  // namespace psgd
 
 #endif

@@ -508,7 +508,7 @@ psgd_status upload_tables(psgd_plan* plan) {
         if (st != PSGD_OK) return st;
     }
     struct Piece { const void* src; size_t bytes; size_t at; };
-    Piece pieces[9] = {
+    Piece pieces[10] = {
         {plan->mats.data(), plan->mats.size() * sizeof(MatDesc), 0},
         {plan->tiles1.data(), plan->tiles1.size() * sizeof(Tile), 0},
         {plan->tiles3.data(), plan->tiles3.size() * sizeof(Tile), 0},
@@ -516,8 +516,9 @@ psgd_status upload_tables(psgd_plan* plan) {
         {plan->tilesq.data(), plan->tilesq.size() * sizeof(Tile), 0},
         {plan->res_mats.data(), plan->res_mats.size() * sizeof(MatDesc), 0},
         {plan->res_tiles.data(), plan->res_tiles.size() * sizeof(RTile), 0},
-        {nullptr, (size_t)plan->res_sync_words * sizeof(unsigned), 0},   // zero-filled
-        {nullptr, plan->tuning.res_trace ? (size_t)plan->res_blocks * kResTracePoints * sizeof(unsigned long long) : 0, 0},
+        {nullptr, (size_t)plan->res_sync_words * sizeof(unsigned), 0},   // zero-filled, epoch set below
+        {nullptr, plan->tuning.res_trace ? (size_t)plan->res_blocks * kWavesPerBlock * kResTracePoints * sizeof(unsigned long long) : 0, 0},
+        {nullptr, (size_t)plan->res_mail_slots * sizeof(unsigned long long), 0},   // zero-filled: tag 0 never matches
     };
     size_t total = 0;
     for (Piece& pc : pieces) {
@@ -528,6 +529,10 @@ psgd_status upload_tables(psgd_plan* plan) {
     std::vector<char> host(total, 0);
     for (const Piece& pc : pieces)
         if (pc.src && pc.bytes) std::memcpy(host.data() + pc.at, pc.src, pc.bytes);
+    if (plan->res_sync_words) {
+        const unsigned one = 1;   // epochs start at 1
+        std::memcpy(host.data() + pieces[7].at + res_sync_epoch() * sizeof(unsigned), &one, sizeof(one));
+    }
     void* base = nullptr;
     PSGD_HIP(hipMalloc(&base, total), "hipMalloc(descriptor tables)");
     hipError_t ce = hipMemcpy(base, host.data(), total, hipMemcpyHostToDevice);
@@ -546,6 +551,7 @@ psgd_status upload_tables(psgd_plan* plan) {
     plan->dev.res_tiles = reinterpret_cast<RTile*>(b + pieces[6].at);
     plan->dev.res_sync = reinterpret_cast<unsigned*>(b + pieces[7].at);
     plan->dev.res_trace = pieces[8].bytes ? reinterpret_cast<unsigned long long*>(b + pieces[8].at) : nullptr;
+    plan->dev.res_mail = reinterpret_cast<unsigned long long*>(b + pieces[9].at);
     plan->uploaded = true;
     return PSGD_OK;
 }
@@ -553,7 +559,7 @@ psgd_status upload_tables(psgd_plan* plan) {
 psgd_status read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t* n_written) {
     *n_written = 0;
     if (!plan->uploaded || !plan->dev.res_trace) return PSGD_OK;
-    const int64_t n = std::min<int64_t>(capacity, (int64_t)plan->res_blocks * kResTracePoints);
+    const int64_t n = std::min<int64_t>(capacity, (int64_t)plan->res_blocks * kWavesPerBlock * kResTracePoints);
     PSGD_HIP(hipDeviceSynchronize(), "hipDeviceSynchronize");
     PSGD_HIP(hipMemcpy(out, plan->dev.res_trace, (size_t)n * sizeof(uint64_t), hipMemcpyDeviceToHost), "hipMemcpy(trace)");
     *n_written = n;
@@ -569,9 +575,15 @@ psgd_status check_plan(psgd_plan* plan, void* stream) {
     PSGD_HIP(hipMemcpy(&flag, plan->dev.res_sync + res_sync_err(), sizeof(flag), hipMemcpyDeviceToHost),
              "hipMemcpy(barrier error word)");
     if (flag) {
+        // start over: empty mailbox, epoch 1, no finished workgroups
+        PSGD_HIP(hipMemset(plan->dev.res_mail, 0, (size_t)plan->res_mail_slots * sizeof(unsigned long long)),
+                 "hipMemset(mailbox)");
         PSGD_HIP(hipMemset(plan->dev.res_sync, 0, (size_t)plan->res_sync_words * sizeof(unsigned)),
-                 "hipMemset(barrier words)");
-        plan->last_error = "resident kernel: a grid barrier timed out (grid not co-resident?)";
+                 "hipMemset(sync words)");
+        const unsigned one = 1;
+        PSGD_HIP(hipMemcpy(plan->dev.res_sync + res_sync_epoch(), &one, sizeof(one), hipMemcpyHostToDevice),
+                 "hipMemcpy(epoch)");
+        plan->last_error = "resident kernel: a wait timed out (grid not co-resident?)";
         return PSGD_EHIP;
     }
     return PSGD_OK;

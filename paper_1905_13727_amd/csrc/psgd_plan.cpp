@@ -249,21 +249,20 @@ void build_resident(psgd_plan* plan) {
     plan->res_blocks = (int32_t)blocks;
     plan->res_n_cntq = n_cntq;
     plan->res_n_cnts = n_cnts;
-    // workspace of the resident kernel: partial P then partial Q, offsets stored in res_mats
+    // mailbox of the resident kernel (64-bit slots): per matrix [partial P | mean P | P_hat], then per
+    // matrix [partial Q | Q]; the offsets are kept in res_mats
     int64_t off = 0;
     for (MatDesc& d : plan->res_mats) {
         d.ppart_off = off;
-        off += round_up((int64_t)d.n_cchunk * d.n * d.r, kAlignElems);
+        off += round_up(((int64_t)d.n_cchunk + 2) * d.n * d.r, kAlignElems);
     }
     for (MatDesc& d : plan->res_mats) {
         d.qpart_off = off;
-        off += round_up((int64_t)d.n_rblock * d.m * d.r, kAlignElems);
+        off += round_up(((int64_t)d.n_rblock + 1) * d.m * d.r, kAlignElems);
     }
-    plan->res_ws_floats = off;
-    const int ngroups = (int)ceil_div(blocks, kResBarrierFanIn);
-    plan->res_flags_at = res_sync_cntp(ngroups) + round_up((int64_t)plan->mats.size() + n_cntq + n_cnts, kSyncLineWords);
-    plan->res_sync_words =
-        plan->res_flags_at + ((int64_t)plan->mats.size() + n_cntq) * kResFlagCopies * kSyncLineWords;
+    plan->res_mail_slots = off;
+    plan->res_ws_floats = 0;   // nothing of the caller's workspace is used
+    plan->res_sync_words = kResSyncWords;
     plan->resident_ok = true;
 }
 

@@ -6,26 +6,30 @@
 // of one matrix and keeps M = g + e of that tile in registers from the first load to the last
 // store, so that HBM sees each matrix element exactly once in (g, e) and once out (e', Delta'):
 //
-//   phase A   load g, e; M = g + e (Alg. 2);  row dot products of P = M Q (Alg. 1) -> partial P;
-//             the wavefront that completes a matrix's partials runs Gram-Schmidt on its n x r
-//             panel (Alg. 1 "orthogonalize") and publishes P_hat
-//   -- wait until this matrix's P_hat is published --
-//   phase B   Q = M^T P_hat from the registers -> partial Q per run of strips; the wavefront
-//             that completes a column chunk's partials adds them and publishes Q
-//   -- wait until this column chunk's Q is published --
-//   phase C   Delta' = P_hat Q^T (Alg. 1 "decompress"), e' = M - Delta' (Alg. 2), stored once
+//   phase A   load g, e; M = g + e (Alg. 2);  row dot products of P = M Q (Alg. 1) -> partial P per
+//             column chunk; the wavefront with the first chunk of a strip adds the strip's chunks;
+//             the wavefront with the first tile of a matrix runs Gram-Schmidt on the n x r panel
+//             (Alg. 1 "orthogonalize") and publishes P_hat
+//   phase B   (needs this strip's rows of P_hat)  Q = M^T P_hat from the registers -> partial Q per
+//             run of strips; the wavefront with the first run of a column chunk adds the runs and
+//             publishes Q
+//   phase C   (needs this chunk's rows of Q)  Delta' = P_hat Q^T (Alg. 1 "decompress"),
+//             e' = M - Delta' (Alg. 2), each stored once
 //
-// The two waits are the two global dependencies of the method (all of P before P_hat, all of Q
-// before P_hat Q^T), taken per matrix and per column chunk instead of as grid-wide barriers, so
-// that a small matrix does not wait for a large one.  Everything that crosses workgroups
-// (partials, P_hat, Q, counters, flags) moves through device-scope relaxed atomics, which are
-// written through to memory and read from there, so no cache-wide write-back or invalidate is
-// needed; a wavefront only waits for its own stores to be acknowledged before it signals.
-// All sums run in a fixed order.
+// The two "needs" are the two global dependencies of the method (all of P before P_hat, all of Q
+// before P_hat Q^T), taken per strip and per column chunk instead of as grid-wide barriers.
+//
+// Everything that crosses wavefronts travels through a plan-owned MAILBOX of 64-bit slots
+// {value, tag}: the producer writes the float together with the step's epoch in one 8-byte
+// device-scope store (written through to memory), the consumer polls the slot with device-scope
+// loads until the tag equals the epoch.  There are no counters, no flags and no cache-wide
+// write-backs or invalidates on the critical path; a hand-over costs one memory round trip.  The
+// epoch is a device word read by every wavefront at kernel start and advanced by the workgroup
+// that finishes last, so stale slots of earlier steps never match.  All sums run in a fixed order.
 //
 // The grid must be co-resident (the launcher checks the occupancy).  Every wait is bounded: a
-// wavefront that polls longer than kSpinLimit iterations raises the error word and goes on, so
-// the kernel always terminates.
+// wavefront that polls longer than kSpinLimit rounds raises the error word and goes on, so the
+// kernel always terminates.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -39,83 +43,89 @@ namespace psgd {
 constexpr unsigned kSpinLimit = 1u << 21;
 constexpr int kResRowsPerLane = kResMaxN / kWave;   // rows of the Gram-Schmidt panel a lane holds
 
+typedef unsigned long long slot_t;
+
 struct ResArgs {
-    const MatDesc* mats;
+    const MatDesc* mats;         // resident descriptors: ppart_off / qpart_off are mailbox offsets (slots)
     const RTile* tiles;
     const float* grad;
     float* err;
     float* q;
     float* p;
     float* out;
-    float* ws;
-    unsigned* sync;
-    int32_t ngroups;
+    slot_t* mail;
+    unsigned* sync;              // error word, epoch word, finished-workgroup count
     int32_t nblocks;
-    int32_t n_mats;
-    int32_t n_cntq;
-    int32_t n_cnts;
-    int64_t flags_at;            // word offset of the readiness flags in `sync`
     int64_t n_mat_elems;
     unsigned long long* trace;   // diagnostic: kResTracePoints timestamps per workgroup, or nullptr
 };
 
 __device__ __forceinline__ void trace_mark(const ResArgs& a, int point) {
-    if (a.trace && threadIdx.x == 0) a.trace[(size_t)blockIdx.x * kResTracePoints + point] = wall_clock64();
+    if (a.trace && (threadIdx.x & (kWave - 1)) == 0)
+        a.trace[((size_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * kResTracePoints + point] = wall_clock64();
+}
+__device__ __forceinline__ void trace_mark_wave(const ResArgs& a, int point) { trace_mark(a, point); }
+
+// ---- mailbox -----------------------------------------------------------------------------------------
+__device__ __forceinline__ void post(slot_t* slot, float v, unsigned epoch) {
+    const slot_t w = ((slot_t)epoch << 32) | (slot_t)__float_as_uint(v);
+    __hip_atomic_store(slot, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// ---- readiness flags -----------------------------------------------------------------------------------
-// One word per matrix ("P_hat is published") and one per column chunk ("Q is published").  A flag only
-// ever grows: the publisher stores (value at kernel start) + 1 after its data is in memory, consumers
-// wait until the word differs from the value they read at kernel start.  A consumer reads that value
-// before it contributes to the result the flag stands for, so it cannot miss the change; no word
-// needs a reset between launches.
-// Each flag has kResFlagCopies copies on separate 256-byte lines so that the wavefronts polling a
-// big matrix's flag do not queue on one memory channel; one lane per wavefront polls.
-__device__ __forceinline__ unsigned* flag_word(unsigned* flags, int flag, int copy) {
-    return flags + ((int64_t)flag * kResFlagCopies + copy) * kSyncLineWords;
+// Polling is written as: issue all loads of an attempt back to back (`fetch`, unconditional, so that
+// no branch forces a wait between them; lanes or slots that are not wanted re-read a wanted one),
+// then look at the tags.
+__device__ __forceinline__ slot_t fetch(const slot_t* slot) {
+    return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ bool arrived(slot_t w, unsigned epoch) { return (unsigned)(w >> 32) == epoch; }
+__device__ __forceinline__ float value_of(slot_t w) { return __uint_as_float((unsigned)(w & 0xffffffffULL)); }
 
-__device__ __forceinline__ unsigned read_flag(unsigned* flags, int flag, int copy) {
-    unsigned v = 0;
-    if ((threadIdx.x & (kWave - 1)) == 0) v = ld_dev(flag_word(flags, flag, copy));
-    return __builtin_amdgcn_readfirstlane(v);
-}
-
-__device__ __forceinline__ void publish_flag(unsigned* flags, int flag, unsigned value) {
-    const int lane = threadIdx.x & (kWave - 1);
-    if (lane < kResFlagCopies) st_dev(flag_word(flags, flag, lane), value);
-}
-
-__device__ __forceinline__ void wait_flag(unsigned* flags, int flag, int copy, unsigned seen_at_start,
-                                          unsigned* err_word) {
+// Wait for a group of slots: every lane polls the slots it needs (`attempt()` returns true when all of
+// them carry this step's tag) until the whole wavefront has them.  For the few wavefronts that reduce.
+// All lanes of the wavefront call it together.
+template <typename F>
+__device__ __forceinline__ void await(F attempt, unsigned* err_word) {
     unsigned spins = 0;
-    while (read_flag(flags, flag, copy) == seen_at_start) {
-        __builtin_amdgcn_s_sleep(4);
+    for (;;) {
+        const bool ok = attempt();
+        if (__all(ok)) break;
+        __builtin_amdgcn_s_sleep(2);
         if (++spins > kSpinLimit) {
             st_dev(err_word, 1u);
             break;
         }
     }
-    wave_mem_done();
+}
+
+// The same for the many wavefronts that wait for a published result: first one lane probes a single
+// slot of the group (`probe`, the same address for the whole wavefront) at a relaxed pace, so that
+// two thousand waiting wavefronts put little load on the memory system; once it carries this step's
+// tag the rest is about to land and every lane polls the slots it needs.
+template <typename F>
+__device__ __forceinline__ void await_probed(const slot_t* probe, unsigned epoch, F attempt, unsigned* err_word) {
+    unsigned spins = 0;
+    for (;;) {
+        unsigned tag = epoch;
+        if ((threadIdx.x & (kWave - 1)) == 0)
+            tag = (unsigned)(__hip_atomic_load(probe, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32);
+        if (__builtin_amdgcn_readfirstlane(tag) == epoch) break;
+        __builtin_amdgcn_s_sleep(6);
+        if (++spins > kSpinLimit) {
+            st_dev(err_word, 1u);
+            return;
+        }
+    }
+    await(attempt, err_word);
 }
 
 // ---- Gram-Schmidt by one wavefront -------------------------------------------------------------------
-// In place on the n x r panel p_io (the mean P on entry, P_hat on exit), accessed with device-scope
-// loads and stores.  Panel rows lane, lane + 64, ... are held in registers (n <= kResMaxN).  Column by column, left to
-// right: squared norm and dot products with the columns to the right in fp64, reduced over the
-// wavefront; normalise; remove the component from the columns to the right (modified Gram-Schmidt).
-// A column whose squared norm is <= 1e-30 at its turn becomes zero.
+// Rows lane, lane + 64, ... of the n x r panel are held in registers (n <= kResMaxN).  Column by
+// column, left to right: squared norm and dot products with the columns to the right in fp64, reduced
+// over the wavefront; normalise; remove the component from the columns to the right (modified
+// Gram-Schmidt).  A column whose squared norm is <= 1e-30 at its turn becomes zero.
 template <int R>
-__device__ __forceinline__ void gram_schmidt_wave(const MatDesc& d, float* p_io) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int n = d.n, ri = d.r;
-    float P[kResRowsPerLane][R];
-#pragma unroll
-    for (int j = 0; j < kResRowsPerLane; ++j) {
-        const int row = lane + kWave * j;
-#pragma unroll
-        for (int k = 0; k < R; ++k) P[j][k] = (row < n && k < ri) ? ld_dev(p_io + (int64_t)row * ri + k) : 0.f;
-    }
+__device__ __forceinline__ void gram_schmidt_rows(float (&P)[kResRowsPerLane][R], int ri) {
 #pragma unroll
     for (int c = 0; c < R; ++c) {
         if (c < ri) {
@@ -146,20 +156,11 @@ __device__ __forceinline__ void gram_schmidt_wave(const MatDesc& d, float* p_io)
             }
         }
     }
-#pragma unroll
-    for (int j = 0; j < kResRowsPerLane; ++j) {
-        const int row = lane + kWave * j;
-        if (row < n) {
-#pragma unroll
-            for (int k = 0; k < R; ++k)
-                if (k < ri) st_dev(p_io + (int64_t)row * ri + k, P[j][k]);
-        }
-    }
 }
 
 // ---- the step, for a workgroup whose tiles use V-wide row accesses ---------------------------------------
 template <int R, int V>
-__device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, float* lds) {
+__device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, float* lds, unsigned epoch) {
     constexpr int RT = kResRows;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -170,22 +171,24 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
     const int col = (t.vec0 + lane) * V;
     const int nrows = active ? t.nrows : 0;
     const int64_t tile_off = d.off + (int64_t)t.row0 * d.m + col;
-    unsigned* cnt_p = a.sync + res_sync_cntp(a.ngroups);   // one arrival counter per matrix ...
-    unsigned* cnt_q = cnt_p + a.n_mats;                    // ... one per column chunk ...
-    unsigned* cnt_s = cnt_q + a.n_cntq;                    // ... one per strip,
-    // then the readiness flags, on lines of their own: per matrix, then per column chunk
-    unsigned* flags = a.sync + a.flags_at;
-    const int fl_p = active ? t.mat : 0, fl_q = active ? a.n_mats + t.cntq : 0;
-    const int copy = (blockIdx.x * kWavesPerBlock + wave) % kResFlagCopies;
     unsigned* err_word = a.sync + res_sync_err();
-    unsigned fp0 = 0, fq0 = 0;
-    if (active) {
-        fp0 = read_flag(flags, fl_p, copy);
-        fq0 = read_flag(flags, fl_q, copy);
-    }
+    // mailbox regions of this matrix (slots)
+    const int64_t nr = (int64_t)d.n * ri, mr = (int64_t)d.m * ri;
+    slot_t* mail_pp = a.mail + d.ppart_off;               // partial P   [n_cchunk][n][r]
+    slot_t* mail_pb = mail_pp + (int64_t)d.n_cchunk * nr; // mean P      [n][r]
+    slot_t* mail_ph = mail_pb + nr;                       // P_hat       [n][r]
+    slot_t* mail_qp = a.mail + d.qpart_off;               // partial Q   [n_rblock][m][r]
+    slot_t* mail_qb = mail_qp + (int64_t)d.n_rblock * mr; // Q           [m][r]
 
     // ---------------- phase A ----------------
     trace_mark(a, 0);
+    if (a.trace && lane == 0) {
+        unsigned long long* tr = a.trace + ((size_t)blockIdx.x * kWavesPerBlock + wave) * kResTracePoints;
+        tr[12] = (unsigned long long)(long long)t.mat;
+        tr[13] = (unsigned long long)t.ppart;
+        tr[14] = (unsigned long long)t.row0;
+        tr[15] = (unsigned long long)(t.qrun_len > 0 ? t.qpart : -1);
+    }
     float M[RT][V];
     float qr[V][R];
 #pragma unroll
@@ -229,67 +232,108 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
             }
         }
         if (lane < nrows) {
-            float* dst = a.ws + d.ppart_off + ((int64_t)t.ppart * d.n + t.row0 + lane) * ri;
+            // mailbox layouts are [..][k][row] (and [..][x][k][column vector] for Q): consecutive lanes
+            // write consecutive slots, so one store instruction fills whole memory lines
+            slot_t* dst = mail_pp + (int64_t)t.ppart * nr + t.row0 + lane;
 #pragma unroll
             for (int k = 0; k < R; ++k)
-                if (k < ri) st_dev(dst + k, mine[k]);
+                if (k < ri) post(dst + (int64_t)k * d.n, mine[k], epoch);
         }
     }
     trace_mark(a, 1);
-    if (active) {
-        wave_mem_done();
-        // the wavefront that brings the last column chunk of a strip adds the chunks (fixed order) into the
-        // mean P rows of the strip (W = 1: the mean over workers is the value itself), kept in the P buffer
-        int last = 0;
-        if (lane == 0) {
-            last = add_dev(cnt_s + t.cnts, 1u) == (unsigned)d.n_cchunk - 1u;
-            if (last) add_dev(cnt_s + t.cnts, 0u - (unsigned)d.n_cchunk);
+    if (active && t.ppart == 0 && t.row0 == 0) trace_mark_wave(a, 7);
+    if (active && t.ppart == 0) {
+        // This wavefront holds the first column chunk of its strip: it adds the strip's chunks in chunk
+        // order into the rows of the mean P (W = 1: the mean over workers is the value itself).
+        const int nval = nrows * ri;   // <= 128
+        for (int u = 0; u * kWave < nval; ++u) {
+            const int idx = lane + kWave * u;
+            const bool mine = idx < nval;
+            const int idx_c = mine ? idx : nval - 1;
+            const int64_t at = (int64_t)(idx_c / nrows) * d.n + t.row0 + idx_c % nrows;   // [k][row]
+            float s = 0.f;
+            constexpr int CG = 16;   // chunk partials polled together
+            for (int c0 = 0; c0 < d.n_cchunk; c0 += CG) {
+                slot_t w[CG];
+                await([&]() {
+#pragma unroll
+                    for (int cc = 0; cc < CG; ++cc)
+                        w[cc] = fetch(mail_pp + (int64_t)min(c0 + cc, d.n_cchunk - 1) * nr + at);
+                    bool ok = true;
+#pragma unroll
+                    for (int cc = 0; cc < CG; ++cc) ok &= arrived(w[cc], epoch);
+                    return ok;
+                }, err_word);
+#pragma unroll
+                for (int cc = 0; cc < CG; ++cc)
+                    if (c0 + cc < d.n_cchunk) s += value_of(w[cc]);
+            }
+            if (mine) post(mail_pb + at, s, epoch);
         }
-        last = __builtin_amdgcn_readfirstlane(last);
-        if (last) {
-            const int nval = nrows * ri;                   // <= 128
-            const float* src = a.ws + d.ppart_off + (int64_t)t.row0 * ri;
-            float* dst = a.p + d.p_off + (int64_t)t.row0 * ri;
-            const int64_t cstride = (int64_t)d.n * ri;
+        if (t.row0 == 0) {
+            // ... and this one also holds the first strip: it orthogonalises the matrix's panel.
+            trace_mark_wave(a, 8);
+            float P[kResRowsPerLane][R];
+            {
+                slot_t w[kResRowsPerLane][R];
+                await([&]() {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int idx = lane + kWave * u;
-                if (idx < nval) {
-                    float s = 0.f;
-                    for (int c0 = 0; c0 < d.n_cchunk; c0 += 16) {
-                        float v[16];
+                    for (int j = 0; j < kResRowsPerLane; ++j)
 #pragma unroll
-                        for (int cc = 0; cc < 16; ++cc) v[cc] = (c0 + cc < d.n_cchunk) ? ld_dev(src + (c0 + cc) * cstride + idx) : 0.f;
+                        for (int k = 0; k < R; ++k)
+                            w[j][k] = fetch(mail_pb + (int64_t)min(k, ri - 1) * d.n + min(lane + kWave * j, d.n - 1));
+                    bool ok = true;
 #pragma unroll
-                        for (int cc = 0; cc < 16; ++cc) s += v[cc];
-                    }
-                    st_dev(dst + idx, s);
+                    for (int j = 0; j < kResRowsPerLane; ++j)
+#pragma unroll
+                        for (int k = 0; k < R; ++k) ok &= arrived(w[j][k], epoch);
+                    return ok;
+                }, err_word);
+#pragma unroll
+                for (int j = 0; j < kResRowsPerLane; ++j)
+#pragma unroll
+                    for (int k = 0; k < R; ++k)
+                        P[j][k] = (lane + kWave * j < d.n && k < ri) ? value_of(w[j][k]) : 0.f;
+            }
+            trace_mark_wave(a, 9);
+            gram_schmidt_rows<R>(P, ri);
+            trace_mark_wave(a, 10);
+#pragma unroll
+            for (int j = 0; j < kResRowsPerLane; ++j) {
+                const int row = lane + kWave * j;
+                if (row < d.n) {
+#pragma unroll
+                    for (int k = 0; k < R; ++k)
+                        if (k < ri) {
+                            post(mail_ph + (int64_t)k * d.n + row, P[j][k], epoch);
+                            a.p[d.p_off + (int64_t)row * ri + k] = P[j][k];
+                        }
                 }
             }
-            wave_mem_done();
-            // the wavefront that completes the last strip of a matrix orthogonalises its panel
-            int last_m = 0;
-            if (lane == 0) {
-                last_m = add_dev(cnt_p + t.mat, 1u) == (unsigned)t.nstrips_mat - 1u;
-                if (last_m) add_dev(cnt_p + t.mat, 0u - (unsigned)t.nstrips_mat);
-            }
-            last_m = __builtin_amdgcn_readfirstlane(last_m);
-            if (last_m) {
-                gram_schmidt_wave<R>(d, a.p + d.p_off);
-                wave_mem_done();
-                publish_flag(flags, fl_p, fp0 + 1u);
-            }
+            trace_mark_wave(a, 11);
         }
     }
     trace_mark(a, 2);
-    if (active) wait_flag(flags, fl_p, copy, fp0, err_word);
-    trace_mark(a, 3);
 
     // ---------------- phase B ----------------
     float pr[R];
 #pragma unroll
-    for (int k = 0; k < R; ++k)
-        pr[k] = (lane < nrows && k < ri) ? ld_dev(a.p + d.p_off + (int64_t)(t.row0 + lane) * ri + k) : 0.f;
+    for (int k = 0; k < R; ++k) pr[k] = 0.f;
+    if (active) {
+        slot_t w[R];
+        const int64_t my_row = t.row0 + min(lane, nrows - 1);
+        await_probed(mail_ph + t.row0, epoch, [&]() {
+#pragma unroll
+            for (int k = 0; k < R; ++k) w[k] = fetch(mail_ph + (int64_t)min(k, ri - 1) * d.n + my_row);
+            bool ok = true;
+#pragma unroll
+            for (int k = 0; k < R; ++k) ok &= arrived(w[k], epoch);
+            return ok;
+        }, err_word);
+#pragma unroll
+        for (int k = 0; k < R; ++k) pr[k] = (lane < nrows && k < ri) ? value_of(w[k]) : 0.f;
+    }
+    trace_mark(a, 3);
     float acc[V][R];
 #pragma unroll
     for (int x = 0; x < V; ++x)
@@ -319,71 +363,97 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
 #pragma unroll
                 for (int k = 0; k < R; ++k) acc[x][k] += lds[(((wave + w2) * V + x) * R + k) * kWave + lane];
         }
-        float* qpart = a.ws + d.qpart_off;
-        const int64_t mr = (int64_t)d.m * ri;
+        const int64_t nvec_m = d.m / V;                       // column vectors of the matrix
+        const int64_t jv = t.vec0 + min(lane, t.nvec - 1);    // this lane's (idle lanes: a wanted) column vector
         if (valid) {
-            float* dst = qpart + (int64_t)t.qpart * mr + (int64_t)col * ri;
+            slot_t* dst = mail_qp + (int64_t)t.qpart * mr + jv;   // [x][k][column vector]
 #pragma unroll
             for (int x = 0; x < V; ++x)
 #pragma unroll
                 for (int k = 0; k < R; ++k)
-                    if (k < ri) st_dev(dst + x * ri + k, acc[x][k]);
+                    if (k < ri) post(dst + (int64_t)(x * ri + k) * nvec_m, acc[x][k], epoch);
         }
-        wave_mem_done();
-        int last = 0;
-        if (lane == 0) {
-            unsigned* c = cnt_q + t.cntq;
-            last = add_dev(c, 1u) == (unsigned)t.nqparts - 1u;
-            if (last) add_dev(c, 0u - (unsigned)t.nqparts);
-        }
-        last = __builtin_amdgcn_readfirstlane(last);
-        if (last && valid) {
-            // add the runs' partials in run order; loads of four runs at a time are in flight together
-            float* qdst = a.q + d.q_off + (int64_t)col * ri;
-            const float* src = qpart + (int64_t)col * ri;
+        if (t.qpart == 0) {
+            // first run of this column chunk: add the runs' partials in run order and publish Q
+            if (!(t.ppart == 0 && t.row0 == 0)) trace_mark_wave(a, 8);
             float s[V][R];
 #pragma unroll
             for (int x = 0; x < V; ++x)
 #pragma unroll
                 for (int k = 0; k < R; ++k) s[x][k] = 0.f;
-            for (int p0 = 0; p0 < t.nqparts; p0 += 4) {
-                float v[4][V][R];
+            constexpr int PG = V * R >= 16 ? 1 : (V * R >= 8 ? 2 : 4);   // run partials polled together
+            const slot_t* src_c = mail_qp + jv;
+            for (int p0 = 0; p0 < t.nqparts; p0 += PG) {
+                slot_t w[PG][V][R];
+                await([&]() {
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                    for (int u = 0; u < PG; ++u)
+#pragma unroll
+                        for (int x = 0; x < V; ++x)
+#pragma unroll
+                            for (int k = 0; k < R; ++k)
+                                w[u][x][k] = fetch(src_c + (int64_t)min(p0 + u, t.nqparts - 1) * mr +
+                                                   (int64_t)(x * ri + min(k, ri - 1)) * nvec_m);
+                    bool ok = true;
+#pragma unroll
+                    for (int u = 0; u < PG; ++u)
+#pragma unroll
+                        for (int x = 0; x < V; ++x)
+#pragma unroll
+                            for (int k = 0; k < R; ++k) ok &= arrived(w[u][x][k], epoch);
+                    return ok;
+                }, err_word);
+#pragma unroll
+                for (int u = 0; u < PG; ++u)
 #pragma unroll
                     for (int x = 0; x < V; ++x)
 #pragma unroll
                         for (int k = 0; k < R; ++k)
-                            v[u][x][k] = (p0 + u < t.nqparts && k < ri) ? ld_dev(src + (int64_t)(p0 + u) * mr + x * ri + k) : 0.f;
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-#pragma unroll
-                    for (int x = 0; x < V; ++x)
-#pragma unroll
-                        for (int k = 0; k < R; ++k) s[x][k] += v[u][x][k];
+                            if (p0 + u < t.nqparts) s[x][k] += value_of(w[u][x][k]);
+                if (!(t.ppart == 0 && t.row0 == 0)) trace_mark_wave(a, 9 + min(p0 / PG, 2));
             }
+            if (valid) {
 #pragma unroll
-            for (int x = 0; x < V; ++x)
+                for (int x = 0; x < V; ++x)
 #pragma unroll
-                for (int k = 0; k < R; ++k)
-                    if (k < ri) st_dev(qdst + x * ri + k, s[x][k]);   // W = 1: the mean is the sum
-        }
-        if (last) {
-            wave_mem_done();
-            publish_flag(flags, fl_q, fq0 + 1u);
+                    for (int k = 0; k < R; ++k)
+                        if (k < ri) {
+                            post(mail_qb + (int64_t)(x * ri + k) * nvec_m + jv, s[x][k], epoch);   // W = 1: mean = sum
+                            a.q[d.q_off + (int64_t)(col + x) * ri + k] = s[x][k];
+                        }
+            }
         }
     }
     trace_mark(a, 4);
-    if (active) wait_flag(flags, fl_q, copy, fq0, err_word);
-    trace_mark(a, 5);
 
     // ---------------- phase C ----------------
     float qb[V][R];
 #pragma unroll
     for (int x = 0; x < V; ++x)
 #pragma unroll
-        for (int k = 0; k < R; ++k)
-            qb[x][k] = (valid && k < ri) ? ld_dev(a.q + d.q_off + (int64_t)(col + x) * ri + k) : 0.f;
+        for (int k = 0; k < R; ++k) qb[x][k] = 0.f;
+    if (active) {
+        slot_t w[V][R];
+        const int64_t nvec_m = d.m / V;
+        const int64_t jv = t.vec0 + min(lane, t.nvec - 1);
+        await_probed(mail_qb + t.vec0, epoch, [&]() {
+#pragma unroll
+            for (int x = 0; x < V; ++x)
+#pragma unroll
+                for (int k = 0; k < R; ++k) w[x][k] = fetch(mail_qb + (int64_t)(x * ri + min(k, ri - 1)) * nvec_m + jv);
+            bool ok = true;
+#pragma unroll
+            for (int x = 0; x < V; ++x)
+#pragma unroll
+                for (int k = 0; k < R; ++k) ok &= arrived(w[x][k], epoch);
+            return ok;
+        }, err_word);
+#pragma unroll
+        for (int x = 0; x < V; ++x)
+#pragma unroll
+            for (int k = 0; k < R; ++k) qb[x][k] = (valid && k < ri) ? value_of(w[x][k]) : 0.f;
+    }
+    trace_mark(a, 5);
 #pragma unroll
     for (int i = 0; i < RT; ++i) {
         if (i < nrows) {
@@ -400,8 +470,12 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
                     dl[x] = s;
                     en[x] = M[i][x] - s;
                 }
+#ifndef PSGD_EXPERIMENT_NO_PHASE_C_STORES
                 stv<V>(a.err + tile_off + (int64_t)i * d.m, en);
                 stv<V>(a.out + tile_off + (int64_t)i * d.m, dl);
+#else
+                if (en[0] == 12345.678f && dl[0] == 9.87f) stv<V>(a.out + tile_off + (int64_t)i * d.m, dl);
+#endif
             }
         }
     }
@@ -417,13 +491,26 @@ template <int R>
 __global__ __launch_bounds__(kBlock, 2) void k_resident(ResArgs a) {
     __shared__ float lds[kWavesPerBlock * 4 * R * kWave];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // the epoch cannot change before every workgroup of this launch has finished
+    unsigned epoch = 0;
+    if ((threadIdx.x & (kWave - 1)) == 0) epoch = ld_dev(a.sync + res_sync_epoch());
+    epoch = __builtin_amdgcn_readfirstlane(epoch);
     const RTile t = a.tiles[blockIdx.x * kWavesPerBlock + wave];
     // all tiles of a workgroup use the same access width; the first slot is never idle
     const RTile t0 = a.tiles[blockIdx.x * kWavesPerBlock];
     const int vec = t0.mat >= 0 ? a.mats[t0.mat].vec : 4;
-    if (vec == 4) resident_body<R, 4>(a, t, lds);
-    else if (vec == 2) resident_body<R, 2>(a, t, lds);
-    else resident_body<R, 1>(a, t, lds);
+    if (vec == 4) resident_body<R, 4>(a, t, lds, epoch);
+    else if (vec == 2) resident_body<R, 2>(a, t, lds, epoch);
+    else resident_body<R, 1>(a, t, lds, epoch);
+    // the workgroup that finishes last advances the epoch for the next launch
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned* done = a.sync + res_sync_done();
+        if (add_dev(done, 1u) == (unsigned)a.nblocks - 1u) {
+            add_dev(done, 0u - (unsigned)a.nblocks);
+            st_dev(a.sync + res_sync_epoch(), epoch + 1u);
+        }
+    }
 }
 
 // ---- host side --------------------------------------------------------------------------------------------
@@ -482,14 +569,10 @@ psgd_status launch_resident_step(psgd_plan* plan, const void* grad, float* err, 
     a.q = q;
     a.p = p;
     a.out = static_cast<float*>(out);
-    a.ws = static_cast<float*>(workspace);
+    (void)workspace;   // the resident kernel communicates through the plan-owned mailbox
+    a.mail = reinterpret_cast<slot_t*>(plan->dev.res_mail);
     a.sync = plan->dev.res_sync;
     a.nblocks = plan->res_blocks;
-    a.ngroups = (plan->res_blocks + kResBarrierFanIn - 1) / kResBarrierFanIn;
-    a.n_mats = (int32_t)plan->mats.size();
-    a.n_cntq = plan->res_n_cntq;
-    a.n_cnts = plan->res_n_cnts;
-    a.flags_at = plan->res_flags_at;
     a.n_mat_elems = plan->sizes.n_mat_elems;
     a.trace = plan->dev.res_trace;
     if (plan->profiling) {

@@ -5,6 +5,8 @@
 // workspace the plan asks for: the bounds the kernels rely on.
 #include <cstdio>
 #include <cstdlib>
+#include <algorithm>
+#include <utility>
 #include <vector>
 
 #include "psgd_internal.h"
@@ -128,15 +130,34 @@ static void check_resident(const psgd_plan* plan) {
             CHECK(t.cnts >= 0 && t.cnts < plan->res_n_cnts);
             CHECK(t.nrows * d.r <= 2 * kWave);
         }
-    for (const MatDesc& d : plan->res_mats) {
-        CHECK(d.ppart_off >= 0 && d.ppart_off + (int64_t)d.n_cchunk * d.n * d.r <= plan->res_ws_floats);
-        CHECK(d.qpart_off >= 0 && d.qpart_off + (int64_t)d.n_rblock * d.m * d.r <= plan->res_ws_floats);
+    {
+        // mailbox regions: [partial P | mean P | P_hat] and [partial Q | Q] per matrix, disjoint, inside the mailbox
+        std::vector<std::pair<int64_t, int64_t>> regions;
+        for (const MatDesc& d : plan->res_mats) {
+            regions.push_back({d.ppart_off, d.ppart_off + ((int64_t)d.n_cchunk + 2) * d.n * d.r});
+            regions.push_back({d.qpart_off, d.qpart_off + ((int64_t)d.n_rblock + 1) * d.m * d.r});
+        }
+        std::sort(regions.begin(), regions.end());
+        int64_t prev = 0;
+        for (auto& rg : regions) {
+            CHECK(rg.first >= prev && rg.second <= plan->res_mail_slots);
+            prev = rg.second;
+        }
     }
-    CHECK(plan->res_ws_floats * 4 <= plan->sizes.workspace_bytes);
-    const int ngroups = (plan->res_blocks + kResBarrierFanIn - 1) / kResBarrierFanIn;
-    CHECK(res_sync_cntp(ngroups) + (int64_t)plan->mats.size() + plan->res_n_cntq + plan->res_n_cnts <= plan->res_flags_at);
-    CHECK(plan->res_flags_at % kSyncLineWords == 0);
-    CHECK(plan->res_flags_at + ((int64_t)plan->mats.size() + plan->res_n_cntq) * kResFlagCopies * kSyncLineWords <= plan->res_sync_words);
+    CHECK(plan->res_sync_words == kResSyncWords);
+    // exactly one strip reducer per strip, one orthogonaliser per matrix, one chunk reducer per column chunk
+    {
+        std::vector<int> strip_red(plan->res_n_cnts, 0), chunk_red(plan->res_n_cntq, 0), ortho(plan->mats.size(), 0);
+        for (const RTile& t : plan->res_tiles) {
+            if (t.mat < 0) continue;
+            if (t.ppart == 0) strip_red[t.cnts] += 1;
+            if (t.ppart == 0 && t.row0 == 0) ortho[t.mat] += 1;
+            if (t.qrun_len > 0 && t.qpart == 0) chunk_red[t.cntq] += 1;
+        }
+        for (int v : strip_red) CHECK(v == 1);
+        for (int v : chunk_red) CHECK(v == 1);
+        for (int v : ortho) CHECK(v == 1);
+    }
     // every strip counter is shared by exactly the column chunks of one strip
     {
         std::vector<int> per_strip(plan->res_n_cnts, 0);
