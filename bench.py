@@ -31,7 +31,10 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # HBM bytes per launch of a kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
 # copy kernel of known size (see profiles/); keyed by (workload, rank, workers, kernel).  None = not
 # measured for that configuration.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/resident_resnet18_r2.md: 98.8 MB fetched + 93.5 MB written
+    ("resnet18", 2, 1, "k_resident"): 192366695,
+}
 
 
 def parse():
@@ -49,6 +52,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing")
     ap.add_argument("--tune", action="append", default=[], help="key=value planner tuning (experiments)")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="also run a plain device copy of this many MiB five times (a kernel of known traffic "
+                         "against which rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled)")
     return ap.parse_args()
 
 
@@ -152,6 +158,15 @@ def main():
 
     def step(i):
         plan.step(grads[i % len(grads)], err, q, p, out, ws, sh)
+
+    if args.copy_calibration > 0:
+        n = args.copy_calibration * 1024 * 1024 // 4
+        src = torch.randn(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)      # reads and writes args.copy_calibration MiB each
+        torch.cuda.synchronize(dev)
+        del src, dst
 
     for i in range(args.warmup):
         step(i)
