@@ -19,20 +19,23 @@ constexpr int kMaxVecPerLaneK1 = 4;  // column vectors a lane owns per row in th
 constexpr int kMaxVecPerLaneK3 = 2;  // column vectors a lane owns in the Q = M^T P and decompress kernels
 constexpr int kOrthoBlock = 256;   // threads of the single-workgroup Gram-Schmidt kernel
 constexpr int kValuMaxRank = 8;    // ranks up to this run on the vector-ALU kernels
+constexpr int kPanelFloats = 12288;  // n*r up to this: Gram-Schmidt by one workgroup with the panel in LDS (48 KB)
+constexpr int kGramRows = 256;     // rows per workgroup of the tall-panel Gram / apply kernels
 
 // One matrix of the model.
 struct MatDesc {
     int64_t off;        // element offset in the matrix region
     int64_t p_off;      // float offset in packed P
     int64_t q_off;      // float offset in packed Q
-    int64_t ppart_off;  // float offset in the workspace: partial P, [n_cchunk][n][r]
-    int64_t qpart_off;  // float offset in the workspace: partial Q, [n_rblock][m][r]
+    int64_t ppart_off;  // float offset in the workspace: partial P, [W * n_cchunk][n][r]
+    int64_t qpart_off;  // float offset in the workspace: partial Q, [W * n_rblock][m][r]
+    int64_t gram_off;   // tall panels: offset (in doubles) of the Gram partials, [n_gblock][r*r]
     int32_t n, m, r;    // rows, columns, effective rank
     int32_t vec;        // elements per vector access along a row (4, 2 or 1)
     int32_t n_cchunk;   // column chunks of the P = M Q kernel (partials to sum)
     int32_t n_rblock;   // row blocks of the Q = M^T P kernel (partials to sum)
     int32_t tensor;     // index in the caller's shape list
-    int32_t pad_;
+    int32_t n_gblock;   // tall panels: row blocks of the Gram / apply kernels; 0 = panel fits one workgroup's LDS
 };
 
 // One workgroup's share of a streaming kernel.
@@ -94,6 +97,8 @@ struct DeviceTables {
     Tile* tiles3 = nullptr;
     Tile* tiles4 = nullptr;
     Tile* tilesq = nullptr;
+    Tile* tiles_gram = nullptr;
+    int32_t* small_mats = nullptr;
     MatDesc* res_mats = nullptr;
     RTile* res_tiles = nullptr;
     unsigned* res_sync = nullptr;  // error word, epoch, finished-workgroup count
@@ -115,6 +120,9 @@ struct psgd_plan {
     std::vector<int32_t> tensor_mat;        // per tensor: matrix index or -1
     std::vector<psgd::MatDesc> mats;
     std::vector<psgd::Tile> tiles1, tiles3, tiles4, tilesq;
+    std::vector<psgd::Tile> tiles_gram;     // row blocks of tall panels (Cholesky-QR)
+    std::vector<int32_t> small_mats;        // matrices orthogonalised by one workgroup (Gram-Schmidt in LDS)
+    int64_t ws_gram_doubles = 0;            // workspace: Gram partials, after the float regions
     int32_t max_n = 0;
     int64_t ws_ppart_floats = 0;            // workspace: partial P region (floats)
     int64_t ws_qpart_floats = 0;            // workspace: partial Q region, starts after partial P

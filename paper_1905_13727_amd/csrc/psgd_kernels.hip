@@ -121,13 +121,14 @@ template <int R>
 __global__ __launch_bounds__(kBlock) void k_ef_right(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                      const float* __restrict__ grad, float* __restrict__ err,
                                                      const float* __restrict__ q, float* __restrict__ ws,
-                                                     int64_t gstride, int64_t estride, int64_t ppart_wstride) {
-    const Tile t = tiles[blockIdx.x];
+                                                     int64_t gstride, int64_t estride) {
+    Tile t = tiles[blockIdx.x];
     const MatDesc d = mats[t.mat];
     const int w = blockIdx.y;
     const float* g = grad + (int64_t)w * gstride;
     float* e = err + (int64_t)w * estride;
-    float* pp = ws + (int64_t)w * ppart_wstride;
+    float* pp = ws;
+    t.part += w * d.n_cchunk;   // partial slices: [worker][column chunk]
     if (d.vec == 4) ef_right_tile<R, 4>(t, d, g, e, q, pp);
     else if (d.vec == 2) ef_right_tile<R, 2>(t, d, g, e, q, pp);
     else ef_right_tile<R, 1>(t, d, g, e, q, pp);
@@ -142,28 +143,34 @@ __global__ __launch_bounds__(kBlock) void k_ef_right(const MatDesc* __restrict__
 // removes its component from the others.  A column whose squared norm is <= 1e-30 when its
 // turn comes is set to zero.
 
-constexpr int kPanelFloats = 12288;  // 48 KB of LDS
+// sum of `nparts` partial slices (stride `stride` floats) at `src`, in slice order, eight loads in flight
+__device__ __forceinline__ float sum_parts(const float* __restrict__ src, int nparts, int64_t stride) {
+    float s = 0.f;
+    int c = 0;
+    for (; c + 8 <= nparts; c += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(c + u) * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; c < nparts; ++c) s += src[(int64_t)c * stride];
+    return s;
+}
 
-__global__ __launch_bounds__(kOrthoBlock) void k_ortho(const MatDesc* __restrict__ mats, const float* __restrict__ ws,
-                                                       float* __restrict__ p, int workers, int64_t ppart_wstride) {
+__global__ __launch_bounds__(kOrthoBlock) void k_ortho(const MatDesc* __restrict__ mats, const int32_t* __restrict__ which,
+                                                       const float* __restrict__ ws, float* __restrict__ p, int workers) {
     __shared__ float panel[kPanelFloats];
     __shared__ double red[kOrthoBlock / kWave][kValuMaxRank];
-    const MatDesc d = mats[blockIdx.x];
+    const MatDesc d = mats[which[blockIdx.x]];
     const int n = d.n, r = d.r;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-    const int64_t nr = (int64_t)n * r;
-    const bool in_lds = nr <= kPanelFloats;
-    float* P = in_lds ? panel : (p + d.p_off);
+    const int64_t nr = (int64_t)n * r;    // <= kPanelFloats (planner)
+    float* P = panel;
     const float inv_w = 1.0f / (float)workers;
+    const int nparts = workers * d.n_cchunk;
 
-    for (int64_t idx = tid; idx < nr; idx += kOrthoBlock) {
-        float s = 0.f;
-        for (int w = 0; w < workers; ++w) {
-            const float* src = ws + (int64_t)w * ppart_wstride + d.ppart_off + idx;
-            for (int c = 0; c < d.n_cchunk; ++c) s += src[(int64_t)c * nr];
-        }
-        P[idx] = s * inv_w;
-    }
+    for (int64_t idx = tid; idx < nr; idx += kOrthoBlock) P[idx] = sum_parts(ws + d.ppart_off + idx, nparts, nr) * inv_w;
     __syncthreads();
 
     for (int j = 0; j < r; ++j) {
@@ -215,9 +222,129 @@ __global__ __launch_bounds__(kOrthoBlock) void k_ortho(const MatDesc* __restrict
         }
         __syncthreads();
     }
-    if (in_lds) {
-        float* dst = p + d.p_off;
-        for (int64_t idx = tid; idx < nr; idx += kOrthoBlock) dst[idx] = panel[idx];
+    float* dst = p + d.p_off;
+    for (int64_t idx = tid; idx < nr; idx += kOrthoBlock) dst[idx] = panel[idx];
+}
+
+// ---- tall panels (n*r above the LDS panel): the same orthonormal factor by Cholesky-QR --------------
+//
+// Gram-Schmidt yields P_hat = P R^-1 with R upper triangular, positive diagonal (the paper's remark
+// "Orthogonalization is a linear operation"); that R is the Cholesky factor of the Gram matrix
+// P^T P.  For a panel too tall for one workgroup the factor is computed that way, over many
+// workgroups: k_gram sums the partials into the mean P (stored in the P buffer) and reduces the
+// Gram matrix of its row block in fp64; k_chol_apply adds the blocks' Gram matrices in block order,
+// factorises (fp64, r <= 8) and solves P_hat R = P row by row.  A pivot <= 1e-30 (the squared norm
+// Gram-Schmidt would find for that column at its turn) gives a zero column.
+
+__global__ __launch_bounds__(kBlock) void k_gram(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
+                                                 const float* __restrict__ ws, float* __restrict__ p,
+                                                 double* __restrict__ gram, int workers) {
+    __shared__ double red[kWavesPerBlock][kValuMaxRank * kValuMaxRank];
+    const Tile t = tiles[blockIdx.x];
+    const MatDesc d = mats[t.mat];
+    const int r = d.r, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int64_t nr = (int64_t)d.n * r;
+    const float inv_w = 1.0f / (float)workers;
+    const int nparts = workers * d.n_cchunk;
+    double g[kValuMaxRank][kValuMaxRank];
+#pragma unroll
+    for (int a = 0; a < kValuMaxRank; ++a)
+#pragma unroll
+        for (int b = 0; b < kValuMaxRank; ++b) g[a][b] = 0.0;
+    for (int i = t.row0 + tid; i < t.row0 + t.nrows; i += kBlock) {
+        float row[kValuMaxRank];
+#pragma unroll
+        for (int k = 0; k < kValuMaxRank; ++k) {
+            row[k] = 0.f;
+            if (k < r) {
+                row[k] = sum_parts(ws + d.ppart_off + (int64_t)i * r + k, nparts, nr) * inv_w;
+                p[d.p_off + (int64_t)i * r + k] = row[k];
+            }
+        }
+#pragma unroll
+        for (int a = 0; a < kValuMaxRank; ++a)
+#pragma unroll
+            for (int b = a; b < kValuMaxRank; ++b)
+                if (b < r) g[a][b] += (double)row[a] * (double)row[b];
+    }
+#pragma unroll
+    for (int a = 0; a < kValuMaxRank; ++a)
+#pragma unroll
+        for (int b = a; b < kValuMaxRank; ++b)
+            if (b < r) {
+                const double v = wave_sum(g[a][b]);
+                if (lane == 0) red[wave][a * kValuMaxRank + b] = v;
+            }
+    __syncthreads();
+    if (tid < r * r) {
+        const int a = tid / r, b = tid % r;
+        double v = 0.0;
+        if (b >= a)
+            for (int wv = 0; wv < kWavesPerBlock; ++wv) v += red[wv][a * kValuMaxRank + b];
+        gram[d.gram_off + (int64_t)t.part * r * r + tid] = v;   // upper triangle, zeros below
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_chol_apply(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
+                                                       const double* __restrict__ gram, float* __restrict__ p) {
+    __shared__ double part[kWavesPerBlock][kValuMaxRank * kValuMaxRank];
+    __shared__ double Rm[kValuMaxRank][kValuMaxRank];   // upper triangular factor
+    __shared__ double rinv[kValuMaxRank];               // 1 / R_jj, 0 for a zero column
+    const Tile t = tiles[blockIdx.x];
+    const MatDesc d = mats[t.mat];
+    const int r = d.r, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    // Gram matrix = sum of the row blocks' matrices in block order: four slices of blocks, then the slices
+    if (lane < r * r) {
+        const int per = (d.n_gblock + kWavesPerBlock - 1) / kWavesPerBlock;
+        const int b0 = wave * per, b1 = min(d.n_gblock, b0 + per);
+        double v = 0.0;
+        for (int b = b0; b < b1; ++b) v += gram[d.gram_off + (int64_t)b * r * r + lane];
+        part[wave][lane] = v;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double G[kValuMaxRank][kValuMaxRank];
+        for (int a = 0; a < r; ++a)
+            for (int b = a; b < r; ++b)
+                G[a][b] = ((part[0][a * r + b] + part[1][a * r + b]) + part[2][a * r + b]) + part[3][a * r + b];
+        // Cholesky, row by row of R (upper): R_jj = sqrt(G_jj - sum_k R_kj^2), R_jc = (G_jc - sum_k R_kj R_kc) / R_jj
+        for (int j = 0; j < r; ++j) {
+            double piv = G[j][j];
+            for (int k = 0; k < j; ++k) piv -= Rm[k][j] * Rm[k][j];
+            if (piv <= 1e-30) {
+                rinv[j] = 0.0;
+                for (int c = j; c < r; ++c) Rm[j][c] = 0.0;
+            } else {
+                const double rjj = sqrt(piv);
+                Rm[j][j] = rjj;
+                rinv[j] = 1.0 / rjj;
+                for (int c = j + 1; c < r; ++c) {
+                    double v = G[j][c];
+                    for (int k = 0; k < j; ++k) v -= Rm[k][j] * Rm[k][c];
+                    Rm[j][c] = v / rjj;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = t.row0 + tid; i < t.row0 + t.nrows; i += kBlock) {
+        float* row = p + d.p_off + (int64_t)i * r;
+        double ph[kValuMaxRank];
+#pragma unroll
+        for (int j = 0; j < kValuMaxRank; ++j) {
+            if (j < r) {
+                double v = (double)row[j];
+#pragma unroll
+                for (int k = 0; k < kValuMaxRank; ++k)
+                    if (k < j) v -= ph[k] * Rm[k][j];
+                ph[j] = v * rinv[j];
+            } else {
+                ph[j] = 0.0;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kValuMaxRank; ++j)
+            if (j < r) row[j] = (float)ph[j];
     }
 }
 
@@ -327,13 +454,14 @@ __device__ __forceinline__ void left_tile(const Tile& t, const MatDesc& d, const
 template <int R, int NV>
 __global__ __launch_bounds__(kBlock) void k_left(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                  const float* __restrict__ err, const float* __restrict__ p,
-                                                 float* __restrict__ ws, int64_t estride, int64_t qpart_wstride) {
+                                                 float* __restrict__ ws, int64_t estride) {
     __shared__ float lds[(kWavesPerBlock - 1) * kWave * NV * 4 * R];
-    const Tile t = tiles[blockIdx.x];
+    Tile t = tiles[blockIdx.x];
     const MatDesc d = mats[t.mat];
     const int w = blockIdx.y;
     const float* e = err + (int64_t)w * estride;
-    float* qp = ws + (int64_t)w * qpart_wstride;
+    float* qp = ws;
+    t.part += w * d.n_rblock;   // partial slices: [worker][row block]
     if (d.vec == 4) left_tile<R, 4, NV>(t, d, e, p, qp, lds);
     else if (d.vec == 2) left_tile<R, 2, NV>(t, d, e, p, qp, lds);
     else left_tile<R, 1, NV>(t, d, e, p, qp, lds);
@@ -342,20 +470,23 @@ __global__ __launch_bounds__(kBlock) void k_left(const MatDesc* __restrict__ mat
 // ---- k_q_reduce: Q = (1/W) sum over workers and row blocks of the partials ------------------------
 
 __global__ __launch_bounds__(kBlock) void k_q_reduce(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
-                                                     const float* __restrict__ ws, float* __restrict__ q, int workers,
-                                                     int64_t qpart_wstride) {
+                                                     const float* __restrict__ ws, float* __restrict__ q, int workers) {
+    // 64 elements per workgroup; wavefront g adds slice g of the partials (slice order), then the four
+    // slices are added in slice order
+    __shared__ float part[kWavesPerBlock][kWave];
     const Tile t = tiles[blockIdx.x];
     const MatDesc d = mats[t.mat];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int64_t mr = (int64_t)d.m * d.r;
-    const float inv_w = 1.0f / (float)workers;
-    for (int64_t idx = t.elem0 + threadIdx.x; idx < t.elem0 + t.nelem; idx += kBlock) {
-        float s = 0.f;
-        for (int w = 0; w < workers; ++w) {
-            const float* src = ws + (int64_t)w * qpart_wstride + d.qpart_off + idx;
-            for (int b = 0; b < d.n_rblock; ++b) s += src[(int64_t)b * mr];
-        }
-        q[d.q_off + idx] = s * inv_w;
-    }
+    const int nparts = workers * d.n_rblock;
+    const int per = (nparts + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int b0 = min(nparts, wave * per), b1 = min(nparts, b0 + per);
+    float s = 0.f;
+    if (lane < t.nelem) s = sum_parts(ws + d.qpart_off + (int64_t)b0 * mr + t.elem0 + lane, b1 - b0, mr);
+    part[wave][lane] = s;
+    __syncthreads();
+    if (wave == 0 && lane < t.nelem)
+        q[d.q_off + t.elem0 + lane] = (((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane]) * (1.0f / (float)workers);
 }
 
 // ---- k_decomp: Delta' = P_hat Q^T, e_w = M_w - Delta', vectors averaged ---------------------------
@@ -508,7 +639,7 @@ psgd_status upload_tables(psgd_plan* plan) {
         if (st != PSGD_OK) return st;
     }
     struct Piece { const void* src; size_t bytes; size_t at; };
-    Piece pieces[10] = {
+    Piece pieces[12] = {
         {plan->mats.data(), plan->mats.size() * sizeof(MatDesc), 0},
         {plan->tiles1.data(), plan->tiles1.size() * sizeof(Tile), 0},
         {plan->tiles3.data(), plan->tiles3.size() * sizeof(Tile), 0},
@@ -519,6 +650,8 @@ psgd_status upload_tables(psgd_plan* plan) {
         {nullptr, (size_t)plan->res_sync_words * sizeof(unsigned), 0},   // zero-filled, epoch set below
         {nullptr, plan->tuning.res_trace ? (size_t)plan->res_blocks * kWavesPerBlock * kResTracePoints * sizeof(unsigned long long) : 0, 0},
         {nullptr, (size_t)plan->res_mail_slots * sizeof(unsigned long long), 0},   // zero-filled: tag 0 never matches
+        {plan->tiles_gram.data(), plan->tiles_gram.size() * sizeof(Tile), 0},
+        {plan->small_mats.data(), plan->small_mats.size() * sizeof(int32_t), 0},
     };
     size_t total = 0;
     for (Piece& pc : pieces) {
@@ -552,6 +685,8 @@ psgd_status upload_tables(psgd_plan* plan) {
     plan->dev.res_sync = reinterpret_cast<unsigned*>(b + pieces[7].at);
     plan->dev.res_trace = pieces[8].bytes ? reinterpret_cast<unsigned long long*>(b + pieces[8].at) : nullptr;
     plan->dev.res_mail = reinterpret_cast<unsigned long long*>(b + pieces[9].at);
+    plan->dev.tiles_gram = reinterpret_cast<Tile*>(b + pieces[10].at);
+    plan->dev.small_mats = reinterpret_cast<int32_t*>(b + pieces[11].at);
     plan->uploaded = true;
     return PSGD_OK;
 }
@@ -594,19 +729,18 @@ static void launch_ef_right(psgd_plan* plan, const float* grad, float* err, cons
                             hipStream_t s) {
     dim3 grid((unsigned)plan->tiles1.size(), (unsigned)plan->workers);
     hipLaunchKernelGGL((k_ef_right<R>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles1, grad, err, q, ws,
-                       plan->sizes.grad_stride, plan->sizes.err_stride, plan->ws_ppart_floats);
+                       plan->sizes.grad_stride, plan->sizes.err_stride);
 }
 
 template <int R>
 static void launch_left(psgd_plan* plan, const float* err, const float* p, float* ws, hipStream_t s) {
     dim3 grid((unsigned)plan->tiles3.size(), (unsigned)plan->workers);
-    float* qpart = ws + (int64_t)plan->workers * plan->ws_ppart_floats;  // after all workers' partial P
     if (plan->tuning.k3_nv == 1)
-        hipLaunchKernelGGL((k_left<R, 1>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles3, err, p, qpart,
-                           plan->sizes.err_stride, plan->ws_qpart_floats);
+        hipLaunchKernelGGL((k_left<R, 1>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles3, err, p, ws,
+                           plan->sizes.err_stride);
     else
-        hipLaunchKernelGGL((k_left<R, 2>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles3, err, p, qpart,
-                           plan->sizes.err_stride, plan->ws_qpart_floats);
+        hipLaunchKernelGGL((k_left<R, 2>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles3, err, p, ws,
+                           plan->sizes.err_stride);
 }
 
 template <int R>
@@ -659,18 +793,29 @@ psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float
     PSGD_HIP(hipGetLastError(), "launch k_ef_right");
     PSGD_MARK(1);
 
-    hipLaunchKernelGGL(k_ortho, dim3((unsigned)plan->mats.size()), dim3(kOrthoBlock), 0, s, plan->dev.mats, ws, p,
-                       plan->workers, plan->ws_ppart_floats);
-    PSGD_HIP(hipGetLastError(), "launch k_ortho");
+    if (!plan->small_mats.empty()) {
+        hipLaunchKernelGGL(k_ortho, dim3((unsigned)plan->small_mats.size()), dim3(kOrthoBlock), 0, s, plan->dev.mats,
+                           plan->dev.small_mats, ws, p, plan->workers);
+        PSGD_HIP(hipGetLastError(), "launch k_ortho");
+    }
+    if (!plan->tiles_gram.empty()) {
+        const size_t float_bytes = (size_t)(plan->ws_ppart_floats + plan->ws_qpart_floats) * sizeof(float);
+        double* gram = reinterpret_cast<double*>(static_cast<char*>(workspace) + (float_bytes + 255) / 256 * 256);
+        hipLaunchKernelGGL(k_gram, dim3((unsigned)plan->tiles_gram.size()), dim3(kBlock), 0, s, plan->dev.mats,
+                           plan->dev.tiles_gram, ws, p, gram, plan->workers);
+        PSGD_HIP(hipGetLastError(), "launch k_gram");
+        hipLaunchKernelGGL(k_chol_apply, dim3((unsigned)plan->tiles_gram.size()), dim3(kBlock), 0, s, plan->dev.mats,
+                           plan->dev.tiles_gram, gram, p);
+        PSGD_HIP(hipGetLastError(), "launch k_chol_apply");
+    }
     PSGD_MARK(2);
 
     PSGD_RANK_SWITCH(launch_left, plan, err, p, ws, s);
     PSGD_HIP(hipGetLastError(), "launch k_left");
     PSGD_MARK(3);
 
-    float* qpart = ws + (int64_t)plan->workers * plan->ws_ppart_floats;
     hipLaunchKernelGGL(k_q_reduce, dim3((unsigned)plan->tilesq.size()), dim3(kBlock), 0, s, plan->dev.mats,
-                       plan->dev.tilesq, qpart, q, plan->workers, plan->ws_qpart_floats);
+                       plan->dev.tilesq, ws, q, plan->workers);
     PSGD_HIP(hipGetLastError(), "launch k_q_reduce");
     PSGD_MARK(4);
     return PSGD_OK;
@@ -690,8 +835,8 @@ psgd_status launch_decompress(psgd_plan* plan, const float* p, const float* q, f
     if (plan->profiling) {
         // measurement mode: wait, then add this step's per-kernel times (compress must have run first)
         PSGD_HIP(hipEventSynchronize(static_cast<hipEvent_t>(plan->events[6])), "hipEventSynchronize");
-        static const int first[PSGD_N_KERNELS] = {0, 1, 2, 3, 5};
-        for (int k = 0; k < PSGD_N_KERNELS; ++k) {
+        static const int first[5] = {0, 1, 2, 3, 5};
+        for (int k = 0; k < 5; ++k) {
             float ms = 0.f;
             hipError_t e = hipEventElapsedTime(&ms, static_cast<hipEvent_t>(plan->events[first[k]]),
                                                static_cast<hipEvent_t>(plan->events[first[k] + 1]));

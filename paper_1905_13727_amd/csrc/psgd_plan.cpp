@@ -85,34 +85,57 @@ psgd_status build_tables(psgd_plan* plan) {
         plan->tiles4.push_back(t);
     }
 
-    // workspace: [W][partial P], then [W][partial Q]; offsets are within one worker's slice
-    int64_t pp = 0, qp = 0;
+    // workspace: partial P of every matrix ([W * n_cchunk][n][r] each), then partial Q
+    // ([W * n_rblock][m][r] each), then (doubles) the Gram partials of the tall panels
+    const int64_t W = plan->workers;
+    int64_t pp = 0, qp = 0, gp = 0;
+    plan->tiles_gram.clear();
+    plan->small_mats.clear();
     for (size_t i = 0; i < nm; ++i) {
         MatDesc& d = plan->mats[i];
         d.n_cchunk = ncc[i];
         d.n_rblock = nrb[i];
         d.ppart_off = pp;
-        pp += round_up((int64_t)d.n_cchunk * d.n * d.r, kAlignElems);
+        pp += round_up(W * d.n_cchunk * d.n * d.r, kAlignElems);
+        if ((int64_t)d.n * d.r <= kPanelFloats) {
+            d.n_gblock = 0;
+            d.gram_off = 0;
+            plan->small_mats.push_back((int32_t)i);
+        } else {
+            d.n_gblock = (int32_t)ceil_div(d.n, kGramRows);
+            d.gram_off = gp;
+            gp += round_up((int64_t)d.n_gblock * d.r * d.r, 32);
+            for (int32_t b = 0; b < d.n_gblock; ++b) {
+                Tile t{};
+                t.mat = (int32_t)i;
+                t.row0 = b * kGramRows;
+                t.nrows = std::min<int32_t>(kGramRows, d.n - t.row0);
+                t.part = b;
+                plan->tiles_gram.push_back(t);
+            }
+        }
     }
     for (size_t i = 0; i < nm; ++i) {
         MatDesc& d = plan->mats[i];
-        d.qpart_off = qp;
-        qp += round_up((int64_t)d.n_rblock * d.m * d.r, kAlignElems);
+        d.qpart_off = pp + qp;
+        qp += round_up(W * d.n_rblock * d.m * d.r, kAlignElems);
     }
     plan->ws_ppart_floats = pp;
     plan->ws_qpart_floats = qp;
-    plan->sizes.workspace_bytes = std::max<int64_t>(256, (int64_t)plan->workers * (pp + qp) * (int64_t)sizeof(float));
+    plan->ws_gram_doubles = gp;
+    plan->sizes.workspace_bytes =
+        std::max<int64_t>(256, round_up((pp + qp) * (int64_t)sizeof(float), 256) + gp * (int64_t)sizeof(double));
 
-    // Q reduction: slices of each matrix's m x r panel
+    // Q reduction: slices of 64 elements of each matrix's m x r panel (4 part-slices per element in a workgroup)
     plan->tilesq.clear();
     for (size_t i = 0; i < nm; ++i) {
         const MatDesc& d = plan->mats[i];
         const int64_t total = (int64_t)d.m * d.r;
-        for (int64_t e = 0; e < total; e += tu.q_reduce_elems) {
+        for (int64_t e = 0; e < total; e += kWave) {
             Tile t{};
             t.mat = (int32_t)i;
             t.elem0 = e;
-            t.nelem = std::min<int64_t>(tu.q_reduce_elems, total - e);
+            t.nelem = std::min<int64_t>(kWave, total - e);
             plan->tilesq.push_back(t);
         }
     }

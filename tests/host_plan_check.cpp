@@ -198,15 +198,40 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
         CHECK(d.r >= 1 && d.r <= rank && d.r <= d.n && d.r <= d.m);
         CHECK(d.p_off + (int64_t)d.n * d.r <= plan->sizes.p_elems);
         CHECK(d.q_off + (int64_t)d.m * d.r <= plan->sizes.q_elems);
-        CHECK(d.ppart_off + (int64_t)d.n_cchunk * d.n * d.r <= plan->ws_ppart_floats);
-        CHECK(d.qpart_off + (int64_t)d.n_rblock * d.m * d.r <= plan->ws_qpart_floats);
+        CHECK(d.ppart_off >= 0 && d.ppart_off + (int64_t)workers * d.n_cchunk * d.n * d.r <= plan->ws_ppart_floats);
+        CHECK(d.qpart_off >= plan->ws_ppart_floats &&
+              d.qpart_off + (int64_t)workers * d.n_rblock * d.m * d.r <= plan->ws_ppart_floats + plan->ws_qpart_floats);
+        if ((int64_t)d.n * d.r > kPanelFloats) {
+            CHECK(d.n_gblock == (d.n + kGramRows - 1) / kGramRows);
+            CHECK(d.gram_off >= 0 && d.gram_off + (int64_t)d.n_gblock * d.r * d.r <= plan->ws_gram_doubles);
+        } else {
+            CHECK(d.n_gblock == 0);
+        }
     }
-    CHECK((int64_t)workers * (plan->ws_ppart_floats + plan->ws_qpart_floats) * 4 <= plan->sizes.workspace_bytes);
+    {
+        // every matrix is orthogonalised exactly once: by one workgroup (small) or by its row blocks (tall)
+        std::vector<int> small(plan->mats.size(), 0);
+        std::vector<int64_t> rows(plan->mats.size(), 0);
+        for (int32_t i : plan->small_mats) { CHECK(i >= 0 && i < (int)plan->mats.size()); small[i] += 1; }
+        for (const Tile& t : plan->tiles_gram) {
+            CHECK(t.mat >= 0 && t.mat < (int)plan->mats.size());
+            const MatDesc& d = plan->mats[t.mat];
+            CHECK(t.part >= 0 && t.part < d.n_gblock && t.row0 == rows[t.mat] && t.nrows > 0 && t.nrows <= kGramRows);
+            rows[t.mat] += t.nrows;
+        }
+        for (size_t i = 0; i < plan->mats.size(); ++i) {
+            const MatDesc& d = plan->mats[i];
+            if (d.n_gblock == 0) CHECK(small[i] == 1 && rows[i] == 0 && (int64_t)d.n * d.r <= kPanelFloats);
+            else CHECK(small[i] == 0 && rows[i] == d.n);
+        }
+    }
+    CHECK(((plan->ws_ppart_floats + plan->ws_qpart_floats) * 4 + 255) / 256 * 256 + plan->ws_gram_doubles * 8 <=
+          plan->sizes.workspace_bytes);
     CHECK(plan->sizes.grad_stride >= plan->sizes.n_mat_elems + plan->sizes.n_vec_elems);
     // Q-reduction slices cover each m x r panel exactly once
     std::vector<int64_t> covered(plan->mats.size(), 0);
     for (const Tile& t : plan->tilesq) {
-        CHECK(t.mat >= 0 && t.elem0 == covered[t.mat] && t.nelem > 0);
+        CHECK(t.mat >= 0 && t.elem0 == covered[t.mat] && t.nelem > 0 && t.nelem <= kWave);
         covered[t.mat] += t.nelem;
     }
     for (size_t i = 0; i < plan->mats.size(); ++i) CHECK(covered[i] == (int64_t)plan->mats[i].m * plan->mats[i].r);
@@ -218,7 +243,7 @@ int main() {
         {{64, 27}, {64, 576}, {64, 576}},
         {{37, 91}, {7, 1}, {50, 650}, {130, 1028}, {5, 3}, {300, 2}, {1, 40}, {1031, 1}, {3, 4700}, {257, 260}},
         {{512, 4608}, {10, 512}, {128, 64}, {9610, 1}},
-        {{2600, 650}, {3328, 650}},
+        {{2600, 650}, {3328, 650}, {33280, 650}, {5000, 3}},
         {{1, 2}, {2, 1}},
         {{37, 91}, {7, 1}, {50, 650}, {130, 1028}, {5, 3}, {300, 2}, {1, 40}, {1031, 1}, {3, 4700}, {257, 260},
          {512, 36}, {64, 27}},

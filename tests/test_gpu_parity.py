@@ -116,6 +116,41 @@ def test_ragged_shapes_three_workers(rank):
     _run(_workload(shapes), rank=rank, workers=3, steps=4, seed=rank)
 
 
+@pytest.mark.parametrize("rank,workers", [(1, 1), (3, 2), (4, 1), (8, 2)])
+def test_tall_panels(rank, workers):
+    """Panels too tall for one workgroup's LDS take the multi-workgroup Cholesky-QR route (same
+    orthonormal factor as Gram-Schmidt): ragged last row block, several Gram blocks, W = 1 and 2,
+    and an all-zero gradient on the same plan shape."""
+    _need_gpu()
+    from gpu_harness import GpuRun
+    shapes = [(7000, 36), (33,), (13001, 6), (2600, 650), (64, 64)]
+    wl = _workload(shapes)
+    _run(wl, rank=rank, workers=workers, steps=3, seed=40 + rank, expect_resident=False)
+    from paper_1905_13727_amd import workloads as WL
+    g = GpuRun(shapes, rank, workers, WL.initial_q(wl, rank, 1))
+    r = g.step([[np.zeros(s, dtype=np.float32) for s in shapes] for _ in range(workers)])
+    for t, s in enumerate(shapes):
+        if len(s) == 2:
+            assert np.abs(r["P_hat"][t]).max() == 0 and np.abs(r["Q"][t]).max() == 0
+            assert np.abs(r["err"][0][t]).max() == 0 and np.abs(r["out"][t]).max() == 0
+
+
+def test_lstm_r4_10_steps():
+    """LSTM-shaped set (tied embedding with 5 % of the rows non-zero per step), rank 4."""
+    _need_gpu()
+    from paper_1905_13727_amd import workloads as WL
+    _run(WL.lstm(), rank=4, workers=1, steps=10, seed=0, resync=RESYNC, expect_resident=False)
+
+
+def test_resnet18_16_workers():
+    """ResNet18-shaped set with 16 simulated workers, ranks 1, 2, 4 (a few steps each: the oracle
+    needs 16 times the single-worker time)."""
+    _need_gpu()
+    from paper_1905_13727_amd import workloads as WL
+    for rank in (1, 2, 4):
+        _run(WL.resnet18(), rank=rank, workers=16, steps=2, seed=rank, expect_resident=False)
+
+
 def test_small_tiles_many_partials():
     """Forces many column chunks and row blocks per matrix so that the fixed-order partial
     sums are exercised."""
