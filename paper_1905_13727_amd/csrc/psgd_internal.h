@@ -15,12 +15,15 @@ constexpr int kWave = 64;          // gfx950 wavefront
 constexpr int kBlock = 256;        // threads per workgroup in the streaming kernels (4 waves)
 constexpr int kWavesPerBlock = kBlock / kWave;
 constexpr int kAlignElems = 64;    // every matrix starts on a multiple of this many elements
-constexpr int kMaxVecPerLaneK1 = 4;  // column vectors a lane owns per row in the P = M Q kernel
+constexpr int kMaxVecPerLaneK1 = 2;  // column vectors a lane owns per row in the P = M Q kernel
 constexpr int kMaxVecPerLaneK3 = 2;  // column vectors a lane owns in the Q = M^T P and decompress kernels
 constexpr int kOrthoBlock = 256;   // threads of the single-workgroup Gram-Schmidt kernel
 constexpr int kValuMaxRank = 8;    // ranks up to this run on the vector-ALU kernels
 constexpr int kPanelFloats = 12288;  // n*r up to this: Gram-Schmidt by one workgroup with the panel in LDS (48 KB)
-constexpr int kGramRows = 256;     // rows per workgroup of the tall-panel Gram / apply kernels
+constexpr int kGramRows = 1024;    // rows per workgroup of the tall-panel Gram / apply kernels
+constexpr int kPreReduceParts = 16; // more partial-P slices than this: a reduction kernel runs before the orthogonalisation
+constexpr int kOrthoMaxRows = 1024; // panels with more rows take the multi-workgroup route
+constexpr int kMfmaCols = 128;     // super-row columns a wavefront covers per 16-row step in the matrix-core P = M Q kernel
 
 // One matrix of the model.
 struct MatDesc {
@@ -36,6 +39,8 @@ struct MatDesc {
     int32_t n_rblock;   // row blocks of the Q = M^T P kernel (partials to sum)
     int32_t tensor;     // index in the caller's shape list
     int32_t n_gblock;   // tall panels: row blocks of the Gram / apply kernels; 0 = panel fits one workgroup's LDS
+    int32_t pack;       // rows fused into one "super-row" so that its length pack*m is a multiple of 4 (1, 2 or 4)
+    int32_t pad_;
 };
 
 // One workgroup's share of a streaming kernel.
@@ -80,12 +85,13 @@ struct RTile {
 
 struct Tuning {
     int64_t k1_rows = 32;   // rows per workgroup tile, P = M Q
-    int64_t k1_nv = 4;      // column vectors per lane (<= kMaxVecPerLaneK1)
+    int64_t k1_nv = 2;      // column vectors per lane (<= kMaxVecPerLaneK1)
     int64_t k3_rows = 128;  // rows per workgroup tile, Q = M^T P
     int64_t k3_nv = 1;      // column vectors per lane (<= kMaxVecPerLaneK3)
     int64_t k4_rows = 64;   // rows per workgroup tile, decompress + residual
     int64_t k4_nv = 1;
     int64_t q_reduce_elems = 1024;  // elements per workgroup in the Q reduction
+    int64_t k1_mfma = 0;    // 1: P = M Q on the matrix cores when pack * rank <= 16 for every matrix (slower for now)
     int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream
     int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height
     int64_t res_trace = 0;  // 1: the resident kernel records phase timestamps (diagnostic)
@@ -98,6 +104,7 @@ struct DeviceTables {
     Tile* tiles4 = nullptr;
     Tile* tilesq = nullptr;
     Tile* tiles_gram = nullptr;
+    Tile* tilesp = nullptr;
     int32_t* small_mats = nullptr;
     MatDesc* res_mats = nullptr;
     RTile* res_tiles = nullptr;
@@ -123,6 +130,9 @@ struct psgd_plan {
     std::vector<psgd::Tile> tiles_gram;     // row blocks of tall panels (Cholesky-QR)
     std::vector<int32_t> small_mats;        // matrices orthogonalised by one workgroup (Gram-Schmidt in LDS)
     int64_t ws_gram_doubles = 0;            // workspace: Gram partials, after the float regions
+    bool k1_on_mfma = false;                // tiles1 are laid out for the matrix-core kernel
+    std::vector<psgd::Tile> tilesp;         // 64-element slices of the n x r panels (pre-reduction of partial P)
+    bool p_pre_reduce = false;              // some matrix has more than kPreReduceParts partial-P slices
     int32_t max_n = 0;
     int64_t ws_ppart_floats = 0;            // workspace: partial P region (floats)
     int64_t ws_qpart_floats = 0;            // workspace: partial Q region, starts after partial P

@@ -33,11 +33,13 @@ namespace psgd {
 // loads, writes M over e, and the wavefront reduces R dot products per row.  Partial sums
 // of different column chunks / workers go to separate slices of the workspace.
 
-template <int R, int V>
+template <int R, int V, int NV>
 __device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, const float* __restrict__ g,
                                               float* __restrict__ e, const float* __restrict__ q,
                                               float* __restrict__ ppart) {
-    constexpr int NV = kMaxVecPerLaneK1;
+    // rows per step: all their loads are in flight together; RS * R results fit the 64 lanes
+    constexpr int RS = (16 / NV) * R <= kWave ? 16 / NV : 8;
+    static_assert(RS * R <= kWave, "one lane per (row, rank) result of a step");
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int ri = d.r;
@@ -60,64 +62,56 @@ __device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, c
     int rb, rn;
     wave_rows(t.nrows, wave, &rb, &rn);
     const int i_begin = t.row0 + rb, i_end = i_begin + rn;
-    for (int i = i_begin; i < i_end; i += 2) {
-        const bool two = (i + 1) < i_end;
-        const int64_t row_a = d.off + (int64_t)i * d.m;
-        const int64_t row_b = row_a + d.m;
-        float ga[NV][V], ea[NV][V], gb[NV][V], eb[NV][V];
+    for (int i0 = i_begin; i0 < i_end; i0 += RS) {
+        const int rows = min(RS, i_end - i0);
+        float mv[RS][NV][V];
+        // every load of the step is issued before anything is used
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            if (valid[v]) {
-                ldv_stream<V>(g + row_a + col[v], ga[v]);
-                ldv<V>(e + row_a + col[v], ea[v]);
-                if (two) {
-                    ldv_stream<V>(g + row_b + col[v], gb[v]);
-                    ldv<V>(e + row_b + col[v], eb[v]);
+        for (int i = 0; i < RS; ++i)
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                if (i < rows && valid[v]) {
+                    ldv_stream<V>(g + d.off + (int64_t)(i0 + i) * d.m + col[v], mv[i][v]);
+                } else {
+#pragma unroll
+                    for (int x = 0; x < V; ++x) mv[i][v][x] = 0.f;
+                }
+            }
+#pragma unroll
+        for (int i = 0; i < RS; ++i)
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+                if (i < rows && valid[v]) {
+                    float ev[V];
+                    ldv<V>(e + d.off + (int64_t)(i0 + i) * d.m + col[v], ev);
+#pragma unroll
+                    for (int x = 0; x < V; ++x) mv[i][v][x] += ev[x];
+                    stv<V>(e + d.off + (int64_t)(i0 + i) * d.m + col[v], mv[i][v]);
+                }
+        // RS * R dot products, reduced over the wavefront; lane i * R + k keeps the result of (row i, rank k)
+        float mine = 0.f;
+#pragma unroll
+        for (int i = 0; i < RS; ++i) {
+            if (i < rows) {
+#pragma unroll
+                for (int k = 0; k < R; ++k) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int v = 0; v < NV; ++v)
+#pragma unroll
+                        for (int x = 0; x < V; ++x) s = fmaf(mv[i][v][x], qr[v][x][k], s);
+                    s = wave_sum(s);
+                    if (lane == i * R + k) mine = s;
                 }
             }
         }
-        float acc_a[R], acc_b[R];
-#pragma unroll
-        for (int k = 0; k < R; ++k) acc_a[k] = acc_b[k] = 0.f;
-#pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            if (valid[v]) {
-                float ma[V];
-#pragma unroll
-                for (int x = 0; x < V; ++x) {
-                    ma[x] = ga[v][x] + ea[v][x];
-#pragma unroll
-                    for (int k = 0; k < R; ++k) acc_a[k] = fmaf(ma[x], qr[v][x][k], acc_a[k]);
-                }
-                stv<V>(e + row_a + col[v], ma);
-                if (two) {
-                    float mb[V];
-#pragma unroll
-                    for (int x = 0; x < V; ++x) {
-                        mb[x] = gb[v][x] + eb[v][x];
-#pragma unroll
-                        for (int k = 0; k < R; ++k) acc_b[k] = fmaf(mb[x], qr[v][x][k], acc_b[k]);
-                    }
-                    stv<V>(e + row_b + col[v], mb);
-                }
-            }
-        }
-        float out_a = 0.f, out_b = 0.f;
-#pragma unroll
-        for (int k = 0; k < R; ++k) {
-            const float sa = wave_sum(acc_a[k]);
-            const float sb = wave_sum(acc_b[k]);
-            if (lane == k) { out_a = sa; out_b = sb; }
-        }
-        if (lane < ri) {
-            float* dst = ppart + d.ppart_off + ((int64_t)t.part * d.n + i) * ri + lane;
-            dst[0] = out_a;
-            if (two) dst[ri] = out_b;
-        }
+        const int li = lane / R, lk = lane % R;
+        if (li < rows && lk < ri)
+            ppart[d.ppart_off + ((int64_t)t.part * d.n + i0 + li) * ri + lk] = mine;
     }
 }
 
-template <int R>
+template <int R, int NV>
 __global__ __launch_bounds__(kBlock) void k_ef_right(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                      const float* __restrict__ grad, float* __restrict__ err,
                                                      const float* __restrict__ q, float* __restrict__ ws,
@@ -127,21 +121,115 @@ __global__ __launch_bounds__(kBlock) void k_ef_right(const MatDesc* __restrict__
     const int w = blockIdx.y;
     const float* g = grad + (int64_t)w * gstride;
     float* e = err + (int64_t)w * estride;
-    float* pp = ws;
     t.part += w * d.n_cchunk;   // partial slices: [worker][column chunk]
-    if (d.vec == 4) ef_right_tile<R, 4>(t, d, g, e, q, pp);
-    else if (d.vec == 2) ef_right_tile<R, 2>(t, d, g, e, q, pp);
-    else ef_right_tile<R, 1>(t, d, g, e, q, pp);
+    if (d.vec == 4) ef_right_tile<R, 4, NV>(t, d, g, e, q, ws);
+    else if (d.vec == 2) ef_right_tile<R, 2, NV>(t, d, g, e, q, ws);
+    else ef_right_tile<R, 1, NV>(t, d, g, e, q, ws);
 }
 
-// ---- k_ortho: P_bar = mean of the partials, then modified Gram-Schmidt ----------------------------
+// ---- k_ef_right_mfma: the same on the matrix cores -------------------------------------------------
 //
-// One workgroup per matrix.  The n x r panel lives in LDS when it fits, else in the P
-// buffer itself.  Round j reduces, over all rows, the squared norm of column j and its dot
-// products with the columns to its right (fp64 accumulation of fp32 data, wavefront
-// reduction then a fixed-order sum over the 4 wavefronts), then normalises column j and
-// removes its component from the others.  A column whose squared norm is <= 1e-30 when its
-// turn comes is set to zero.
+// P = M Q is a product with a tiny inner shape (n x m times m x r, r <= 16): written for the vector
+// ALUs, most instructions are the cross-lane sums of the row dot products.  v_mfma_f32_16x16x4_f32
+// does the multiply and the sum over columns in one instruction: A = a 16 x 4 block of M (lane l
+// supplies row l % 16, column 4 (l / 16) + c of a 16-column group, taken from the c-th component
+// of one 16-byte load), B = the matching 4 x 16 block of Q, padded with zeros beyond the rank.
+// fp32 in, fp32 accumulate.  Rows whose length is not a multiple of 4 are fused in pairs / fours
+// into "super-rows" of length pack * m (a multiple of 4, so every 16-byte load is aligned); the rank
+// axis then carries one block of r outputs per fused row: B'[c'][s r + j] = Q[c' - s m][j] for
+// columns c' of sub-row s, so that a load that straddles two rows feeds both dot products.
+//
+// A wavefront walks a strip of super-rows 16 at a time over a chunk of kMfmaCols columns, keeping
+// the B blocks of the chunk in registers; M = g + e is written back as it goes.
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(kBlock) void k_ef_right_mfma(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
+                                                          const float* __restrict__ grad, float* __restrict__ err,
+                                                          const float* __restrict__ q, float* __restrict__ ws,
+                                                          int64_t gstride, int64_t estride) {
+    constexpr int NG = kMfmaCols / 16;   // 16-column groups per chunk
+    const Tile t = tiles[blockIdx.x];
+    const MatDesc d = mats[t.mat];
+    const int w = blockIdx.y;
+    const float* g = grad + (int64_t)w * gstride + d.off;
+    float* e = err + (int64_t)w * estride + d.off;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int ri = d.r, pack = d.pack, m = d.m, n = d.n;
+    const int sm = pack * m;                       // super-row length
+    const int li = lane & 15, kb = lane >> 4;
+    const int c_end = t.vec0 + t.nvec;             // first column after the chunk
+
+    // B blocks of the chunk: lane holds, for group u and component c, B'[col'][j] with
+    // col' = vec0 + 16 u + 4 kb + c and j = li
+    float bq[NG][4];
+    {
+        const int s_j = li / ri, jj = li % ri;     // fused-row block and rank index of this lane's output column
+#pragma unroll
+        for (int u = 0; u < NG; ++u)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int colp = t.vec0 + 16 * u + 4 * kb + c;
+                float v = 0.f;
+                if (colp < c_end && s_j < pack) {
+                    const int s = colp / m, col = colp - s * m;
+                    if (s == s_j) v = q[d.q_off + (int64_t)col * ri + jj];
+                }
+                bq[u][c] = v;
+            }
+    }
+
+    // the four wavefronts take 16-row steps of the tile's super-rows in turn
+    const int nsteps = (t.nrows + 15) / 16;
+    for (int step = wave; step < nsteps; step += kWavesPerBlock) {
+        const int srow = t.row0 + 16 * step + li;                  // this lane's super-row
+        const int rows_here = min(pack, n - pack * srow);          // real rows in it (<= 0: none)
+        const int valid_len = rows_here > 0 ? rows_here * m : 0;   // valid prefix of the super-row
+        const int64_t base = (int64_t)srow * sm;
+        v4f gv[NG], ev[NG];
+#pragma unroll
+        for (int u = 0; u < NG; ++u) {
+            const int colp = t.vec0 + 16 * u + 4 * kb;
+            gv[u] = v4f{0.f, 0.f, 0.f, 0.f};
+            ev[u] = v4f{0.f, 0.f, 0.f, 0.f};
+            if (colp < c_end && colp < valid_len) {
+                gv[u] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(g + base + colp));
+                ev[u] = *reinterpret_cast<const v4f*>(e + base + colp);
+            }
+        }
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < NG; ++u) {
+            const int colp = t.vec0 + 16 * u + 4 * kb;
+            v4f mv = gv[u] + ev[u];
+            if (colp < c_end && colp < valid_len) {
+                if (colp + 4 <= valid_len) {
+                    *reinterpret_cast<v4f*>(e + base + colp) = mv;
+                } else {
+                    // the last real row ends inside this vector: what follows is not part of the matrix
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        if (colp + c < valid_len) e[base + colp + c] = mv[c];
+                        else mv[c] = 0.f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(mv[c], bq[u][c], acc, 0, 0, 0);
+        }
+        // acc[v] = P'[super-row 16 step + 4 kb + v][li]: fused row li / ri, rank li % ri
+        const int s_j = li / ri, jj = li % ri;
+        if (s_j < pack) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = pack * (t.row0 + 16 * step + 4 * kb + v) + s_j;
+                if (16 * step + 4 * kb + v < t.nrows && row < n)
+                    ws[d.ppart_off + ((int64_t)(w * d.n_cchunk + t.part) * n + row) * ri + jj] = acc[v];
+            }
+        }
+    }
+}
 
 // sum of `nparts` partial slices (stride `stride` floats) at `src`, in slice order, eight loads in flight
 __device__ __forceinline__ float sum_parts(const float* __restrict__ src, int nparts, int64_t stride) {
@@ -159,7 +247,8 @@ __device__ __forceinline__ float sum_parts(const float* __restrict__ src, int np
 }
 
 __global__ __launch_bounds__(kOrthoBlock) void k_ortho(const MatDesc* __restrict__ mats, const int32_t* __restrict__ which,
-                                                       const float* __restrict__ ws, float* __restrict__ p, int workers) {
+                                                       const float* __restrict__ ws, float* __restrict__ p, int workers,
+                                                       int pre_reduced) {
     __shared__ float panel[kPanelFloats];
     __shared__ double red[kOrthoBlock / kWave][kValuMaxRank];
     const MatDesc d = mats[which[blockIdx.x]];
@@ -168,9 +257,27 @@ __global__ __launch_bounds__(kOrthoBlock) void k_ortho(const MatDesc* __restrict
     const int64_t nr = (int64_t)n * r;    // <= kPanelFloats (planner)
     float* P = panel;
     const float inv_w = 1.0f / (float)workers;
-    const int nparts = workers * d.n_cchunk;
+    const int nparts = pre_reduced ? 1 : workers * d.n_cchunk;
 
-    for (int64_t idx = tid; idx < nr; idx += kOrthoBlock) P[idx] = sum_parts(ws + d.ppart_off + idx, nparts, nr) * inv_w;
+    // mean over workers / column chunks: four panel elements per thread in flight
+    for (int64_t base = tid; base < nr; base += 4 * kOrthoBlock) {
+        float s[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < nparts; ++c) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t idx = base + (int64_t)u * kOrthoBlock;
+                v[u] = idx < nr ? ws[d.ppart_off + (int64_t)c * nr + idx] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) s[u] += v[u];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t idx = base + (int64_t)u * kOrthoBlock;
+            if (idx < nr) P[idx] = s[u] * inv_w;
+        }
+    }
     __syncthreads();
 
     for (int j = 0; j < r; ++j) {
@@ -238,14 +345,14 @@ __global__ __launch_bounds__(kOrthoBlock) void k_ortho(const MatDesc* __restrict
 
 __global__ __launch_bounds__(kBlock) void k_gram(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                  const float* __restrict__ ws, float* __restrict__ p,
-                                                 double* __restrict__ gram, int workers) {
+                                                 double* __restrict__ gram, int workers, int pre_reduced) {
     __shared__ double red[kWavesPerBlock][kValuMaxRank * kValuMaxRank];
     const Tile t = tiles[blockIdx.x];
     const MatDesc d = mats[t.mat];
     const int r = d.r, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     const int64_t nr = (int64_t)d.n * r;
     const float inv_w = 1.0f / (float)workers;
-    const int nparts = workers * d.n_cchunk;
+    const int nparts = pre_reduced ? 1 : workers * d.n_cchunk;
     double g[kValuMaxRank][kValuMaxRank];
 #pragma unroll
     for (int a = 0; a < kValuMaxRank; ++a)
@@ -297,8 +404,18 @@ __global__ __launch_bounds__(kBlock) void k_chol_apply(const MatDesc* __restrict
     if (lane < r * r) {
         const int per = (d.n_gblock + kWavesPerBlock - 1) / kWavesPerBlock;
         const int b0 = wave * per, b1 = min(d.n_gblock, b0 + per);
+        const double* src = gram + d.gram_off + lane;
+        const int64_t stride = (int64_t)r * r;
         double v = 0.0;
-        for (int b = b0; b < b1; ++b) v += gram[d.gram_off + (int64_t)b * r * r + lane];
+        int b = b0;
+        for (; b + 8 <= b1; b += 8) {   // eight loads in flight, added in block order
+            double x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) x[u] = src[(int64_t)(b + u) * stride];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v += x[u];
+        }
+        for (; b < b1; ++b) v += src[(int64_t)b * stride];
         part[wave][lane] = v;
     }
     __syncthreads();
@@ -469,24 +586,30 @@ __global__ __launch_bounds__(kBlock) void k_left(const MatDesc* __restrict__ mat
 
 // ---- k_q_reduce: Q = (1/W) sum over workers and row blocks of the partials ------------------------
 
+// 64 elements per workgroup; wavefront g adds slice g of the partials (slice order), then the four slices
+// are added in slice order.  for_p = 0: partial Q -> Q (mean over workers).  for_p = 1: partial P -> first
+// partial slice (plain sum; used when there are many slices, so that the orthogonalisation reads one).
 __global__ __launch_bounds__(kBlock) void k_q_reduce(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
-                                                     const float* __restrict__ ws, float* __restrict__ q, int workers) {
-    // 64 elements per workgroup; wavefront g adds slice g of the partials (slice order), then the four
-    // slices are added in slice order
+                                                     float* __restrict__ ws, float* __restrict__ q, int workers,
+                                                     int for_p) {
     __shared__ float part[kWavesPerBlock][kWave];
     const Tile t = tiles[blockIdx.x];
     const MatDesc d = mats[t.mat];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int64_t mr = (int64_t)d.m * d.r;
-    const int nparts = workers * d.n_rblock;
+    const int64_t stride = for_p ? (int64_t)d.n * d.r : (int64_t)d.m * d.r;
+    const int nparts = workers * (for_p ? d.n_cchunk : d.n_rblock);
+    float* src = ws + (for_p ? d.ppart_off : d.qpart_off);
     const int per = (nparts + kWavesPerBlock - 1) / kWavesPerBlock;
     const int b0 = min(nparts, wave * per), b1 = min(nparts, b0 + per);
     float s = 0.f;
-    if (lane < t.nelem) s = sum_parts(ws + d.qpart_off + (int64_t)b0 * mr + t.elem0 + lane, b1 - b0, mr);
+    if (lane < t.nelem) s = sum_parts(src + (int64_t)b0 * stride + t.elem0 + lane, b1 - b0, stride);
     part[wave][lane] = s;
-    __syncthreads();
-    if (wave == 0 && lane < t.nelem)
-        q[d.q_off + t.elem0 + lane] = (((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane]) * (1.0f / (float)workers);
+    __syncthreads();   // every slice of these 64 elements has been read before slice 0 is overwritten
+    if (wave == 0 && lane < t.nelem) {
+        const float v = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
+        if (for_p) src[t.elem0 + lane] = v;
+        else q[d.q_off + t.elem0 + lane] = v * (1.0f / (float)workers);
+    }
 }
 
 // ---- k_decomp: Delta' = P_hat Q^T, e_w = M_w - Delta', vectors averaged ---------------------------
@@ -639,7 +762,7 @@ psgd_status upload_tables(psgd_plan* plan) {
         if (st != PSGD_OK) return st;
     }
     struct Piece { const void* src; size_t bytes; size_t at; };
-    Piece pieces[12] = {
+    Piece pieces[13] = {
         {plan->mats.data(), plan->mats.size() * sizeof(MatDesc), 0},
         {plan->tiles1.data(), plan->tiles1.size() * sizeof(Tile), 0},
         {plan->tiles3.data(), plan->tiles3.size() * sizeof(Tile), 0},
@@ -652,6 +775,7 @@ psgd_status upload_tables(psgd_plan* plan) {
         {nullptr, (size_t)plan->res_mail_slots * sizeof(unsigned long long), 0},   // zero-filled: tag 0 never matches
         {plan->tiles_gram.data(), plan->tiles_gram.size() * sizeof(Tile), 0},
         {plan->small_mats.data(), plan->small_mats.size() * sizeof(int32_t), 0},
+        {plan->tilesp.data(), plan->tilesp.size() * sizeof(Tile), 0},
     };
     size_t total = 0;
     for (Piece& pc : pieces) {
@@ -687,6 +811,7 @@ psgd_status upload_tables(psgd_plan* plan) {
     plan->dev.res_mail = reinterpret_cast<unsigned long long*>(b + pieces[9].at);
     plan->dev.tiles_gram = reinterpret_cast<Tile*>(b + pieces[10].at);
     plan->dev.small_mats = reinterpret_cast<int32_t*>(b + pieces[11].at);
+    plan->dev.tilesp = reinterpret_cast<Tile*>(b + pieces[12].at);
     plan->uploaded = true;
     return PSGD_OK;
 }
@@ -728,8 +853,12 @@ template <int R>
 static void launch_ef_right(psgd_plan* plan, const float* grad, float* err, const float* q, float* ws,
                             hipStream_t s) {
     dim3 grid((unsigned)plan->tiles1.size(), (unsigned)plan->workers);
-    hipLaunchKernelGGL((k_ef_right<R>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles1, grad, err, q, ws,
-                       plan->sizes.grad_stride, plan->sizes.err_stride);
+    if (plan->tuning.k1_nv == 1)
+        hipLaunchKernelGGL((k_ef_right<R, 1>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles1, grad, err, q,
+                           ws, plan->sizes.grad_stride, plan->sizes.err_stride);
+    else
+        hipLaunchKernelGGL((k_ef_right<R, 2>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles1, grad, err, q,
+                           ws, plan->sizes.grad_stride, plan->sizes.err_stride);
 }
 
 template <int R>
@@ -789,20 +918,32 @@ psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float
     if (plan->mats.empty()) return PSGD_OK;
 
     PSGD_MARK(0);
-    PSGD_RANK_SWITCH(launch_ef_right, plan, g, err, q, ws, s);
+    if (plan->k1_on_mfma) {
+        hipLaunchKernelGGL(k_ef_right_mfma, dim3((unsigned)plan->tiles1.size(), (unsigned)plan->workers), dim3(kBlock), 0, s,
+                           plan->dev.mats, plan->dev.tiles1, g, err, q, ws, plan->sizes.grad_stride,
+                           plan->sizes.err_stride);
+    } else {
+        PSGD_RANK_SWITCH(launch_ef_right, plan, g, err, q, ws, s);
+    }
     PSGD_HIP(hipGetLastError(), "launch k_ef_right");
     PSGD_MARK(1);
 
+    const int pre_reduced = plan->p_pre_reduce ? 1 : 0;
+    if (pre_reduced) {
+        hipLaunchKernelGGL(k_q_reduce, dim3((unsigned)plan->tilesp.size()), dim3(kBlock), 0, s, plan->dev.mats,
+                           plan->dev.tilesp, ws, static_cast<float*>(nullptr), plan->workers, 1);
+        PSGD_HIP(hipGetLastError(), "launch k_q_reduce (partial P)");
+    }
     if (!plan->small_mats.empty()) {
         hipLaunchKernelGGL(k_ortho, dim3((unsigned)plan->small_mats.size()), dim3(kOrthoBlock), 0, s, plan->dev.mats,
-                           plan->dev.small_mats, ws, p, plan->workers);
+                           plan->dev.small_mats, ws, p, plan->workers, pre_reduced);
         PSGD_HIP(hipGetLastError(), "launch k_ortho");
     }
     if (!plan->tiles_gram.empty()) {
         const size_t float_bytes = (size_t)(plan->ws_ppart_floats + plan->ws_qpart_floats) * sizeof(float);
         double* gram = reinterpret_cast<double*>(static_cast<char*>(workspace) + (float_bytes + 255) / 256 * 256);
         hipLaunchKernelGGL(k_gram, dim3((unsigned)plan->tiles_gram.size()), dim3(kBlock), 0, s, plan->dev.mats,
-                           plan->dev.tiles_gram, ws, p, gram, plan->workers);
+                           plan->dev.tiles_gram, ws, p, gram, plan->workers, pre_reduced);
         PSGD_HIP(hipGetLastError(), "launch k_gram");
         hipLaunchKernelGGL(k_chol_apply, dim3((unsigned)plan->tiles_gram.size()), dim3(kBlock), 0, s, plan->dev.mats,
                            plan->dev.tiles_gram, gram, p);
@@ -815,7 +956,7 @@ psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float
     PSGD_MARK(3);
 
     hipLaunchKernelGGL(k_q_reduce, dim3((unsigned)plan->tilesq.size()), dim3(kBlock), 0, s, plan->dev.mats,
-                       plan->dev.tilesq, ws, q, plan->workers);
+                       plan->dev.tilesq, ws, q, plan->workers, 0);
     PSGD_HIP(hipGetLastError(), "launch k_q_reduce");
     PSGD_MARK(4);
     return PSGD_OK;

@@ -70,7 +70,34 @@ psgd_status build_tables(psgd_plan* plan) {
         return PSGD_EINVAL;
     const size_t nm = plan->mats.size();
     std::vector<int32_t> nrb(nm, 0), ncc(nm, 0);
-    streaming_tiles(plan, tu.k1_rows, tu.k1_nv, true, &plan->tiles1, nullptr, &ncc);
+    // P = M Q: matrix-core tiling (16-row steps of super-rows x kMfmaCols columns per wavefront) when every
+    // matrix fits pack * rank <= 16, else the vector-ALU tiling
+    plan->k1_on_mfma = tu.k1_mfma != 0;
+    for (const MatDesc& d : plan->mats)
+        if (d.pack * d.r > 16) plan->k1_on_mfma = false;
+    if (plan->k1_on_mfma) {
+        plan->tiles1.clear();
+        const int64_t rows_per_tile = round_up(std::max<int64_t>(tu.k1_rows, 16), 16);   // super-rows per workgroup
+        for (size_t i = 0; i < nm; ++i) {
+            const MatDesc& d = plan->mats[i];
+            const int64_t sm = (int64_t)d.pack * d.m, sn = ceil_div(d.n, d.pack);
+            const int64_t nchunk = ceil_div(sm, kMfmaCols);
+            ncc[i] = (int32_t)nchunk;
+            for (int64_t r0 = 0; r0 < sn; r0 += rows_per_tile)
+                for (int64_t c = 0; c < nchunk; ++c) {
+                    Tile t{};
+                    t.mat = (int32_t)i;
+                    t.row0 = (int32_t)r0;                                        // first super-row
+                    t.nrows = (int32_t)std::min<int64_t>(rows_per_tile, sn - r0); // super-rows
+                    t.vec0 = (int32_t)(c * kMfmaCols);                           // first super-row column
+                    t.nvec = (int32_t)std::min<int64_t>(kMfmaCols, sm - c * kMfmaCols);   // columns
+                    t.part = (int32_t)c;
+                    plan->tiles1.push_back(t);
+                }
+        }
+    } else {
+        streaming_tiles(plan, tu.k1_rows, tu.k1_nv, true, &plan->tiles1, nullptr, &ncc);
+    }
     streaming_tiles(plan, tu.k3_rows, tu.k3_nv, false, &plan->tiles3, &nrb, nullptr);
     streaming_tiles(plan, tu.k4_rows, tu.k4_nv, false, &plan->tiles4, nullptr, nullptr);
 
@@ -97,7 +124,7 @@ psgd_status build_tables(psgd_plan* plan) {
         d.n_rblock = nrb[i];
         d.ppart_off = pp;
         pp += round_up(W * d.n_cchunk * d.n * d.r, kAlignElems);
-        if ((int64_t)d.n * d.r <= kPanelFloats) {
+        if ((int64_t)d.n * d.r <= kPanelFloats && d.n <= kOrthoMaxRows) {
             d.n_gblock = 0;
             d.gram_off = 0;
             plan->small_mats.push_back((int32_t)i);
@@ -126,6 +153,21 @@ psgd_status build_tables(psgd_plan* plan) {
     plan->sizes.workspace_bytes =
         std::max<int64_t>(256, round_up((pp + qp) * (int64_t)sizeof(float), 256) + gp * (int64_t)sizeof(double));
 
+    // the same slicing of the n x r panels, used when a matrix has many partial-P slices
+    plan->tilesp.clear();
+    plan->p_pre_reduce = false;
+    for (size_t i = 0; i < nm; ++i) {
+        const MatDesc& d = plan->mats[i];
+        if (W * d.n_cchunk > kPreReduceParts) plan->p_pre_reduce = true;
+        const int64_t total = (int64_t)d.n * d.r;
+        for (int64_t e = 0; e < total; e += kWave) {
+            Tile t{};
+            t.mat = (int32_t)i;
+            t.elem0 = e;
+            t.nelem = std::min<int64_t>(kWave, total - e);
+            plan->tilesp.push_back(t);
+        }
+    }
     // Q reduction: slices of 64 elements of each matrix's m x r panel (4 part-slices per element in a workgroup)
     plan->tilesq.clear();
     for (size_t i = 0; i < nm; ++i) {
@@ -333,6 +375,7 @@ psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_
             d.m = (int32_t)shapes[t].cols;
             d.r = std::min<int32_t>(rank, std::min(d.n, d.m));
             d.vec = (d.m % 4 == 0) ? 4 : (d.m % 2 == 0 ? 2 : 1);
+            d.pack = 4 / d.vec;
             d.off = N;
             d.p_off = P;
             d.q_off = Q;
@@ -425,6 +468,7 @@ psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value
     else if (!strcmp(key, "k4_rows")) tu.k4_rows = value;
     else if (!strcmp(key, "k4_nv")) tu.k4_nv = value;
     else if (!strcmp(key, "q_reduce_elems")) tu.q_reduce_elems = value;
+    else if (!strcmp(key, "k1_mfma")) tu.k1_mfma = value;
     else if (!strcmp(key, "resident")) tu.resident = value;
     else if (!strcmp(key, "res_rows")) tu.res_rows = value;
     else if (!strcmp(key, "res_trace")) tu.res_trace = value;

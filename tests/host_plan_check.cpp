@@ -168,6 +168,40 @@ static void check_resident(const psgd_plan* plan) {
     }
 }
 
+static void check_p_tiling(const psgd_plan* plan) {
+    if (plan->k1_on_mfma) {
+        // matrix-core tiling of P = M Q: tiles are (super-rows x super-row columns); every element once
+        std::vector<std::vector<unsigned char>> seen(plan->mats.size());
+        for (size_t i = 0; i < plan->mats.size(); ++i) seen[i].assign((size_t)plan->mats[i].n * plan->mats[i].m, 0);
+        for (const Tile& t : plan->tiles1) {
+            CHECK(t.mat >= 0 && t.mat < (int)plan->mats.size());
+            const MatDesc& d = plan->mats[t.mat];
+            const int64_t sm = (int64_t)d.pack * d.m, sn = (d.n + d.pack - 1) / d.pack;
+            CHECK(d.pack * d.r <= 16 && sm % 4 == 0 && d.off % 4 == 0);
+            CHECK(t.row0 >= 0 && t.nrows > 0 && t.row0 + t.nrows <= sn && t.row0 % 16 == 0);
+            CHECK(t.vec0 >= 0 && t.vec0 % kMfmaCols == 0 && t.nvec > 0 && t.nvec <= kMfmaCols && t.vec0 + t.nvec <= sm);
+            CHECK(t.part >= 0 && t.part < d.n_cchunk && t.part == t.vec0 / kMfmaCols);
+            for (int64_t I = t.row0; I < t.row0 + t.nrows; ++I)
+                for (int64_t c = t.vec0; c < t.vec0 + t.nvec; ++c) {
+                    const int64_t row = I * d.pack + c / d.m, col = c % d.m;
+                    if (row >= d.n) continue;
+                    unsigned char& sf = seen[t.mat][(size_t)row * d.m + col];
+                    CHECK(sf == 0);
+                    sf = 1;
+                }
+        }
+        for (auto& v : seen)
+            for (unsigned char sf : v) CHECK(sf == 1);
+        // a 16-byte load that starts on a valid element ends inside the matrix's padded extent
+        for (const MatDesc& d : plan->mats) {
+            const int64_t padded = ((int64_t)d.n * d.m + kAlignElems - 1) / kAlignElems * kAlignElems;
+            CHECK(((int64_t)d.n * d.m + 3) / 4 * 4 <= padded);
+        }
+    } else {
+        check_cover(plan, plan->tiles1, (int)plan->tuning.k1_nv, 1);
+    }
+}
+
 static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int workers, const Tuning* tu) {
     psgd_plan* plan = nullptr;
     CHECK(psgd_plan_create(shapes.data(), (int)shapes.size(), rank, workers, PSGD_F32, PSGD_F32, &plan) == PSGD_OK);
@@ -181,12 +215,19 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
         CHECK(psgd_plan_set_tuning(plan, "q_reduce_elems", tu->q_reduce_elems) == PSGD_OK);
     }
     check_resident(plan);
+    {
+        // both tilings of P = M Q are checked (check_cover below sees whichever is active; flip and check the other)
+        const int64_t was = plan->tuning.k1_mfma;
+        CHECK(psgd_plan_set_tuning(plan, "k1_mfma", was ? 0 : 1) == PSGD_OK);
+        check_p_tiling(plan);
+        CHECK(psgd_plan_set_tuning(plan, "k1_mfma", was) == PSGD_OK);
+    }
     for (int64_t rr : {5, 8, 13, 32}) {
         CHECK(psgd_plan_set_tuning(plan, "res_rows", rr) == PSGD_OK);
         check_resident(plan);
     }
     CHECK(psgd_plan_set_tuning(plan, "res_rows", 0) == PSGD_OK);
-    check_cover(plan, plan->tiles1, (int)plan->tuning.k1_nv, 1);
+    check_p_tiling(plan);
     check_cover(plan, plan->tiles3, (int)plan->tuning.k3_nv, 2);
     check_cover(plan, plan->tiles4, (int)plan->tuning.k4_nv, 0);
     // flat layout: matrices do not overlap, stay inside N, are 64-aligned
@@ -201,7 +242,7 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
         CHECK(d.ppart_off >= 0 && d.ppart_off + (int64_t)workers * d.n_cchunk * d.n * d.r <= plan->ws_ppart_floats);
         CHECK(d.qpart_off >= plan->ws_ppart_floats &&
               d.qpart_off + (int64_t)workers * d.n_rblock * d.m * d.r <= plan->ws_ppart_floats + plan->ws_qpart_floats);
-        if ((int64_t)d.n * d.r > kPanelFloats) {
+        if ((int64_t)d.n * d.r > kPanelFloats || d.n > kOrthoMaxRows) {
             CHECK(d.n_gblock == (d.n + kGramRows - 1) / kGramRows);
             CHECK(d.gram_off >= 0 && d.gram_off + (int64_t)d.n_gblock * d.r * d.r <= plan->ws_gram_doubles);
         } else {
@@ -221,7 +262,7 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
         }
         for (size_t i = 0; i < plan->mats.size(); ++i) {
             const MatDesc& d = plan->mats[i];
-            if (d.n_gblock == 0) CHECK(small[i] == 1 && rows[i] == 0 && (int64_t)d.n * d.r <= kPanelFloats);
+            if (d.n_gblock == 0) CHECK(small[i] == 1 && rows[i] == 0 && (int64_t)d.n * d.r <= kPanelFloats && d.n <= kOrthoMaxRows);
             else CHECK(small[i] == 0 && rows[i] == d.n);
         }
     }
@@ -235,6 +276,12 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
         covered[t.mat] += t.nelem;
     }
     for (size_t i = 0; i < plan->mats.size(); ++i) CHECK(covered[i] == (int64_t)plan->mats[i].m * plan->mats[i].r);
+    std::vector<int64_t> covered_p(plan->mats.size(), 0);
+    for (const Tile& t : plan->tilesp) {
+        CHECK(t.mat >= 0 && t.elem0 == covered_p[t.mat] && t.nelem > 0 && t.nelem <= kWave);
+        covered_p[t.mat] += t.nelem;
+    }
+    for (size_t i = 0; i < plan->mats.size(); ++i) CHECK(covered_p[i] == (int64_t)plan->mats[i].n * plan->mats[i].r);
     psgd_plan_destroy(plan);
 }
 

@@ -151,6 +151,16 @@ def test_resnet18_16_workers():
         _run(WL.resnet18(), rank=rank, workers=16, steps=2, seed=rank, expect_resident=False)
 
 
+@pytest.mark.parametrize("rank", [1, 2, 4])
+def test_matrix_core_right_product(rank):
+    """P = M Q on the matrix cores (tuning k1_mfma = 1): rows fused into super-rows when the row
+    length is not a multiple of 4, ragged last super-row and column chunk, W = 2."""
+    _need_gpu()
+    shapes = [(37, 91), (7,), (51, 650), (130, 1028), (5, 3), (300, 2), (1, 40), (3, 4700), (257, 260), (2600, 650)]
+    _run(_workload(shapes), rank=rank, workers=2, steps=3, seed=50 + rank, tuning={"k1_mfma": 1},
+         expect_resident=False)
+
+
 def test_small_tiles_many_partials():
     """Forces many column chunks and row blocks per matrix so that the fixed-order partial
     sums are exercised."""
