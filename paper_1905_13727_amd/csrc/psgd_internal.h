@@ -57,7 +57,8 @@ struct Tile {
 };
 
 // Resident path: one wavefront keeps one tile of M in registers through the whole step.
-constexpr int kResRows = 32;         // most rows of a resident tile (registers: kResRows * vec floats per lane)
+constexpr int kResRows = 32;         // most rows of a resident tile (registers: rows * vec floats per lane) ...
+constexpr int res_rows_for_rank(int r) { return r <= 2 ? 32 : 24; }   // ... fewer when the rank needs the registers
 constexpr int kResMinRows = 8;       // strips are not made thinner than this
 constexpr int kResMaxN = 512;        // tallest matrix the single-wavefront Gram-Schmidt handles (8 rows per lane)
 constexpr int kResMaxRank = 4;

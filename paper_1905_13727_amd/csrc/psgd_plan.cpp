@@ -298,12 +298,13 @@ void build_resident(psgd_plan* plan) {
     };
 
     int h = 0;
+    const int max_rows = res_rows_for_rank(plan->rank);
     if (tu.res_rows > 0) {
-        if (tu.res_rows > kResRows) return;
+        if (tu.res_rows > max_rows) return;
         h = (int)tu.res_rows;
         if (layout(h, nullptr, nullptr, nullptr, nullptr) > max_blocks) return;
     } else {
-        for (int cand = kResMinRows; cand <= kResRows; ++cand) {
+        for (int cand = kResMinRows; cand <= max_rows; ++cand) {
             if (layout(cand, nullptr, nullptr, nullptr, nullptr) <= max_blocks) { h = cand; break; }
         }
         if (!h) return;

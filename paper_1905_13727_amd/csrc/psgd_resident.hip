@@ -161,7 +161,7 @@ __device__ __forceinline__ void gram_schmidt_rows(float (&P)[kResRowsPerLane][R]
 // ---- the step, for a workgroup whose tiles use V-wide row accesses ---------------------------------------
 template <int R, int V>
 __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, float* lds, unsigned epoch) {
-    constexpr int RT = kResRows;
+    constexpr int RT = res_rows_for_rank(R);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const bool active = t.mat >= 0;

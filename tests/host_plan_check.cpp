@@ -92,7 +92,7 @@ static void check_resident(const psgd_plan* plan) {
             CHECK(d.n <= kResMaxN);
             if (!vec) vec = d.vec;
             CHECK(vec == d.vec);   // one access width per workgroup
-            CHECK(t.nrows > 0 && t.nrows <= kResRows && t.row0 >= 0 && t.row0 + t.nrows <= d.n);
+            CHECK(t.nrows > 0 && t.nrows <= res_rows_for_rank(plan->rank) && t.row0 >= 0 && t.row0 + t.nrows <= d.n);
             CHECK(t.nvec > 0 && t.nvec <= kWave && t.vec0 >= 0 && (int64_t)(t.vec0 + t.nvec) * d.vec <= d.m);
             CHECK(t.ppart >= 0 && t.ppart < d.n_cchunk);
             CHECK(t.cntq >= 0 && t.cntq < plan->res_n_cntq);
@@ -222,8 +222,9 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
         check_p_tiling(plan);
         CHECK(psgd_plan_set_tuning(plan, "k1_mfma", was) == PSGD_OK);
     }
-    for (int64_t rr : {5, 8, 13, 32}) {
+    for (int64_t rr : {5, 8, 13, 24, 32}) {
         CHECK(psgd_plan_set_tuning(plan, "res_rows", rr) == PSGD_OK);
+        if (rr > res_rows_for_rank(rank)) CHECK(!plan->resident_ok);
         check_resident(plan);
     }
     CHECK(psgd_plan_set_tuning(plan, "res_rows", 0) == PSGD_OK);
