@@ -41,6 +41,7 @@ struct MatDesc {
     int32_t n_gblock;   // tall panels: row blocks of the Gram / apply kernels; 0 = panel fits one workgroup's LDS
     int32_t pack;       // rows fused into one "super-row" so that its length pack*m is a multiple of 4 (1, 2 or 4)
     int32_t pad_;
+    int64_t chol_off;   // matrix-core path: offset (in doubles) of this matrix's Cholesky factor, r*r + r values
 };
 
 // One workgroup's share of a streaming kernel.
@@ -92,6 +93,7 @@ struct Tuning {
     int64_t k4_rows = 64;   // rows per workgroup tile, decompress + residual
     int64_t k4_nv = 1;
     int64_t q_reduce_elems = 1024;  // elements per workgroup in the Q reduction
+    int64_t hr_k3_rows = 1024;  // matrix-core Q = M^T P: rows per workgroup (four strips)
     int64_t k1_mfma = 0;    // 1: P = M Q on the matrix cores when pack * rank <= 16 for every matrix (slower for now)
     int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream
     int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height
@@ -106,6 +108,9 @@ struct DeviceTables {
     Tile* tilesq = nullptr;
     Tile* tiles_gram = nullptr;
     Tile* tilesp = nullptr;
+    Tile* hr_tiles1 = nullptr;
+    Tile* hr_tiles3 = nullptr;
+    Tile* hr_tiles4 = nullptr;
     int32_t* small_mats = nullptr;
     MatDesc* res_mats = nullptr;
     RTile* res_tiles = nullptr;
@@ -132,6 +137,11 @@ struct psgd_plan {
     std::vector<int32_t> small_mats;        // matrices orthogonalised by one workgroup (Gram-Schmidt in LDS)
     int64_t ws_gram_doubles = 0;            // workspace: Gram partials, after the float regions
     bool k1_on_mfma = false;                // tiles1 are laid out for the matrix-core kernel
+    // matrix-core path (rank > 8, or bf16 gradients / output)
+    bool hr = false;
+    int32_t hr_nt = 1;                      // 16-wide rank tiles
+    std::vector<psgd::Tile> hr_tiles1, hr_tiles3, hr_tiles4;
+    int64_t ws_chol_doubles = 0;
     std::vector<psgd::Tile> tilesp;         // 64-element slices of the n x r panels (pre-reduction of partial P)
     bool p_pre_reduce = false;              // some matrix has more than kPreReduceParts partial-P slices
     int32_t max_n = 0;
@@ -173,6 +183,12 @@ psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float
 psgd_status launch_decompress(psgd_plan* plan, const float* p, const float* q, float* err,
                               const void* grad, void* out, void* workspace, void* stream);
 psgd_status set_profiling(psgd_plan* plan, bool enable);
+psgd_status launch_q_reduce(psgd_plan* plan, float* ws, float* q, void* stream);
+psgd_status finish_profiled_step(psgd_plan* plan);
+psgd_status hr_compress(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* workspace,
+                        void* stream);
+psgd_status hr_decompress(psgd_plan* plan, const float* p, const float* q, float* err, const void* grad, void* out,
+                          void* stream);
 psgd_status check_plan(psgd_plan* plan, void* stream);
 psgd_status read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t* n_written);
 psgd_status resident_check_device(psgd_plan* plan);

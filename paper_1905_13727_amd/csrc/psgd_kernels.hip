@@ -762,7 +762,7 @@ psgd_status upload_tables(psgd_plan* plan) {
         if (st != PSGD_OK) return st;
     }
     struct Piece { const void* src; size_t bytes; size_t at; };
-    Piece pieces[13] = {
+    Piece pieces[16] = {
         {plan->mats.data(), plan->mats.size() * sizeof(MatDesc), 0},
         {plan->tiles1.data(), plan->tiles1.size() * sizeof(Tile), 0},
         {plan->tiles3.data(), plan->tiles3.size() * sizeof(Tile), 0},
@@ -776,6 +776,9 @@ psgd_status upload_tables(psgd_plan* plan) {
         {plan->tiles_gram.data(), plan->tiles_gram.size() * sizeof(Tile), 0},
         {plan->small_mats.data(), plan->small_mats.size() * sizeof(int32_t), 0},
         {plan->tilesp.data(), plan->tilesp.size() * sizeof(Tile), 0},
+        {plan->hr_tiles1.data(), plan->hr_tiles1.size() * sizeof(Tile), 0},
+        {plan->hr_tiles3.data(), plan->hr_tiles3.size() * sizeof(Tile), 0},
+        {plan->hr_tiles4.data(), plan->hr_tiles4.size() * sizeof(Tile), 0},
     };
     size_t total = 0;
     for (Piece& pc : pieces) {
@@ -812,6 +815,9 @@ psgd_status upload_tables(psgd_plan* plan) {
     plan->dev.tiles_gram = reinterpret_cast<Tile*>(b + pieces[10].at);
     plan->dev.small_mats = reinterpret_cast<int32_t*>(b + pieces[11].at);
     plan->dev.tilesp = reinterpret_cast<Tile*>(b + pieces[12].at);
+    plan->dev.hr_tiles1 = reinterpret_cast<Tile*>(b + pieces[13].at);
+    plan->dev.hr_tiles3 = reinterpret_cast<Tile*>(b + pieces[14].at);
+    plan->dev.hr_tiles4 = reinterpret_cast<Tile*>(b + pieces[15].at);
     plan->uploaded = true;
     return PSGD_OK;
 }
@@ -900,7 +906,7 @@ static void launch_decomp(psgd_plan* plan, float* err, const float* p, const flo
     }
 
 static psgd_status check_ready(psgd_plan* plan) {
-    if (plan->grad_dtype != PSGD_F32 || plan->out_dtype != PSGD_F32) return PSGD_EUNSUPPORTED;
+    if (!plan->hr && (plan->grad_dtype != PSGD_F32 || plan->out_dtype != PSGD_F32)) return PSGD_EUNSUPPORTED;
     if (!plan->uploaded) {
         psgd_status st = upload_tables(plan);
         if (st != PSGD_OK) return st;
@@ -912,6 +918,7 @@ psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float
                             void* stream) {
     psgd_status st = check_ready(plan);
     if (st != PSGD_OK) return st;
+    if (plan->hr) return hr_compress(plan, grad, err, q, p, workspace, stream);
     hipStream_t s = static_cast<hipStream_t>(stream);
     float* ws = static_cast<float*>(workspace);
     const float* g = static_cast<const float*>(grad);
@@ -955,10 +962,17 @@ psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float
     PSGD_HIP(hipGetLastError(), "launch k_left");
     PSGD_MARK(3);
 
+    st = launch_q_reduce(plan, ws, q, stream);
+    if (st != PSGD_OK) return st;
+    PSGD_MARK(4);
+    return PSGD_OK;
+}
+
+psgd_status launch_q_reduce(psgd_plan* plan, float* ws, float* q, void* stream) {
+    hipStream_t s = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(k_q_reduce, dim3((unsigned)plan->tilesq.size()), dim3(kBlock), 0, s, plan->dev.mats,
                        plan->dev.tilesq, ws, q, plan->workers, 0);
     PSGD_HIP(hipGetLastError(), "launch k_q_reduce");
-    PSGD_MARK(4);
     return PSGD_OK;
 }
 
@@ -967,25 +981,29 @@ psgd_status launch_decompress(psgd_plan* plan, const float* p, const float* q, f
     (void)workspace;
     psgd_status st = check_ready(plan);
     if (st != PSGD_OK) return st;
+    if (plan->hr) return hr_decompress(plan, p, q, err, grad, out, stream);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (plan->tiles4.empty()) return PSGD_OK;
     PSGD_MARK(5);
     PSGD_RANK_SWITCH(launch_decomp, plan, err, p, q, static_cast<const float*>(grad), static_cast<float*>(out), s);
     PSGD_HIP(hipGetLastError(), "launch k_decomp");
     PSGD_MARK(6);
-    if (plan->profiling) {
-        // measurement mode: wait, then add this step's per-kernel times (compress must have run first)
-        PSGD_HIP(hipEventSynchronize(static_cast<hipEvent_t>(plan->events[6])), "hipEventSynchronize");
-        static const int first[5] = {0, 1, 2, 3, 5};
-        for (int k = 0; k < 5; ++k) {
-            float ms = 0.f;
-            hipError_t e = hipEventElapsedTime(&ms, static_cast<hipEvent_t>(plan->events[first[k]]),
-                                               static_cast<hipEvent_t>(plan->events[first[k] + 1]));
-            if (e != hipSuccess) return hip_fail(plan, e, "hipEventElapsedTime");
-            plan->kernel_ms[k] += ms;
-        }
-        ++plan->profiled_steps;
+    return finish_profiled_step(plan);
+}
+
+// measurement mode: wait for the step, then add its per-kernel times (compress must have run first)
+psgd_status finish_profiled_step(psgd_plan* plan) {
+    if (!plan->profiling) return PSGD_OK;
+    PSGD_HIP(hipEventSynchronize(static_cast<hipEvent_t>(plan->events[6])), "hipEventSynchronize");
+    static const int first[5] = {0, 1, 2, 3, 5};
+    for (int k = 0; k < 5; ++k) {
+        float ms = 0.f;
+        hipError_t e = hipEventElapsedTime(&ms, static_cast<hipEvent_t>(plan->events[first[k]]),
+                                           static_cast<hipEvent_t>(plan->events[first[k] + 1]));
+        if (e != hipSuccess) return hip_fail(plan, e, "hipEventElapsedTime");
+        plan->kernel_ms[k] += ms;
     }
+    ++plan->profiled_steps;
     return PSGD_OK;
 }
 

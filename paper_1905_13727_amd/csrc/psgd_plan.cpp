@@ -62,7 +62,87 @@ static void streaming_tiles(const psgd_plan* plan, int64_t rows_per_tile, int64_
 
 void build_resident(psgd_plan* plan);
 
+// Matrix-core path: its own tilings and workspace layout.
+static psgd_status build_hr_tables(psgd_plan* plan) {
+    const Tuning& tu = plan->tuning;
+    if (tu.hr_k3_rows < 64) return PSGD_EINVAL;
+    const int64_t W = plan->workers;
+    const size_t nm = plan->mats.size();
+    plan->tiles1.clear(); plan->tiles3.clear(); plan->tiles4.clear(); plan->tilesp.clear();
+    plan->small_mats.clear(); plan->tiles_gram.clear(); plan->tilesq.clear();
+    plan->hr_tiles1.clear(); plan->hr_tiles3.clear(); plan->hr_tiles4.clear();
+    plan->k1_on_mfma = false;
+    plan->p_pre_reduce = false;
+    const int64_t right_rows = 256;   // 4 wavefronts x 64 rows (kHrRightRows)
+    const int64_t decomp_rows = 256;
+    int64_t pp = 0, qp = 0, gp = 0, cp = 0;
+    for (size_t i = 0; i < nm; ++i) {
+        MatDesc& d = plan->mats[i];
+        d.n_cchunk = 1;
+        const int64_t nrb = ceil_div(d.n, tu.hr_k3_rows);
+        d.n_rblock = (int32_t)(nrb * kWavesPerBlock);
+        d.n_gblock = (int32_t)ceil_div(d.n, kGramRows);
+        d.ppart_off = pp;
+        pp += round_up(W * d.n * d.r, kAlignElems);
+        d.gram_off = gp;
+        gp += round_up((int64_t)d.n_gblock * d.r * d.r, 32);
+        d.chol_off = cp;
+        cp += round_up((int64_t)d.r * d.r + d.r, 32);
+        for (int64_t r0 = 0; r0 < d.n; r0 += right_rows) {
+            Tile t{};
+            t.mat = (int32_t)i; t.row0 = (int32_t)r0; t.nrows = (int32_t)std::min<int64_t>(right_rows, d.n - r0);
+            t.vec0 = 0; t.nvec = d.m;
+            plan->hr_tiles1.push_back(t);
+        }
+        for (int64_t b = 0; b < nrb; ++b)
+            for (int64_t c0 = 0; c0 < d.m; c0 += 128) {
+                Tile t{};
+                t.mat = (int32_t)i; t.row0 = (int32_t)(b * tu.hr_k3_rows);
+                t.nrows = (int32_t)std::min<int64_t>(tu.hr_k3_rows, d.n - t.row0);
+                t.vec0 = (int32_t)c0; t.nvec = (int32_t)std::min<int64_t>(128, d.m - c0);
+                t.part = (int32_t)b;
+                plan->hr_tiles3.push_back(t);
+            }
+        for (int64_t r0 = 0; r0 < d.n; r0 += decomp_rows)
+            for (int64_t c0 = 0; c0 < d.m; c0 += 128) {
+                Tile t{};
+                t.mat = (int32_t)i; t.row0 = (int32_t)r0; t.nrows = (int32_t)std::min<int64_t>(decomp_rows, d.n - r0);
+                t.vec0 = (int32_t)c0; t.nvec = (int32_t)std::min<int64_t>(128, d.m - c0);
+                plan->hr_tiles4.push_back(t);
+            }
+        for (int32_t b = 0; b < d.n_gblock; ++b) {
+            Tile t{};
+            t.mat = (int32_t)i; t.row0 = b * kGramRows; t.nrows = std::min<int32_t>(kGramRows, d.n - t.row0);
+            t.part = b;
+            plan->tiles_gram.push_back(t);
+        }
+    }
+    for (size_t i = 0; i < nm; ++i) {
+        MatDesc& d = plan->mats[i];
+        d.qpart_off = pp + qp;
+        qp += round_up(W * d.n_rblock * d.m * d.r, kAlignElems);
+        const int64_t total = (int64_t)d.m * d.r;
+        for (int64_t e = 0; e < total; e += kWave) {
+            Tile t{};
+            t.mat = (int32_t)i; t.elem0 = e; t.nelem = std::min<int64_t>(kWave, total - e);
+            plan->tilesq.push_back(t);
+        }
+    }
+    plan->ws_ppart_floats = pp;
+    plan->ws_qpart_floats = qp;
+    plan->ws_gram_doubles = gp;
+    plan->ws_chol_doubles = cp;
+    plan->sizes.workspace_bytes =
+        std::max<int64_t>(256, round_up((pp + qp) * (int64_t)sizeof(float), 256) + (gp + cp) * (int64_t)sizeof(double));
+    plan->resident_ok = false;
+    plan->res_tiles.clear(); plan->res_mats.clear();
+    plan->res_ws_floats = 0; plan->res_blocks = 0; plan->res_mail_slots = 0; plan->res_sync_words = 0;
+    plan->tables_built = true;
+    return PSGD_OK;
+}
+
 psgd_status build_tables(psgd_plan* plan) {
+    if (plan->hr) return build_hr_tables(plan);
     const Tuning& tu = plan->tuning;
     if (tu.k1_rows < 1 || tu.k3_rows < 1 || tu.k4_rows < 1 || tu.k1_nv < 1 ||
         tu.k1_nv > kMaxVecPerLaneK1 || tu.k3_nv < 1 || tu.k3_nv > kMaxVecPerLaneK3 || tu.k4_nv < 1 ||
@@ -351,14 +431,19 @@ psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_
         if (shapes[t].rows > INT32_MAX || shapes[t].cols > INT32_MAX) return PSGD_EUNSUPPORTED;
     }
     if (rank > PSGD_MAX_RANK) return PSGD_EUNSUPPORTED;
-    if (rank > kValuMaxRank) return PSGD_EUNSUPPORTED;            // matrix-core path: not built yet
-    if (grad_dtype != PSGD_F32 || out_dtype != PSGD_F32) return PSGD_EUNSUPPORTED;
+    // ranks above 8 and bf16 data run on the matrix-core kernels, which need row lengths that are multiples of 4
+    const bool needs_hr = rank > kValuMaxRank || grad_dtype != PSGD_F32 || out_dtype != PSGD_F32;
+    if (needs_hr)
+        for (int32_t t = 0; t < n_tensors; ++t)
+            if (shapes[t].cols != 1 && shapes[t].cols % 4 != 0) return PSGD_EUNSUPPORTED;
 
     psgd_plan* plan = new (std::nothrow) psgd_plan();
     if (!plan) return PSGD_ENOMEM;
     try {
         plan->rank = rank;
         plan->workers = workers;
+        plan->hr = needs_hr;
+        plan->hr_nt = rank <= 16 ? 1 : (rank <= 32 ? 2 : 4);
         plan->grad_dtype = grad_dtype;
         plan->out_dtype = out_dtype;
         plan->shapes.assign(shapes, shapes + n_tensors);
@@ -470,6 +555,7 @@ psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value
     else if (!strcmp(key, "k4_nv")) tu.k4_nv = value;
     else if (!strcmp(key, "q_reduce_elems")) tu.q_reduce_elems = value;
     else if (!strcmp(key, "k1_mfma")) tu.k1_mfma = value;
+    else if (!strcmp(key, "hr_k3_rows")) tu.hr_k3_rows = value;
     else if (!strcmp(key, "resident")) tu.resident = value;
     else if (!strcmp(key, "res_rows")) tu.res_rows = value;
     else if (!strcmp(key, "res_trace")) tu.res_trace = value;

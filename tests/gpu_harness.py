@@ -22,20 +22,24 @@ def rel_fro(a, b):
 
 
 class GpuRun:
-    def __init__(self, shapes, rank, workers, q0, tuning=None, device="cuda:0"):
+    def __init__(self, shapes, rank, workers, q0, tuning=None, device="cuda:0", grad_bf16=False, out_bf16=False):
         self.dev = torch.device(device)
-        self.plan = B.Plan(shapes, rank, workers)
+        self.grad_bf16, self.out_bf16 = grad_bf16, out_bf16
+        self.plan = B.Plan(shapes, rank, workers, B.PSGD_BF16 if grad_bf16 else B.PSGD_F32,
+                           B.PSGD_BF16 if out_bf16 else B.PSGD_F32)
         for k, v in (tuning or {}).items():
             self.plan.set_tuning(k, v)
         self.lay = FlatLayout(self.plan, shapes)
         s = self.plan.sizes
         self.W = workers
         f32 = dict(dtype=torch.float32, device=self.dev)
-        self.grad = torch.zeros(workers * s.grad_stride, **f32)
+        self.grad = torch.zeros(workers * s.grad_stride, dtype=torch.bfloat16 if grad_bf16 else torch.float32,
+                                device=self.dev)
         self.err = torch.zeros(workers * max(1, s.err_stride), **f32)
         self.q = torch.from_numpy(self.lay.pack_q(q0)).to(self.dev) if s.q_elems else torch.zeros(1, **f32)
         self.p = torch.full((max(1, s.p_elems),), float("nan"), **f32)
-        self.out = torch.full((max(1, s.out_elems),), float("nan"), **f32)
+        self.out = torch.full((max(1, s.out_elems),), float("nan"),
+                              dtype=torch.bfloat16 if out_bf16 else torch.float32, device=self.dev)
         self.ws = torch.empty(s.workspace_bytes // 4 + 64, **f32)
 
     def upload(self, grads):
@@ -43,7 +47,8 @@ class GpuRun:
         host = np.zeros((self.W, s.grad_stride), dtype=np.float32)
         for w in range(self.W):
             host[w, : s.n_mat_elems + s.n_vec_elems] = self.lay.pack_flat(grads[w])
-        self.grad.copy_(torch.from_numpy(host.reshape(-1)))
+        # bf16 gradients: the caller passes fp32 arrays that hold exactly representable bf16 values
+        self.grad.copy_(torch.from_numpy(host.reshape(-1)).to(self.grad.dtype))
 
     def set_err(self, errs):
         s = self.plan.sizes
@@ -75,7 +80,7 @@ class GpuRun:
         return {
             "P_hat": self.lay.unpack_p(self.p.cpu().numpy()),
             "Q": self.lay.unpack_q(self.q.cpu().numpy()),
-            "out": self.lay.unpack_flat(self.out.cpu().numpy()),
+            "out": self.lay.unpack_flat(self.out.float().cpu().numpy()),
             "err": [self.lay.unpack_flat(err[w], matrices_only=True) if err is not None else
                     [None] * len(self.lay.shapes) for w in range(self.W)],
         }
@@ -106,7 +111,7 @@ class OracleRun:
         return res
 
 
-def compare(gpu, ora, shapes, workers, rank=None, grads=None, prev_errs=None):
+def compare(gpu, ora, shapes, workers, rank=None, grads=None, prev_errs=None, out_bf16=False):
     """Worst relative Frobenius errors over tensors (and workers) for P_hat, Q, E', Delta'.
 
     Degenerate case of the method: when the effective rank equals min(n, m) the
@@ -117,7 +122,19 @@ def compare(gpu, ora, shapes, workers, rank=None, grads=None, prev_errs=None):
     which needs `rank`, `grads` and `prev_errs` (the oracle's e_w before the step)."""
     worst = {"P_hat": 0.0, "Q": 0.0, "err": 0.0, "out": 0.0}
     for t, s in enumerate(shapes):
-        worst["out"] = max(worst["out"], rel_fro(gpu["out"][t], np.asarray(ora["out"][t]).reshape(gpu["out"][t].shape)))
+        want = np.asarray(ora["out"][t]).reshape(gpu["out"][t].shape)
+        if out_bf16:
+            # Delta' stored as bf16 (round to nearest even of the fp32 value): each element within half a
+            # bf16 ulp of the oracle's value plus the fp32 error of the product (1e-4 of the tensor's rms);
+            # reported as 0 when it holds
+            got = gpu["out"][t].astype(np.float64)
+            rms = np.linalg.norm(want) / np.sqrt(want.size)
+            tol = np.abs(want) * 2.0 ** -8 + 1e-4 * rms + 1e-30
+            worst["out"] = max(worst["out"], 0.0 if (np.abs(got - want) <= tol).all() else np.inf)
+            # and nothing worse than bf16 resolution overall
+            worst["out"] = max(worst["out"], 0.0 if rel_fro(got, want) <= 2.0 ** -8 else np.inf)
+        else:
+            worst["out"] = max(worst["out"], rel_fro(gpu["out"][t], want))
         if len(s) == 1:
             continue
         worst["P_hat"] = max(worst["P_hat"], rel_fro(gpu["P_hat"][t], ora["P_hat"][t]))

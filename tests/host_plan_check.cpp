@@ -286,6 +286,66 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
     psgd_plan_destroy(plan);
 }
 
+// Matrix-core path (rank > 8): every tiling covers each element once and every partial slice is in bounds.
+static void check_hr_plan(const std::vector<psgd_shape>& shapes, int rank, int workers) {
+    psgd_plan* plan = nullptr;
+    CHECK(psgd_plan_create(shapes.data(), (int)shapes.size(), rank, workers, PSGD_F32, PSGD_F32, &plan) == PSGD_OK);
+    CHECK(plan->hr && !plan->resident_ok);
+    CHECK(plan->hr_nt * 16 >= rank);
+    auto cover = [&](const std::vector<Tile>& tiles, bool full_rows) {
+        std::vector<std::vector<unsigned char>> seen(plan->mats.size());
+        for (size_t i = 0; i < plan->mats.size(); ++i) seen[i].assign((size_t)plan->mats[i].n * plan->mats[i].m, 0);
+        for (const Tile& t : tiles) {
+            CHECK(t.mat >= 0 && t.mat < (int)plan->mats.size());
+            const MatDesc& d = plan->mats[t.mat];
+            CHECK(d.m % 4 == 0 && t.row0 >= 0 && t.nrows > 0 && t.row0 + t.nrows <= d.n);
+            CHECK(t.vec0 >= 0 && t.vec0 % 4 == 0 && t.nvec > 0 && t.vec0 + t.nvec <= d.m);
+            if (full_rows) CHECK(t.vec0 == 0 && t.nvec == d.m && t.nrows <= 256);
+            else CHECK(t.nvec <= 128);
+            for (int i = t.row0; i < t.row0 + t.nrows; ++i)
+                for (int j = t.vec0; j < t.vec0 + t.nvec; ++j) {
+                    unsigned char& sf = seen[t.mat][(size_t)i * d.m + j];
+                    CHECK(sf == 0);
+                    sf = 1;
+                }
+        }
+        for (auto& v : seen)
+            for (unsigned char sf : v) CHECK(sf == 1);
+    };
+    cover(plan->hr_tiles1, true);
+    cover(plan->hr_tiles3, false);
+    cover(plan->hr_tiles4, false);
+    for (const Tile& t : plan->hr_tiles3) {
+        const MatDesc& d = plan->mats[t.mat];
+        CHECK(t.part >= 0 && (t.part + 1) * kWavesPerBlock <= d.n_rblock);
+    }
+    std::vector<int64_t> rows(plan->mats.size(), 0);
+    for (const Tile& t : plan->tiles_gram) {
+        const MatDesc& d = plan->mats[t.mat];
+        CHECK(t.part >= 0 && t.part < d.n_gblock && t.row0 == rows[t.mat] && t.nrows > 0 && t.nrows <= kGramRows);
+        rows[t.mat] += t.nrows;
+    }
+    for (size_t i = 0; i < plan->mats.size(); ++i) {
+        const MatDesc& d = plan->mats[i];
+        CHECK(rows[i] == d.n && d.n_cchunk == 1);
+        CHECK(d.ppart_off >= 0 && d.ppart_off + (int64_t)workers * d.n * d.r <= plan->ws_ppart_floats);
+        CHECK(d.qpart_off >= plan->ws_ppart_floats &&
+              d.qpart_off + (int64_t)workers * d.n_rblock * d.m * d.r <= plan->ws_ppart_floats + plan->ws_qpart_floats);
+        CHECK(d.gram_off >= 0 && d.gram_off + (int64_t)d.n_gblock * d.r * d.r <= plan->ws_gram_doubles);
+        CHECK(d.chol_off >= 0 && d.chol_off + (int64_t)d.r * d.r + d.r <= plan->ws_chol_doubles);
+        CHECK(d.r <= PSGD_MAX_RANK);
+    }
+    CHECK(((plan->ws_ppart_floats + plan->ws_qpart_floats) * 4 + 255) / 256 * 256 +
+              (plan->ws_gram_doubles + plan->ws_chol_doubles) * 8 <= plan->sizes.workspace_bytes);
+    std::vector<int64_t> covered(plan->mats.size(), 0);
+    for (const Tile& t : plan->tilesq) {
+        CHECK(t.mat >= 0 && t.elem0 == covered[t.mat] && t.nelem > 0 && t.nelem <= kWave);
+        covered[t.mat] += t.nelem;
+    }
+    for (size_t i = 0; i < plan->mats.size(); ++i) CHECK(covered[i] == (int64_t)plan->mats[i].m * plan->mats[i].r);
+    psgd_plan_destroy(plan);
+}
+
 int main() {
     std::vector<std::vector<psgd_shape>> sets = {
         {{64, 27}, {64, 576}, {64, 576}},
@@ -311,6 +371,16 @@ int main() {
                 check_plan(s, rank, W, &small);
                 check_plan(s, rank, W, &big);
             }
+    {
+        std::vector<psgd_shape> tr = {{1000, 256}, {256, 256}, {77, 1}, {1024, 256}, {256, 1024}, {20, 12}, {3000, 64}};
+        for (int rank : {9, 16, 17, 32, 64})
+            for (int W : {1, 2}) check_hr_plan(tr, rank, W);
+        // a row length that is not a multiple of 4 is refused on this path
+        std::vector<psgd_shape> odd = {{64, 650}};
+        psgd_plan* plan = nullptr;
+        CHECK(psgd_plan_create(odd.data(), 1, 16, 1, PSGD_F32, PSGD_F32, &plan) == PSGD_EUNSUPPORTED);
+        CHECK(psgd_plan_create(odd.data(), 1, 4, 1, PSGD_BF16, PSGD_F32, &plan) == PSGD_EUNSUPPORTED);
+    }
     std::printf("OK\n");
     return 0;
 }

@@ -38,12 +38,12 @@ def _need_gpu():
 
 
 def _run(wl, rank, workers, steps, seed=0, tuning=None, split=False, verbose=True, resync=None,
-         expect_resident=None):
+         expect_resident=None, grad_bf16=False, out_bf16=False):
     from paper_1905_13727_amd import workloads as WL
     from gpu_harness import GpuRun, OracleRun, compare
     factors = WL.planted_factors(wl, seed)
     q0 = WL.initial_q(wl, rank, seed)
-    gpu = GpuRun(wl.shapes, rank, workers, q0, tuning)
+    gpu = GpuRun(wl.shapes, rank, workers, q0, tuning, grad_bf16=grad_bf16, out_bf16=out_bf16)
     ora = OracleRun(wl.shapes, rank, workers, q0)
     worst_all = {"P_hat": 0.0, "Q": 0.0, "err": 0.0, "out": 0.0}
     for t in range(steps):
@@ -52,10 +52,12 @@ def _run(wl, rank, workers, steps, seed=0, tuning=None, split=False, verbose=Tru
             gpu.set_err(ora.errs)
             gpu.set_q(ora.Qs)
         grads = [WL.gradients(wl, factors, seed, t, w) for w in range(workers)]
+        if grad_bf16:   # the gradient both sides see is the bf16 rounding of the fp32 sample, upcast exactly
+            grads = [[WL.bf16_round(g) for g in gw] for gw in grads]
         rg = gpu.step(grads, split=split)
         prev_errs = ora.errs
         ro = ora.step(grads)
-        worst = compare(rg, ro, wl.shapes, workers, rank, grads, prev_errs)
+        worst = compare(rg, ro, wl.shapes, workers, rank, grads, prev_errs, out_bf16=out_bf16)
         for k in worst:
             worst_all[k] = max(worst_all[k], worst[k])
         assert worst["P_hat"] <= TOL and worst["Q"] <= TOL and worst["err"] <= TOL and worst["out"] <= TOL, \
@@ -160,6 +162,22 @@ def test_matrix_core_right_product(rank):
     shapes = [(37, 91), (7,), (51, 650), (130, 1028), (5, 3), (300, 2), (1, 40), (3, 4700), (257, 260), (2600, 650)]
     _run(_workload(shapes), rank=rank, workers=2, steps=3, seed=50 + rank, tuning={"k1_mfma": 1},
          expect_resident=False)
+
+
+TRANSFORMER_SMALL = [(1000, 256), (256,), (256, 256), (256, 256), (1024, 256), (1024,), (256, 1024), (20, 12), (3000, 64)]
+
+
+@pytest.mark.parametrize("rank,workers,gbf,obf", [(16, 1, False, False), (32, 2, False, False), (9, 1, False, False),
+                                                  (64, 1, False, False), (16, 1, True, True), (32, 1, True, False),
+                                                  (4, 2, True, True), (2, 1, False, True)])
+def test_matrix_core_path(rank, workers, gbf, obf):
+    """Ranks above 8 and bf16 gradients / output run on the matrix-core kernels: a small
+    transformer-shaped set (ragged row blocks and column chunks, a matrix smaller than the rank,
+    vectors), planted rank 64 with a 1/k spectrum."""
+    _need_gpu()
+    from paper_1905_13727_amd import workloads as WL
+    wl = WL.Workload("tr-small", list(TRANSFORMER_SMALL), 64, 1.0 / np.arange(1, 65), 0.001)
+    _run(wl, rank=rank, workers=workers, steps=3, seed=60 + rank, expect_resident=False, grad_bf16=gbf, out_bf16=obf)
 
 
 def test_small_tiles_many_partials():
