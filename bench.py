@@ -42,7 +42,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="resnet18", choices=["tiny", "resnet18", "lstm"])
+    ap.add_argument("--workload", default="resnet18", choices=["tiny", "resnet18", "lstm", "transformer"])
+    ap.add_argument("--layers", type=int, default=24, help="transformer workload: number of layers")
+    ap.add_argument("--grad-dtype", default=None, choices=["f32", "bf16"], help="default: the workload's")
+    ap.add_argument("--out-dtype", default=None, choices=["f32", "bf16"], help="default: same as the gradient")
     ap.add_argument("--rank", type=int, default=None)
     ap.add_argument("--workers", type=int, default=1)
     ap.add_argument("--grad-buffers", type=int, default=4, help="distinct gradient batches cycled through")
@@ -58,12 +61,12 @@ def parse():
     return ap.parse_args()
 
 
-def device_gradients(wl, lay, plan, workers, seed, torch, dev):
+def device_gradients(wl, lay, plan, workers, seed, torch, dev, dtype=None):
     """One flat [W][grad_stride] gradient batch generated on the GPU: planted low rank + noise."""
     s = plan.sizes
     gen = torch.Generator(device=dev)
     gen.manual_seed(seed)
-    grad = torch.zeros(workers * s.grad_stride, dtype=torch.float32, device=dev)
+    grad = torch.zeros(workers * s.grad_stride, dtype=dtype or torch.float32, device=dev)
     fac_gen = torch.Generator(device=dev)
     fac_gen.manual_seed(12345)
     sv = torch.tensor(np.asarray(wl.singular_values), dtype=torch.float32, device=dev)
@@ -72,7 +75,7 @@ def device_gradients(wl, lay, plan, workers, seed, torch, dev):
         if len(shape) == 1:
             for w in range(workers):
                 grad[w * s.grad_stride + off: w * s.grad_stride + off + shape[0]] = \
-                    wl.sigma * torch.randn(shape[0], generator=gen, device=dev)
+                    (wl.sigma * torch.randn(shape[0], generator=gen, device=dev)).to(grad.dtype)
             continue
         n, m = shape
         k = min(wl.planted_rank, n, m)
@@ -87,7 +90,7 @@ def device_gradients(wl, lay, plan, workers, seed, torch, dev):
             g = base + wl.sigma * torch.randn(n, m, generator=gen, device=dev)
             if mask is not None:
                 g = g * mask
-            grad[w * s.grad_stride + off: w * s.grad_stride + off + n * m] = g.reshape(-1)
+            grad[w * s.grad_stride + off: w * s.grad_stride + off + n * m] = g.reshape(-1).to(grad.dtype)
     return grad
 
 
@@ -136,22 +139,26 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     dev = torch.device("cuda:0")
-    wl = WL.by_name(args.workload)
-    rank = args.rank if args.rank is not None else (4 if args.workload == "lstm" else 2)
+    wl = WL.transformer(args.layers) if args.workload == "transformer" else WL.by_name(args.workload)
+    rank = args.rank if args.rank is not None else (4 if args.workload in ("lstm", "transformer") else 2)
     W = args.workers
-    plan = B.Plan(wl.shapes, rank, W)
+    gdt = args.grad_dtype or wl.grad_dtype
+    odt = args.out_dtype or gdt
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16}
+    plan = B.Plan(wl.shapes, rank, W, B.PSGD_BF16 if gdt == "bf16" else B.PSGD_F32,
+                  B.PSGD_BF16 if odt == "bf16" else B.PSGD_F32)
     for kv in args.tune:
         k, v = kv.split("=")
         plan.set_tuning(k, int(v))
     lay = FlatLayout(plan, wl.shapes)
     s = plan.sizes
 
-    grads = [device_gradients(wl, lay, plan, W, 100 + i, torch, dev) for i in range(args.grad_buffers)]
+    grads = [device_gradients(wl, lay, plan, W, 100 + i, torch, dev, tdt[gdt]) for i in range(args.grad_buffers)]
     err = torch.zeros(W * s.err_stride, dtype=torch.float32, device=dev)
     q0 = WL.initial_q(wl, rank, 0)
     q = torch.from_numpy(lay.pack_q(q0)).to(dev)
     p = torch.zeros(s.p_elems, dtype=torch.float32, device=dev)
-    out = torch.zeros(s.out_elems, dtype=torch.float32, device=dev)
+    out = torch.zeros(s.out_elems, dtype=tdt[odt], device=dev)
     ws = torch.empty(s.workspace_bytes // 4 + 64, dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream(dev)
     sh = stream.cuda_stream
@@ -207,15 +214,16 @@ def main():
     payload_mat = s.payload_elems - s.n_vec_elems
     L = s.n_vec_elems
     # algorithmic bytes per launch of each kernel (fp32): what the kernel itself has to move
+    gsz, osz = (2 if gdt == "bf16" else 4), (2 if odt == "bf16" else 4)
     kernel_bytes = {
-        "k_ef_right": payload_mat * W * 12,                       # read g, read e, write M
-        "k_left": payload_mat * W * 4,                            # read M
-        "k_decomp": payload_mat * (W * 8 + 4) + L * (W * 4 + 4),  # read M, write e', write Delta' once
+        "k_ef_right": payload_mat * W * (gsz + 8),                          # read g, read e, write M
+        "k_left": payload_mat * W * 4,                                      # read M
+        "k_decomp": payload_mat * (W * 8 + osz) + L * (W * gsz + osz),      # read M, write e', write Delta' once
         "k_resident": int(s.bytes_min),                           # read g, e; write e', Delta': each once
     }
     dom = max(kernel_bytes, key=lambda k: kavg.get(k, 0.0))
     achieved = kernel_bytes[dom] / (kavg[dom] * 1e-3) / 1e9 if kavg[dom] > 0 else 0.0
-    grad_bytes = W * (payload_mat + L) * 4
+    grad_bytes = W * (payload_mat + L) * gsz
     value = grad_bytes / (ms_per_step * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC.get((wl.name, rank, W, dom))
 
@@ -230,10 +238,11 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f32" if gdt == "f32" else "f32 (bf16 gradients)",
         "data": "synthetic",
-        "config": {"workload": "%s-shaped gradient set, W=%d simulated worker(s), rank %d, fp32" % (wl.name, W, rank),
-                   "mode": "resident (one kernel, M kept in registers)" if resident else "streaming (five kernels)",
+        "config": {"workload": "%s-shaped gradient set, W=%d simulated worker(s), rank %d, gradients %s, output %s"
+                               % (wl.name, W, rank, gdt, odt),
+                   "mode": "resident (one kernel, M kept in registers)" if resident else "streaming (one kernel per phase)",
                    "matrices": int(s.n_matrices), "matrix_elems": int(payload_mat), "vector_elems": int(L),
                    "grad_buffers": len(grads)},
         "stream_model": {"bytes_per_step": int(s.bytes_stream),
