@@ -64,97 +64,202 @@ __device__ __forceinline__ void store_out4(void* base, int64_t idx, v4f v) {
     }
 }
 
+// ---- buffer addressing ----------------------------------------------------------------------------------
+// Raw buffer descriptors (base, byte range) let a wavefront address a tile with one 32-bit lane offset per
+// access: a lane whose offset lies at or beyond the range reads zeros and its stores are dropped, so ragged
+// tiles need no branches.  The whole address goes into the lane offset (the scalar offset operand is not
+// part of the range check).  Ranges and offsets stay below 2^31 bytes (row lengths are limited when the
+// plan is made), which makes kOutOfRange, and kOutOfRange plus any valid offset, out of range for every
+// descriptor.
+typedef __amdgpu_buffer_rsrc_t buf_rsrc;
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+constexpr unsigned kOutOfRange = 0x80000000u;
+constexpr int kRsrcFlags = 0x00020000;   // raw 32-bit data format word of gfx9-family descriptors
+
+__device__ __forceinline__ buf_rsrc make_rsrc(const void* base, int64_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, kRsrcFlags);
+}
+__device__ __forceinline__ float buf_load_f32(buf_rsrc r, unsigned off) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
+}
+__device__ __forceinline__ v4f buf_load_v4f(buf_rsrc r, unsigned off) {
+    const v4u x = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+    return v4f{__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w)};
+}
+__device__ __forceinline__ void buf_store_v4f(buf_rsrc r, unsigned off, v4f v) {
+    const v4u x{__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
+    __builtin_amdgcn_raw_buffer_store_b128(x, r, (int)off, 0, 0);
+}
+// four gradient elements, read once (non-temporal)
+template <bool BF>
+__device__ __forceinline__ v4f buf_load_grad4(buf_rsrc r, unsigned off) {
+    if constexpr (BF) {
+        const v2u x = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 2);
+        return v4f{__uint_as_float(x.x << 16), __uint_as_float(x.x & 0xffff0000u), __uint_as_float(x.y << 16),
+                   __uint_as_float(x.y & 0xffff0000u)};
+    } else {
+        const v4u x = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 2);
+        return v4f{__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w)};
+    }
+}
+
 // ---- k_hr_right: P_w = M Q ------------------------------------------------------------------------------
-// A wavefront owns a strip of rows (16 at a time) and walks the whole row in chunks of 64 columns;
-// per chunk it fetches the Q block of the chunk (B operands) and, for each 16-row step of its strip,
-// loads g and e, stores M and issues 16 NT instructions.  The accumulators of all steps stay in
-// registers across the chunks, so nothing is split over columns: one partial per worker.//
+// A workgroup owns a block of rows and walks the whole row in chunks of 64 columns.  Global memory is
+// touched in row-contiguous pieces only (a load instruction covers 4 rows x 64 columns: 256-byte runs of
+// e, 128- or 256-byte runs of g); M = g + e goes back over e in the same shape and into a 16 x 64 tile in
+// LDS private to the wavefront, from which the lanes fetch their A operands (row li, columns
+// 16 u + 4 kb ..+3).  The Q rows of the chunk (B operands) are staged in LDS once per workgroup, double
+// buffered, one barrier per chunk.  g and e of the next 16-row step are in flight while the current
+// one is multiplied.  The accumulators of the wavefront's 16 STEPS rows stay in registers across the
+// chunks.  Rows longer than the plan's column limit are split over workgroups, one partial P per worker
+// and column range, summed (in index order) by k_hr_gram.
+//
 // Above rank 8 the products are accumulated in fp64 (v_mfma_f64_16x16x4_f64, the fp32 operands widen
 // exactly): with r columns P spans singular directions whose weights differ by (sigma_1 / sigma_r)^2,
 // and the orthogonalisation divides every column by its own norm, so an error that is small against the
 // largest column is not small against the smallest.  fp32 accumulation leaves P_hat 2-3e-5 off at
 // r = 16 on a 1/k spectrum; fp64 accumulation (one rounding to fp32 at the end) keeps it at 1e-6.
 // The fp64 output tile is D[4 v + kb][li] (fp32: D[4 kb + v][li]).
-constexpr int kHrRightRows = 256;    // rows per workgroup
+constexpr int kHrChunk = 64;          // columns per chunk
+constexpr int kHrAStride = kHrChunk + 4;   // floats per LDS row of an A tile (b128 reads of 16 rows spread over the banks)
 
 typedef double v4d __attribute__((ext_vector_type(4)));
 
 template <int NT, bool BF, bool F64>
-__global__ __launch_bounds__(kBlock) void k_hr_right(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
-                                                     const void* __restrict__ grad, float* __restrict__ err,
-                                                     const float* __restrict__ q, float* __restrict__ ws,
-                                                     int64_t gstride, int64_t estride) {
-    // register budget: accumulators for STEPS 16-row steps and the B operands of U 16-column groups
-    constexpr int STEPS = (F64 && NT == 4) ? 1 : ((F64 && NT == 2) || NT == 4 ? 2 : 4);
-    constexpr int U = (F64 && NT >= 2) ? 2 : 4;
-    constexpr int ROWS_W = kHrRightRows / kWavesPerBlock;   // 64 rows per wavefront, in passes of 16 STEPS
+__global__ __launch_bounds__(kBlock, 2) void k_hr_right(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
+                                                        const void* __restrict__ grad, float* __restrict__ err,
+                                                        const float* __restrict__ q, float* __restrict__ ws,
+                                                        int64_t gstride, int64_t estride) {
+    constexpr int STEPS = 2;                          // 16-row steps per wavefront and pass: 128 rows per workgroup and pass
+    constexpr int RP = 16 * NT;                       // padded rank
+    constexpr int BST = RP + 4;                       // floats per LDS row of the staged Q chunk
+    constexpr int BPT = kHrChunk * RP / kBlock;       // staged Q elements per thread
     typedef typename std::conditional<F64, v4d, v4f>::type acc_t;
     typedef typename std::conditional<F64, double, float>::type b_t;
+    __shared__ float Bs[2][kHrChunk][BST];
+    __shared__ __attribute__((aligned(16))) float As[kWavesPerBlock][16][kHrAStride];
+
     const Tile t = tiles[blockIdx.x];
     const MatDesc d = mats[t.mat];
     const int w = blockIdx.y;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int li = lane & 15, kb = lane >> 4;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 15, kb = lane >> 4;      // matrix-core roles
+    const int lr = lane >> 4, lc = 4 * (lane & 15);   // loader roles: row within a group of 4, first column
     const int ri = d.r, m = d.m, n = d.n;
-    const int64_t goff = (int64_t)w * gstride + d.off;
-    float* e = err + (int64_t)w * estride + d.off;
+    constexpr int GS = BF ? 2 : 4;                  // bytes per gradient element
+    const char* gmat = static_cast<const char*>(grad) + ((int64_t)w * gstride + d.off) * GS;
+    float* emat = err + (int64_t)w * estride + d.off;
     const int row_end = min(n, t.row0 + t.nrows);
+    const int col0 = t.vec0;   // first of this workgroup's columns (a multiple of 64); they end with the row or at a multiple of 64
+    const int nchunks = (t.nvec + kHrChunk - 1) / kHrChunk;
+    const int part = w * d.n_cchunk + t.part;
+    float (*at)[kHrAStride] = As[wave];
 
-    for (int pass = 0; pass < ROWS_W / (16 * STEPS); ++pass) {
-        const int row_w = t.row0 + wave * ROWS_W + pass * 16 * STEPS;
-        if (row_w >= row_end) break;
+    // Q rows of a chunk: element idx of the 64 x RP block is Q[c0 + idx / RP][idx % RP]; rows past the
+    // matrix fall outside the buffer (zero), padded rank columns get the out-of-range offset themselves
+    const buf_rsrc qres = make_rsrc(q + d.q_off, (int64_t)m * ri * 4);
+    unsigned qoff[BPT];
+#pragma unroll
+    for (int k = 0; k < BPT; ++k) {
+        const int idx = tid + k * kBlock;
+        const int j = idx % RP;
+        qoff[k] = j < ri ? (unsigned)((idx / RP) * ri + j) * 4u : kOutOfRange;
+    }
+    auto stage_load = [&](int c0, float (&br)[BPT]) {
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) br[k] = buf_load_f32(qres, qoff[k] + (unsigned)(c0 * ri * 4));
+    };
+    auto stage_store = [&](int buf, const float (&br)[BPT]) {
+#pragma unroll
+        for (int k = 0; k < BPT; ++k) {
+            const int idx = tid + k * kBlock;
+            Bs[buf][idx / RP][idx % RP] = br[k];
+        }
+    };
+
+    for (int row_p = t.row0; row_p < row_end; row_p += kWavesPerBlock * 16 * STEPS) {
+        const int row_w = row_p + wave * 16 * STEPS;
         acc_t acc[STEPS][NT];
 #pragma unroll
         for (int s = 0; s < STEPS; ++s)
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) acc[s][nt] = acc_t{0, 0, 0, 0};
 
-        for (int c0 = 0; c0 < m; c0 += 16 * U) {
-            // B operands of the chunk: Q[c0 + 16 u + 4 kb + c][16 nt + li]
-            b_t bq[U][4][NT];
+        // Buffer descriptors whose range ends with the last valid row of the strip: the lanes' offsets
+        // (4 i + lr) m + lc are the same for every step and chunk, only the scalar offset moves, and rows
+        // past the end read zeros / drop their stores.  Columns past the row end (last chunk) are sent
+        // out of range explicitly.
+        const int rows_w = max(0, min(16 * STEPS, row_end - row_w));
+        const int64_t base_w = (int64_t)min(row_w, row_end) * m;
+        const buf_rsrc eres = make_rsrc(emat + base_w, (int64_t)rows_w * m * 4);
+        const buf_rsrc gres = make_rsrc(gmat + base_w * GS, (int64_t)rows_w * m * GS);
+        unsigned voff[4];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+        for (int i = 0; i < 4; ++i) voff[i] = (unsigned)(4 * i + lr) * (unsigned)m + (unsigned)lc;
+        // a step s starts 16 s rows further down: added to the lane offset (the range check looks at the lane
+        // offset only)
+        auto data_load = [&](int c0, int s, v4f (&gv)[4], v4f (&ev)[4]) {
+            const bool col_ok = c0 + lc < m;
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const int col = c0 + 16 * u + 4 * kb + c;
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) {
-                        const int j = 16 * nt + li;
-                        bq[u][c][nt] = (col < m && j < ri) ? (b_t)q[d.q_off + (int64_t)col * ri + j] : (b_t)0;
-                    }
-                }
+            for (int i = 0; i < 4; ++i) {
+                const unsigned el = voff[i] + (unsigned)(16 * s * m + c0);
+                gv[i] = buf_load_grad4<BF>(gres, col_ok ? el * GS : kOutOfRange);
+                ev[i] = buf_load_v4f(eres, col_ok ? el * 4u : kOutOfRange);
+            }
+        };
+
+        float br[BPT];
+        __syncthreads();   // the previous pass has finished with Bs
+        stage_load(col0, br);
+        stage_store(0, br);
+        v4f gn[4], en[4];
+        data_load(col0, 0, gn, en);
+        for (int ch = 0; ch < nchunks; ++ch) {
+            const int c0 = col0 + ch * kHrChunk;
+            const int buf = ch & 1;
+            __syncthreads();   // Bs[buf] is complete; Bs[buf ^ 1] is no longer read
+            const bool more = ch + 1 < nchunks;
+            if (more) stage_load(c0 + kHrChunk, br);
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
-                const int row = row_w + 16 * s + li;
-                const bool row_ok = row < row_end;
-                v4f gv[U], ev[U];
+                {
+                    const bool col_ok = c0 + lc < m;
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int col = c0 + 16 * u + 4 * kb;
-                    gv[u] = v4f{0.f, 0.f, 0.f, 0.f};
-                    ev[u] = v4f{0.f, 0.f, 0.f, 0.f};
-                    if (row_ok && col < m) {
-                        gv[u] = load_grad4<BF>(grad, goff + (int64_t)row * m + col);
-                        ev[u] = *reinterpret_cast<const v4f*>(e + (int64_t)row * m + col);
+                    for (int i = 0; i < 4; ++i) {
+                        const v4f mv = gn[i] + en[i];
+                        const unsigned el = voff[i] + (unsigned)(16 * s * m + c0);
+                        buf_store_v4f(eres, col_ok ? el * 4u : kOutOfRange, mv);
+                        *reinterpret_cast<v4f*>(&at[4 * i + lr][lc]) = mv;
                     }
                 }
+                // g and e of the next step (or of the next chunk's first step)
+                if (s + 1 < STEPS) data_load(c0, s + 1, gn, en);
+                else if (more) data_load(c0 + kHrChunk, 0, gn, en);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int col = c0 + 16 * u + 4 * kb;
-                    const v4f mv = gv[u] + ev[u];
-                    if (row_ok && col < m) *reinterpret_cast<v4f*>(e + (int64_t)row * m + col) = mv;
+                for (int u = 0; u < 4; ++u) {
+                    const v4f a = *reinterpret_cast<const v4f*>(&at[li][16 * u + 4 * kb]);
 #pragma unroll
                     for (int c = 0; c < 4; ++c)
 #pragma unroll
                         for (int nt = 0; nt < NT; ++nt) {
+                            const float b = Bs[buf][16 * u + 4 * kb + c][16 * nt + li];
                             if constexpr (F64)
-                                acc[s][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)mv[c], bq[u][c][nt], acc[s][nt], 0, 0, 0);
+                                acc[s][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a[c], (double)b, acc[s][nt], 0, 0, 0);
                             else
-                                acc[s][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(mv[c], bq[u][c][nt], acc[s][nt], 0, 0, 0);
+                                acc[s][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[c], b, acc[s][nt], 0, 0, 0);
                         }
                 }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             }
+            if (more) stage_store(buf ^ 1, br);
         }
 #pragma unroll
         for (int s = 0; s < STEPS; ++s)
@@ -165,7 +270,7 @@ __global__ __launch_bounds__(kBlock) void k_hr_right(const MatDesc* __restrict__
                 for (int v = 0; v < 4; ++v) {
                     const int row = row_w + 16 * s + (F64 ? 4 * v + kb : 4 * kb + v);
                     if (j < ri && row < row_end)
-                        ws[d.ppart_off + ((int64_t)w * n + row) * ri + j] = (float)acc[s][nt][v];
+                        ws[d.ppart_off + ((int64_t)part * n + row) * ri + j] = (float)acc[s][nt][v];
                 }
             }
     }
@@ -175,7 +280,7 @@ __global__ __launch_bounds__(kBlock) void k_hr_right(const MatDesc* __restrict__
 constexpr int kHrMaxRank = PSGD_MAX_RANK;
 constexpr int kHrGramRows = 128;   // panel rows staged in LDS at a time by the Gram kernel
 
-// Row block of kGramRows rows: mean P (sum over workers, * 1/W) -> P buffer; Gram matrix of the block in
+// Row block of kGramRows rows: mean P (sum over workers and column ranges, * 1/W) -> P buffer; Gram matrix of the block in
 // fp64 -> gram[block][r*r].  Thread t owns entries (a, b) with a * r + b = t, t + 256, ...
 __global__ __launch_bounds__(kBlock) void k_hr_gram(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                     const float* __restrict__ ws, float* __restrict__ p,
@@ -198,7 +303,7 @@ __global__ __launch_bounds__(kBlock) void k_hr_gram(const MatDesc* __restrict__ 
             const int i = idx / r, k = idx - i * r;
             const int64_t at = (int64_t)(r0 + i) * r + k;
             float s = 0.f;
-            for (int w = 0; w < workers; ++w) s += ws[d.ppart_off + (int64_t)w * nr + at];
+            for (int w = 0; w < workers * d.n_cchunk; ++w) s += ws[d.ppart_off + (int64_t)w * nr + at];
             s *= inv_w;
             rows[i][k] = s;
             p[d.p_off + at] = s;
@@ -403,66 +508,113 @@ __global__ __launch_bounds__(kBlock) void k_hr_left(const MatDesc* __restrict__ 
 // ---- k_hr_decomp: Delta' = P_hat Q^T, e' = M - Delta' -------------------------------------------------------
 // The product is formed transposed, (Q block 16 x K) (P_hat^T K x 16): A[li][kb] = Q[col0 + li][4 kk + kb],
 // B[kb][li] = P_hat[row0 + li][4 kk + kb], so that lane (kb, li) ends up with Delta'[row0 + li][col0 + 4 kb + v],
-// v = 0..3: four consecutive columns of one row, the same 16 bytes it loads of M and stores of e' and Delta'.
+// v = 0..3: four consecutive columns of one row, the same 16 bytes it loads of M and stores of e' and Delta'
+// (the eight column blocks of a step cover 512 contiguous bytes of each row).  The Q rows of the workgroup's
+// 128 columns are staged in LDS once; M and P_hat of the next 16-row step are in flight while the current one
+// is multiplied.  Buffer addressing: each wavefront's descriptors end with its last row.
 constexpr int kHrDecompBlocks = 8;   // 16-column blocks per wavefront (128 columns)
 
+template <bool BF>
+__device__ __forceinline__ void buf_store_out4(buf_rsrc r, unsigned off, v4f v) {
+    if constexpr (BF) {
+        v2u x;
+        x.x = (unsigned)f32_to_bf16(v.x) | ((unsigned)f32_to_bf16(v.y) << 16);
+        x.y = (unsigned)f32_to_bf16(v.z) | ((unsigned)f32_to_bf16(v.w) << 16);
+        __builtin_amdgcn_raw_buffer_store_b64(x, r, (int)off, 0, 0);
+    } else {
+        buf_store_v4f(r, off, v);
+    }
+}
+
 template <int NT, bool BF>
-__global__ __launch_bounds__(kBlock) void k_hr_decomp(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
-                                                      float* __restrict__ err, const float* __restrict__ p,
-                                                      const float* __restrict__ q, void* __restrict__ out,
-                                                      int64_t estride) {
+__global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
+                                                         float* __restrict__ err, const float* __restrict__ p,
+                                                         const float* __restrict__ q, void* __restrict__ out,
+                                                         int64_t estride) {
     constexpr int KK = 4 * NT;   // instructions per 16 x 16 block (K = 16 NT in steps of 4)
     constexpr int CB = kHrDecompBlocks;
+    constexpr int RP = 16 * NT;
+    constexpr int QST = RP + 4;  // floats per LDS row of the staged Q block
+    constexpr int OS = BF ? 2 : 4;
+    __shared__ float Qs[16 * CB][QST];
     const Tile t = tiles[blockIdx.x];
     const MatDesc d = mats[t.mat];
     const int w = blockIdx.y;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, kb = lane >> 4;
     const int ri = d.r, m = d.m;
-    float* e = err + (int64_t)w * estride + d.off;
     const int c0 = t.vec0;
     const int c_end = min(m, c0 + t.nvec);
 
-    float aq[CB][KK];
+    {
+        const buf_rsrc qres = make_rsrc(q + d.q_off, (int64_t)m * ri * 4);
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb) {
-        const int col = c0 + 16 * cb + li;
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            const int k = 4 * kk + kb;
-            aq[cb][kk] = (col < c_end && k < ri) ? q[d.q_off + (int64_t)col * ri + k] : 0.f;
+        for (int x = 0; x < 16 * CB * RP / kBlock; ++x) {
+            const int idx = tid + x * kBlock;
+            const int col = idx / RP, k = idx % RP;
+            const unsigned off = (k < ri && c0 + col < c_end) ? (unsigned)((c0 + col) * ri + k) * 4u : kOutOfRange;
+            Qs[col][k] = buf_load_f32(qres, off);
         }
     }
+    __syncthreads();
+
     int rb, rn;
     wave_rows(t.nrows, wave, &rb, &rn);
-    const int r_begin = t.row0 + rb, r_end = r_begin + rn;
-    for (int r0 = r_begin; r0 < r_end; r0 += 16) {
-        const int row = r0 + li;
-        const bool row_ok = row < r_end;
+    const int r_begin = t.row0 + rb;
+    const int64_t ebase = (int64_t)r_begin * m;
+    const buf_rsrc eres = make_rsrc(err + (int64_t)w * estride + d.off + ebase, (int64_t)rn * m * 4);
+    const buf_rsrc ores = make_rsrc(static_cast<char*>(out) + (d.off + ebase) * OS, (int64_t)rn * m * OS);
+    const buf_rsrc pres = make_rsrc(p + d.p_off + (int64_t)r_begin * ri, (int64_t)rn * ri * 4);
+    // lane offsets in elements, relative to the first row of the strip; out of range where the column (of M) or
+    // the rank index (of P_hat) does not exist
+    unsigned eo[CB], po[KK];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) {
+        const int col = c0 + 16 * cb + 4 * kb;
+        eo[cb] = col < c_end ? (unsigned)(li * m + col) : kOutOfRange;
+    }
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        const int k = 4 * kk + kb;
+        po[kk] = k < ri ? (unsigned)(li * ri + k) : kOutOfRange;
+    }
+    // an out-of-range marker stays out of range after scaling and stepping: the element offsets below are
+    // under 2^26, so it is kept apart by using byte offsets only at the access
+    auto e_off = [&](int cb, int step_el, int bytes) -> unsigned {
+        return eo[cb] == kOutOfRange ? kOutOfRange : (eo[cb] + (unsigned)step_el) * (unsigned)bytes;
+    };
+    auto load_step = [&](int r_rel, v4f (&mv)[CB], float (&bp)[KK]) {
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+            bp[kk] = buf_load_f32(pres, po[kk] == kOutOfRange ? kOutOfRange : (po[kk] + (unsigned)(r_rel * ri)) * 4u);
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) mv[cb] = buf_load_v4f(eres, e_off(cb, r_rel * m, 4));
+    };
+
+    v4f mvn[CB];
+    float bpn[KK];
+    load_step(0, mvn, bpn);
+    for (int r_rel = 0; r_rel < rn; r_rel += 16) {
+        v4f mv[CB];
         float bp[KK];
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            const int k = 4 * kk + kb;
-            bp[kk] = (row_ok && k < ri) ? p[d.p_off + (int64_t)row * ri + k] : 0.f;
-        }
-        v4f mv[CB];
+        for (int cb = 0; cb < CB; ++cb) mv[cb] = mvn[cb];
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-            const int col = c0 + 16 * cb + 4 * kb;
-            mv[cb] = v4f{0.f, 0.f, 0.f, 0.f};
-            if (row_ok && col < c_end) mv[cb] = *reinterpret_cast<const v4f*>(e + (int64_t)row * m + col);
-        }
+        for (int kk = 0; kk < KK; ++kk) bp[kk] = bpn[kk];
+        if (r_rel + 16 < rn) load_step(r_rel + 16, mvn, bpn);
+        // at two and four rank tiles the Q operands are fetched from LDS at every step instead of being kept
+        // in registers for the whole strip (64 or 128 of them)
+        if constexpr (NT >= 2) asm volatile("" ::: "memory");
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
             v4f acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(aq[cb][kk], bp[kk], acc, 0, 0, 0);
-            const int col = c0 + 16 * cb + 4 * kb;
-            if (row_ok && col < c_end) {
-                *reinterpret_cast<v4f*>(e + (int64_t)row * m + col) = mv[cb] - acc;
-                if (w == 0) store_out4<BF>(out, d.off + (int64_t)row * m + col, acc);
-            }
+            for (int kk = 0; kk < KK; ++kk)
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Qs[16 * cb + li][4 * kk + kb], bp[kk], acc, 0, 0, 0);
+            buf_store_v4f(eres, e_off(cb, r_rel * m, 4), mv[cb] - acc);
+            if (w == 0) buf_store_out4<BF>(ores, e_off(cb, r_rel * m, OS), acc);
         }
     }
 }

@@ -65,7 +65,9 @@ void build_resident(psgd_plan* plan);
 // Matrix-core path: its own tilings and workspace layout.
 static psgd_status build_hr_tables(psgd_plan* plan) {
     const Tuning& tu = plan->tuning;
-    if (tu.hr_k3_rows < 64) return PSGD_EINVAL;
+    if (tu.hr_k3_rows < 64 || tu.hr_k1_rows < 64 || tu.hr_k1_rows > 256 || tu.hr_k1_rows % 64 != 0 ||
+        tu.hr_k1_cols < 64 || tu.hr_k1_cols % 64 != 0)
+        return PSGD_EINVAL;
     const int64_t W = plan->workers;
     const size_t nm = plan->mats.size();
     plan->tiles1.clear(); plan->tiles3.clear(); plan->tiles4.clear(); plan->tilesp.clear();
@@ -73,27 +75,30 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
     plan->hr_tiles1.clear(); plan->hr_tiles3.clear(); plan->hr_tiles4.clear();
     plan->k1_on_mfma = false;
     plan->p_pre_reduce = false;
-    const int64_t right_rows = 256;   // 4 wavefronts x 64 rows (kHrRightRows)
+    const int64_t right_rows = tu.hr_k1_rows;
     const int64_t decomp_rows = 256;
     int64_t pp = 0, qp = 0, gp = 0, cp = 0;
     for (size_t i = 0; i < nm; ++i) {
         MatDesc& d = plan->mats[i];
-        d.n_cchunk = 1;
+        d.n_cchunk = (int32_t)ceil_div(d.m, tu.hr_k1_cols);
         const int64_t nrb = ceil_div(d.n, tu.hr_k3_rows);
         d.n_rblock = (int32_t)(nrb * kWavesPerBlock);
-        d.n_gblock = (int32_t)ceil_div(d.n, kGramRows);
+        d.n_gblock = (int32_t)ceil_div(d.n, kHrGramTileRows);
         d.ppart_off = pp;
-        pp += round_up(W * d.n * d.r, kAlignElems);
+        pp += round_up(W * d.n_cchunk * d.n * d.r, kAlignElems);
         d.gram_off = gp;
         gp += round_up((int64_t)d.n_gblock * d.r * d.r, 32);
         d.chol_off = cp;
         cp += round_up((int64_t)d.r * d.r + d.r, 32);
-        for (int64_t r0 = 0; r0 < d.n; r0 += right_rows) {
-            Tile t{};
-            t.mat = (int32_t)i; t.row0 = (int32_t)r0; t.nrows = (int32_t)std::min<int64_t>(right_rows, d.n - r0);
-            t.vec0 = 0; t.nvec = d.m;
-            plan->hr_tiles1.push_back(t);
-        }
+        for (int64_t r0 = 0; r0 < d.n; r0 += right_rows)
+            for (int64_t cc = 0; cc < d.n_cchunk; ++cc) {
+                Tile t{};
+                t.mat = (int32_t)i; t.row0 = (int32_t)r0; t.nrows = (int32_t)std::min<int64_t>(right_rows, d.n - r0);
+                t.vec0 = (int32_t)(cc * tu.hr_k1_cols);
+                t.nvec = (int32_t)std::min<int64_t>(tu.hr_k1_cols, d.m - t.vec0);
+                t.part = (int32_t)cc;
+                plan->hr_tiles1.push_back(t);
+            }
         for (int64_t b = 0; b < nrb; ++b)
             for (int64_t c0 = 0; c0 < d.m; c0 += 128) {
                 Tile t{};
@@ -112,7 +117,7 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
             }
         for (int32_t b = 0; b < d.n_gblock; ++b) {
             Tile t{};
-            t.mat = (int32_t)i; t.row0 = b * kGramRows; t.nrows = std::min<int32_t>(kGramRows, d.n - t.row0);
+            t.mat = (int32_t)i; t.row0 = b * kHrGramTileRows; t.nrows = std::min<int32_t>(kHrGramTileRows, d.n - t.row0);
             t.part = b;
             plan->tiles_gram.push_back(t);
         }
@@ -432,10 +437,11 @@ psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_
     }
     if (rank > PSGD_MAX_RANK) return PSGD_EUNSUPPORTED;
     // ranks above 8 and bf16 data run on the matrix-core kernels, which need row lengths that are multiples of 4
+    // and short enough for 32-bit byte offsets within a tile of rows
     const bool needs_hr = rank > kValuMaxRank || grad_dtype != PSGD_F32 || out_dtype != PSGD_F32;
     if (needs_hr)
         for (int32_t t = 0; t < n_tensors; ++t)
-            if (shapes[t].cols != 1 && shapes[t].cols % 4 != 0) return PSGD_EUNSUPPORTED;
+            if (shapes[t].cols != 1 && (shapes[t].cols % 4 != 0 || shapes[t].cols > kHrMaxCols)) return PSGD_EUNSUPPORTED;
 
     psgd_plan* plan = new (std::nothrow) psgd_plan();
     if (!plan) return PSGD_ENOMEM;
@@ -556,6 +562,8 @@ psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value
     else if (!strcmp(key, "q_reduce_elems")) tu.q_reduce_elems = value;
     else if (!strcmp(key, "k1_mfma")) tu.k1_mfma = value;
     else if (!strcmp(key, "hr_k3_rows")) tu.hr_k3_rows = value;
+    else if (!strcmp(key, "hr_k1_rows")) tu.hr_k1_rows = value;
+    else if (!strcmp(key, "hr_k1_cols")) tu.hr_k1_cols = value;
     else if (!strcmp(key, "resident")) tu.resident = value;
     else if (!strcmp(key, "res_rows")) tu.res_rows = value;
     else if (!strcmp(key, "res_trace")) tu.res_trace = value;

@@ -300,7 +300,9 @@ static void check_hr_plan(const std::vector<psgd_shape>& shapes, int rank, int w
             const MatDesc& d = plan->mats[t.mat];
             CHECK(d.m % 4 == 0 && t.row0 >= 0 && t.nrows > 0 && t.row0 + t.nrows <= d.n);
             CHECK(t.vec0 >= 0 && t.vec0 % 4 == 0 && t.nvec > 0 && t.vec0 + t.nvec <= d.m);
-            if (full_rows) CHECK(t.vec0 == 0 && t.nvec == d.m && t.nrows <= 256);
+            if (full_rows)   // P = M Q tiles: column ranges start at multiples of 64, name their partial, bytes fit 31 bits
+                CHECK(t.vec0 % 64 == 0 && t.nrows <= 256 && t.part >= 0 && t.part < d.n_cchunk &&
+                      t.vec0 == (int64_t)t.part * plan->tuning.hr_k1_cols && (int64_t)t.nrows * d.m * 4 < (1LL << 31));
             else CHECK(t.nvec <= 128);
             for (int i = t.row0; i < t.row0 + t.nrows; ++i)
                 for (int j = t.vec0; j < t.vec0 + t.nvec; ++j) {
@@ -322,13 +324,13 @@ static void check_hr_plan(const std::vector<psgd_shape>& shapes, int rank, int w
     std::vector<int64_t> rows(plan->mats.size(), 0);
     for (const Tile& t : plan->tiles_gram) {
         const MatDesc& d = plan->mats[t.mat];
-        CHECK(t.part >= 0 && t.part < d.n_gblock && t.row0 == rows[t.mat] && t.nrows > 0 && t.nrows <= kGramRows);
+        CHECK(t.part >= 0 && t.part < d.n_gblock && t.row0 == rows[t.mat] && t.nrows > 0 && t.nrows <= kHrGramTileRows);
         rows[t.mat] += t.nrows;
     }
     for (size_t i = 0; i < plan->mats.size(); ++i) {
         const MatDesc& d = plan->mats[i];
-        CHECK(rows[i] == d.n && d.n_cchunk == 1);
-        CHECK(d.ppart_off >= 0 && d.ppart_off + (int64_t)workers * d.n * d.r <= plan->ws_ppart_floats);
+        CHECK(rows[i] == d.n && d.n_cchunk == (d.m + plan->tuning.hr_k1_cols - 1) / plan->tuning.hr_k1_cols);
+        CHECK(d.ppart_off >= 0 && d.ppart_off + (int64_t)workers * d.n_cchunk * d.n * d.r <= plan->ws_ppart_floats);
         CHECK(d.qpart_off >= plan->ws_ppart_floats &&
               d.qpart_off + (int64_t)workers * d.n_rblock * d.m * d.r <= plan->ws_ppart_floats + plan->ws_qpart_floats);
         CHECK(d.gram_off >= 0 && d.gram_off + (int64_t)d.n_gblock * d.r * d.r <= plan->ws_gram_doubles);
@@ -372,7 +374,8 @@ int main() {
                 check_plan(s, rank, W, &big);
             }
     {
-        std::vector<psgd_shape> tr = {{1000, 256}, {256, 256}, {77, 1}, {1024, 256}, {256, 1024}, {20, 12}, {3000, 64}};
+        std::vector<psgd_shape> tr = {{1000, 256}, {256, 256}, {77, 1}, {1024, 256}, {256, 1024}, {20, 12}, {3000, 64},
+                                      {130, 2308}, {64, 4096}};
         for (int rank : {9, 16, 17, 32, 64})
             for (int W : {1, 2}) check_hr_plan(tr, rank, W);
         // a row length that is not a multiple of 4 is refused on this path

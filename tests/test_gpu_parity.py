@@ -164,7 +164,8 @@ def test_matrix_core_right_product(rank):
          expect_resident=False)
 
 
-TRANSFORMER_SMALL = [(1000, 256), (256,), (256, 256), (256, 256), (1024, 256), (1024,), (256, 1024), (20, 12), (3000, 64)]
+TRANSFORMER_SMALL = [(1000, 256), (256,), (256, 256), (256, 256), (1024, 256), (1024,), (256, 1024), (20, 12), (3000, 64),
+                     (130, 2308)]
 
 
 @pytest.mark.parametrize("rank,workers,gbf,obf", [(16, 1, False, False), (32, 2, False, False), (9, 1, False, False),
@@ -178,6 +179,18 @@ def test_matrix_core_path(rank, workers, gbf, obf):
     from paper_1905_13727_amd import workloads as WL
     wl = WL.Workload("tr-small", list(TRANSFORMER_SMALL), 64, 1.0 / np.arange(1, 65), 0.001)
     _run(wl, rank=rank, workers=workers, steps=3, seed=60 + rank, expect_resident=False, grad_bf16=gbf, out_bf16=obf)
+
+
+@pytest.mark.parametrize("rows,cols", [(64, 64), (256, 192), (128, 4096)])
+def test_matrix_core_tilings(rows, cols):
+    """P = M Q on the matrix cores with rows split into many column ranges (partials summed in
+    index order), one range only, and the tallest workgroup tile."""
+    _need_gpu()
+    from paper_1905_13727_amd import workloads as WL
+    wl = WL.Workload("tr-small", list(TRANSFORMER_SMALL), 64, 1.0 / np.arange(1, 65), 0.001)
+    tuning = {"hr_k1_rows": rows, "hr_k1_cols": cols}
+    _run(wl, rank=16, workers=2, steps=2, seed=77, expect_resident=False, tuning=tuning)
+    _run(wl, rank=4, workers=1, steps=2, seed=78, expect_resident=False, tuning=tuning, grad_bf16=True)
 
 
 def test_small_tiles_many_partials():
