@@ -33,36 +33,16 @@ typedef unsigned short bf16_t;
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float((unsigned)h << 16); }
 
-// round to nearest even; NaN stays NaN
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-    unsigned u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+// fp32 -> bf16, round to nearest even (NaN stays NaN): the conversion instruction of the matrix-core generation
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+    const v2bf y = __builtin_convertvector(v2f{lo, hi}, v2bf);
+    unsigned u;
+    __builtin_memcpy(&u, &y, 4);
+    return u;
 }
-
-template <bool BF>
-__device__ __forceinline__ v4f load_grad4(const void* base, int64_t idx) {
-    if constexpr (BF) {
-        typedef unsigned short us4 __attribute__((ext_vector_type(4)));
-        const us4 h = __builtin_nontemporal_load(reinterpret_cast<const us4*>(static_cast<const bf16_t*>(base) + idx));
-        return v4f{bf16_to_f32(h.x), bf16_to_f32(h.y), bf16_to_f32(h.z), bf16_to_f32(h.w)};
-    } else {
-        return __builtin_nontemporal_load(reinterpret_cast<const v4f*>(static_cast<const float*>(base) + idx));
-    }
-}
-
-template <bool BF>
-__device__ __forceinline__ void store_out4(void* base, int64_t idx, v4f v) {
-    if constexpr (BF) {
-        typedef unsigned short us4 __attribute__((ext_vector_type(4)));
-        us4 h;
-        h.x = f32_to_bf16(v.x); h.y = f32_to_bf16(v.y); h.z = f32_to_bf16(v.z); h.w = f32_to_bf16(v.w);
-        *reinterpret_cast<us4*>(static_cast<bf16_t*>(base) + idx) = h;
-    } else {
-        *reinterpret_cast<v4f*>(static_cast<float*>(base) + idx) = v;
-    }
-}
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
 
 // ---- buffer addressing ----------------------------------------------------------------------------------
 // Raw buffer descriptors (base, byte range) let a wavefront address a tile with one 32-bit lane offset per
@@ -77,8 +57,14 @@ typedef unsigned v2u __attribute__((ext_vector_type(2)));
 constexpr unsigned kOutOfRange = 0x80000000u;
 constexpr int kRsrcFlags = 0x00020000;   // raw 32-bit data format word of gfx9-family descriptors
 
+// base and bytes must be the same in every lane of the wavefront; they are moved to scalar registers here so
+// that the descriptor is one (a descriptor held in vector registers makes every access a loop over its values)
 __device__ __forceinline__ buf_rsrc make_rsrc(const void* base, int64_t bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, kRsrcFlags);
+    const unsigned long long b = reinterpret_cast<unsigned long long>(base);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)b);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32));
+    const int nb = __builtin_amdgcn_readfirstlane((int)bytes);
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((unsigned long long)hi << 32) | lo), 0, nb, kRsrcFlags);
 }
 __device__ __forceinline__ float buf_load_f32(buf_rsrc r, unsigned off) {
     return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
@@ -127,7 +113,7 @@ constexpr int kHrAStride = kHrChunk + 4;   // floats per LDS row of an A tile (b
 typedef double v4d __attribute__((ext_vector_type(4)));
 
 template <int NT, bool BF, bool F64>
-__global__ __launch_bounds__(kBlock, 2) void k_hr_right(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
+__global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                         const void* __restrict__ grad, float* __restrict__ err,
                                                         const float* __restrict__ q, float* __restrict__ ws,
                                                         int64_t gstride, int64_t estride) {
@@ -168,9 +154,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_right(const MatDesc* __restric
         const int j = idx % RP;
         qoff[k] = j < ri ? (unsigned)((idx / RP) * ri + j) * 4u : kOutOfRange;
     }
-    auto stage_load = [&](int c0, float (&br)[BPT]) {
+    auto stage_load = [&](int c0, bool wanted, float (&br)[BPT]) {
 #pragma unroll
-        for (int k = 0; k < BPT; ++k) br[k] = buf_load_f32(qres, qoff[k] + (unsigned)(c0 * ri * 4));
+        for (int k = 0; k < BPT; ++k) br[k] = buf_load_f32(qres, wanted ? qoff[k] + (unsigned)(c0 * ri * 4) : kOutOfRange);
     };
     auto stage_store = [&](int buf, const float (&br)[BPT]) {
 #pragma unroll
@@ -201,8 +187,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_right(const MatDesc* __restric
         for (int i = 0; i < 4; ++i) voff[i] = (unsigned)(4 * i + lr) * (unsigned)m + (unsigned)lc;
         // a step s starts 16 s rows further down: added to the lane offset (the range check looks at the lane
         // offset only)
-        auto data_load = [&](int c0, int s, v4f (&gv)[4], v4f (&ev)[4]) {
-            const bool col_ok = c0 + lc < m;
+        auto data_load = [&](int c0, int s, bool wanted, v4f (&gv)[4], v4f (&ev)[4]) {
+            const bool col_ok = wanted && c0 + lc < m;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const unsigned el = voff[i] + (unsigned)(16 * s * m + c0);
@@ -213,16 +199,18 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_right(const MatDesc* __restric
 
         float br[BPT];
         __syncthreads();   // the previous pass has finished with Bs
-        stage_load(col0, br);
+        stage_load(col0, true, br);
         stage_store(0, br);
         v4f gn[4], en[4];
-        data_load(col0, 0, gn, en);
+        data_load(col0, 0, true, gn, en);
         for (int ch = 0; ch < nchunks; ++ch) {
             const int c0 = col0 + ch * kHrChunk;
             const int buf = ch & 1;
             __syncthreads();   // Bs[buf] is complete; Bs[buf ^ 1] is no longer read
+            // requests past the last chunk are sent out of range (nothing is fetched): no branch around a request,
+            // so the waits below count exactly what is outstanding
             const bool more = ch + 1 < nchunks;
-            if (more) stage_load(c0 + kHrChunk, br);
+            stage_load(c0 + kHrChunk, more, br);
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
                 {
@@ -236,8 +224,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_right(const MatDesc* __restric
                     }
                 }
                 // g and e of the next step (or of the next chunk's first step)
-                if (s + 1 < STEPS) data_load(c0, s + 1, gn, en);
-                else if (more) data_load(c0 + kHrChunk, 0, gn, en);
+                if (s + 1 < STEPS) data_load(c0, s + 1, true, gn, en);
+                else data_load(c0 + kHrChunk, 0, more, gn, en);
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -518,8 +506,8 @@ template <bool BF>
 __device__ __forceinline__ void buf_store_out4(buf_rsrc r, unsigned off, v4f v) {
     if constexpr (BF) {
         v2u x;
-        x.x = (unsigned)f32_to_bf16(v.x) | ((unsigned)f32_to_bf16(v.y) << 16);
-        x.y = (unsigned)f32_to_bf16(v.z) | ((unsigned)f32_to_bf16(v.w) << 16);
+        x.x = pack_bf16x2(v.x, v.y);
+        x.y = pack_bf16x2(v.z, v.w);
         __builtin_amdgcn_raw_buffer_store_b64(x, r, (int)off, 0, 0);
     } else {
         buf_store_v4f(r, off, v);
@@ -550,12 +538,19 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restri
 
     {
         const buf_rsrc qres = make_rsrc(q + d.q_off, (int64_t)m * ri * 4);
+        constexpr int QPT = 16 * CB * RP / kBlock;   // staged elements per thread: all requested before the first is stored
+        float qv[QPT];
 #pragma unroll
-        for (int x = 0; x < 16 * CB * RP / kBlock; ++x) {
+        for (int x = 0; x < QPT; ++x) {
             const int idx = tid + x * kBlock;
             const int col = idx / RP, k = idx % RP;
             const unsigned off = (k < ri && c0 + col < c_end) ? (unsigned)((c0 + col) * ri + k) * 4u : kOutOfRange;
-            Qs[col][k] = buf_load_f32(qres, off);
+            qv[x] = buf_load_f32(qres, off);
+        }
+#pragma unroll
+        for (int x = 0; x < QPT; ++x) {
+            const int idx = tid + x * kBlock;
+            Qs[idx / RP][idx % RP] = qv[x];
         }
     }
     __syncthreads();
@@ -565,7 +560,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restri
     const int r_begin = t.row0 + rb;
     const int64_t ebase = (int64_t)r_begin * m;
     const buf_rsrc eres = make_rsrc(err + (int64_t)w * estride + d.off + ebase, (int64_t)rn * m * 4);
-    const buf_rsrc ores = make_rsrc(static_cast<char*>(out) + (d.off + ebase) * OS, (int64_t)rn * m * OS);
+    const buf_rsrc ores = make_rsrc(static_cast<char*>(out) + (d.off + ebase) * OS, w == 0 ? (int64_t)rn * m * OS : 0);
     const buf_rsrc pres = make_rsrc(p + d.p_off + (int64_t)r_begin * ri, (int64_t)rn * ri * 4);
     // lane offsets in elements, relative to the first row of the strip; out of range where the column (of M) or
     // the rank index (of P_hat) does not exist
@@ -603,7 +598,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restri
         for (int cb = 0; cb < CB; ++cb) mv[cb] = mvn[cb];
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) bp[kk] = bpn[kk];
-        if (r_rel + 16 < rn) load_step(r_rel + 16, mvn, bpn);
+        load_step(r_rel + 16, mvn, bpn);   // past the strip's last row: out of range, nothing is fetched
         // at two and four rank tiles the Q operands are fetched from LDS at every step instead of being kept
         // in registers for the whole strip (64 or 128 of them)
         if constexpr (NT >= 2) asm volatile("" ::: "memory");
@@ -614,7 +609,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restri
             for (int kk = 0; kk < KK; ++kk)
                 acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Qs[16 * cb + li][4 * kk + kb], bp[kk], acc, 0, 0, 0);
             buf_store_v4f(eres, e_off(cb, r_rel * m, 4), mv[cb] - acc);
-            if (w == 0) buf_store_out4<BF>(ores, e_off(cb, r_rel * m, OS), acc);
+            buf_store_out4<BF>(ores, e_off(cb, r_rel * m, OS), acc);   // dropped for workers other than the first (empty range)
         }
     }
 }
