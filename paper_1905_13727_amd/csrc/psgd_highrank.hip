@@ -154,9 +154,13 @@ __global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatD
         const int j = idx % RP;
         qoff[k] = j < ri ? (unsigned)((idx / RP) * ri + j) * 4u : kOutOfRange;
     }
+    // an unwanted request (past the last chunk) goes through a descriptor with an empty range: nothing is fetched,
+    // and no branch surrounds the request, so the waits count exactly what is outstanding
+    const buf_rsrc nores = make_rsrc(q + d.q_off, 0);
     auto stage_load = [&](int c0, bool wanted, float (&br)[BPT]) {
+        const buf_rsrc res = wanted ? qres : nores;
 #pragma unroll
-        for (int k = 0; k < BPT; ++k) br[k] = buf_load_f32(qres, wanted ? qoff[k] + (unsigned)(c0 * ri * 4) : kOutOfRange);
+        for (int k = 0; k < BPT; ++k) br[k] = buf_load_f32(res, qoff[k] + (unsigned)(c0 * ri * 4));
     };
     auto stage_store = [&](int buf, const float (&br)[BPT]) {
 #pragma unroll
@@ -188,12 +192,13 @@ __global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatD
         // a step s starts 16 s rows further down: added to the lane offset (the range check looks at the lane
         // offset only)
         auto data_load = [&](int c0, int s, bool wanted, v4f (&gv)[4], v4f (&ev)[4]) {
-            const bool col_ok = wanted && c0 + lc < m;
+            const bool col_ok = c0 + lc < m;
+            const buf_rsrc gr = wanted ? gres : nores, er = wanted ? eres : nores;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const unsigned el = voff[i] + (unsigned)(16 * s * m + c0);
-                gv[i] = buf_load_grad4<BF>(gres, col_ok ? el * GS : kOutOfRange);
-                ev[i] = buf_load_v4f(eres, col_ok ? el * 4u : kOutOfRange);
+                gv[i] = buf_load_grad4<BF>(gr, col_ok ? el * GS : kOutOfRange);
+                ev[i] = buf_load_v4f(er, col_ok ? el * 4u : kOutOfRange);
             }
         };
 
