@@ -112,7 +112,8 @@ PSGD_API psgd_status psgd_plan_sizes(const psgd_plan* plan, psgd_sizes* out_size
 
 /* Placement of tensor `tensor` (index into the shapes array).
  *   flat_off   offset in the flat [N+L] layout (matrix region or vector region)
- *   p_off, q_off, eff_rank   for matrices; -1, -1, 0 for vectors
+ *   p_off, q_off, eff_rank   for matrices (offsets are multiples of 4 floats: each
+ *                            factor is padded to a 16-byte boundary); -1, -1, 0 for vectors
  * Any output pointer may be NULL. */
 PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, int64_t* flat_off,
                               int64_t* p_off, int64_t* q_off, int32_t* eff_rank);

@@ -59,6 +59,41 @@ __device__ __forceinline__ void stv<4>(float* p, const float (&x)[4]) {
     *reinterpret_cast<f4*>(p) = t;
 }
 
+// Rows of a factor that belong to V consecutive matrix columns (or rows): the V * ri consecutive floats at
+// `rows` -> f[V][R], zero beyond ri and everything zero when !valid.  With ri == R (the usual case; ri < R
+// only for matrices smaller than the rank) they are fetched with the widest aligned vector loads instead of
+// V * R scattered dwords.  `rows` must be 16-byte aligned when V * R is a multiple of 4, 8-byte aligned when
+// it is even (factor offsets are multiples of 4 floats and the first column is a multiple of V).
+template <int R, int V>
+__device__ __forceinline__ void load_factor_rows(const float* rows, int ri, bool valid, float (&f)[V][R]) {
+    constexpr int N = V * R;
+    constexpr int WD = N % 4 == 0 ? 4 : (N % 2 == 0 ? 2 : 1);
+    if (ri == R) {
+        float buf[N];
+        if (valid) {
+#pragma unroll
+            for (int j = 0; j < N / WD; ++j) {
+                float t[WD];
+                ldv<WD>(rows + WD * j, t);
+#pragma unroll
+                for (int x = 0; x < WD; ++x) buf[WD * j + x] = t[x];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < N; ++j) buf[j] = 0.f;
+        }
+#pragma unroll
+        for (int x = 0; x < V; ++x)
+#pragma unroll
+            for (int k = 0; k < R; ++k) f[x][k] = buf[x * R + k];
+    } else {
+#pragma unroll
+        for (int x = 0; x < V; ++x)
+#pragma unroll
+            for (int k = 0; k < R; ++k) f[x][k] = (valid && k < ri) ? rows[x * ri + k] : 0.f;
+    }
+}
+
 // ---- wavefront helpers ---------------------------------------------------------------------------
 
 __device__ __forceinline__ float lane_bcast(float v, int src_lane) {

@@ -23,6 +23,7 @@ constexpr int kPanelFloats = 12288;  // n*r up to this: Gram-Schmidt by one work
 constexpr int kGramRows = 1024;    // rows per workgroup of the tall-panel Gram / apply kernels
 constexpr int kPreReduceParts = 16; // more partial-P slices than this: a reduction kernel runs before the orthogonalisation
 constexpr int kOrthoMaxRows = 1024; // panels with more rows take the multi-workgroup route
+constexpr int kFactorAlignElems = 4;        // P and Q of a matrix start at multiples of 4 floats (vector loads of factor rows)
 constexpr int kHrGramTileRows = 128;       // matrix-core path: rows per workgroup of the mean-P / Gram / apply kernels
 constexpr int64_t kHrMaxCols = 1 << 20;   // matrix-core path: longest row (tiles of <= 256 rows are addressed with 31-bit byte offsets)
 constexpr int kMfmaCols = 128;     // super-row columns a wavefront covers per 16-row step in the matrix-core P = M Q kernel

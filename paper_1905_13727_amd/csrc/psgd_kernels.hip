@@ -52,11 +52,7 @@ __device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, c
         const int jv = lane + kWave * v;
         valid[v] = jv < t.nvec;
         col[v] = (t.vec0 + jv) * V;
-#pragma unroll
-        for (int x = 0; x < V; ++x)
-#pragma unroll
-            for (int k = 0; k < R; ++k)
-                qr[v][x][k] = (valid[v] && k < ri) ? q[d.q_off + (int64_t)(col[v] + x) * ri + k] : 0.f;
+        load_factor_rows<R, V>(q + d.q_off + (int64_t)col[v] * ri, ri, valid[v], qr[v]);
     }
 
     int rb, rn;
@@ -498,10 +494,9 @@ __device__ __forceinline__ void left_tile(const Tile& t, const MatDesc& d, const
     for (int g0 = 0; g0 < rn; g0 += kWave) {
         const int gr = min(kWave, rn - g0);
         const int i0 = t.row0 + rb + g0;
-        float pr[R];
-#pragma unroll
-        for (int k = 0; k < R; ++k)
-            pr[k] = (lane < gr && k < ri) ? p[d.p_off + (int64_t)(i0 + lane) * ri + k] : 0.f;
+        float pr1[1][R];
+        load_factor_rows<R, 1>(p + d.p_off + (int64_t)(i0 + lane) * ri, ri, lane < gr, pr1);
+        float (&pr)[R] = pr1[0];
         for (int ii = 0; ii < gr; ii += RU) {
             float x[RU][NV][V];
 #pragma unroll
@@ -630,21 +625,16 @@ __device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, flo
         const int jv = lane + kWave * v;
         valid[v] = jv < t.nvec;
         col[v] = (t.vec0 + jv) * V;
-#pragma unroll
-        for (int x = 0; x < V; ++x)
-#pragma unroll
-            for (int k = 0; k < R; ++k)
-                qr[v][x][k] = (valid[v] && k < ri) ? q[d.q_off + (int64_t)(col[v] + x) * ri + k] : 0.f;
+        load_factor_rows<R, V>(q + d.q_off + (int64_t)col[v] * ri, ri, valid[v], qr[v]);
     }
     int rb, rn;
     wave_rows(t.nrows, wave, &rb, &rn);
     for (int g0 = 0; g0 < rn; g0 += kWave) {
         const int gr = min(kWave, rn - g0);
         const int i0 = t.row0 + rb + g0;
-        float pr[R];
-#pragma unroll
-        for (int k = 0; k < R; ++k)
-            pr[k] = (lane < gr && k < ri) ? p[d.p_off + (int64_t)(i0 + lane) * ri + k] : 0.f;
+        float pr1[1][R];
+        load_factor_rows<R, 1>(p + d.p_off + (int64_t)(i0 + lane) * ri, ri, lane < gr, pr1);
+        float (&pr)[R] = pr1[0];
         for (int ii = 0; ii < gr; ii += RU) {
             float x[RU][NV][V];
 #pragma unroll

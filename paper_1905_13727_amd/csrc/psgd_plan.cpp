@@ -478,8 +478,8 @@ psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_
             plan->max_n = std::max(plan->max_n, d.n);
             const int64_t elems = (int64_t)d.n * d.m;
             N += round_up(elems, kAlignElems);
-            P += (int64_t)d.n * d.r;
-            Q += (int64_t)d.m * d.r;
+            P += round_up((int64_t)d.n * d.r, kFactorAlignElems);   // every factor starts 16-byte aligned
+            Q += round_up((int64_t)d.m * d.r, kFactorAlignElems);
             payload += elems;
             compressed += (int64_t)d.r * ((int64_t)d.n + d.m);
         }

@@ -191,11 +191,7 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
     }
     float M[RT][V];
     float qr[V][R];
-#pragma unroll
-    for (int x = 0; x < V; ++x)
-#pragma unroll
-        for (int k = 0; k < R; ++k)
-            qr[x][k] = (valid && k < ri) ? a.q[d.q_off + (int64_t)(col + x) * ri + k] : 0.f;
+    load_factor_rows<R, V>(a.q + d.q_off + (int64_t)col * ri, ri, valid, qr);
 #pragma unroll
     for (int i = 0; i < RT; ++i) {
         if (i < nrows && valid) {

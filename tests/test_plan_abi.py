@@ -70,7 +70,11 @@ def test_layout_resnet18():
     assert s.n_matrices == 21 and s.n_vec_elems == 9610
     assert s.payload_elems == 11164352 + 9610
     assert s.n_mat_elems == 11164352          # every ResNet18 matrix is a multiple of 64 elements
-    assert s.p_elems == 2 * 4810 and s.q_elems == 2 * 31515
+    # P and Q of each matrix start at multiples of 4 floats
+    up4 = lambda x: (x + 3) // 4 * 4
+    mats = [sh for sh in shapes if len(sh) > 1]
+    assert s.p_elems == sum(up4(2 * sh[0]) for sh in mats) == 2 * 4810
+    assert s.q_elems == sum(up4(2 * int(np.prod(sh[1:]))) for sh in mats) == 2 * 31515 + 2
     # traffic model per matrix element: 12 + 4/W compulsory, 24 + 4/W streaming
     assert s.bytes_min == 11164352 * 16 + 9610 * 8
     assert s.bytes_stream == 11164352 * 28 + 9610 * 8
@@ -96,7 +100,10 @@ def test_effective_rank_and_padding():
     s = plan.sizes
     assert s.n_mat_elems == 64 + 3392 + 256 and s.n_vec_elems == 7
     assert s.grad_stride % 64 == 0 and s.grad_stride >= s.n_mat_elems + 7
-    assert s.p_elems == 5 * 3 + 37 * 4 + 2 * 2 and s.q_elems == 3 * 3 + 91 * 4 + 100 * 2
+    # each factor padded to a multiple of 4 floats
+    assert s.p_elems == 16 + 37 * 4 + 2 * 2 and s.q_elems == 12 + 91 * 4 + 100 * 2
+    assert [plan.offsets(t)[1] for t in (0, 2, 3)] == [0, 16, 16 + 148]
+    assert [plan.offsets(t)[2] for t in (0, 2, 3)] == [0, 12, 12 + 364]
     assert s.workspace_bytes > 0
 
 
