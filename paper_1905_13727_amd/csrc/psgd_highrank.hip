@@ -273,7 +273,7 @@ __global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatD
 constexpr int kHrMaxRank = PSGD_MAX_RANK;
 constexpr int kHrGramRows = 128;   // panel rows staged in LDS at a time by the Gram kernel
 
-// Row block of kGramRows rows: mean P (sum over workers and column ranges, * 1/W) -> P buffer; Gram matrix of the block in
+// Row block (at most kHrGramTileRows rows): mean P (sum over workers and column ranges, * 1/W) -> P buffer; Gram matrix of the block in
 // fp64 -> gram[block][r*r].  Thread t owns entries (a, b) with a * r + b = t, t + 256, ...
 __global__ __launch_bounds__(kBlock) void k_hr_gram(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                     const float* __restrict__ ws, float* __restrict__ p,

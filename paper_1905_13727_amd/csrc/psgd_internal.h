@@ -20,7 +20,7 @@ constexpr int kMaxVecPerLaneK3 = 2;  // column vectors a lane owns in the Q = M^
 constexpr int kOrthoBlock = 256;   // threads of the single-workgroup Gram-Schmidt kernel
 constexpr int kValuMaxRank = 8;    // ranks up to this run on the vector-ALU kernels
 constexpr int kPanelFloats = 12288;  // n*r up to this: Gram-Schmidt by one workgroup with the panel in LDS (48 KB)
-constexpr int kGramRows = 1024;    // rows per workgroup of the tall-panel Gram / apply kernels
+constexpr int kGramRows = 256;     // rows per workgroup of the tall-panel Gram / apply kernels
 constexpr int kPreReduceParts = 16; // more partial-P slices than this: a reduction kernel runs before the orthogonalisation
 constexpr int kOrthoMaxRows = 1024; // panels with more rows take the multi-workgroup route
 constexpr int kFactorAlignElems = 4;        // P and Q of a matrix start at multiples of 4 floats (vector loads of factor rows)

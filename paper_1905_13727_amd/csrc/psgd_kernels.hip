@@ -335,7 +335,7 @@ __global__ __launch_bounds__(kOrthoBlock) void k_ortho(const MatDesc* __restrict
 // "Orthogonalization is a linear operation"); that R is the Cholesky factor of the Gram matrix
 // P^T P.  For a panel too tall for one workgroup the factor is computed that way, over many
 // workgroups: k_gram sums the partials into the mean P (stored in the P buffer) and reduces the
-// Gram matrix of its row block in fp64; k_chol_apply adds the blocks' Gram matrices in block order,
+// Gram matrix of its row block in fp64; k_chol_apply adds the blocks' Gram matrices in a fixed order,
 // factorises (fp64, r <= 8) and solves P_hat R = P row by row.  A pivot <= 1e-30 (the squared norm
 // Gram-Schmidt would find for that column at its turn) gives a zero column.
 
@@ -390,51 +390,76 @@ __global__ __launch_bounds__(kBlock) void k_gram(const MatDesc* __restrict__ mat
 
 __global__ __launch_bounds__(kBlock) void k_chol_apply(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                        const double* __restrict__ gram, float* __restrict__ p) {
-    __shared__ double part[kWavesPerBlock][kValuMaxRank * kValuMaxRank];
+    constexpr int kMaxSlices = 16;
+    __shared__ double part[kMaxSlices][kValuMaxRank * kValuMaxRank];
     __shared__ double Rm[kValuMaxRank][kValuMaxRank];   // upper triangular factor
     __shared__ double rinv[kValuMaxRank];               // 1 / R_jj, 0 for a zero column
     const Tile t = tiles[blockIdx.x];
     const MatDesc d = mats[t.mat];
     const int r = d.r, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-    // Gram matrix = sum of the row blocks' matrices in block order: four slices of blocks, then the slices
-    if (lane < r * r) {
-        const int per = (d.n_gblock + kWavesPerBlock - 1) / kWavesPerBlock;
-        const int b0 = wave * per, b1 = min(d.n_gblock, b0 + per);
-        const double* src = gram + d.gram_off + lane;
-        const int64_t stride = (int64_t)r * r;
-        double v = 0.0;
-        int b = b0;
-        for (; b + 8 <= b1; b += 8) {   // eight loads in flight, added in block order
-            double x[8];
+    // Gram matrix = sum of the row blocks' matrices: the blocks are cut into consecutive slices (4, 8 or 16 of
+    // them, as many as lanes allow: one lane per matrix entry and slice), each slice summed in block order,
+    // then the slices in slice order
+    const int nent = r * r;
+    const int per_wave = nent <= 16 ? 4 : (nent <= 32 ? 2 : 1);   // slices per wavefront
+    const int nslices = kWavesPerBlock * per_wave;
+    {
+        const int lanes_per = kWave / per_wave;
+        const int ent = lane % lanes_per, sl = wave * per_wave + lane / lanes_per;
+        if (ent < nent) {
+            const int per = (d.n_gblock + nslices - 1) / nslices;
+            const int b0 = min(d.n_gblock, sl * per), b1 = min(d.n_gblock, b0 + per);
+            const double* src = gram + d.gram_off + ent;
+            const int64_t stride = nent;
+            double v = 0.0;
+            int b = b0;
+            for (; b + 8 <= b1; b += 8) {   // eight loads in flight, added in block order
+                double x[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) x[u] = src[(int64_t)(b + u) * stride];
+                for (int u = 0; u < 8; ++u) x[u] = src[(int64_t)(b + u) * stride];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v += x[u];
+                for (int u = 0; u < 8; ++u) v += x[u];
+            }
+            for (; b < b1; ++b) v += src[(int64_t)b * stride];
+            part[sl][ent] = v;
         }
-        for (; b < b1; ++b) v += src[(int64_t)b * stride];
-        part[wave][lane] = v;
     }
     __syncthreads();
     if (tid == 0) {
+        // Every index below is a compile-time constant (loops unrolled to the largest rank, rows and columns
+        // past r switched off by predicates), so the matrix lives in registers; R overwrites G's upper triangle.
         double G[kValuMaxRank][kValuMaxRank];
-        for (int a = 0; a < r; ++a)
-            for (int b = a; b < r; ++b)
-                G[a][b] = ((part[0][a * r + b] + part[1][a * r + b]) + part[2][a * r + b]) + part[3][a * r + b];
+#pragma unroll
+        for (int a = 0; a < kValuMaxRank; ++a)
+#pragma unroll
+            for (int b = a; b < kValuMaxRank; ++b)
+            {
+                double v = 0.0;
+                if (b < r)
+                    for (int sl = 0; sl < nslices; ++sl) v += part[sl][a * r + b];
+                G[a][b] = v;
+            }
         // Cholesky, row by row of R (upper): R_jj = sqrt(G_jj - sum_k R_kj^2), R_jc = (G_jc - sum_k R_kj R_kc) / R_jj
-        for (int j = 0; j < r; ++j) {
-            double piv = G[j][j];
-            for (int k = 0; k < j; ++k) piv -= Rm[k][j] * Rm[k][j];
-            if (piv <= 1e-30) {
-                rinv[j] = 0.0;
-                for (int c = j; c < r; ++c) Rm[j][c] = 0.0;
-            } else {
-                const double rjj = sqrt(piv);
+#pragma unroll
+        for (int j = 0; j < kValuMaxRank; ++j) {
+            if (j < r) {
+                double piv = G[j][j];
+#pragma unroll
+                for (int k = 0; k < j; ++k) piv -= G[k][j] * G[k][j];
+                const bool dead = piv <= 1e-30;
+                const double rjj = dead ? 0.0 : sqrt(piv);
+                const double rj = dead ? 0.0 : 1.0 / rjj;
+                rinv[j] = rj;
+                G[j][j] = rjj;
                 Rm[j][j] = rjj;
-                rinv[j] = 1.0 / rjj;
-                for (int c = j + 1; c < r; ++c) {
+#pragma unroll
+                for (int c = j + 1; c < kValuMaxRank; ++c) {
                     double v = G[j][c];
-                    for (int k = 0; k < j; ++k) v -= Rm[k][j] * Rm[k][c];
-                    Rm[j][c] = v / rjj;
+#pragma unroll
+                    for (int k = 0; k < j; ++k) v -= G[k][j] * G[k][c];
+                    v = dead ? 0.0 : v * rj;     // a zero column takes no part in the later ones
+                    G[j][c] = v;
+                    if (c < r) Rm[j][c] = v;
                 }
             }
         }
