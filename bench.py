@@ -31,6 +31,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # HBM bytes per launch of a kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
 # copy kernel of known size (see profiles/); keyed by (workload, rank, workers, kernel).  None = not
 # measured for that configuration.
+METRIC = "PowerSGD step gradient GB/s + % HBM peak, ResNet18 shapes r=2"   # the headline metric and its workload
+
 MEASURED_TRAFFIC = {
     # profiles/resident_resnet18_r2.md: 98.8 MB fetched + 93.5 MB written
     ("resnet18", 2, 1, "k_resident"): 192366695,
@@ -228,7 +230,8 @@ def main():
     traffic = MEASURED_TRAFFIC.get((wl.name, rank, W, dom))
 
     rec = {
-        "metric": "PowerSGD step gradient GB/s + % HBM peak, ResNet18 shapes r=2",
+        "metric": METRIC if (wl.name, rank, W) == ("resnet18", 2, 1) and gdt == "f32" and odt == "f32"
+                  else "PowerSGD step gradient GB/s + %% HBM peak, %s shapes W=%d r=%d" % (wl.name, W, rank),
         "value": round(value, 3),
         "unit": "GB/s",
         "n_gpus": 1,
