@@ -245,7 +245,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s-shaped gradient set, W=%d simulated worker(s), rank %d, gradients %s, output %s"
                                % (wl.name, W, rank, gdt, odt),
-                   "mode": "resident (one kernel, M kept in registers)" if resident else "streaming (one kernel per phase)",
+                   "mode": "resident (one kernel, M kept in registers)" if resident else
+                           ("matrix cores (one kernel per phase)" if rank > 8 or gdt != "f32" or odt != "f32"
+                            else "streaming (one kernel per phase)"),
                    "matrices": int(s.n_matrices), "matrix_elems": int(payload_mat), "vector_elems": int(L),
                    "grad_buffers": len(grads)},
         "stream_model": {"bytes_per_step": int(s.bytes_stream),
@@ -255,6 +257,8 @@ def main():
                       "GBps": round(s.bytes_min / (ms_per_step * 1e-3) / 1e9, 2),
                       "frac_of_hbm_peak": round(s.bytes_min / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "cold_ms_per_step": cold_ms,
+        "cold_stream_model_frac_of_hbm_peak": (round(s.bytes_stream / (cold_ms["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+                                               if cold_ms else None),
         "kernel_ms": {k: round(v, 5) for k, v in kavg.items()},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
