@@ -54,6 +54,9 @@ def parse():
     ap.add_argument("--profile-steps", type=int, default=50, help="steps of the per-kernel HIP-event pass")
     ap.add_argument("--cold-steps", type=int, default=20,
                     help="steps of the cold-cache pass (caches flushed before each step, outside the timing)")
+    ap.add_argument("--update", choices=["none", "fused", "separate"], default="none",
+                    help="also apply the momentum / parameter update of Algorithm 2: fused into the step "
+                         "(psgd_step_update) or as separate elementwise kernels after psgd_step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing")
     ap.add_argument("--tune", action="append", default=[], help="key=value planner tuning (experiments)")
@@ -165,8 +168,21 @@ def main():
     stream = torch.cuda.current_stream(dev)
     sh = stream.cuda_stream
 
+    if args.update != "none":   # Algorithm 2's last two lines: momentum and parameter buffers shaped like `out`
+        mom = torch.zeros(s.out_elems, dtype=torch.float32, device=dev)
+        par = torch.randn(s.out_elems, dtype=torch.float32, device=dev)
+        if args.update == "separate" and odt != "f32":
+            print("bench.py: --update separate needs an f32 output", file=sys.stderr)
+            return 2
+
     def step(i):
-        plan.step(grads[i % len(grads)], err, q, p, out, ws, sh)
+        if args.update == "fused":
+            plan.step_update(grads[i % len(grads)], err, q, p, mom, par, 0.01, 0.9, ws, sh)
+        else:
+            plan.step(grads[i % len(grads)], err, q, p, out, ws, sh)
+            if args.update == "separate":   # the same update as three elementwise torch kernels on Delta'
+                mom.mul_(0.9).add_(out)
+                par.add_(out + mom, alpha=-0.01)
 
     if args.copy_calibration > 0:
         n = args.copy_calibration * 1024 * 1024 // 4
@@ -249,7 +265,7 @@ def main():
                            ("matrix cores (one kernel per phase)" if rank > 8 or gdt != "f32" or odt != "f32"
                             else "streaming (one kernel per phase)"),
                    "matrices": int(s.n_matrices), "matrix_elems": int(payload_mat), "vector_elems": int(L),
-                   "grad_buffers": len(grads)},
+                   "grad_buffers": len(grads), "update": args.update},
         "stream_model": {"bytes_per_step": int(s.bytes_stream),
                          "GBps": round(s.bytes_stream / (ms_per_step * 1e-3) / 1e9, 2),
                          "frac_of_hbm_peak": round(s.bytes_stream / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},

@@ -162,6 +162,24 @@ PSGD_API psgd_status psgd_decompress(psgd_plan* plan, const float* p, const floa
 PSGD_API psgd_status psgd_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p,
                       void* out, void* workspace, void* hip_stream);
 
+/* The step fused with the last two lines of Algorithm 2 (error-feedback SGD with
+ * momentum): m <- lambda m + Delta' ; x <- x - gamma (Delta' + m).  Delta' is not
+ * stored: the decompression pass reads and writes the momentum and parameter
+ * buffers instead (8 bytes per element less traffic than psgd_step followed by a
+ * separate update).  Vector-shaped tensors take Delta' = mean over workers of g_w.
+ *   mom   (device, in/out) m [N+L] float, laid out like `out` of psgd_decompress
+ *   param (device, in/out) x [N+L] float, same layout
+ *   lr, momentum           gamma and lambda
+ * All other arguments, the resident / streaming choice and the stream rules are
+ * those of psgd_step / psgd_decompress; a plan's out_dtype is not used here.
+ * Errors: PSGD_EINVAL for null pointers or NaN step sizes. */
+PSGD_API psgd_status psgd_step_update(psgd_plan* plan, const void* grad, float* err, float* q, float* p,
+                             float* mom, float* param, float lr, float momentum, void* workspace,
+                             void* hip_stream);
+PSGD_API psgd_status psgd_decompress_update(psgd_plan* plan, const float* p, const float* q, float* err,
+                                   const void* grad, float* mom, float* param, float lr, float momentum,
+                                   void* workspace, void* hip_stream);
+
 /* Per-kernel timing for benchmarks.  With profiling enabled, psgd_compress and
  * psgd_decompress record HIP events on the caller's stream around each of their
  * kernels, and psgd_decompress (hence psgd_step) WAITS for the stream at its

@@ -68,6 +68,10 @@ def load_library(path: Optional[str] = None):
     lib.psgd_step.restype = C.c_int
     lib.psgd_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psgd_plan_set_profiling.restype = C.c_int
+    lib.psgd_step_update.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_float, C.c_float, vp, vp]
+    lib.psgd_step_update.restype = C.c_int
+    lib.psgd_decompress_update.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_float, C.c_float, vp, vp]
+    lib.psgd_decompress_update.restype = C.c_int
     lib.psgd_plan_set_profiling.argtypes = [vp, i32]
     lib.psgd_plan_kernel_times.restype = C.c_int
     lib.psgd_plan_kernel_times.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -165,6 +169,16 @@ class Plan:
     def step(self, grad, err, q, p, out, workspace, stream=None):
         self._check(self._lib.psgd_step(self._h, _ptr(grad), _ptr(err), _ptr(q), _ptr(p), _ptr(out),
                                         _ptr(workspace), _ptr(stream)), "psgd_step")
+
+    def step_update(self, grad, err, q, p, mom, param, lr, momentum, workspace, stream=None):
+        self._check(self._lib.psgd_step_update(self._h, _ptr(grad), _ptr(err), _ptr(q), _ptr(p), _ptr(mom), _ptr(param),
+                                               float(lr), float(momentum), _ptr(workspace), _ptr(stream)),
+                    "psgd_step_update")
+
+    def decompress_update(self, p, q, err, grad, mom, param, lr, momentum, workspace, stream=None):
+        self._check(self._lib.psgd_decompress_update(self._h, _ptr(p), _ptr(q), _ptr(err), _ptr(grad), _ptr(mom),
+                                                     _ptr(param), float(lr), float(momentum), _ptr(workspace),
+                                                     _ptr(stream)), "psgd_decompress_update")
 
     def set_profiling(self, enable: bool):
         self._check(self._lib.psgd_plan_set_profiling(self._h, 1 if enable else 0), "psgd_plan_set_profiling")

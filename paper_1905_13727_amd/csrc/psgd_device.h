@@ -94,6 +94,17 @@ __device__ __forceinline__ void load_factor_rows(const float* rows, int ri, bool
     }
 }
 
+// Algorithm 2, last two lines, for V consecutive elements whose momentum and parameter values have been loaded:
+// m <- lambda m + Delta' ; x <- x - gamma (Delta' + m).
+template <int V>
+__device__ __forceinline__ void momentum_step(float (&m)[V], float (&x)[V], const float (&dl)[V], float lr, float lam) {
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        m[i] = fmaf(lam, m[i], dl[i]);
+        x[i] = fmaf(-lr, dl[i] + m[i], x[i]);
+    }
+}
+
 // ---- wavefront helpers ---------------------------------------------------------------------------
 
 __device__ __forceinline__ float lane_bcast(float v, int src_lane) {

@@ -12,7 +12,8 @@
 //                        the orthonormal factor Gram-Schmidt yields (remark "Orthogonalization is a
 //                        linear operation"), for panels of any height                    (Alg. 1)
 //   k_hr_left<NT>        Q_w = M^T P_hat, one partial per wavefront's row strip          (Alg. 1)
-//   k_hr_decomp<NT, BF>  Delta' = P_hat Q^T, e' = M - Delta', Delta' stored fp32 or bf16  (Alg. 1, Alg. 2)
+//   k_hr_decomp<NT, OM>  Delta' = P_hat Q^T, e' = M - Delta', Delta' stored fp32 or bf16, or folded into the
+//                        momentum / parameter update                                     (Alg. 1, Alg. 2)
 //   k_hr_vec<BFI, BFO>   mean of the vector-shaped tensors                                (Alg. 1 line 1)
 //
 // Lane roles of the 16x16x4 instruction (lane l, li = l % 16, kb = l / 16): A[li][kb], B[kb][li],
@@ -519,11 +520,15 @@ __device__ __forceinline__ void buf_store_out4(buf_rsrc r, unsigned off, v4f v) 
     }
 }
 
-template <int NT, bool BF>
+// OM: what becomes of Delta': 0 stored as fp32, 1 stored as bf16, 2 not stored but folded into the momentum and
+// parameter buffers (Algorithm 2's last two lines)
+template <int NT, int OM>
 __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                          float* __restrict__ err, const float* __restrict__ p,
                                                          const float* __restrict__ q, void* __restrict__ out,
-                                                         int64_t estride) {
+                                                         int64_t estride, UpdateArgs upd) {
+    constexpr bool BF = OM == 1;
+    constexpr bool UPD = OM == 2;
     constexpr int KK = 4 * NT;   // instructions per 16 x 16 block (K = 16 NT in steps of 4)
     constexpr int CB = kHrDecompBlocks;
     constexpr int RP = 16 * NT;
@@ -565,7 +570,11 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restri
     const int r_begin = t.row0 + rb;
     const int64_t ebase = (int64_t)r_begin * m;
     const buf_rsrc eres = make_rsrc(err + (int64_t)w * estride + d.off + ebase, (int64_t)rn * m * 4);
-    const buf_rsrc ores = make_rsrc(static_cast<char*>(out) + (d.off + ebase) * OS, w == 0 ? (int64_t)rn * m * OS : 0);
+    // Delta' (or momentum and parameters) belong to worker 0's workgroups: the others get empty ranges
+    const buf_rsrc ores = make_rsrc(UPD ? nullptr : static_cast<char*>(out) + (d.off + ebase) * OS,
+                                    (!UPD && w == 0) ? (int64_t)rn * m * OS : 0);
+    const buf_rsrc mres = make_rsrc(UPD ? upd.mom + d.off + ebase : nullptr, (UPD && w == 0) ? (int64_t)rn * m * 4 : 0);
+    const buf_rsrc xres = make_rsrc(UPD ? upd.param + d.off + ebase : nullptr, (UPD && w == 0) ? (int64_t)rn * m * 4 : 0);
     const buf_rsrc pres = make_rsrc(p + d.p_off + (int64_t)r_begin * ri, (int64_t)rn * ri * 4);
     // lane offsets in elements, relative to the first row of the strip; out of range where the column (of M) or
     // the rank index (of P_hat) does not exist
@@ -606,6 +615,14 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restri
         load_step(r_rel + 16, mvn, bpn);   // past the strip's last row: out of range, nothing is fetched
         // at two and four rank tiles the Q operands are fetched from LDS at every step instead of being kept
         // in registers for the whole strip (64 or 128 of them)
+        v4f mo[UPD ? CB : 1], pa[UPD ? CB : 1];
+        if constexpr (UPD) {   // momentum and parameters of this step: requested before the products are issued
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                mo[cb] = buf_load_v4f(mres, e_off(cb, r_rel * m, 4));
+                pa[cb] = buf_load_v4f(xres, e_off(cb, r_rel * m, 4));
+            }
+        }
         if constexpr (NT >= 2) asm volatile("" ::: "memory");
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
@@ -614,14 +631,22 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restri
             for (int kk = 0; kk < KK; ++kk)
                 acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Qs[16 * cb + li][4 * kk + kb], bp[kk], acc, 0, 0, 0);
             buf_store_v4f(eres, e_off(cb, r_rel * m, 4), mv[cb] - acc);
-            buf_store_out4<BF>(ores, e_off(cb, r_rel * m, OS), acc);   // dropped for workers other than the first (empty range)
+            if constexpr (UPD) {
+                float m4[4] = {mo[cb].x, mo[cb].y, mo[cb].z, mo[cb].w}, x4[4] = {pa[cb].x, pa[cb].y, pa[cb].z, pa[cb].w};
+                const float d4[4] = {acc.x, acc.y, acc.z, acc.w};
+                momentum_step<4>(m4, x4, d4, upd.lr, upd.lam);
+                buf_store_v4f(mres, e_off(cb, r_rel * m, 4), v4f{m4[0], m4[1], m4[2], m4[3]});
+                buf_store_v4f(xres, e_off(cb, r_rel * m, 4), v4f{x4[0], x4[1], x4[2], x4[3]});
+            } else {
+                buf_store_out4<BF>(ores, e_off(cb, r_rel * m, OS), acc);   // dropped for workers other than the first (empty range)
+            }
         }
     }
 }
 
 template <bool BFI, bool BFO>
 __global__ __launch_bounds__(kBlock) void k_hr_vec(const void* __restrict__ grad, void* __restrict__ out, int workers,
-                                                   int64_t gstride, int64_t n_mat_elems, int64_t n_vec) {
+                                                   int64_t gstride, int64_t n_mat_elems, int64_t n_vec, UpdateArgs upd) {
     const float inv_w = 1.0f / (float)workers;
     for (int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x; idx < n_vec; idx += (int64_t)gridDim.x * kBlock) {
         float s = 0.f;
@@ -631,8 +656,17 @@ __global__ __launch_bounds__(kBlock) void k_hr_vec(const void* __restrict__ grad
             else s += static_cast<const float*>(grad)[at];
         }
         s *= inv_w;
-        if constexpr (BFO) static_cast<bf16_t*>(out)[n_mat_elems + idx] = f32_to_bf16(s);
-        else static_cast<float*>(out)[n_mat_elems + idx] = s;
+        if (upd.mom) {
+            float m1[1] = {upd.mom[n_mat_elems + idx]}, x1[1] = {upd.param[n_mat_elems + idx]};
+            const float d1[1] = {s};
+            momentum_step<1>(m1, x1, d1, upd.lr, upd.lam);
+            upd.mom[n_mat_elems + idx] = m1[0];
+            upd.param[n_mat_elems + idx] = x1[0];
+        } else if constexpr (BFO) {
+            static_cast<bf16_t*>(out)[n_mat_elems + idx] = f32_to_bf16(s);
+        } else {
+            static_cast<float*>(out)[n_mat_elems + idx] = s;
+        }
     }
 }
 
@@ -674,14 +708,16 @@ static void hr_launch_right(psgd_plan* plan, const void* grad, float* err, const
 }
 
 template <int NT>
-static void hr_launch_decomp(psgd_plan* plan, float* err, const float* p, const float* q, void* out, hipStream_t s) {
+static void hr_launch_decomp(psgd_plan* plan, float* err, const float* p, const float* q, void* out, hipStream_t s,
+                             const UpdateArgs& upd) {
     dim3 grid((unsigned)plan->hr_tiles4.size(), (unsigned)plan->workers);
-    if (plan->out_dtype == PSGD_BF16)
-        hipLaunchKernelGGL((k_hr_decomp<NT, true>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles4, err, p, q,
-                           out, plan->sizes.err_stride);
-    else
-        hipLaunchKernelGGL((k_hr_decomp<NT, false>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles4, err, p, q,
-                           out, plan->sizes.err_stride);
+#define HR_DECOMP(OMV)                                                                                                \
+    hipLaunchKernelGGL((k_hr_decomp<NT, OMV>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles4, err, p, q, \
+                       out, plan->sizes.err_stride, upd)
+    if (upd.mom) HR_DECOMP(2);
+    else if (plan->out_dtype == PSGD_BF16) HR_DECOMP(1);
+    else HR_DECOMP(0);
+#undef HR_DECOMP
 }
 
 static double* hr_doubles(psgd_plan* plan, void* workspace) {
@@ -740,14 +776,14 @@ psgd_status hr_compress(psgd_plan* plan, const void* grad, float* err, float* q,
 }
 
 psgd_status hr_decompress(psgd_plan* plan, const float* p, const float* q, float* err, const void* grad, void* out,
-                          void* stream) {
+                          void* stream, const UpdateArgs& upd) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int nt = plan->hr_nt;
     HR_MARK(5);
     if (!plan->hr_tiles4.empty()) {
-        if (nt == 1) hr_launch_decomp<1>(plan, err, p, q, out, s);
-        else if (nt == 2) hr_launch_decomp<2>(plan, err, p, q, out, s);
-        else hr_launch_decomp<4>(plan, err, p, q, out, s);
+        if (nt == 1) hr_launch_decomp<1>(plan, err, p, q, out, s, upd);
+        else if (nt == 2) hr_launch_decomp<2>(plan, err, p, q, out, s, upd);
+        else hr_launch_decomp<4>(plan, err, p, q, out, s, upd);
         HR_CHECK("launch k_hr_decomp");
     }
     const int64_t L = plan->sizes.n_vec_elems;
@@ -756,16 +792,16 @@ psgd_status hr_decompress(psgd_plan* plan, const float* p, const float* q, float
         const bool bi = plan->grad_dtype == PSGD_BF16, bo = plan->out_dtype == PSGD_BF16;
         if (bi && bo)
             hipLaunchKernelGGL((k_hr_vec<true, true>), dim3(blocks), dim3(kBlock), 0, s, grad, out, plan->workers,
-                               plan->sizes.grad_stride, plan->sizes.n_mat_elems, L);
+                               plan->sizes.grad_stride, plan->sizes.n_mat_elems, L, upd);
         else if (bi)
             hipLaunchKernelGGL((k_hr_vec<true, false>), dim3(blocks), dim3(kBlock), 0, s, grad, out, plan->workers,
-                               plan->sizes.grad_stride, plan->sizes.n_mat_elems, L);
+                               plan->sizes.grad_stride, plan->sizes.n_mat_elems, L, upd);
         else if (bo)
             hipLaunchKernelGGL((k_hr_vec<false, true>), dim3(blocks), dim3(kBlock), 0, s, grad, out, plan->workers,
-                               plan->sizes.grad_stride, plan->sizes.n_mat_elems, L);
+                               plan->sizes.grad_stride, plan->sizes.n_mat_elems, L, upd);
         else
             hipLaunchKernelGGL((k_hr_vec<false, false>), dim3(blocks), dim3(kBlock), 0, s, grad, out, plan->workers,
-                               plan->sizes.grad_stride, plan->sizes.n_mat_elems, L);
+                               plan->sizes.grad_stride, plan->sizes.n_mat_elems, L, upd);
         HR_CHECK("launch k_hr_vec");
     }
     HR_MARK(6);

@@ -178,6 +178,14 @@ struct psgd_plan {
 };
 
 namespace psgd {
+// Algorithm 2's last two lines fused into the decompression: m <- lambda m + Delta', x <- x - gamma (Delta' + m),
+// on buffers laid out like `out` (fp32); Delta' itself is then not stored.  mom == nullptr: plain decompression.
+struct UpdateArgs {
+    float* mom = nullptr;
+    float* param = nullptr;
+    float lr = 0.f;
+    float lam = 0.f;
+};
 // host planner (psgd_plan.cpp)
 psgd_status build_tables(psgd_plan* plan);
 // device side (psgd_kernels.hip)
@@ -186,19 +194,20 @@ void free_tables(psgd_plan* plan);
 psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float* q, float* p,
                             void* workspace, void* stream);
 psgd_status launch_decompress(psgd_plan* plan, const float* p, const float* q, float* err,
-                              const void* grad, void* out, void* workspace, void* stream);
+                              const void* grad, void* out, void* workspace, void* stream,
+                              const UpdateArgs& upd = UpdateArgs());
 psgd_status set_profiling(psgd_plan* plan, bool enable);
 psgd_status launch_q_reduce(psgd_plan* plan, float* ws, float* q, void* stream);
 psgd_status finish_profiled_step(psgd_plan* plan);
 psgd_status hr_compress(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* workspace,
                         void* stream);
 psgd_status hr_decompress(psgd_plan* plan, const float* p, const float* q, float* err, const void* grad, void* out,
-                          void* stream);
+                          void* stream, const UpdateArgs& upd);
 psgd_status check_plan(psgd_plan* plan, void* stream);
 psgd_status read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t* n_written);
 psgd_status resident_check_device(psgd_plan* plan);
 psgd_status launch_resident_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,
-                                 void* workspace, void* stream);
+                                 void* workspace, void* stream, const UpdateArgs& upd = UpdateArgs());
 // The resident kernel's synchronisation words (units of unsigned), one 256-byte line each: an error word
 // (a wait gave up), the epoch that tags this step's mailbox slots, the count of finished workgroups.
 constexpr int kSyncLineWords = 64;

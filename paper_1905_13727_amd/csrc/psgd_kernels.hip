@@ -634,11 +634,11 @@ __global__ __launch_bounds__(kBlock) void k_q_reduce(const MatDesc* __restrict__
 
 // ---- k_decomp: Delta' = P_hat Q^T, e_w = M_w - Delta', vectors averaged ---------------------------
 
-template <int R, int V, int NV>
+template <int R, int V, int NV, bool UPD>
 __device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, float* __restrict__ e,
                                             const float* __restrict__ p, const float* __restrict__ q,
-                                            float* __restrict__ out, bool write_out) {
-    constexpr int RU = 8;
+                                            float* __restrict__ out, bool write_out, const UpdateArgs& upd) {
+    constexpr int RU = UPD ? 4 : 8;   // rows whose loads are in flight together (momentum and parameters ride along)
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int ri = d.r;
@@ -662,13 +662,22 @@ __device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, flo
         float (&pr)[R] = pr1[0];
         for (int ii = 0; ii < gr; ii += RU) {
             float x[RU][NV][V];
+            float mo[UPD ? RU : 1][NV][V], pa[UPD ? RU : 1][NV][V];
 #pragma unroll
             for (int u = 0; u < RU; ++u) {
                 if (ii + u < gr) {
                     const int64_t row = d.off + (int64_t)(i0 + ii + u) * d.m;
 #pragma unroll
                     for (int v = 0; v < NV; ++v)
-                        if (valid[v]) ldv<V>(e + row + col[v], x[u][v]);
+                        if (valid[v]) {
+                            ldv<V>(e + row + col[v], x[u][v]);
+                            if constexpr (UPD) {
+                                if (write_out) {
+                                    ldv<V>(upd.mom + row + col[v], mo[u][v]);
+                                    ldv<V>(upd.param + row + col[v], pa[u][v]);
+                                }
+                            }
+                        }
                 }
             }
 #pragma unroll
@@ -691,7 +700,15 @@ __device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, flo
                                 en[xx] = x[u][v][xx] - s;
                             }
                             stv<V>(e + row + col[v], en);
-                            if (write_out) stv<V>(out + row + col[v], dl);
+                            if (write_out) {
+                                if constexpr (UPD) {
+                                    momentum_step<V>(mo[u][v], pa[u][v], dl, upd.lr, upd.lam);
+                                    stv<V>(upd.mom + row + col[v], mo[u][v]);
+                                    stv<V>(upd.param + row + col[v], pa[u][v]);
+                                } else {
+                                    stv<V>(out + row + col[v], dl);
+                                }
+                            }
                         }
                 }
             }
@@ -699,12 +716,12 @@ __device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, flo
     }
 }
 
-template <int R, int NV>
+template <int R, int NV, bool UPD>
 __global__ __launch_bounds__(kBlock) void k_decomp(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                    float* __restrict__ err, const float* __restrict__ p,
                                                    const float* __restrict__ q, const float* __restrict__ grad,
                                                    float* __restrict__ out, int workers, int64_t gstride,
-                                                   int64_t estride, int64_t n_mat_elems) {
+                                                   int64_t estride, int64_t n_mat_elems, UpdateArgs upd) {
     const Tile t = tiles[blockIdx.x];
     const int w = blockIdx.y;
     if (t.mat < 0) {
@@ -713,15 +730,23 @@ __global__ __launch_bounds__(kBlock) void k_decomp(const MatDesc* __restrict__ m
         for (int64_t idx = t.elem0 + threadIdx.x; idx < t.elem0 + t.nelem; idx += kBlock) {
             float s = 0.f;
             for (int ww = 0; ww < workers; ++ww) s += grad[(int64_t)ww * gstride + n_mat_elems + idx];
-            out[n_mat_elems + idx] = s * inv_w;
+            if constexpr (UPD) {
+                float m1[1] = {upd.mom[n_mat_elems + idx]}, x1[1] = {upd.param[n_mat_elems + idx]};
+                const float d1[1] = {s * inv_w};
+                momentum_step<1>(m1, x1, d1, upd.lr, upd.lam);
+                upd.mom[n_mat_elems + idx] = m1[0];
+                upd.param[n_mat_elems + idx] = x1[0];
+            } else {
+                out[n_mat_elems + idx] = s * inv_w;
+            }
         }
         return;
     }
     const MatDesc d = mats[t.mat];
     float* e = err + (int64_t)w * estride;
-    if (d.vec == 4) decomp_tile<R, 4, NV>(t, d, e, p, q, out, w == 0);
-    else if (d.vec == 2) decomp_tile<R, 2, NV>(t, d, e, p, q, out, w == 0);
-    else decomp_tile<R, 1, NV>(t, d, e, p, q, out, w == 0);
+    if (d.vec == 4) decomp_tile<R, 4, NV, UPD>(t, d, e, p, q, out, w == 0, upd);
+    else if (d.vec == 2) decomp_tile<R, 2, NV, UPD>(t, d, e, p, q, out, w == 0, upd);
+    else decomp_tile<R, 1, NV, UPD>(t, d, e, p, q, out, w == 0, upd);
 }
 
 // ---- host side ------------------------------------------------------------------------------------
@@ -895,16 +920,20 @@ static void launch_left(psgd_plan* plan, const float* err, const float* p, float
 
 template <int R>
 static void launch_decomp(psgd_plan* plan, float* err, const float* p, const float* q, const float* grad, float* out,
-                          hipStream_t s) {
+                          hipStream_t s, const UpdateArgs& upd) {
     dim3 grid((unsigned)plan->tiles4.size(), (unsigned)plan->workers);
-    if (plan->tuning.k4_nv == 1)
-        hipLaunchKernelGGL((k_decomp<R, 1>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles4, err, p, q,
-                           grad, out, plan->workers, plan->sizes.grad_stride, plan->sizes.err_stride,
-                           plan->sizes.n_mat_elems);
-    else
-        hipLaunchKernelGGL((k_decomp<R, 2>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles4, err, p, q,
-                           grad, out, plan->workers, plan->sizes.grad_stride, plan->sizes.err_stride,
-                           plan->sizes.n_mat_elems);
+#define PSGD_LAUNCH_DECOMP(NVV, UPDV)                                                                                  \
+    hipLaunchKernelGGL((k_decomp<R, NVV, UPDV>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles4, err, p, q, \
+                       grad, out, plan->workers, plan->sizes.grad_stride, plan->sizes.err_stride,                      \
+                       plan->sizes.n_mat_elems, upd)
+    if (upd.mom) {
+        if (plan->tuning.k4_nv == 1) PSGD_LAUNCH_DECOMP(1, true);
+        else PSGD_LAUNCH_DECOMP(2, true);
+    } else {
+        if (plan->tuning.k4_nv == 1) PSGD_LAUNCH_DECOMP(1, false);
+        else PSGD_LAUNCH_DECOMP(2, false);
+    }
+#undef PSGD_LAUNCH_DECOMP
 }
 
 #define PSGD_RANK_SWITCH(fn, ...)                       \
@@ -992,15 +1021,15 @@ psgd_status launch_q_reduce(psgd_plan* plan, float* ws, float* q, void* stream) 
 }
 
 psgd_status launch_decompress(psgd_plan* plan, const float* p, const float* q, float* err, const void* grad, void* out,
-                              void* workspace, void* stream) {
+                              void* workspace, void* stream, const UpdateArgs& upd) {
     (void)workspace;
     psgd_status st = check_ready(plan);
     if (st != PSGD_OK) return st;
-    if (plan->hr) return hr_decompress(plan, p, q, err, grad, out, stream);
+    if (plan->hr) return hr_decompress(plan, p, q, err, grad, out, stream, upd);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (plan->tiles4.empty()) return PSGD_OK;
     PSGD_MARK(5);
-    PSGD_RANK_SWITCH(launch_decomp, plan, err, p, q, static_cast<const float*>(grad), static_cast<float*>(out), s);
+    PSGD_RANK_SWITCH(launch_decomp, plan, err, p, q, static_cast<const float*>(grad), static_cast<float*>(out), s, upd);
     PSGD_HIP(hipGetLastError(), "launch k_decomp");
     PSGD_MARK(6);
     return finish_profiled_step(plan);

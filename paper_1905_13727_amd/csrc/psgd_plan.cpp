@@ -607,6 +607,36 @@ psgd_status psgd_step(psgd_plan* plan, const void* grad, float* err, float* q, f
     return launch_decompress(plan, p, q, err, grad, out, workspace, hip_stream);
 }
 
+static bool update_args(const psgd_plan* plan, float* mom, float* param, float lr, float momentum, UpdateArgs* upd) {
+    (void)plan;
+    if (!mom || !param || !(lr == lr) || !(momentum == momentum)) return false;   // null or NaN
+    upd->mom = mom;
+    upd->param = param;
+    upd->lr = lr;
+    upd->lam = momentum;
+    return true;
+}
+
+psgd_status psgd_decompress_update(psgd_plan* plan, const float* p, const float* q, float* err, const void* grad,
+                                   float* mom, float* param, float lr, float momentum, void* workspace,
+                                   void* hip_stream) {
+    UpdateArgs upd;
+    if (!plan || !p || !q || !err || !grad || !workspace || !update_args(plan, mom, param, lr, momentum, &upd))
+        return PSGD_EINVAL;
+    return launch_decompress(plan, p, q, err, grad, nullptr, workspace, hip_stream, upd);
+}
+
+psgd_status psgd_step_update(psgd_plan* plan, const void* grad, float* err, float* q, float* p, float* mom,
+                             float* param, float lr, float momentum, void* workspace, void* hip_stream) {
+    UpdateArgs upd;
+    if (!plan || bad_ptrs(grad, err, q, p, workspace) || !update_args(plan, mom, param, lr, momentum, &upd))
+        return PSGD_EINVAL;
+    if (plan->resident_ok) return launch_resident_step(plan, grad, err, q, p, nullptr, workspace, hip_stream, upd);
+    psgd_status st = launch_compress(plan, grad, err, q, p, workspace, hip_stream);
+    if (st != PSGD_OK) return st;
+    return launch_decompress(plan, p, q, err, grad, nullptr, workspace, hip_stream, upd);
+}
+
 psgd_status psgd_plan_set_profiling(psgd_plan* plan, int32_t enable) {
     if (!plan) return PSGD_EINVAL;
     return set_profiling(plan, enable != 0);

@@ -58,6 +58,7 @@ struct ResArgs {
     int32_t nblocks;
     int64_t n_mat_elems;
     unsigned long long* trace;   // diagnostic: kResTracePoints timestamps per workgroup, or nullptr
+    UpdateArgs upd;              // UPD kernels: momentum / parameter buffers and step sizes (Algorithm 2's last lines)
 };
 
 __device__ __forceinline__ void trace_mark(const ResArgs& a, int point) {
@@ -159,7 +160,7 @@ __device__ __forceinline__ void gram_schmidt_rows(float (&P)[kResRowsPerLane][R]
 }
 
 // ---- the step, for a workgroup whose tiles use V-wide row accesses ---------------------------------------
-template <int R, int V>
+template <int R, int V, bool UPD>
 __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, float* lds, unsigned epoch) {
     constexpr int RT = res_rows_for_rank(R);
     const int lane = threadIdx.x & (kWave - 1);
@@ -450,40 +451,69 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
             for (int k = 0; k < R; ++k) qb[x][k] = (valid && k < ri) ? value_of(w[x][k]) : 0.f;
     }
     trace_mark(a, 5);
+    constexpr int CG = UPD ? 4 : 1;   // rows whose momentum / parameter loads are in flight together
 #pragma unroll
-    for (int i = 0; i < RT; ++i) {
-        if (i < nrows) {
-            float pk[R];
+    for (int i0 = 0; i0 < RT; i0 += CG) {
+        float mo[CG][V], pa[CG][V];
+        if constexpr (UPD) {
 #pragma unroll
-            for (int k = 0; k < R; ++k) pk[k] = lane_bcast(pr[k], i);
-            if (valid) {
-                float dl[V], en[V];
-#pragma unroll
-                for (int x = 0; x < V; ++x) {
-                    float s = 0.f;
-#pragma unroll
-                    for (int k = 0; k < R; ++k) s = fmaf(pk[k], qb[x][k], s);
-                    dl[x] = s;
-                    en[x] = M[i][x] - s;
+            for (int u = 0; u < CG; ++u)
+                if (i0 + u < RT && i0 + u < nrows && valid) {
+                    ldv<V>(a.upd.mom + tile_off + (int64_t)(i0 + u) * d.m, mo[u]);
+                    ldv<V>(a.upd.param + tile_off + (int64_t)(i0 + u) * d.m, pa[u]);
                 }
+        }
+#pragma unroll
+        for (int u = 0; u < CG; ++u) {
+            const int i = i0 + u;
+            if (i < RT && i < nrows) {
+                float pk[R];
+#pragma unroll
+                for (int k = 0; k < R; ++k) pk[k] = lane_bcast(pr[k], i);
+                if (valid) {
+                    float dl[V], en[V];
+#pragma unroll
+                    for (int x = 0; x < V; ++x) {
+                        float s = 0.f;
+#pragma unroll
+                        for (int k = 0; k < R; ++k) s = fmaf(pk[k], qb[x][k], s);
+                        dl[x] = s;
+                        en[x] = M[i < RT ? i : 0][x] - s;
+                    }
 #ifndef PSGD_EXPERIMENT_NO_PHASE_C_STORES
-                stv<V>(a.err + tile_off + (int64_t)i * d.m, en);
-                stv<V>(a.out + tile_off + (int64_t)i * d.m, dl);
+                    stv<V>(a.err + tile_off + (int64_t)i * d.m, en);
+                    if constexpr (UPD) {
+                        momentum_step<V>(mo[u], pa[u], dl, a.upd.lr, a.upd.lam);
+                        stv<V>(a.upd.mom + tile_off + (int64_t)i * d.m, mo[u]);
+                        stv<V>(a.upd.param + tile_off + (int64_t)i * d.m, pa[u]);
+                    } else {
+                        stv<V>(a.out + tile_off + (int64_t)i * d.m, dl);
+                    }
 #else
-                if (en[0] == 12345.678f && dl[0] == 9.87f) stv<V>(a.out + tile_off + (int64_t)i * d.m, dl);
+                    if (en[0] == 12345.678f && dl[0] == 9.87f) stv<V>(a.out + tile_off + (int64_t)i * d.m, dl);
 #endif
+                }
             }
         }
     }
     if (t.mat == -1) {
         // vector-shaped tensors, W = 1: Delta' is the gradient itself
-        for (int64_t idx = t.elem0 + lane; idx < t.elem0 + t.nelem; idx += kWave)
-            a.out[a.n_mat_elems + idx] = a.grad[a.n_mat_elems + idx];
+        for (int64_t idx = t.elem0 + lane; idx < t.elem0 + t.nelem; idx += kWave) {
+            const float dl1[1] = {a.grad[a.n_mat_elems + idx]};
+            if constexpr (UPD) {
+                float m1[1] = {a.upd.mom[a.n_mat_elems + idx]}, x1[1] = {a.upd.param[a.n_mat_elems + idx]};
+                momentum_step<1>(m1, x1, dl1, a.upd.lr, a.upd.lam);
+                a.upd.mom[a.n_mat_elems + idx] = m1[0];
+                a.upd.param[a.n_mat_elems + idx] = x1[0];
+            } else {
+                a.out[a.n_mat_elems + idx] = dl1[0];
+            }
+        }
     }
     trace_mark(a, 6);
 }
 
-template <int R>
+template <int R, bool UPD>
 __global__ __launch_bounds__(kBlock, 2) void k_resident(ResArgs a) {
     __shared__ float lds[kWavesPerBlock * 4 * R * kWave];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -495,9 +525,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_resident(ResArgs a) {
     // all tiles of a workgroup use the same access width; the first slot is never idle
     const RTile t0 = a.tiles[blockIdx.x * kWavesPerBlock];
     const int vec = t0.mat >= 0 ? a.mats[t0.mat].vec : 4;
-    if (vec == 4) resident_body<R, 4>(a, t, lds, epoch);
-    else if (vec == 2) resident_body<R, 2>(a, t, lds, epoch);
-    else resident_body<R, 1>(a, t, lds, epoch);
+    if (vec == 4) resident_body<R, 4, UPD>(a, t, lds, epoch);
+    else if (vec == 2) resident_body<R, 2, UPD>(a, t, lds, epoch);
+    else resident_body<R, 1, UPD>(a, t, lds, epoch);
     // the workgroup that finishes last advances the epoch for the next launch
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -514,11 +544,16 @@ __global__ __launch_bounds__(kBlock, 2) void k_resident(ResArgs a) {
 template <int R>
 static hipError_t launch_k_resident(const ResArgs& a, int blocks, hipStream_t s, int* max_blocks_per_cu) {
     if (max_blocks_per_cu) {
-        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(max_blocks_per_cu, k_resident<R>, kBlock, 0);
+        int plain = 0, fused = 0;   // both variants must be co-resident
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&plain, k_resident<R, false>, kBlock, 0);
         if (e != hipSuccess) return e;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&fused, k_resident<R, true>, kBlock, 0);
+        if (e != hipSuccess) return e;
+        *max_blocks_per_cu = plain < fused ? plain : fused;
         return hipSuccess;
     }
-    hipLaunchKernelGGL((k_resident<R>), dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
+    if (a.upd.mom) hipLaunchKernelGGL((k_resident<R, true>), dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
+    else hipLaunchKernelGGL((k_resident<R, false>), dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
     return hipGetLastError();
 }
 
@@ -546,18 +581,19 @@ psgd_status resident_check_device(psgd_plan* plan) {
 }
 
 psgd_status launch_resident_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,
-                                 void* workspace, void* stream) {
+                                 void* workspace, void* stream, const UpdateArgs& upd) {
     if (!plan->uploaded) {
         psgd_status st = upload_tables(plan);
         if (st != PSGD_OK) return st;
         if (!plan->resident_ok) {   // upload found that the grid does not fit this device
             st = launch_compress(plan, grad, err, q, p, workspace, stream);
             if (st != PSGD_OK) return st;
-            return launch_decompress(plan, p, q, err, grad, out, workspace, stream);
+            return launch_decompress(plan, p, q, err, grad, out, workspace, stream, upd);
         }
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     ResArgs a{};
+    a.upd = upd;
     a.mats = plan->dev.res_mats;
     a.tiles = plan->dev.res_tiles;
     a.grad = static_cast<const float*>(grad);

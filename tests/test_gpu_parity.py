@@ -22,6 +22,7 @@ g + e = Delta' + e', and that the compression quality ||e'|| / ||M|| follows
 the oracle's.
 """
 import numpy as np
+import torch
 import pytest
 
 torch = pytest.importorskip("torch")
@@ -348,3 +349,85 @@ def test_resnet18_r2_100_steps_never_resynchronised():
             prev[i] = rg["err"][0][i]
         q_gpu, q_ora = np.sqrt(num_g / den_g), np.sqrt(num_o / den_o)
         assert abs(q_gpu - q_ora) <= 0.01 * q_ora, (t, q_gpu, q_ora)
+
+
+# ---- fused momentum / parameter update (Algorithm 2, last two lines) ------------------------------------
+
+def _run_update(wl, rank, workers, steps, seed, lr=0.05, lam=0.9, tuning=None, grad_bf16=False, split=False,
+                expect_resident=None):
+    """psgd_step_update against the oracle's step followed by its momentum_update: the momentum buffer
+    must match to the parity bar (it accumulates Delta'), the parameters to the bar relative to the size of
+    the update they received plus one fp32 rounding of their own magnitude; P_hat, Q, E' as for psgd_step."""
+    from oracle import powersgd_oracle as O
+    from paper_1905_13727_amd import workloads as WL
+    from gpu_harness import GpuRun, OracleRun, compare, rel_fro
+    factors = WL.planted_factors(wl, seed)
+    q0 = WL.initial_q(wl, rank, seed)
+    gpu = GpuRun(wl.shapes, rank, workers, q0, tuning, grad_bf16=grad_bf16)
+    ora = OracleRun(wl.shapes, rank, workers, q0)
+    lay, sizes = gpu.lay, gpu.plan.sizes
+    rng = np.random.default_rng(seed + 1000)
+    x0 = [rng.standard_normal(sh).astype(np.float32) for sh in wl.shapes]
+    m0 = [(0.1 * rng.standard_normal(sh)).astype(np.float32) for sh in wl.shapes]
+    dev = gpu.dev
+    mom = torch.from_numpy(lay.pack_flat(m0)).to(dev)
+    par = torch.from_numpy(lay.pack_flat(x0)).to(dev)
+    assert mom.numel() == sizes.out_elems
+    xo = [a.astype(np.float64) for a in x0]
+    mo = [a.astype(np.float64) for a in m0]
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    for t in range(steps):
+        grads = [WL.gradients(wl, factors, seed, t, w) for w in range(workers)]
+        if grad_bf16:
+            grads = [[WL.bf16_round(g) for g in gw] for gw in grads]
+        gpu.upload(grads)
+        if split:
+            gpu.plan.compress(gpu.grad, gpu.err, gpu.q, gpu.p, gpu.ws, stream)
+            gpu.plan.decompress_update(gpu.p, gpu.q, gpu.err, gpu.grad, mom, par, lr, lam, gpu.ws, stream)
+        else:
+            gpu.plan.step_update(gpu.grad, gpu.err, gpu.q, gpu.p, mom, par, lr, lam, gpu.ws, stream)
+        resident = gpu.plan.check(stream)
+        torch.cuda.synchronize(dev)
+        prev_errs = ora.errs
+        ro = ora.step(grads)
+        got = gpu.download()
+        got["out"] = [np.asarray(ro["out"][i], dtype=np.float32).reshape(np.asarray(got["out"][i]).shape)
+                      for i in range(len(wl.shapes))]    # Delta' is not stored by the fused call
+        worst = compare(got, ro, wl.shapes, workers, rank, grads, prev_errs)
+        assert worst["P_hat"] <= TOL and worst["Q"] <= TOL and worst["err"] <= TOL, (wl.name, t, worst)
+        gm = lay.unpack_flat(mom.cpu().numpy())
+        gx = lay.unpack_flat(par.cpu().numpy())
+        for i, sh in enumerate(wl.shapes):
+            delta = np.asarray(ro["out"][i], dtype=np.float64).reshape(sh)
+            x_new, m_new = O.momentum_update(xo[i], mo[i], delta, lr, lam)
+            assert rel_fro(gm[i].reshape(sh), m_new) <= TOL, (wl.name, t, i, "momentum")
+            upd_norm = np.linalg.norm(lr * (delta + m_new))
+            assert np.linalg.norm(gx[i].reshape(sh).astype(np.float64) - x_new) <= \
+                TOL * upd_norm + 2.0 ** -23 * np.linalg.norm(x_new), (wl.name, t, i, "parameters")
+            xo[i], mo[i] = x_new, m_new
+    if expect_resident is not None:
+        assert resident == expect_resident
+    gpu.plan.destroy()
+
+
+def test_fused_update_resident():
+    _need_gpu()
+    from paper_1905_13727_amd import workloads as WL
+    _run_update(WL.tiny(), rank=2, workers=1, steps=4, seed=3, expect_resident=True)
+    _run_update(_workload(RAGGED_1W), rank=3, workers=1, steps=3, seed=4, expect_resident=True)
+
+
+def test_fused_update_streaming():
+    _need_gpu()
+    _run_update(_workload(RAGGED_1W[:10]), rank=4, workers=3, steps=3, seed=5, expect_resident=False)
+    _run_update(_workload(RAGGED_1W[:10]), rank=2, workers=2, steps=2, seed=6, split=True, expect_resident=False)
+    _run_update(_workload(RAGGED_1W), rank=1, workers=1, steps=2, seed=7, tuning={"resident": 0, "k4_nv": 2},
+                expect_resident=False)
+
+
+def test_fused_update_matrix_cores():
+    _need_gpu()
+    from paper_1905_13727_amd import workloads as WL
+    wl = WL.Workload("tr-small", list(TRANSFORMER_SMALL), 64, 1.0 / np.arange(1, 65), 0.001)
+    _run_update(wl, rank=16, workers=2, steps=2, seed=8, expect_resident=False)
+    _run_update(wl, rank=4, workers=1, steps=2, seed=9, grad_bf16=True, expect_resident=False)
