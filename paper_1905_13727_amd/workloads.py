@@ -172,11 +172,13 @@ def _orthonormal(rng, n, k):
     return q * sgn[None, :]
 
 
-def planted_factors(wl: Workload, seed: int):
-    """Per matrix tensor: (U*s, V) with k' = min(k, n, m) columns; None for vectors."""
+def planted_factors(wl: Workload, seed: int, only=None):
+    """Per matrix tensor: (U*s, V) with k' = min(k, n, m) columns; None for vectors (and, when `only`
+    is a collection of tensor indices, for every tensor outside it: each tensor has its own seeded stream,
+    so a subset is generated exactly as it would be within the whole set)."""
     out = []
     for i, s in enumerate(wl.shapes):
-        if len(s) < 2:
+        if len(s) < 2 or (only is not None and i not in only):
             out.append(None)
             continue
         n, m = s
@@ -188,10 +190,13 @@ def planted_factors(wl: Workload, seed: int):
     return out
 
 
-def gradients(wl: Workload, factors, seed: int, step: int, worker: int):
-    """List of float32 arrays (one per tensor) for (step, worker)."""
+def gradients(wl: Workload, factors, seed: int, step: int, worker: int, only=None):
+    """List of float32 arrays (one per tensor) for (step, worker); None outside `only` when it is given."""
     out = []
     for i, s in enumerate(wl.shapes):
+        if only is not None and i not in only:
+            out.append(None)
+            continue
         rng = _rng(seed, i, step, worker)
         if len(s) < 2:
             out.append((wl.sigma * rng.standard_normal(s)).astype(np.float32))
@@ -208,11 +213,11 @@ def gradients(wl: Workload, factors, seed: int, step: int, worker: int):
     return out
 
 
-def initial_q(wl: Workload, rank: int, seed: int):
-    """Q0 iid N(0,1) per matrix (m x min(r, n, m)), float32; None for vectors."""
+def initial_q(wl: Workload, rank: int, seed: int, only=None):
+    """Q0 iid N(0,1) per matrix (m x min(r, n, m)), float32; None for vectors (and outside `only`)."""
     out = []
     for i, s in enumerate(wl.shapes):
-        if len(s) < 2:
+        if len(s) < 2 or (only is not None and i not in only):
             out.append(None)
             continue
         n, m = s

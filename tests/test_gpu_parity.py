@@ -431,3 +431,86 @@ def test_fused_update_matrix_cores():
     wl = WL.Workload("tr-small", list(TRANSFORMER_SMALL), 64, 1.0 / np.arange(1, 65), 0.001)
     _run_update(wl, rank=16, workers=2, steps=2, seed=8, expect_resident=False)
     _run_update(wl, rank=4, workers=1, steps=2, seed=9, grad_bf16=True, expect_resident=False)
+
+
+# ---- the 24-layer transformer-shaped set at full size, sampled tensors ---------------------------------
+
+@pytest.mark.parametrize("rank", [32, 4])
+def test_transformer_full_size_sampled(rank):
+    """The whole 145-matrix set (1.31 G elements, bf16 gradients and output, fp32 state) runs on the GPU in
+    the launch configuration bench.py times.  The method treats every matrix on its own, so the oracle run
+    on a sample of the tensors alone (the embedding, one matrix of each other shape from the first and the
+    last layer, two vectors) gives exactly what the full-set step must produce for them.  The sampled
+    tensors carry the planted-spectrum recipe from the host generator; the rest is noise drawn on the GPU."""
+    _need_gpu()
+    from oracle import powersgd_oracle as O
+    from paper_1905_13727_amd import binding as B, workloads as WL
+    from paper_1905_13727_amd.flat import FlatLayout
+    from gpu_harness import rel_fro
+    wl = WL.transformer(24)
+    shapes = wl.shapes
+    mat_idx = [i for i, sh in enumerate(shapes) if len(sh) == 2]
+    vec_idx = [i for i, sh in enumerate(shapes) if len(sh) == 1]
+    first = {}
+    for i in mat_idx:
+        first.setdefault(shapes[i], i)
+    last = {}
+    for i in mat_idx:
+        last[shapes[i]] = i
+    sample = sorted(set(first.values()) | set(last.values()) | {vec_idx[0], vec_idx[-1]})
+    assert (50304, 2048) in first and (2048, 8192) in first and len(sample) >= 8
+    dev = torch.device("cuda:0")
+    plan = B.Plan(shapes, rank, 1, B.PSGD_BF16, B.PSGD_BF16)
+    lay = FlatLayout(plan, shapes)
+    s = plan.sizes
+    seed = 90 + rank
+    factors = WL.planted_factors(wl, seed, only=sample)
+    q0 = WL.initial_q(wl, rank, seed, only=sample)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    q = torch.randn(s.q_elems, generator=gen, device=dev)
+    for i in sample:
+        if q0[i] is not None:
+            _, _, qo, r = plan.offsets(i)
+            q[qo: qo + q0[i].size] = torch.from_numpy(q0[i].reshape(-1)).to(dev)
+    err = torch.zeros(s.err_stride, device=dev)
+    p = torch.zeros(s.p_elems, device=dev)
+    out = torch.zeros(s.out_elems, dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(s.workspace_bytes // 4 + 64, device=dev)
+    grad = torch.empty(s.grad_stride, dtype=torch.bfloat16, device=dev)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    Qs = [None if q0[i] is None else q0[i].astype(np.float64) for i in sample]
+    Es = [[None if len(shapes[i]) == 1 else np.zeros(shapes[i]) for i in sample]]
+    sub_shapes = [shapes[i] for i in sample]
+    for t in range(2):
+        grad.normal_(0.0, wl.sigma, generator=gen)
+        g_host = WL.gradients(wl, factors, seed, t, 0, only=sample)
+        sub = []
+        for i in sample:
+            g = WL.bf16_round(g_host[i])
+            sub.append(g)
+            fo = plan.offsets(i)[0]
+            grad[fo: fo + g.size] = torch.from_numpy(g.reshape(-1)).to(dev).to(torch.bfloat16)
+        plan.step(grad, err, q, p, out, ws, stream)
+        assert plan.check(stream) is False
+        torch.cuda.synchronize(dev)
+        ro = O.powersgd_step([sub], Es, Qs, rank)
+        Qs, Es = ro["Q"], ro["err"]
+        for k, i in enumerate(sample):
+            fo, po, qo, r = plan.offsets(i)
+            sh = shapes[i]
+            n_el = int(np.prod(sh))
+            got_out = out[fo: fo + n_el].float().cpu().numpy().reshape(sh).astype(np.float64)
+            want_out = np.asarray(ro["out"][k]).reshape(sh)
+            assert rel_fro(got_out, want_out) <= 2.0 ** -8, (rank, t, i, "out")
+            if len(sh) == 1:
+                continue
+            n, m = sh
+            got_p = p[po: po + n * r].cpu().numpy().reshape(n, r)
+            got_q = q[qo: qo + m * r].cpu().numpy().reshape(m, r)
+            got_e = err[fo: fo + n_el].cpu().numpy().reshape(sh)
+            worst = (rel_fro(got_p, ro["P_hat"][k]), rel_fro(got_q, ro["Q"][k]), rel_fro(got_e, ro["err"][0][k]))
+            print("[transformer full size] r=%d step %d tensor %d %s: P %.2e Q %.2e E %.2e"
+                  % (rank, t, i, sh, *worst), flush=True)
+            assert max(worst) <= TOL, (rank, t, i, sh, worst)
+    plan.destroy()
