@@ -57,6 +57,8 @@ def parse():
     ap.add_argument("--update", choices=["none", "fused", "separate"], default="none",
                     help="also apply the momentum / parameter update of Algorithm 2: fused into the step "
                          "(psgd_step_update) or as separate elementwise kernels after psgd_step")
+    ap.add_argument("--iterations", type=int, default=1,
+                    help="subspace iterations per step (psgd_compress, then psgd_iterate, then psgd_decompress)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing")
     ap.add_argument("--tune", action="append", default=[], help="key=value planner tuning (experiments)")
@@ -176,6 +178,12 @@ def main():
             return 2
 
     def step(i):
+        if args.iterations > 1:   # Appendix G.7: several subspace iterations per step (split calls, never resident)
+            plan.compress(grads[i % len(grads)], err, q, p, ws, sh)
+            for _ in range(args.iterations - 1):
+                plan.iterate(err, q, p, ws, sh)
+            plan.decompress(p, q, err, grads[i % len(grads)], out, ws, sh)
+            return
         if args.update == "fused":
             plan.step_update(grads[i % len(grads)], err, q, p, mom, par, 0.01, 0.9, ws, sh)
         else:
@@ -265,7 +273,8 @@ def main():
                            ("matrix cores (one kernel per phase)" if rank > 8 or gdt != "f32" or odt != "f32"
                             else "streaming (one kernel per phase)"),
                    "matrices": int(s.n_matrices), "matrix_elems": int(payload_mat), "vector_elems": int(L),
-                   "grad_buffers": len(grads), "update": args.update},
+                   "grad_buffers": len(grads), "update": args.update,
+                   "iterations": args.iterations},
         "stream_model": {"bytes_per_step": int(s.bytes_stream),
                          "GBps": round(s.bytes_stream / (ms_per_step * 1e-3) / 1e9, 2),
                          "frac_of_hbm_peak": round(s.bytes_stream / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},

@@ -162,6 +162,18 @@ PSGD_API psgd_status psgd_decompress(psgd_plan* plan, const float* p, const floa
 PSGD_API psgd_status psgd_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p,
                       void* out, void* workspace, void* hip_stream);
 
+/* One more subspace iteration of Algorithm 1 on the update already held in `err`
+ * (M_w = g_w + e_w as left there by psgd_compress): P = mean_w M_w Q, orthogonalise,
+ * Q = mean_w M_w^T P_hat.  Nothing is added to err and err is not written.
+ * psgd_compress followed by k-1 calls of psgd_iterate, then psgd_decompress, is the
+ * compressor with k iterations per step of Appendix G.7 ("best approximation" as k
+ * grows; started from a fresh random Q it is the variant without warm start of
+ * Table 2).  Always the streaming or matrix-core kernels (no resident mode).
+ *   err (device, const in effect)  M_w  [W][N] float
+ *   q   (device, in/out), p (device, out), workspace, hip_stream: as psgd_compress */
+PSGD_API psgd_status psgd_iterate(psgd_plan* plan, float* err, float* q, float* p, void* workspace,
+                         void* hip_stream);
+
 /* The step fused with the last two lines of Algorithm 2 (error-feedback SGD with
  * momentum): m <- lambda m + Delta' ; x <- x - gamma (Delta' + m).  Delta' is not
  * stored: the decompression pass reads and writes the momentum and parameter

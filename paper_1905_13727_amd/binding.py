@@ -68,6 +68,8 @@ def load_library(path: Optional[str] = None):
     lib.psgd_step.restype = C.c_int
     lib.psgd_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psgd_plan_set_profiling.restype = C.c_int
+    lib.psgd_iterate.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.psgd_iterate.restype = C.c_int
     lib.psgd_step_update.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_float, C.c_float, vp, vp]
     lib.psgd_step_update.restype = C.c_int
     lib.psgd_decompress_update.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_float, C.c_float, vp, vp]
@@ -169,6 +171,10 @@ class Plan:
     def step(self, grad, err, q, p, out, workspace, stream=None):
         self._check(self._lib.psgd_step(self._h, _ptr(grad), _ptr(err), _ptr(q), _ptr(p), _ptr(out),
                                         _ptr(workspace), _ptr(stream)), "psgd_step")
+
+    def iterate(self, err, q, p, workspace, stream=None):
+        self._check(self._lib.psgd_iterate(self._h, _ptr(err), _ptr(q), _ptr(p), _ptr(workspace), _ptr(stream)),
+                    "psgd_iterate")
 
     def step_update(self, grad, err, q, p, mom, param, lr, momentum, workspace, stream=None):
         self._check(self._lib.psgd_step_update(self._h, _ptr(grad), _ptr(err), _ptr(q), _ptr(p), _ptr(mom), _ptr(param),

@@ -117,7 +117,7 @@ template <int NT, bool BF, bool F64>
 __global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                         const void* __restrict__ grad, float* __restrict__ err,
                                                         const float* __restrict__ q, float* __restrict__ ws,
-                                                        int64_t gstride, int64_t estride) {
+                                                        int64_t gstride, int64_t estride, int add) {
     constexpr int STEPS = 2;                          // 16-row steps per wavefront and pass: 128 rows per workgroup and pass
     constexpr int RP = 16 * NT;                       // padded rank
     constexpr int BST = RP + 4;                       // floats per LDS row of the staged Q chunk
@@ -185,8 +185,11 @@ __global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatD
         // out of range explicitly.
         const int rows_w = max(0, min(16 * STEPS, row_end - row_w));
         const int64_t base_w = (int64_t)min(row_w, row_end) * m;
+        // add == 0 (one more iteration on the M already stored): the gradient descriptor is empty (zeros are read),
+        // and so is the one M would be stored through
         const buf_rsrc eres = make_rsrc(emat + base_w, (int64_t)rows_w * m * 4);
-        const buf_rsrc gres = make_rsrc(gmat + base_w * GS, (int64_t)rows_w * m * GS);
+        const buf_rsrc esto = make_rsrc(emat + base_w, add ? (int64_t)rows_w * m * 4 : 0);
+        const buf_rsrc gres = make_rsrc(gmat + base_w * GS, add ? (int64_t)rows_w * m * GS : 0);
         unsigned voff[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) voff[i] = (unsigned)(4 * i + lr) * (unsigned)m + (unsigned)lc;
@@ -225,7 +228,7 @@ __global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatD
                     for (int i = 0; i < 4; ++i) {
                         const v4f mv = gn[i] + en[i];
                         const unsigned el = voff[i] + (unsigned)(16 * s * m + c0);
-                        buf_store_v4f(eres, col_ok ? el * 4u : kOutOfRange, mv);
+                        buf_store_v4f(esto, col_ok ? el * 4u : kOutOfRange, mv);
                         *reinterpret_cast<v4f*>(&at[4 * i + lr][lc]) = mv;
                     }
                 }
@@ -694,18 +697,16 @@ static psgd_status hr_fail(psgd_plan* plan, const char* what) {
     } while (0)
 
 template <int NT>
-static void hr_launch_right(psgd_plan* plan, const void* grad, float* err, const float* q, float* ws, hipStream_t s) {
+static void hr_launch_right(psgd_plan* plan, const void* grad, float* err, const float* q, float* ws, hipStream_t s,
+                            bool add) {
     dim3 grid((unsigned)plan->hr_tiles1.size(), (unsigned)plan->workers);
     // fp64 accumulation at every rank of this path: it costs nothing next to the loads (2.88 against 2.92 ms on
     // the transformer set) and at rank 4 fp32 accumulation left P_hat up to 8e-6 off after two steps
-    const bool bf = plan->grad_dtype == PSGD_BF16, f64 = true;
-#define HR_RIGHT(BFV, F64V)                                                                                       \
-    hipLaunchKernelGGL((k_hr_right<NT, BFV, F64V>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles1, \
-                       grad, err, q, ws, plan->sizes.grad_stride, plan->sizes.err_stride)
-    if (bf && f64) HR_RIGHT(true, true);
-    else if (bf) HR_RIGHT(true, false);
-    else if (f64) HR_RIGHT(false, true);
-    else HR_RIGHT(false, false);
+#define HR_RIGHT(BFV)                                                                                             \
+    hipLaunchKernelGGL((k_hr_right<NT, BFV, true>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles1, \
+                       grad, err, q, ws, plan->sizes.grad_stride, plan->sizes.err_stride, add ? 1 : 0)
+    if (plan->grad_dtype == PSGD_BF16) HR_RIGHT(true);
+    else HR_RIGHT(false);
 #undef HR_RIGHT
 }
 
@@ -728,15 +729,15 @@ static double* hr_doubles(psgd_plan* plan, void* workspace) {
 }
 
 psgd_status hr_compress(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* workspace,
-                        void* stream) {
+                        void* stream, bool add) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     float* ws = static_cast<float*>(workspace);
     if (plan->mats.empty()) return PSGD_OK;
     const int nt = plan->hr_nt;
     HR_MARK(0);
-    if (nt == 1) hr_launch_right<1>(plan, grad, err, q, ws, s);
-    else if (nt == 2) hr_launch_right<2>(plan, grad, err, q, ws, s);
-    else hr_launch_right<4>(plan, grad, err, q, ws, s);
+    if (nt == 1) hr_launch_right<1>(plan, grad, err, q, ws, s, add);
+    else if (nt == 2) hr_launch_right<2>(plan, grad, err, q, ws, s, add);
+    else hr_launch_right<4>(plan, grad, err, q, ws, s, add);
     HR_CHECK("launch k_hr_right");
     HR_MARK(1);
     double* gram = hr_doubles(plan, workspace);

@@ -191,8 +191,9 @@ psgd_status build_tables(psgd_plan* plan);
 // device side (psgd_kernels.hip)
 psgd_status upload_tables(psgd_plan* plan);
 void free_tables(psgd_plan* plan);
+// add = false: one more subspace iteration on the update already held in err (grad is not read, err not written)
 psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float* q, float* p,
-                            void* workspace, void* stream);
+                            void* workspace, void* stream, bool add = true);
 psgd_status launch_decompress(psgd_plan* plan, const float* p, const float* q, float* err,
                               const void* grad, void* out, void* workspace, void* stream,
                               const UpdateArgs& upd = UpdateArgs());
@@ -200,7 +201,7 @@ psgd_status set_profiling(psgd_plan* plan, bool enable);
 psgd_status launch_q_reduce(psgd_plan* plan, float* ws, float* q, void* stream);
 psgd_status finish_profiled_step(psgd_plan* plan);
 psgd_status hr_compress(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* workspace,
-                        void* stream);
+                        void* stream, bool add);
 psgd_status hr_decompress(psgd_plan* plan, const float* p, const float* q, float* err, const void* grad, void* out,
                           void* stream, const UpdateArgs& upd);
 psgd_status check_plan(psgd_plan* plan, void* stream);

@@ -33,7 +33,8 @@ namespace psgd {
 // loads, writes M over e, and the wavefront reduces R dot products per row.  Partial sums
 // of different column chunks / workers go to separate slices of the workspace.
 
-template <int R, int V, int NV>
+// ADD = false: one more subspace iteration on an update that already sits in e (nothing is added, e is not written)
+template <int R, int V, int NV, bool ADD>
 __device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, const float* __restrict__ g,
                                               float* __restrict__ e, const float* __restrict__ q,
                                               float* __restrict__ ppart) {
@@ -66,7 +67,7 @@ __device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, c
         for (int i = 0; i < RS; ++i)
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
-                if (i < rows && valid[v]) {
+                if (ADD && i < rows && valid[v]) {
                     ldv_stream<V>(g + d.off + (int64_t)(i0 + i) * d.m + col[v], mv[i][v]);
                 } else {
 #pragma unroll
@@ -82,7 +83,7 @@ __device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, c
                     ldv<V>(e + d.off + (int64_t)(i0 + i) * d.m + col[v], ev);
 #pragma unroll
                     for (int x = 0; x < V; ++x) mv[i][v][x] += ev[x];
-                    stv<V>(e + d.off + (int64_t)(i0 + i) * d.m + col[v], mv[i][v]);
+                    if constexpr (ADD) stv<V>(e + d.off + (int64_t)(i0 + i) * d.m + col[v], mv[i][v]);
                 }
         // RS * R dot products, reduced over the wavefront; lane i * R + k keeps the result of (row i, rank k)
         float mine = 0.f;
@@ -107,7 +108,7 @@ __device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, c
     }
 }
 
-template <int R, int NV>
+template <int R, int NV, bool ADD>
 __global__ __launch_bounds__(kBlock) void k_ef_right(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                      const float* __restrict__ grad, float* __restrict__ err,
                                                      const float* __restrict__ q, float* __restrict__ ws,
@@ -118,9 +119,9 @@ __global__ __launch_bounds__(kBlock) void k_ef_right(const MatDesc* __restrict__
     const float* g = grad + (int64_t)w * gstride;
     float* e = err + (int64_t)w * estride;
     t.part += w * d.n_cchunk;   // partial slices: [worker][column chunk]
-    if (d.vec == 4) ef_right_tile<R, 4, NV>(t, d, g, e, q, ws);
-    else if (d.vec == 2) ef_right_tile<R, 2, NV>(t, d, g, e, q, ws);
-    else ef_right_tile<R, 1, NV>(t, d, g, e, q, ws);
+    if (d.vec == 4) ef_right_tile<R, 4, NV, ADD>(t, d, g, e, q, ws);
+    else if (d.vec == 2) ef_right_tile<R, 2, NV, ADD>(t, d, g, e, q, ws);
+    else ef_right_tile<R, 1, NV, ADD>(t, d, g, e, q, ws);
 }
 
 // ---- k_ef_right_mfma: the same on the matrix cores -------------------------------------------------
@@ -897,14 +898,19 @@ psgd_status check_plan(psgd_plan* plan, void* stream) {
 
 template <int R>
 static void launch_ef_right(psgd_plan* plan, const float* grad, float* err, const float* q, float* ws,
-                            hipStream_t s) {
+                            hipStream_t s, bool add) {
     dim3 grid((unsigned)plan->tiles1.size(), (unsigned)plan->workers);
-    if (plan->tuning.k1_nv == 1)
-        hipLaunchKernelGGL((k_ef_right<R, 1>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles1, grad, err, q,
-                           ws, plan->sizes.grad_stride, plan->sizes.err_stride);
-    else
-        hipLaunchKernelGGL((k_ef_right<R, 2>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles1, grad, err, q,
-                           ws, plan->sizes.grad_stride, plan->sizes.err_stride);
+#define PSGD_LAUNCH_RIGHT(NVV, ADDV)                                                                                     \
+    hipLaunchKernelGGL((k_ef_right<R, NVV, ADDV>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles1, grad, err, \
+                       q, ws, plan->sizes.grad_stride, plan->sizes.err_stride)
+    if (add) {
+        if (plan->tuning.k1_nv == 1) PSGD_LAUNCH_RIGHT(1, true);
+        else PSGD_LAUNCH_RIGHT(2, true);
+    } else {
+        if (plan->tuning.k1_nv == 1) PSGD_LAUNCH_RIGHT(1, false);
+        else PSGD_LAUNCH_RIGHT(2, false);
+    }
+#undef PSGD_LAUNCH_RIGHT
 }
 
 template <int R>
@@ -959,10 +965,11 @@ static psgd_status check_ready(psgd_plan* plan) {
 }
 
 psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* workspace,
-                            void* stream) {
+                            void* stream, bool add) {
     psgd_status st = check_ready(plan);
     if (st != PSGD_OK) return st;
-    if (plan->hr) return hr_compress(plan, grad, err, q, p, workspace, stream);
+    if (plan->hr) return hr_compress(plan, grad, err, q, p, workspace, stream, add);
+    if (!add && plan->k1_on_mfma) return PSGD_EUNSUPPORTED;   // the experimental matrix-core K1 always adds
     hipStream_t s = static_cast<hipStream_t>(stream);
     float* ws = static_cast<float*>(workspace);
     const float* g = static_cast<const float*>(grad);
@@ -974,7 +981,7 @@ psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float
                            plan->dev.mats, plan->dev.tiles1, g, err, q, ws, plan->sizes.grad_stride,
                            plan->sizes.err_stride);
     } else {
-        PSGD_RANK_SWITCH(launch_ef_right, plan, g, err, q, ws, s);
+        PSGD_RANK_SWITCH(launch_ef_right, plan, g, err, q, ws, s, add);
     }
     PSGD_HIP(hipGetLastError(), "launch k_ef_right");
     PSGD_MARK(1);

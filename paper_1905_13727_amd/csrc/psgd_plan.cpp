@@ -607,6 +607,12 @@ psgd_status psgd_step(psgd_plan* plan, const void* grad, float* err, float* q, f
     return launch_decompress(plan, p, q, err, grad, out, workspace, hip_stream);
 }
 
+psgd_status psgd_iterate(psgd_plan* plan, float* err, float* q, float* p, void* workspace, void* hip_stream) {
+    if (!plan || !err || !q || !p || !workspace) return PSGD_EINVAL;
+    // the gradient pointer is not dereferenced when nothing is added; err stands in so that it is never null
+    return launch_compress(plan, err, err, q, p, workspace, hip_stream, false);
+}
+
 static bool update_args(const psgd_plan* plan, float* mom, float* param, float lr, float momentum, UpdateArgs* upd) {
     (void)plan;
     if (!mom || !param || !(lr == lr) || !(momentum == momentum)) return false;   // null or NaN

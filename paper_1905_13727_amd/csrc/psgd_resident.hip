@@ -480,7 +480,6 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
                         dl[x] = s;
                         en[x] = M[i < RT ? i : 0][x] - s;
                     }
-#ifndef PSGD_EXPERIMENT_NO_PHASE_C_STORES
                     stv<V>(a.err + tile_off + (int64_t)i * d.m, en);
                     if constexpr (UPD) {
                         momentum_step<V>(mo[u], pa[u], dl, a.upd.lr, a.upd.lam);
@@ -489,9 +488,6 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
                     } else {
                         stv<V>(a.out + tile_off + (int64_t)i * d.m, dl);
                     }
-#else
-                    if (en[0] == 12345.678f && dl[0] == 9.87f) stv<V>(a.out + tile_off + (int64_t)i * d.m, dl);
-#endif
                 }
             }
         }

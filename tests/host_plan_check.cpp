@@ -19,7 +19,7 @@ psgd_status read_trace(psgd_plan*, uint64_t*, int64_t, int64_t*) { return PSGD_E
 psgd_status launch_resident_step(psgd_plan*, const void*, float*, float*, float*, void*, void*, void*, const UpdateArgs&) {
     return PSGD_EHIP;
 }
-psgd_status launch_compress(psgd_plan*, const void*, float*, float*, float*, void*, void*) { return PSGD_EHIP; }
+psgd_status launch_compress(psgd_plan*, const void*, float*, float*, float*, void*, void*, bool) { return PSGD_EHIP; }
 psgd_status launch_decompress(psgd_plan*, const float*, const float*, float*, const void*, void*, void*, void*,
                               const UpdateArgs&) {
     return PSGD_EHIP;

@@ -514,3 +514,68 @@ def test_transformer_full_size_sampled(rank):
                   % (rank, t, i, sh, *worst), flush=True)
             assert max(worst) <= TOL, (rank, t, i, sh, worst)
     plan.destroy()
+
+
+# ---- several subspace iterations per step (Appendix G.7) --------------------------------------------------
+
+def _run_iterations(wl, rank, workers, iterations, seed, tuning=None, grad_bf16=False):
+    """psgd_compress, iterations - 1 calls of psgd_iterate, psgd_decompress, from a fresh Q every step,
+    against the oracle's best_approx_compress on the same M = g + e followed by its decompression."""
+    from oracle import powersgd_oracle as O
+    from paper_1905_13727_amd import workloads as WL
+    from gpu_harness import GpuRun, rel_fro
+    factors = WL.planted_factors(wl, seed)
+    gpu = GpuRun(wl.shapes, rank, workers, WL.initial_q(wl, rank, seed), tuning, grad_bf16=grad_bf16)
+    stream = torch.cuda.current_stream(gpu.dev).cuda_stream
+    mats = [i for i, sh in enumerate(wl.shapes) if len(sh) > 1]
+    errs = [[None if len(sh) == 1 else np.zeros(O.matrix_view(sh)) for sh in wl.shapes] for _ in range(workers)]
+    for t in range(2):
+        q0 = WL.initial_q(wl, rank, seed + 100 + t)    # no warm start: a fresh Q every step
+        gpu.set_q(q0)
+        grads = [WL.gradients(wl, factors, seed, t, w) for w in range(workers)]
+        if grad_bf16:
+            grads = [[WL.bf16_round(g) for g in gw] for gw in grads]
+        gpu.upload(grads)
+        gpu.plan.compress(gpu.grad, gpu.err, gpu.q, gpu.p, gpu.ws, stream)
+        for _ in range(iterations - 1):
+            gpu.plan.iterate(gpu.err, gpu.q, gpu.p, gpu.ws, stream)
+        gpu.plan.decompress(gpu.p, gpu.q, gpu.err, gpu.grad, gpu.out, gpu.ws, stream)
+        gpu.plan.check(stream)
+        torch.cuda.synchronize(gpu.dev)
+        got = gpu.download()
+        new_errs = [[None] * len(wl.shapes) for _ in range(workers)]
+        for i in mats:
+            sh = O.matrix_view(wl.shapes[i])
+            Ms = [np.asarray(grads[w][i], dtype=np.float64).reshape(sh) + errs[w][i] for w in range(workers)]
+            P_hat, Q = O.best_approx_compress(Ms, q0[i].astype(np.float64), iterations)
+            delta = O.decompress(P_hat, Q)
+            assert rel_fro(got["P_hat"][i], P_hat) <= TOL, (wl.name, t, i, "P_hat", rel_fro(got["P_hat"][i], P_hat))
+            assert rel_fro(got["Q"][i], Q) <= TOL, (wl.name, t, i, "Q")
+            assert rel_fro(np.asarray(got["out"][i]).reshape(sh), delta) <= TOL, (wl.name, t, i, "out")
+            for w in range(workers):
+                new_errs[w][i] = Ms[w] - delta
+                # full-rank case: the new error memory is a rounding residue, measured against ||M_w|| (as in compare())
+                scale = np.linalg.norm(Ms[w]) if min(rank, *sh) == min(sh) else np.linalg.norm(new_errs[w][i])
+                assert np.linalg.norm(np.asarray(got["err"][w][i]).reshape(sh) - new_errs[w][i]) <= TOL * scale, \
+                    (wl.name, t, i, w, "err")
+        # the oracle carries its own error memory on (rounded to fp32 as the GPU holds it)
+        errs = [[None if e is None else e.astype(np.float32).astype(np.float64) for e in ew] for ew in new_errs]
+        gpu.set_err([[np.zeros(wl.shapes[i], dtype=np.float32) if e is None else e.reshape(wl.shapes[i])
+                      for i, e in enumerate(ew)] for ew in errs])
+    gpu.plan.destroy()
+
+
+@pytest.mark.parametrize("iterations", [2, 4])
+def test_iterations_streaming(iterations):
+    _need_gpu()
+    from paper_1905_13727_amd import workloads as WL
+    _run_iterations(WL.tiny(), rank=2, workers=1, iterations=iterations, seed=11)
+    _run_iterations(_workload(RAGGED_1W[:10]), rank=3, workers=2, iterations=iterations, seed=12)
+
+
+def test_iterations_matrix_cores():
+    _need_gpu()
+    from paper_1905_13727_amd import workloads as WL
+    wl = WL.Workload("tr-small", list(TRANSFORMER_SMALL), 64, 1.0 / np.arange(1, 65), 0.001)
+    _run_iterations(wl, rank=16, workers=1, iterations=3, seed=13)
+    _run_iterations(wl, rank=4, workers=2, iterations=2, seed=14, grad_bf16=True)
