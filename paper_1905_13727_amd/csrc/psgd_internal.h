@@ -103,6 +103,7 @@ struct Tuning {
     int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream
     int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height
     int64_t res_trace = 0;  // 1: the resident kernel records phase timestamps (diagnostic)
+    int64_t xcd_order = 1;  // 1: tile lists are ordered so that each accelerator die (own L2) works on one contiguous range of tiles
 };
 
 struct DeviceTables {

@@ -60,6 +60,24 @@ static void streaming_tiles(const psgd_plan* plan, int64_t rows_per_tile, int64_
     }
 }
 
+// Workgroups are handed to the 8 accelerator dies (XCDs, one L2 each) round robin by their linear index.  With
+// the tile list permuted so that entry b is the (b / 8)-th tile of the b % 8-th contiguous eighth of the list,
+// each die works through one contiguous range of tiles: neighbouring tiles (column chunks of the same rows, the
+// next row block) share cache lines at their edges when rows are not multiples of the line size, and those lines
+// then stay within one L2 instead of being fetched and partially written back by two.
+static void order_for_xcds(std::vector<Tile>& tiles) {
+    constexpr size_t X = 8;
+    const size_t nb = tiles.size();
+    if (nb < 2 * X) return;
+    const size_t per = nb / X, rem = nb % X;
+    std::vector<Tile> out(nb);
+    for (size_t b = 0; b < nb; ++b) {
+        const size_t x = b % X, k = b / X;
+        out[b] = tiles[x * per + std::min(x, rem) + k];
+    }
+    tiles.swap(out);
+}
+
 void build_resident(psgd_plan* plan);
 
 // Matrix-core path: its own tilings and workspace layout.
@@ -142,6 +160,11 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
     plan->resident_ok = false;
     plan->res_tiles.clear(); plan->res_mats.clear();
     plan->res_ws_floats = 0; plan->res_blocks = 0; plan->res_mail_slots = 0; plan->res_sync_words = 0;
+    if (tu.xcd_order) {
+        order_for_xcds(plan->hr_tiles1);
+        order_for_xcds(plan->hr_tiles3);
+        order_for_xcds(plan->hr_tiles4);
+    }
     plan->tables_built = true;
     return PSGD_OK;
 }
@@ -269,6 +292,11 @@ psgd_status build_tables(psgd_plan* plan) {
     build_resident(plan);
     plan->sizes.workspace_bytes =
         std::max<int64_t>(plan->sizes.workspace_bytes, plan->res_ws_floats * (int64_t)sizeof(float));
+    if (tu.xcd_order) {
+        order_for_xcds(plan->tiles1);
+        order_for_xcds(plan->tiles3);
+        order_for_xcds(plan->tiles4);
+    }
     plan->tables_built = true;
     return PSGD_OK;
 }
@@ -562,6 +590,7 @@ psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value
     else if (!strcmp(key, "q_reduce_elems")) tu.q_reduce_elems = value;
     else if (!strcmp(key, "k1_mfma")) tu.k1_mfma = value;
     else if (!strcmp(key, "hr_k3_rows")) tu.hr_k3_rows = value;
+    else if (!strcmp(key, "xcd_order")) tu.xcd_order = value;
     else if (!strcmp(key, "hr_k1_rows")) tu.hr_k1_rows = value;
     else if (!strcmp(key, "hr_k1_cols")) tu.hr_k1_cols = value;
     else if (!strcmp(key, "resident")) tu.resident = value;

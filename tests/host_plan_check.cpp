@@ -41,9 +41,14 @@ static void check_cover(const psgd_plan* plan, const std::vector<Tile>& tiles, i
     std::vector<std::vector<unsigned char>> seen(plan->mats.size());
     for (size_t i = 0; i < plan->mats.size(); ++i) seen[i].assign((size_t)plan->mats[i].n * plan->mats[i].m, 0);
     int64_t vec_seen = 0;
+    std::vector<unsigned char> vseen((size_t)plan->sizes.n_vec_elems, 0);
     for (const Tile& t : tiles) {
-        if (t.mat < 0) {
-            CHECK(t.elem0 == vec_seen && t.nelem > 0);
+        if (t.mat < 0) {   // a slice of the vector-shaped tensors; the list may be in any order (it is ordered for the dies)
+            CHECK(t.elem0 >= 0 && t.nelem > 0 && t.elem0 + t.nelem <= plan->sizes.n_vec_elems);
+            for (int64_t e = t.elem0; e < t.elem0 + t.nelem; ++e) {
+                CHECK(vseen[(size_t)e] == 0);
+                vseen[(size_t)e] = 1;
+            }
             vec_seen += t.nelem;
             continue;
         }
