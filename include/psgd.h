@@ -98,7 +98,8 @@ typedef struct {
  * Errors: PSGD_EINVAL for null pointers, n_tensors < 1, rank < 1, workers < 1,
  * a non-positive dimension; PSGD_EUNSUPPORTED for rank > PSGD_MAX_RANK, or,
  * when rank > 8 or a dtype is PSGD_BF16 (the matrix-core kernels), a matrix whose
- * column count is not a multiple of 4 or exceeds 2^20; PSGD_ENOMEM. */
+ * column count is not a multiple of 4 or exceeds 2^20, or with more than 2^22 rows;
+ * PSGD_ENOMEM. */
 #define PSGD_MAX_RANK 64
 PSGD_API psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_t rank,
                              int32_t workers, psgd_dtype grad_dtype, psgd_dtype out_dtype,

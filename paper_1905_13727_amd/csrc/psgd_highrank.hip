@@ -277,50 +277,87 @@ __global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatD
 constexpr int kHrMaxRank = PSGD_MAX_RANK;
 constexpr int kHrGramRows = 128;   // panel rows staged in LDS at a time by the Gram kernel
 
-// Row block (at most kHrGramTileRows rows): mean P (sum over workers and column ranges, * 1/W) -> P buffer; Gram matrix of the block in
-// fp64 -> gram[block][r*r].  Thread t owns entries (a, b) with a * r + b = t, t + 256, ...
+// Row block: mean P (sum over workers and column ranges, * 1/W) -> P buffer; Gram matrix of the block in fp64 ->
+// gram[block][r*r].  The block is staged 128 rows at a time in LDS; the Gram matrix is accumulated on the fp64
+// matrix cores: output tile (ta, tb) of 16 x 16 entries is sum over rows of P[row][16 ta + i] P[row][16 tb + j],
+// four rows per instruction (A[i][k] = P[4 s + k][16 ta + i], B[k][j] = P[4 s + k][16 tb + j]); the NT^2 tiles
+// are dealt to the four wavefronts.  Rows beyond the block and rank columns beyond r are zero in LDS.
+template <int NT>
 __global__ __launch_bounds__(kBlock) void k_hr_gram(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                     const float* __restrict__ ws, float* __restrict__ p,
                                                     double* __restrict__ gram, int workers) {
-    __shared__ float rows[kHrGramRows][kHrMaxRank + 1];
+    constexpr int RP = 16 * NT;
+    constexpr int TPW = (NT * NT + kWavesPerBlock - 1) / kWavesPerBlock;   // output tiles per wavefront
+    __shared__ float rows[kHrGramRows][RP + 1];
     const Tile t = tiles[blockIdx.x];
     const MatDesc d = mats[t.mat];
     const int r = d.r, tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    const int li = lane & 15, kb = lane >> 4;
     const int64_t nr = (int64_t)d.n * r;
     const float inv_w = 1.0f / (float)workers;
-    const int nent = r * r;
-    constexpr int EPT = (kHrMaxRank * kHrMaxRank + kBlock - 1) / kBlock;   // entries per thread
-    double g[EPT];
+    const int nparts = workers * d.n_cchunk;
+    v4d acc[TPW];
 #pragma unroll
-    for (int x = 0; x < EPT; ++x) g[x] = 0.0;
+    for (int x = 0; x < TPW; ++x) acc[x] = v4d{0.0, 0.0, 0.0, 0.0};
     for (int r0 = t.row0; r0 < t.row0 + t.nrows; r0 += kHrGramRows) {
         const int nrow = min(kHrGramRows, t.row0 + t.nrows - r0);
         __syncthreads();
-        for (int idx = tid; idx < nrow * r; idx += kBlock) {
-            const int i = idx / r, k = idx - i * r;
-            const int64_t at = (int64_t)(r0 + i) * r + k;
-            float s = 0.f;
-            for (int w = 0; w < workers * d.n_cchunk; ++w) s += ws[d.ppart_off + (int64_t)w * nr + at];
-            s *= inv_w;
-            rows[i][k] = s;
-            p[d.p_off + at] = s;
+        // every thread's EPT elements of a partial slice are requested together (out-of-range ones through an
+        // offset beyond the descriptor), slice after slice in slice order
+        constexpr int EPT = kHrGramRows * RP / kBlock;
+        float v[EPT];
+        unsigned off[EPT];
+#pragma unroll
+        for (int x = 0; x < EPT; ++x) {
+            const int idx = tid + x * kBlock;
+            const int i = idx / RP, k = idx % RP;
+            v[x] = 0.f;
+            off[x] = (i < nrow && k < r) ? (unsigned)(((int64_t)(r0 + i) * r + k) * 4) : kOutOfRange;
+        }
+        for (int w = 0; w < nparts; ++w) {
+            const buf_rsrc pres = make_rsrc(ws + d.ppart_off + (int64_t)w * nr, nr * 4);   // one slice: n r floats
+            float t4[EPT];
+#pragma unroll
+            for (int x = 0; x < EPT; ++x) t4[x] = buf_load_f32(pres, off[x]);
+#pragma unroll
+            for (int x = 0; x < EPT; ++x) v[x] += t4[x];
+        }
+#pragma unroll
+        for (int x = 0; x < EPT; ++x) {
+            const int idx = tid + x * kBlock;
+            const int i = idx / RP, k = idx % RP;
+            v[x] *= inv_w;
+            if (i < nrow && k < r) p[d.p_off + (int64_t)(r0 + i) * r + k] = v[x];
+            rows[i][k] = v[x];
         }
         __syncthreads();
 #pragma unroll
-        for (int x = 0; x < EPT; ++x) {
-            const int ent = tid + x * kBlock;
-            if (ent < nent) {
-                const int a = ent / r, b = ent - a * r;
-                double acc = g[x];
-                for (int i = 0; i < nrow; ++i) acc += (double)rows[i][a] * (double)rows[i][b];
-                g[x] = acc;
+        for (int x = 0; x < TPW; ++x) {
+            const int pair = wave + x * kWavesPerBlock;
+            if (pair < NT * NT) {
+                const int ta = pair / NT, tb = pair % NT;
+#pragma unroll 8
+                for (int s = 0; s < kHrGramRows / 4; ++s) {
+                    const double av = (double)rows[4 * s + kb][16 * ta + li];
+                    const double bv = (double)rows[4 * s + kb][16 * tb + li];
+                    acc[x] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[x], 0, 0, 0);
+                }
             }
         }
     }
+    const int nent = r * r;
 #pragma unroll
-    for (int x = 0; x < EPT; ++x) {
-        const int ent = tid + x * kBlock;
-        if (ent < nent) gram[d.gram_off + (int64_t)t.part * nent + ent] = g[x];
+    for (int x = 0; x < TPW; ++x) {
+        const int pair = wave + x * kWavesPerBlock;
+        if (pair < NT * NT) {
+            const int ta = pair / NT, tb = pair % NT;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int ga = 16 * ta + 4 * v + kb, gb = 16 * tb + li;   // fp64 output tile: D[4 v + kb][li]
+                if (ga < r && gb < r) gram[d.gram_off + (int64_t)t.part * nent + ga * r + gb] = acc[x][v];
+            }
+        }
     }
 }
 
@@ -391,32 +428,64 @@ __global__ __launch_bounds__(kBlock) void k_hr_chol(const MatDesc* __restrict__ 
     for (int ent = tid; ent < nent; ent += kBlock) dst[ent] = X[ent / r][ent % r];
 }
 
-// P_hat = P R^-1 (R^-1 upper triangular, fp64), row by row, in place in the P buffer.
-template <int RMAX>
+// P_hat = P R^-1 (R^-1 upper triangular, fp64), in place in the P buffer, on the fp64 matrix cores: output tile
+// (16 rows, rank tile tj) = sum over k of P[row][k] X[k][16 tj + j], four k per instruction.  A wavefront takes
+// 16 rows at a time and reads them (all rank columns) before it writes any of them.
+template <int NT>
 __global__ __launch_bounds__(kBlock) void k_hr_apply(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                      const double* __restrict__ chol, float* __restrict__ p) {
-    __shared__ double X[RMAX][RMAX + 1];
+    constexpr int RP = 16 * NT;
+    __shared__ double X[RP][RP + 1];
     const Tile t = tiles[blockIdx.x];
     const MatDesc d = mats[t.mat];
-    const int r = d.r, tid = threadIdx.x, nent = r * r;
+    const int r = d.r, tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    const int li = lane & 15, kb = lane >> 4;
     const double* src = chol + d.chol_off;
-    for (int ent = tid; ent < RMAX * RMAX; ent += kBlock) {
-        const int a = ent / RMAX, b = ent % RMAX;
-        X[a][b] = (a < r && b < r) ? src[a * r + b] : 0.0;
-    }
-    (void)nent;
-    __syncthreads();
-    for (int i = t.row0 + tid; i < t.row0 + t.nrows; i += kBlock) {
-        float* row = p + d.p_off + (int64_t)i * r;
-        float pb[RMAX];
+    {
+        constexpr int XPT = RP * RP / kBlock;   // all requested before the first is stored
+        double xv[XPT];
 #pragma unroll
-        for (int k = 0; k < RMAX; ++k) pb[k] = k < r ? row[k] : 0.f;
-        for (int j = 0; j < r; ++j) {
-            double acc = 0.0;
-#pragma unroll
-            for (int k = 0; k < RMAX; ++k) acc += (double)pb[k] * X[k][j];   // X[k][j] = 0 for k > j
-            row[j] = (float)acc;
+        for (int x = 0; x < XPT; ++x) {
+            const int ent = tid + x * kBlock;
+            const int a = ent / RP, b = ent % RP;
+            xv[x] = src[(a < r && b < r) ? a * r + b : 0];
         }
+#pragma unroll
+        for (int x = 0; x < XPT; ++x) {
+            const int ent = tid + x * kBlock;
+            const int a = ent / RP, b = ent % RP;
+            X[a][b] = (a < r && b < r) ? xv[x] : 0.0;
+        }
+    }
+    __syncthreads();
+    const int row_end = t.row0 + t.nrows;
+    const buf_rsrc pres = make_rsrc(p + d.p_off, (int64_t)d.n * r * 4);
+    for (int r0 = t.row0 + 16 * wave; r0 < row_end; r0 += 16 * kWavesPerBlock) {
+        // A operands: P[r0 + li][4 s + kb] for s = 0 .. RP / 4 - 1
+        double av[RP / 4];
+#pragma unroll
+        for (int s = 0; s < RP / 4; ++s) {
+            const int k = 4 * s + kb;
+            const unsigned off = (r0 + li < row_end && k < r) ? (unsigned)(((int64_t)(r0 + li) * r + k) * 4) : kOutOfRange;
+            av[s] = (double)buf_load_f32(pres, off);
+        }
+        v4d acc[NT];
+#pragma unroll
+        for (int tj = 0; tj < NT; ++tj) {
+            acc[tj] = v4d{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int s = 0; s < RP / 4; ++s)
+                acc[tj] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[s], X[4 * s + kb][16 * tj + li], acc[tj], 0, 0, 0);
+        }
+        // every lane's loads of these 16 rows are complete (their values were consumed) before the stores
+#pragma unroll
+        for (int tj = 0; tj < NT; ++tj)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = r0 + 4 * v + kb, j = 16 * tj + li;   // D[4 v + kb][li]
+                if (row < row_end && j < r) p[d.p_off + (int64_t)row * r + j] = (float)acc[tj][v];
+            }
     }
 }
 
@@ -424,7 +493,8 @@ __global__ __launch_bounds__(kBlock) void k_hr_apply(const MatDesc* __restrict__
 // Lane (kb, li) loads 16 bytes at row 4 t + kb, columns c0 + 64 g + 4 li .. + 3; component c of that load
 // is the A operand of the instruction that accumulates the columns c0 + 64 g + 4 i + c (i = 0..15).
 // B operand: P_hat[row 4 t + kb][16 nt + li].  A wavefront walks its strip of rows 16 at a time (four
-// such loads per column group in flight) and writes one partial Q per strip.
+// such loads per column group in flight); the workgroup's four strips are added in LDS and one partial Q per
+// row block is written.
 constexpr int kHrLeftGroups = 2;   // 64-column groups per wavefront (128 columns)
 
 template <int NT>
@@ -484,8 +554,35 @@ __global__ __launch_bounds__(kBlock) void k_hr_left(const MatDesc* __restrict__ 
                     for (int nt = 0; nt < NT; ++nt)
                         acc[g][c][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s][g][c], b[s][nt], acc[g][c][nt], 0, 0, 0);
     }
-    // acc[g][c][nt][v] = Q[c0 + 64 g + 4 (4 kb + v) + c][16 nt + li] for this strip
-    const int part = (w * d.n_rblock) + t.part * kWavesPerBlock + wave;
+    // acc[g][c][nt][v] = Q[c0 + 64 g + 4 (4 kb + v) + c][16 nt + li] for this strip.  The four strips of the
+    // workgroup are added through LDS as (s0 + s1) + (s2 + s3), so that one partial per row block is written.
+    constexpr int ACC = NG * 4 * NT;   // accumulator vectors per lane
+    __shared__ v4f stage[2][ACC][kWave];
+    auto put = [&](int slot) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) stage[slot][(g * 4 + c) * NT + nt][lane] = acc[g][c][nt];
+    };
+    auto take = [&](int slot) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[g][c][nt] += stage[slot][(g * 4 + c) * NT + nt][lane];
+    };
+    if (wave & 1) put(wave >> 1);
+    __syncthreads();
+    if (!(wave & 1)) take(wave >> 1);
+    __syncthreads();
+    if (wave == 2) put(0);
+    __syncthreads();
+    if (wave != 0) return;
+    take(0);
+    const int part = w * d.n_rblock + t.part;
     float* dst = ws + d.qpart_off + (int64_t)part * m * ri;
 #pragma unroll
     for (int g = 0; g < NG; ++g)
@@ -742,20 +839,25 @@ psgd_status hr_compress(psgd_plan* plan, const void* grad, float* err, float* q,
     HR_MARK(1);
     double* gram = hr_doubles(plan, workspace);
     double* chol = gram + plan->ws_gram_doubles;
-    hipLaunchKernelGGL(k_hr_gram, dim3((unsigned)plan->tiles_gram.size()), dim3(kBlock), 0, s, plan->dev.mats,
-                       plan->dev.tiles_gram, ws, p, gram, plan->workers);
+    const dim3 ggrid((unsigned)plan->tiles_gram.size());
+    if (nt == 1)
+        hipLaunchKernelGGL((k_hr_gram<1>), ggrid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles_gram, ws, p, gram,
+                           plan->workers);
+    else if (nt == 2)
+        hipLaunchKernelGGL((k_hr_gram<2>), ggrid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles_gram, ws, p, gram,
+                           plan->workers);
+    else
+        hipLaunchKernelGGL((k_hr_gram<4>), ggrid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles_gram, ws, p, gram,
+                           plan->workers);
     HR_CHECK("launch k_hr_gram");
     hipLaunchKernelGGL(k_hr_chol, dim3((unsigned)plan->mats.size()), dim3(kBlock), 0, s, plan->dev.mats, gram, chol);
     HR_CHECK("launch k_hr_chol");
-    if (plan->rank <= 16)
-        hipLaunchKernelGGL((k_hr_apply<16>), dim3((unsigned)plan->tiles_gram.size()), dim3(kBlock), 0, s, plan->dev.mats,
-                           plan->dev.tiles_gram, chol, p);
-    else if (plan->rank <= 32)
-        hipLaunchKernelGGL((k_hr_apply<32>), dim3((unsigned)plan->tiles_gram.size()), dim3(kBlock), 0, s, plan->dev.mats,
-                           plan->dev.tiles_gram, chol, p);
+    if (nt == 1)
+        hipLaunchKernelGGL((k_hr_apply<1>), ggrid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles_gram, chol, p);
+    else if (nt == 2)
+        hipLaunchKernelGGL((k_hr_apply<2>), ggrid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles_gram, chol, p);
     else
-        hipLaunchKernelGGL((k_hr_apply<64>), dim3((unsigned)plan->tiles_gram.size()), dim3(kBlock), 0, s, plan->dev.mats,
-                           plan->dev.tiles_gram, chol, p);
+        hipLaunchKernelGGL((k_hr_apply<4>), ggrid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles_gram, chol, p);
     HR_CHECK("launch k_hr_apply");
     HR_MARK(2);
     {

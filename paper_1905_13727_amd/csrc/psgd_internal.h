@@ -25,6 +25,7 @@ constexpr int kPreReduceParts = 16; // more partial-P slices than this: a reduct
 constexpr int kOrthoMaxRows = 1024; // panels with more rows take the multi-workgroup route
 constexpr int kFactorAlignElems = 4;        // P and Q of a matrix start at multiples of 4 floats (vector loads of factor rows)
 constexpr int kHrGramTileRows = 128;       // matrix-core path: rows per workgroup of the mean-P / Gram / apply kernels
+constexpr int64_t kHrMaxRows = 1 << 22;   // matrix-core path: tallest matrix (an n x 64 factor is addressed with 31-bit byte offsets)
 constexpr int64_t kHrMaxCols = 1 << 20;   // matrix-core path: longest row (tiles of <= 256 rows are addressed with 31-bit byte offsets)
 constexpr int kMfmaCols = 128;     // super-row columns a wavefront covers per 16-row step in the matrix-core P = M Q kernel
 
@@ -93,12 +94,13 @@ struct Tuning {
     int64_t k1_nv = 2;      // column vectors per lane (<= kMaxVecPerLaneK1)
     int64_t k3_rows = 128;  // rows per workgroup tile, Q = M^T P
     int64_t k3_nv = 1;      // column vectors per lane (<= kMaxVecPerLaneK3)
-    int64_t k4_rows = 64;   // rows per workgroup tile, decompress + residual
+    int64_t k4_rows = 32;   // rows per workgroup tile, decompress + residual
     int64_t k4_nv = 1;
     int64_t q_reduce_elems = 1024;  // elements per workgroup in the Q reduction
-    int64_t hr_k3_rows = 1024;  // matrix-core Q = M^T P: rows per workgroup (four strips)
+    int64_t hr_k3_rows = 2048;  // matrix-core Q = M^T P: rows per workgroup (four strips)
+    int64_t hr_k4_rows = 128;   // matrix-core decompression: rows per workgroup (four strips of 16-row steps)
     int64_t hr_k1_rows = 128;   // matrix-core P = M Q: rows per workgroup (multiple of 64, at most 256)
-    int64_t hr_k1_cols = 1024;  // matrix-core P = M Q: columns per workgroup (multiple of 64); longer rows are split and their partial P summed
+    int64_t hr_k1_cols = 2048;  // matrix-core P = M Q: columns per workgroup (multiple of 64); longer rows are split and their partial P summed
     int64_t k1_mfma = 0;    // 1: P = M Q on the matrix cores when pack * rank <= 16 for every matrix (slower for now)
     int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream
     int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height

@@ -84,7 +84,7 @@ void build_resident(psgd_plan* plan);
 static psgd_status build_hr_tables(psgd_plan* plan) {
     const Tuning& tu = plan->tuning;
     if (tu.hr_k3_rows < 64 || tu.hr_k1_rows < 64 || tu.hr_k1_rows > 256 || tu.hr_k1_rows % 64 != 0 ||
-        tu.hr_k1_cols < 64 || tu.hr_k1_cols % 64 != 0)
+        tu.hr_k1_cols < 64 || tu.hr_k1_cols % 64 != 0 || tu.hr_k4_rows < 16 || tu.hr_k4_rows > 1024)
         return PSGD_EINVAL;
     const int64_t W = plan->workers;
     const size_t nm = plan->mats.size();
@@ -94,14 +94,17 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
     plan->k1_on_mfma = false;
     plan->p_pre_reduce = false;
     const int64_t right_rows = tu.hr_k1_rows;
-    const int64_t decomp_rows = 256;
+    const int64_t decomp_rows = tu.hr_k4_rows;
     int64_t pp = 0, qp = 0, gp = 0, cp = 0;
     for (size_t i = 0; i < nm; ++i) {
         MatDesc& d = plan->mats[i];
         d.n_cchunk = (int32_t)ceil_div(d.m, tu.hr_k1_cols);
         const int64_t nrb = ceil_div(d.n, tu.hr_k3_rows);
-        d.n_rblock = (int32_t)(nrb * kWavesPerBlock);
-        d.n_gblock = (int32_t)ceil_div(d.n, kHrGramTileRows);
+        d.n_rblock = (int32_t)nrb;   // one partial Q per row block (the workgroup adds its four strips itself)
+        // Gram blocks: 128 rows each, more for very tall panels so that the one workgroup that adds up a matrix's
+        // blocks has at most 64 of them
+        const int64_t gram_rows = kHrGramTileRows * ceil_div(d.n, (int64_t)kHrGramTileRows * 64);
+        d.n_gblock = (int32_t)ceil_div(d.n, gram_rows);
         d.ppart_off = pp;
         pp += round_up(W * d.n_cchunk * d.n * d.r, kAlignElems);
         d.gram_off = gp;
@@ -135,7 +138,7 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
             }
         for (int32_t b = 0; b < d.n_gblock; ++b) {
             Tile t{};
-            t.mat = (int32_t)i; t.row0 = b * kHrGramTileRows; t.nrows = std::min<int32_t>(kHrGramTileRows, d.n - t.row0);
+            t.mat = (int32_t)i; t.row0 = (int32_t)(b * gram_rows); t.nrows = (int32_t)std::min<int64_t>(gram_rows, d.n - t.row0);
             t.part = b;
             plan->tiles_gram.push_back(t);
         }
@@ -469,7 +472,9 @@ psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_
     const bool needs_hr = rank > kValuMaxRank || grad_dtype != PSGD_F32 || out_dtype != PSGD_F32;
     if (needs_hr)
         for (int32_t t = 0; t < n_tensors; ++t)
-            if (shapes[t].cols != 1 && (shapes[t].cols % 4 != 0 || shapes[t].cols > kHrMaxCols)) return PSGD_EUNSUPPORTED;
+            if (shapes[t].cols != 1 && (shapes[t].cols % 4 != 0 || shapes[t].cols > kHrMaxCols ||
+                                        shapes[t].rows > kHrMaxRows))
+                return PSGD_EUNSUPPORTED;
 
     psgd_plan* plan = new (std::nothrow) psgd_plan();
     if (!plan) return PSGD_ENOMEM;
@@ -591,6 +596,7 @@ psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value
     else if (!strcmp(key, "k1_mfma")) tu.k1_mfma = value;
     else if (!strcmp(key, "hr_k3_rows")) tu.hr_k3_rows = value;
     else if (!strcmp(key, "xcd_order")) tu.xcd_order = value;
+    else if (!strcmp(key, "hr_k4_rows")) tu.hr_k4_rows = value;
     else if (!strcmp(key, "hr_k1_rows")) tu.hr_k1_rows = value;
     else if (!strcmp(key, "hr_k1_cols")) tu.hr_k1_cols = value;
     else if (!strcmp(key, "resident")) tu.resident = value;

@@ -327,12 +327,12 @@ static void check_hr_plan(const std::vector<psgd_shape>& shapes, int rank, int w
     cover(plan->hr_tiles4, false);
     for (const Tile& t : plan->hr_tiles3) {
         const MatDesc& d = plan->mats[t.mat];
-        CHECK(t.part >= 0 && (t.part + 1) * kWavesPerBlock <= d.n_rblock);
+        CHECK(t.part >= 0 && t.part < d.n_rblock);
     }
     std::vector<int64_t> rows(plan->mats.size(), 0);
     for (const Tile& t : plan->tiles_gram) {
         const MatDesc& d = plan->mats[t.mat];
-        CHECK(t.part >= 0 && t.part < d.n_gblock && t.row0 == rows[t.mat] && t.nrows > 0 && t.nrows <= kHrGramTileRows);
+        CHECK(t.part >= 0 && t.part < d.n_gblock && t.row0 == rows[t.mat] && t.nrows > 0 && t.nrows <= 1024 * 1024 && d.n_gblock <= 64);
         rows[t.mat] += t.nrows;
     }
     for (size_t i = 0; i < plan->mats.size(); ++i) {
