@@ -500,7 +500,8 @@ constexpr int kHrLeftGroups = 2;   // 64-column groups per wavefront (128 column
 template <int NT>
 __global__ __launch_bounds__(kBlock) void k_hr_left(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                     const float* __restrict__ err, const float* __restrict__ p,
-                                                    float* __restrict__ ws, int64_t estride) {
+                                                    float* __restrict__ ws, float* __restrict__ q, int workers,
+                                                    int64_t estride) {
     constexpr int NG = kHrLeftGroups;
     const Tile t = tiles[blockIdx.x];
     const MatDesc d = mats[t.mat];
@@ -582,8 +583,9 @@ __global__ __launch_bounds__(kBlock) void k_hr_left(const MatDesc* __restrict__ 
     __syncthreads();
     if (wave != 0) return;
     take(0);
+    // the only partial of its matrix is the result itself (mean over one worker): it goes straight into Q
     const int part = w * d.n_rblock + t.part;
-    float* dst = ws + d.qpart_off + (int64_t)part * m * ri;
+    float* dst = workers * d.n_rblock == 1 ? q + d.q_off : ws + d.qpart_off + (int64_t)part * m * ri;
 #pragma unroll
     for (int g = 0; g < NG; ++g)
 #pragma unroll
@@ -864,13 +866,13 @@ psgd_status hr_compress(psgd_plan* plan, const void* grad, float* err, float* q,
         dim3 grid((unsigned)plan->hr_tiles3.size(), (unsigned)plan->workers);
         if (nt == 1)
             hipLaunchKernelGGL((k_hr_left<1>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles3, err, p, ws,
-                               plan->sizes.err_stride);
+                               q, plan->workers, plan->sizes.err_stride);
         else if (nt == 2)
             hipLaunchKernelGGL((k_hr_left<2>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles3, err, p, ws,
-                               plan->sizes.err_stride);
+                               q, plan->workers, plan->sizes.err_stride);
         else
             hipLaunchKernelGGL((k_hr_left<4>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles3, err, p, ws,
-                               plan->sizes.err_stride);
+                               q, plan->workers, plan->sizes.err_stride);
     }
     HR_CHECK("launch k_hr_left");
     HR_MARK(3);

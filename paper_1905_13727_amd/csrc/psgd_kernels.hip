@@ -1021,6 +1021,7 @@ psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float
 
 psgd_status launch_q_reduce(psgd_plan* plan, float* ws, float* q, void* stream) {
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (plan->tilesq.empty()) return PSGD_OK;   // every Q was written directly
     hipLaunchKernelGGL(k_q_reduce, dim3((unsigned)plan->tilesq.size()), dim3(kBlock), 0, s, plan->dev.mats,
                        plan->dev.tilesq, ws, q, plan->workers, 0);
     PSGD_HIP(hipGetLastError(), "launch k_q_reduce");

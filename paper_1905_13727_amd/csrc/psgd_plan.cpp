@@ -147,7 +147,8 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
         MatDesc& d = plan->mats[i];
         d.qpart_off = pp + qp;
         qp += round_up(W * d.n_rblock * d.m * d.r, kAlignElems);
-        const int64_t total = (int64_t)d.m * d.r;
+        // a matrix with a single partial Q (one worker, one row block) has it written straight into Q
+        const int64_t total = W * d.n_rblock > 1 ? (int64_t)d.m * d.r : 0;
         for (int64_t e = 0; e < total; e += kWave) {
             Tile t{};
             t.mat = (int32_t)i; t.elem0 = e; t.nelem = std::min<int64_t>(kWave, total - e);
