@@ -37,6 +37,10 @@ def test_status_strings():
     (dict(shapes=[], rank=2), B.PSGD_EINVAL),
     (dict(shapes=[(4, 4)], rank=B.PSGD_MAX_RANK + 1), B.PSGD_EUNSUPPORTED),
     (dict(shapes=[(4, 4)], rank=2, grad_dtype=7), B.PSGD_EINVAL),
+    # the matrix-core kernels (rank > 8 or bf16) need row lengths that are multiples of 4, at most 2^20
+    (dict(shapes=[(64, 650)], rank=16), B.PSGD_EUNSUPPORTED),
+    (dict(shapes=[(64, 650)], rank=2, grad_dtype=B.PSGD_BF16), B.PSGD_EUNSUPPORTED),
+    (dict(shapes=[(8, (1 << 20) + 4)], rank=16), B.PSGD_EUNSUPPORTED),
 ])
 def test_invalid_plans(kwargs, status):
     with pytest.raises(B.PsgdError) as ei:
@@ -53,6 +57,11 @@ def test_null_pointers_are_rejected_without_a_gpu():
     assert lib.psgd_step(plan._h, None, None, None, None, None, None, None) == B.PSGD_EINVAL
     assert lib.psgd_compress(None, 1, 1, 1, 1, 1, None) == B.PSGD_EINVAL
     assert lib.psgd_decompress(plan._h, 1, 1, None, 1, 1, 1, None) == B.PSGD_EINVAL
+    assert lib.psgd_iterate(plan._h, None, 1, 1, 1, None) == B.PSGD_EINVAL
+    assert lib.psgd_iterate(None, 1, 1, 1, 1, None) == B.PSGD_EINVAL
+    assert lib.psgd_step_update(plan._h, 1, 1, 1, 1, None, 1, 0.1, 0.9, 1, None) == B.PSGD_EINVAL     # no momentum buffer
+    assert lib.psgd_step_update(plan._h, 1, 1, 1, 1, 1, 1, float("nan"), 0.9, 1, None) == B.PSGD_EINVAL  # NaN step size
+    assert lib.psgd_decompress_update(plan._h, 1, 1, 1, 1, 1, None, 0.1, 0.9, 1, None) == B.PSGD_EINVAL
     assert lib.psgd_plan_sizes(plan._h, None) == B.PSGD_EINVAL
     assert lib.psgd_plan_offsets(plan._h, 5, None, None, None, None) == B.PSGD_EINVAL
     lib.psgd_plan_destroy(None)
