@@ -59,6 +59,70 @@ __device__ __forceinline__ void stv<4>(float* p, const float (&x)[4]) {
     *reinterpret_cast<f4*>(p) = t;
 }
 
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// ---- buffer addressing ----------------------------------------------------------------------------------
+// Raw buffer descriptors (base, byte range) let a wavefront address a tile with one 32-bit lane offset per
+// access: a lane whose offset lies at or beyond the range reads zeros and its stores are dropped, so ragged
+// tiles need no branches.  The whole address goes into the lane offset (the scalar offset operand is not
+// part of the range check).  Ranges and offsets stay below 2^31 bytes (row lengths are limited when the
+// plan is made), which makes kOutOfRange, and kOutOfRange plus any valid offset, out of range for every
+// descriptor.
+typedef __amdgpu_buffer_rsrc_t buf_rsrc;
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+constexpr unsigned kOutOfRange = 0x80000000u;
+constexpr int kRsrcFlags = 0x00020000;   // raw 32-bit data format word of gfx9-family descriptors
+
+// base and bytes must be the same in every lane of the wavefront; they are moved to scalar registers here so
+// that the descriptor is one (a descriptor held in vector registers makes every access a loop over its values)
+__device__ __forceinline__ buf_rsrc make_rsrc(const void* base, int64_t bytes) {
+    const unsigned long long b = reinterpret_cast<unsigned long long>(base);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)b);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32));
+    const int nb = __builtin_amdgcn_readfirstlane((int)bytes);
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(((unsigned long long)hi << 32) | lo), 0, nb, kRsrcFlags);
+}
+__device__ __forceinline__ float buf_load_f32(buf_rsrc r, unsigned off) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
+}
+__device__ __forceinline__ v4f buf_load_v4f(buf_rsrc r, unsigned off) {
+    const v4u x = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+    return v4f{__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w)};
+}
+__device__ __forceinline__ void buf_store_v4f(buf_rsrc r, unsigned off, v4f v) {
+    const v4u x{__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
+    __builtin_amdgcn_raw_buffer_store_b128(x, r, (int)off, 0, 0);
+}
+// V consecutive floats through a descriptor (V = 1, 2, 4); `stream`: read once (non-temporal)
+template <int V>
+__device__ __forceinline__ void buf_ldv(buf_rsrc r, unsigned off, float (&x)[V], bool stream = false) {
+    if constexpr (V == 4) {
+        const v4u t = stream ? __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 2)
+                             : __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+        x[0] = __uint_as_float(t.x); x[1] = __uint_as_float(t.y); x[2] = __uint_as_float(t.z); x[3] = __uint_as_float(t.w);
+    } else if constexpr (V == 2) {
+        const v2u t = stream ? __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 2)
+                             : __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 0);
+        x[0] = __uint_as_float(t.x); x[1] = __uint_as_float(t.y);
+    } else {
+        x[0] = __uint_as_float(stream ? __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 2)
+                                      : __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
+    }
+}
+template <int V>
+__device__ __forceinline__ void buf_stv(buf_rsrc r, unsigned off, const float (&x)[V]) {
+    if constexpr (V == 4) {
+        const v4u t{__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3])};
+        __builtin_amdgcn_raw_buffer_store_b128(t, r, (int)off, 0, 0);
+    } else if constexpr (V == 2) {
+        const v2u t{__float_as_uint(x[0]), __float_as_uint(x[1])};
+        __builtin_amdgcn_raw_buffer_store_b64(t, r, (int)off, 0, 0);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(x[0]), r, (int)off, 0, 0);
+    }
+}
+
 // Rows of a factor that belong to V consecutive matrix columns (or rows): the V * ri consecutive floats at
 // `rows` -> f[V][R], zero beyond ri and everything zero when !valid.  With ri == R (the usual case; ri < R
 // only for matrices smaller than the rank) they are fetched with the widest aligned vector loads instead of

@@ -59,32 +59,54 @@ __device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, c
     int rb, rn;
     wave_rows(t.nrows, wave, &rb, &rn);
     const int i_begin = t.row0 + rb, i_end = i_begin + rn;
+    // Descriptors over the rows of this wavefront's strip: a lane whose columns do not exist carries an
+    // out-of-range offset, a row past the strip lies beyond the range by itself; such loads return zero and
+    // such stores are dropped, so no access sits behind a branch and the waits count exactly what is outstanding.
+    const int64_t strip = d.off + (int64_t)i_begin * d.m;
+    const buf_rsrc gres = make_rsrc(g + strip, ADD ? (int64_t)rn * d.m * 4 : 0);
+    const buf_rsrc eres = make_rsrc(e + strip, (int64_t)rn * d.m * 4);
+    unsigned coff[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) coff[v] = valid[v] ? (unsigned)col[v] * 4u : kOutOfRange;
     for (int i0 = i_begin; i0 < i_end; i0 += RS) {
         const int rows = min(RS, i_end - i0);
+        const unsigned row_off = (unsigned)(i0 - i_begin) * (unsigned)d.m * 4u;
         float mv[RS][NV][V];
         // every load of the step is issued before anything is used
+        if constexpr (ADD) {
 #pragma unroll
-        for (int i = 0; i < RS; ++i)
+            for (int i = 0; i < RS; ++i)
 #pragma unroll
-            for (int v = 0; v < NV; ++v) {
-                if (ADD && i < rows && valid[v]) {
-                    ldv_stream<V>(g + d.off + (int64_t)(i0 + i) * d.m + col[v], mv[i][v]);
-                } else {
+                for (int v = 0; v < NV; ++v)
+                    buf_ldv<V>(gres, coff[v] + row_off + (unsigned)i * (unsigned)d.m * 4u, mv[i][v], true);
+        } else {
+#pragma unroll
+            for (int i = 0; i < RS; ++i)
+#pragma unroll
+                for (int v = 0; v < NV; ++v)
 #pragma unroll
                     for (int x = 0; x < V; ++x) mv[i][v][x] = 0.f;
+        }
+        // e in two halves of the step's rows (registers): all loads of a half in flight, then add and store
+        constexpr int RH = RS / 2;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            float ev[RH][NV][V];
+#pragma unroll
+            for (int i = 0; i < RH; ++i)
+#pragma unroll
+                for (int v = 0; v < NV; ++v)
+                    buf_ldv<V>(eres, coff[v] + row_off + (unsigned)(h * RH + i) * (unsigned)d.m * 4u, ev[i][v]);
+#pragma unroll
+            for (int i = 0; i < RH; ++i)
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+#pragma unroll
+                    for (int x = 0; x < V; ++x) mv[h * RH + i][v][x] += ev[i][v][x];
+                    if constexpr (ADD)
+                        buf_stv<V>(eres, coff[v] + row_off + (unsigned)(h * RH + i) * (unsigned)d.m * 4u, mv[h * RH + i][v]);
                 }
-            }
-#pragma unroll
-        for (int i = 0; i < RS; ++i)
-#pragma unroll
-            for (int v = 0; v < NV; ++v)
-                if (i < rows && valid[v]) {
-                    float ev[V];
-                    ldv<V>(e + d.off + (int64_t)(i0 + i) * d.m + col[v], ev);
-#pragma unroll
-                    for (int x = 0; x < V; ++x) mv[i][v][x] += ev[x];
-                    if constexpr (ADD) stv<V>(e + d.off + (int64_t)(i0 + i) * d.m + col[v], mv[i][v]);
-                }
+        }
         // RS * R dot products, reduced over the wavefront; lane i * R + k keeps the result of (row i, rank k)
         float mine = 0.f;
 #pragma unroll
