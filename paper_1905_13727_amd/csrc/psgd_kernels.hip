@@ -539,6 +539,12 @@ __device__ __forceinline__ void left_tile(const Tile& t, const MatDesc& d, const
     }
     int rb, rn;
     wave_rows(t.nrows, wave, &rb, &rn);
+    // descriptor over the rows of this wavefront's strip: missing columns carry an out-of-range offset, rows past
+    // the strip lie beyond the range; both read zeros (and zero rows of P_hat), so nothing sits behind a branch
+    const buf_rsrc eres = make_rsrc(e + d.off + (int64_t)(t.row0 + rb) * d.m, (int64_t)rn * d.m * 4);
+    unsigned coff[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) coff[v] = valid[v] ? (unsigned)col[v] * 4u : kOutOfRange;
     for (int g0 = 0; g0 < rn; g0 += kWave) {
         const int gr = min(kWave, rn - g0);
         const int i0 = t.row0 + rb + g0;
@@ -547,31 +553,22 @@ __device__ __forceinline__ void left_tile(const Tile& t, const MatDesc& d, const
         float (&pr)[R] = pr1[0];
         for (int ii = 0; ii < gr; ii += RU) {
             float x[RU][NV][V];
+            const unsigned row_off = (unsigned)(g0 + ii) * (unsigned)d.m * 4u;
+#pragma unroll
+            for (int u = 0; u < RU; ++u)
+#pragma unroll
+                for (int v = 0; v < NV; ++v) buf_ldv<V>(eres, coff[v] + row_off + (unsigned)u * (unsigned)d.m * 4u, x[u][v]);
 #pragma unroll
             for (int u = 0; u < RU; ++u) {
-                if (ii + u < gr) {
-                    const int64_t row = d.off + (int64_t)(i0 + ii + u) * d.m;
+                float pk[R];   // lanes at or past gr hold zeros: rows past the group contribute nothing
 #pragma unroll
-                    for (int v = 0; v < NV; ++v)
-                        if (valid[v]) ldv<V>(e + row + col[v], x[u][v]);
-                }
-            }
+                for (int k = 0; k < R; ++k) pk[k] = lane_bcast(pr[k], min(ii + u, kWave - 1));
 #pragma unroll
-            for (int u = 0; u < RU; ++u) {
-                if (ii + u < gr) {
-                    float pk[R];
+                for (int v = 0; v < NV; ++v)
 #pragma unroll
-                    for (int k = 0; k < R; ++k) pk[k] = lane_bcast(pr[k], ii + u);
+                    for (int xx = 0; xx < V; ++xx)
 #pragma unroll
-                    for (int v = 0; v < NV; ++v)
-                        if (valid[v]) {
-#pragma unroll
-                            for (int xx = 0; xx < V; ++xx)
-#pragma unroll
-                                for (int k = 0; k < R; ++k)
-                                    acc[v][xx][k] = fmaf(x[u][v][xx], pk[k], acc[v][xx][k]);
-                        }
-                }
+                        for (int k = 0; k < R; ++k) acc[v][xx][k] = fmaf(x[u][v][xx], pk[k], acc[v][xx][k]);
             }
         }
     }
