@@ -99,7 +99,8 @@ typedef struct {
  * a non-positive dimension; PSGD_EUNSUPPORTED for rank > PSGD_MAX_RANK, or,
  * when rank > 8 or a dtype is PSGD_BF16 (the matrix-core kernels), a matrix whose
  * column count is not a multiple of 4 or exceeds 2^20, or with more than 2^22 rows;
- * PSGD_ENOMEM. */
+ * on the other kernels for a matrix with more than about 64 M columns (a strip of 8
+ * rows is addressed with 31-bit byte offsets); PSGD_ENOMEM. */
 #define PSGD_MAX_RANK 64
 PSGD_API psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_t rank,
                              int32_t workers, psgd_dtype grad_dtype, psgd_dtype out_dtype,

@@ -181,6 +181,11 @@ psgd_status build_tables(psgd_plan* plan) {
         tu.k4_nv > kMaxVecPerLaneK3 || tu.q_reduce_elems < 1 || tu.res_rows < 0 || tu.res_rows > kResRows)
         return PSGD_EINVAL;
     const size_t nm = plan->mats.size();
+    // k_ef_right and k_left address the rows of a wavefront's strip (a quarter of the tile's rows) with 31-bit
+    // byte offsets
+    for (const MatDesc& d : plan->mats)
+        if (ceil_div(std::max(tu.k1_rows, tu.k3_rows), kWavesPerBlock) * d.m * 4 >= (int64_t(1) << 31))
+            return PSGD_EUNSUPPORTED;
     std::vector<int32_t> nrb(nm, 0), ncc(nm, 0);
     // P = M Q: matrix-core tiling (16-row steps of super-rows x kMfmaCols columns per wavefront) when every
     // matrix fits pack * rank <= 16, else the vector-ALU tiling

@@ -41,6 +41,8 @@ def test_status_strings():
     (dict(shapes=[(64, 650)], rank=16), B.PSGD_EUNSUPPORTED),
     (dict(shapes=[(64, 650)], rank=2, grad_dtype=B.PSGD_BF16), B.PSGD_EUNSUPPORTED),
     (dict(shapes=[(8, (1 << 20) + 4)], rank=16), B.PSGD_EUNSUPPORTED),
+    # vector-ALU kernels: a strip of 8 rows must stay below 2^31 bytes
+    (dict(shapes=[(4, 68_000_000)], rank=2), B.PSGD_EUNSUPPORTED),
 ])
 def test_invalid_plans(kwargs, status):
     with pytest.raises(B.PsgdError) as ei:
