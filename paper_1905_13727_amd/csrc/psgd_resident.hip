@@ -193,22 +193,33 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
     float M[RT][V];
     float qr[V][R];
     load_factor_rows<R, V>(a.q + d.q_off + (int64_t)col * ri, ri, valid, qr);
+    {
+        // strip descriptor: rows past the strip are beyond the range, a lane without columns is out of range
+        const int64_t strip = d.off + (int64_t)t.row0 * d.m;
+        const buf_rsrc gres = make_rsrc(a.grad + strip, (int64_t)nrows * d.m * 4);
+        const buf_rsrc eres = make_rsrc(a.err + strip, (int64_t)nrows * d.m * 4);
+        const unsigned coff = valid ? (unsigned)col * 4u : kOutOfRange;
 #pragma unroll
-    for (int i = 0; i < RT; ++i) {
-        if (i < nrows && valid) {
-            ldv_stream<V>(a.grad + tile_off + (int64_t)i * d.m, M[i]);
+        for (int i = 0; i < RT; ++i) buf_ldv<V>(gres, coff + (unsigned)i * (unsigned)d.m * 4u, M[i], true);
+        if constexpr (RT > 24) {
+            // the tallest strips: e row by row behind the arrival of g (no room for a second tile of registers)
+#pragma unroll
+            for (int i = 0; i < RT; ++i) {
+                if (i < nrows && valid) {
+                    float e[V];
+                    ldv<V>(a.err + tile_off + (int64_t)i * d.m, e);
+#pragma unroll
+                    for (int x = 0; x < V; ++x) M[i][x] += e[x];
+                }
+            }
         } else {
+            float e[RT][V];
 #pragma unroll
-            for (int x = 0; x < V; ++x) M[i][x] = 0.f;
-        }
-    }
+            for (int i = 0; i < RT; ++i) buf_ldv<V>(eres, coff + (unsigned)i * (unsigned)d.m * 4u, e[i]);
 #pragma unroll
-    for (int i = 0; i < RT; ++i) {
-        if (i < nrows && valid) {
-            float e[V];
-            ldv<V>(a.err + tile_off + (int64_t)i * d.m, e);
+            for (int i = 0; i < RT; ++i)
 #pragma unroll
-            for (int x = 0; x < V; ++x) M[i][x] += e[x];
+                for (int x = 0; x < V; ++x) M[i][x] += e[i][x];
         }
     }
     {
