@@ -63,6 +63,8 @@ def _run(wl, rank, workers, steps, seed=0, tuning=None, split=False, verbose=Tru
             worst_all[k] = max(worst_all[k], worst[k])
         assert worst["P_hat"] <= TOL and worst["Q"] <= TOL and worst["err"] <= TOL and worst["out"] <= TOL, \
             (wl.name, rank, workers, t, worst)
+        if verbose and steps > 10 and (t + 1) % 10 == 0:   # long runs report as they go
+            print("[parity] %s r=%d W=%d step %d of %d ok" % (wl.name, rank, workers, t + 1, steps), flush=True)
     if verbose:
         print("\n[parity] %s r=%d W=%d steps=%d resync=%s resident=%s worst %s"
               % (wl.name, rank, workers, steps, resync, gpu.resident, worst_all), flush=True)
@@ -139,20 +141,29 @@ def test_tall_panels(rank, workers):
             assert np.abs(r["err"][0][t]).max() == 0 and np.abs(r["out"][t]).max() == 0
 
 
-def test_lstm_r4_10_steps():
+def _steps(env_name, default):
+    """Step count of the long parity runs.  The defaults keep the suite to a few minutes (the fp64 oracle is the
+    slow side: 16 workers cost 2.5 s per step); PSGD_PARITY_STEPS_W16 / PSGD_PARITY_STEPS_LSTM change them."""
+    import os
+    return int(os.environ.get(env_name, default))
+
+
+def test_lstm_r4_100_steps():
     """LSTM-shaped set (tied embedding with 5 % of the rows non-zero per step), rank 4."""
     _need_gpu()
     from paper_1905_13727_amd import workloads as WL
-    _run(WL.lstm(), rank=4, workers=1, steps=10, seed=0, resync=RESYNC, expect_resident=False)
+    _run(WL.lstm(), rank=4, workers=1, steps=_steps("PSGD_PARITY_STEPS_LSTM", 100), seed=0, resync=RESYNC,
+         expect_resident=False)
 
 
 def test_resnet18_16_workers():
-    """ResNet18-shaped set with 16 simulated workers, ranks 1, 2, 4 (a few steps each: the oracle
-    needs 16 times the single-worker time)."""
+    """ResNet18-shaped set with 16 simulated workers, ranks 1, 2, 4 (a few steps each by default: the oracle
+    needs 16 times the single-worker time; 40 steps per rank were run once with PSGD_PARITY_STEPS_W16=40)."""
     _need_gpu()
     from paper_1905_13727_amd import workloads as WL
     for rank in (1, 2, 4):
-        _run(WL.resnet18(), rank=rank, workers=16, steps=2, seed=rank, expect_resident=False)
+        _run(WL.resnet18(), rank=rank, workers=16, steps=_steps("PSGD_PARITY_STEPS_W16", 5), seed=rank, resync=RESYNC,
+             expect_resident=False)
 
 
 @pytest.mark.parametrize("rank", [1, 2, 4])
