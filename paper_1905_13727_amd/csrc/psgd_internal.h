@@ -96,12 +96,13 @@ struct Tuning {
     int64_t k3_nv = 1;      // column vectors per lane (<= kMaxVecPerLaneK3)
     int64_t k4_rows = 32;   // rows per workgroup tile, decompress + residual
     int64_t k4_nv = 1;
-    int64_t q_reduce_elems = 1024;  // elements per workgroup in the Q reduction
+    int64_t q_reduce_elems = 1024;  // accepted, unused (the Q reduction works on 64 elements per workgroup)
     int64_t hr_k3_rows = 2048;  // matrix-core Q = M^T P: rows per workgroup (four strips)
     int64_t hr_k4_rows = 128;   // matrix-core decompression: rows per workgroup (four strips of 16-row steps)
     int64_t hr_k1_rows = 128;   // matrix-core P = M Q: rows per workgroup (multiple of 64, at most 256)
     int64_t hr_k1_cols = 2048;  // matrix-core P = M Q: columns per workgroup (multiple of 64); longer rows are split and their partial P summed
-    int64_t k1_mfma = 0;    // 1: P = M Q on the matrix cores when pack * rank <= 16 for every matrix (slower for now)
+    int64_t k1_mfma = 0;    // 1: P = M Q on the matrix cores when pack * rank <= 16 for every matrix (slower and less
+                            // accurate than the vector kernel at these ranks: kept for experiments)
     int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream
     int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height
     int64_t res_trace = 0;  // 1: the resident kernel records phase timestamps (diagnostic)

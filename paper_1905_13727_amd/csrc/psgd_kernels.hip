@@ -1,17 +1,22 @@
 // HIP kernels for gfx950 (MI355X) and their launchers.
 //
 // One PowerSGD step (arXiv 1905.13727, Algorithm 1 inside the error-feedback
-// loop of Algorithm 2) is five grouped launches over work-lists built by the
+// loop of Algorithm 2) is five to seven grouped launches over work-lists built by the
 // planner; every launch covers all matrices of the model and all W workers:
 //
 //   k_ef_right    M_w = g_w + e_w (stored in e_w's place) fused with the row dot
-//                 products of P_w = M_w Q               (Alg. 2 "Delta_w", Alg. 1 "P <- M Q")
-//   k_ortho       mean over workers / column chunks, then Gram-Schmidt
-//                                                       (Alg. 1 "all reduce mean", "orthogonalize")
+//                 products of P_w = M_w Q               (Alg. 2 "Delta_w", Alg. 1 "P <- M Q");
+//                 without the add, one more subspace iteration on a stored M (Appendix G.7)
+//   k_ortho       mean over workers / column chunks, then Gram-Schmidt in LDS, for panels of
+//                 up to 1024 rows                       (Alg. 1 "all reduce mean", "orthogonalize")
+//   k_gram, k_chol_apply   the same orthonormal factor by Cholesky-QR over many workgroups,
+//                 for taller panels                     (Remark "Orthogonalization is a linear operation")
 //   k_left        column sums of Q_w = M_w^T P_hat      (Alg. 1 "Q <- M^T P_hat")
-//   k_q_reduce    mean over workers / row blocks        (Alg. 1 second "all reduce mean")
+//   k_q_reduce    mean over workers / row blocks        (Alg. 1 second "all reduce mean"); also
+//                 pre-reduces the partial P when there are many
 //   k_decomp      Delta' = P_hat Q^T fused with e_w = M_w - Delta' and with the
-//                 mean of the vector-shaped tensors     (Alg. 1 "decompress", Alg. 2 error memory)
+//                 mean of the vector-shaped tensors     (Alg. 1 "decompress", Alg. 2 error memory);
+//                 optionally with Alg. 2's momentum and parameter update instead of storing Delta'
 //
 // All reductions run in a fixed order (no float atomics): results are
 // bit-reproducible from run to run.
