@@ -260,7 +260,7 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
             const int idx_c = mine ? idx : nval - 1;
             const int64_t at = (int64_t)(idx_c / nrows) * d.n + t.row0 + idx_c % nrows;   // [k][row]
             float s = 0.f;
-            constexpr int CG = 16;   // chunk partials polled together
+            constexpr int CG = 20;   // chunk partials polled together
             for (int c0 = 0; c0 < d.n_cchunk; c0 += CG) {
                 slot_t w[CG];
                 await([&]() {
