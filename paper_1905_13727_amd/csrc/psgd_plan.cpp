@@ -78,6 +78,27 @@ static void order_for_xcds(std::vector<Tile>& tiles) {
     tiles.swap(out);
 }
 
+// The same within groups of consecutive matrices: a group is closed once it holds `min_tiles` tiles, so that a large
+// matrix is spread over all dies by itself (the dies then work on the same matrix at the same time) while small
+// ones are ordered together.  Slices of the vector region (mat < 0) are left where they are.
+static void order_for_xcds_grouped(std::vector<Tile>& tiles, size_t min_tiles) {
+    size_t b = 0;
+    while (b < tiles.size()) {
+        if (tiles[b].mat < 0) { ++b; continue; }
+        size_t e = b;
+        while (e < tiles.size() && tiles[e].mat >= 0) {
+            // extend by one whole matrix
+            const int32_t m = tiles[e].mat;
+            while (e < tiles.size() && tiles[e].mat == m) ++e;
+            if (e - b >= min_tiles) break;
+        }
+        std::vector<Tile> run(tiles.begin() + b, tiles.begin() + e);
+        order_for_xcds(run);
+        std::copy(run.begin(), run.end(), tiles.begin() + b);
+        b = e;
+    }
+}
+
 void build_resident(psgd_plan* plan);
 
 // Matrix-core path: its own tilings and workspace layout.
@@ -164,7 +185,11 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
     plan->resident_ok = false;
     plan->res_tiles.clear(); plan->res_mats.clear();
     plan->res_ws_floats = 0; plan->res_blocks = 0; plan->res_mail_slots = 0; plan->res_sync_words = 0;
-    if (tu.xcd_order) {
+    if (tu.xcd_order >= 2) {
+        order_for_xcds_grouped(plan->hr_tiles1, (size_t)tu.xcd_order);
+        order_for_xcds_grouped(plan->hr_tiles3, (size_t)tu.xcd_order);
+        order_for_xcds_grouped(plan->hr_tiles4, (size_t)tu.xcd_order);
+    } else if (tu.xcd_order) {
         order_for_xcds(plan->hr_tiles1);
         order_for_xcds(plan->hr_tiles3);
         order_for_xcds(plan->hr_tiles4);
@@ -301,7 +326,11 @@ psgd_status build_tables(psgd_plan* plan) {
     build_resident(plan);
     plan->sizes.workspace_bytes =
         std::max<int64_t>(plan->sizes.workspace_bytes, plan->res_ws_floats * (int64_t)sizeof(float));
-    if (tu.xcd_order) {
+    if (tu.xcd_order >= 2) {
+        order_for_xcds_grouped(plan->tiles1, (size_t)tu.xcd_order);
+        order_for_xcds_grouped(plan->tiles3, (size_t)tu.xcd_order);
+        order_for_xcds_grouped(plan->tiles4, (size_t)tu.xcd_order);
+    } else if (tu.xcd_order) {
         order_for_xcds(plan->tiles1);
         order_for_xcds(plan->tiles3);
         order_for_xcds(plan->tiles4);
