@@ -59,6 +59,20 @@ __device__ __forceinline__ void stv<4>(float* p, const float (&x)[4]) {
     *reinterpret_cast<f4*>(p) = t;
 }
 
+// written once and not read again soon (an error memory larger than the caches): non-temporal
+template <int V>
+__device__ __forceinline__ void stv_stream(float* p, const float (&x)[V]) {
+    if constexpr (V == 4) {
+        f4 t; t.x = x[0]; t.y = x[1]; t.z = x[2]; t.w = x[3];
+        __builtin_nontemporal_store(t, reinterpret_cast<f4*>(p));
+    } else if constexpr (V == 2) {
+        f2 t; t.x = x[0]; t.y = x[1];
+        __builtin_nontemporal_store(t, reinterpret_cast<f2*>(p));
+    } else {
+        __builtin_nontemporal_store(x[0], p);
+    }
+}
+
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 // ---- buffer addressing ----------------------------------------------------------------------------------

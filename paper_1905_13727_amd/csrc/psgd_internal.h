@@ -27,6 +27,8 @@ constexpr int kFactorAlignElems = 4;        // P and Q of a matrix start at mult
 constexpr int kHrGramTileRows = 128;       // matrix-core path: rows per workgroup of the mean-P / Gram / apply kernels
 constexpr int64_t kHrMaxRows = 1 << 22;   // matrix-core path: tallest matrix (an n x 64 factor is addressed with 31-bit byte offsets)
 constexpr int64_t kHrMaxCols = 1 << 20;   // matrix-core path: longest row (tiles of <= 256 rows are addressed with 31-bit byte offsets)
+constexpr int64_t kStreamHintBytes = int64_t(320) << 20;   // update matrices of all workers above this (the 256 MB memory-side
+                                                           // cache and a margin): the sweeps after the first treat M as a stream
 constexpr int kMfmaCols = 128;     // super-row columns a wavefront covers per 16-row step in the matrix-core P = M Q kernel
 
 // One matrix of the model.
@@ -103,6 +105,8 @@ struct Tuning {
     int64_t hr_k1_cols = 2048;  // matrix-core P = M Q: columns per workgroup (multiple of 64); longer rows are split and their partial P summed
     int64_t k1_mfma = 0;    // 1: P = M Q on the matrix cores when pack * rank <= 16 for every matrix (slower and less
                             // accurate than the vector kernel at these ranks: kept for experiments)
+    int64_t stream_hints = -1;  // streaming path, sweeps 2 and 3: non-temporal loads of M and stores of the error memory.
+                                // -1: when M of all workers exceeds kStreamHintBytes; 0: never; 1: always
     int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream
     int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height
     int64_t res_trace = 0;  // 1: the resident kernel records phase timestamps (diagnostic)
@@ -155,6 +159,7 @@ struct psgd_plan {
     int64_t ws_chol_doubles = 0;
     std::vector<psgd::Tile> tilesp;         // 64-element slices of the n x r panels (pre-reduction of partial P)
     bool p_pre_reduce = false;              // some matrix has more than kPreReduceParts partial-P slices
+    bool stream_hints = false;              // see Tuning::stream_hints
     int32_t max_n = 0;
     int64_t ws_ppart_floats = 0;            // workspace: partial P region (floats)
     int64_t ws_qpart_floats = 0;            // workspace: partial Q region, starts after partial P

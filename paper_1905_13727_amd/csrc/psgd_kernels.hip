@@ -522,7 +522,9 @@ __global__ __launch_bounds__(kBlock) void k_chol_apply(const MatDesc* __restrict
 // strips of the same columns; their sums are added in LDS in a fixed order and written as
 // one partial per (row block, worker).
 
-template <int R, int V, int NV>
+// STREAM: M is larger than the memory-side cache and will not be found there by the next sweep either way; reading it
+// with non-temporal loads keeps it from pushing out lines that are still waiting to be written back.
+template <int R, int V, int NV, bool STREAM>
 __device__ __forceinline__ void left_tile(const Tile& t, const MatDesc& d, const float* __restrict__ e,
                                           const float* __restrict__ p, float* __restrict__ qpart, float* lds) {
     constexpr int RU = 8;
@@ -562,7 +564,7 @@ __device__ __forceinline__ void left_tile(const Tile& t, const MatDesc& d, const
 #pragma unroll
             for (int u = 0; u < RU; ++u)
 #pragma unroll
-                for (int v = 0; v < NV; ++v) buf_ldv<V>(eres, coff[v] + row_off + (unsigned)u * (unsigned)d.m * 4u, x[u][v]);
+                for (int v = 0; v < NV; ++v) buf_ldv<V>(eres, coff[v] + row_off + (unsigned)u * (unsigned)d.m * 4u, x[u][v], STREAM);
 #pragma unroll
             for (int u = 0; u < RU; ++u) {
                 float pk[R];   // lanes at or past gr hold zeros: rows past the group contribute nothing
@@ -613,7 +615,7 @@ __device__ __forceinline__ void left_tile(const Tile& t, const MatDesc& d, const
     }
 }
 
-template <int R, int NV>
+template <int R, int NV, bool STREAM>
 __global__ __launch_bounds__(kBlock) void k_left(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                  const float* __restrict__ err, const float* __restrict__ p,
                                                  float* __restrict__ ws, int64_t estride) {
@@ -624,9 +626,9 @@ __global__ __launch_bounds__(kBlock) void k_left(const MatDesc* __restrict__ mat
     const float* e = err + (int64_t)w * estride;
     float* qp = ws;
     t.part += w * d.n_rblock;   // partial slices: [worker][row block]
-    if (d.vec == 4) left_tile<R, 4, NV>(t, d, e, p, qp, lds);
-    else if (d.vec == 2) left_tile<R, 2, NV>(t, d, e, p, qp, lds);
-    else left_tile<R, 1, NV>(t, d, e, p, qp, lds);
+    if (d.vec == 4) left_tile<R, 4, NV, STREAM>(t, d, e, p, qp, lds);
+    else if (d.vec == 2) left_tile<R, 2, NV, STREAM>(t, d, e, p, qp, lds);
+    else left_tile<R, 1, NV, STREAM>(t, d, e, p, qp, lds);
 }
 
 // ---- k_q_reduce: Q = (1/W) sum over workers and row blocks of the partials ------------------------
@@ -659,7 +661,8 @@ __global__ __launch_bounds__(kBlock) void k_q_reduce(const MatDesc* __restrict__
 
 // ---- k_decomp: Delta' = P_hat Q^T, e_w = M_w - Delta', vectors averaged ---------------------------
 
-template <int R, int V, int NV, bool UPD>
+// STREAM (see left_tile): M is read with non-temporal loads and the new error memory written with non-temporal stores
+template <int R, int V, int NV, bool UPD, bool STREAM>
 __device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, float* __restrict__ e,
                                             const float* __restrict__ p, const float* __restrict__ q,
                                             float* __restrict__ out, bool write_out, const UpdateArgs& upd) {
@@ -695,7 +698,8 @@ __device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, flo
 #pragma unroll
                     for (int v = 0; v < NV; ++v)
                         if (valid[v]) {
-                            ldv<V>(e + row + col[v], x[u][v]);
+                            if constexpr (STREAM) ldv_stream<V>(e + row + col[v], x[u][v]);
+                            else ldv<V>(e + row + col[v], x[u][v]);
                             if constexpr (UPD) {
                                 if (write_out) {
                                     ldv<V>(upd.mom + row + col[v], mo[u][v]);
@@ -724,7 +728,8 @@ __device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, flo
                                 dl[xx] = s;
                                 en[xx] = x[u][v][xx] - s;
                             }
-                            stv<V>(e + row + col[v], en);
+                            if constexpr (STREAM) stv_stream<V>(e + row + col[v], en);
+                            else stv<V>(e + row + col[v], en);
                             if (write_out) {
                                 if constexpr (UPD) {
                                     momentum_step<V>(mo[u][v], pa[u][v], dl, upd.lr, upd.lam);
@@ -741,7 +746,7 @@ __device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, flo
     }
 }
 
-template <int R, int NV, bool UPD>
+template <int R, int NV, bool UPD, bool STREAM>
 __global__ __launch_bounds__(kBlock) void k_decomp(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                    float* __restrict__ err, const float* __restrict__ p,
                                                    const float* __restrict__ q, const float* __restrict__ grad,
@@ -769,9 +774,9 @@ __global__ __launch_bounds__(kBlock) void k_decomp(const MatDesc* __restrict__ m
     }
     const MatDesc d = mats[t.mat];
     float* e = err + (int64_t)w * estride;
-    if (d.vec == 4) decomp_tile<R, 4, NV, UPD>(t, d, e, p, q, out, w == 0, upd);
-    else if (d.vec == 2) decomp_tile<R, 2, NV, UPD>(t, d, e, p, q, out, w == 0, upd);
-    else decomp_tile<R, 1, NV, UPD>(t, d, e, p, q, out, w == 0, upd);
+    if (d.vec == 4) decomp_tile<R, 4, NV, UPD, STREAM>(t, d, e, p, q, out, w == 0, upd);
+    else if (d.vec == 2) decomp_tile<R, 2, NV, UPD, STREAM>(t, d, e, p, q, out, w == 0, upd);
+    else decomp_tile<R, 1, NV, UPD, STREAM>(t, d, e, p, q, out, w == 0, upd);
 }
 
 // ---- host side ------------------------------------------------------------------------------------
@@ -940,29 +945,40 @@ static void launch_ef_right(psgd_plan* plan, const float* grad, float* err, cons
 template <int R>
 static void launch_left(psgd_plan* plan, const float* err, const float* p, float* ws, hipStream_t s) {
     dim3 grid((unsigned)plan->tiles3.size(), (unsigned)plan->workers);
-    if (plan->tuning.k3_nv == 1)
-        hipLaunchKernelGGL((k_left<R, 1>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles3, err, p, ws,
-                           plan->sizes.err_stride);
-    else
-        hipLaunchKernelGGL((k_left<R, 2>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles3, err, p, ws,
-                           plan->sizes.err_stride);
+#define PSGD_LAUNCH_LEFT(NVV, STREAMV)                                                                                 \
+    hipLaunchKernelGGL((k_left<R, NVV, STREAMV>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles3, err, p, ws, \
+                       plan->sizes.err_stride)
+    if (plan->stream_hints) {
+        if (plan->tuning.k3_nv == 1) PSGD_LAUNCH_LEFT(1, true);
+        else PSGD_LAUNCH_LEFT(2, true);
+    } else {
+        if (plan->tuning.k3_nv == 1) PSGD_LAUNCH_LEFT(1, false);
+        else PSGD_LAUNCH_LEFT(2, false);
+    }
+#undef PSGD_LAUNCH_LEFT
 }
 
 template <int R>
 static void launch_decomp(psgd_plan* plan, float* err, const float* p, const float* q, const float* grad, float* out,
                           hipStream_t s, const UpdateArgs& upd) {
     dim3 grid((unsigned)plan->tiles4.size(), (unsigned)plan->workers);
-#define PSGD_LAUNCH_DECOMP(NVV, UPDV)                                                                                  \
-    hipLaunchKernelGGL((k_decomp<R, NVV, UPDV>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles4, err, p, q, \
-                       grad, out, plan->workers, plan->sizes.grad_stride, plan->sizes.err_stride,                      \
+#define PSGD_LAUNCH_DECOMP(NVV, UPDV, STREAMV)                                                                         \
+    hipLaunchKernelGGL((k_decomp<R, NVV, UPDV, STREAMV>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles4,  \
+                       err, p, q, grad, out, plan->workers, plan->sizes.grad_stride, plan->sizes.err_stride,           \
                        plan->sizes.n_mat_elems, upd)
+#define PSGD_LAUNCH_DECOMP_NV(UPDV, STREAMV)                          \
+    do {                                                              \
+        if (plan->tuning.k4_nv == 1) PSGD_LAUNCH_DECOMP(1, UPDV, STREAMV); \
+        else PSGD_LAUNCH_DECOMP(2, UPDV, STREAMV);                    \
+    } while (0)
     if (upd.mom) {
-        if (plan->tuning.k4_nv == 1) PSGD_LAUNCH_DECOMP(1, true);
-        else PSGD_LAUNCH_DECOMP(2, true);
+        if (plan->stream_hints) PSGD_LAUNCH_DECOMP_NV(true, true);
+        else PSGD_LAUNCH_DECOMP_NV(true, false);
     } else {
-        if (plan->tuning.k4_nv == 1) PSGD_LAUNCH_DECOMP(1, false);
-        else PSGD_LAUNCH_DECOMP(2, false);
+        if (plan->stream_hints) PSGD_LAUNCH_DECOMP_NV(false, true);
+        else PSGD_LAUNCH_DECOMP_NV(false, false);
     }
+#undef PSGD_LAUNCH_DECOMP_NV
 #undef PSGD_LAUNCH_DECOMP
 }
 

@@ -203,7 +203,8 @@ psgd_status build_tables(psgd_plan* plan) {
     const Tuning& tu = plan->tuning;
     if (tu.k1_rows < 1 || tu.k3_rows < 1 || tu.k4_rows < 1 || tu.k1_nv < 1 ||
         tu.k1_nv > kMaxVecPerLaneK1 || tu.k3_nv < 1 || tu.k3_nv > kMaxVecPerLaneK3 || tu.k4_nv < 1 ||
-        tu.k4_nv > kMaxVecPerLaneK3 || tu.q_reduce_elems < 1 || tu.res_rows < 0 || tu.res_rows > kResRows)
+        tu.k4_nv > kMaxVecPerLaneK3 || tu.q_reduce_elems < 1 || tu.res_rows < 0 || tu.res_rows > kResRows ||
+        tu.stream_hints < -1 || tu.stream_hints > 1 || tu.xcd_order < 0)
         return PSGD_EINVAL;
     const size_t nm = plan->mats.size();
     // k_ef_right and k_left address the rows of a wavefront's strip (a quarter of the tile's rows) with 31-bit
@@ -323,6 +324,8 @@ psgd_status build_tables(psgd_plan* plan) {
             plan->tilesq.push_back(t);
         }
     }
+    plan->stream_hints = tu.stream_hints < 0 ? W * plan->sizes.n_mat_elems * (int64_t)sizeof(float) > kStreamHintBytes
+                                             : tu.stream_hints != 0;
     build_resident(plan);
     plan->sizes.workspace_bytes =
         std::max<int64_t>(plan->sizes.workspace_bytes, plan->res_ws_floats * (int64_t)sizeof(float));
@@ -635,6 +638,7 @@ psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value
     else if (!strcmp(key, "hr_k1_rows")) tu.hr_k1_rows = value;
     else if (!strcmp(key, "hr_k1_cols")) tu.hr_k1_cols = value;
     else if (!strcmp(key, "resident")) tu.resident = value;
+    else if (!strcmp(key, "stream_hints")) tu.stream_hints = value;
     else if (!strcmp(key, "res_rows")) tu.res_rows = value;
     else if (!strcmp(key, "res_trace")) tu.res_trace = value;
     else return PSGD_EINVAL;

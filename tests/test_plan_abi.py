@@ -71,6 +71,10 @@ def test_null_pointers_are_rejected_without_a_gpu():
         plan.set_tuning("no_such_key", 1)
     with pytest.raises(B.PsgdError):
         plan.set_tuning("k1_nv", 99)
+    with pytest.raises(B.PsgdError):
+        plan.set_tuning("stream_hints", 2)
+    plan.set_tuning("stream_hints", 1)
+    plan.set_tuning("xcd_order", 0)
     plan.set_tuning("k1_rows", 16)
 
 
