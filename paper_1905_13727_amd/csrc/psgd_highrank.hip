@@ -11,7 +11,7 @@
 //   k_hr_gram / k_hr_chol / k_hr_apply   mean P, Gram matrix in fp64, Cholesky factor, P_hat = P R^-1:
 //                        the orthonormal factor Gram-Schmidt yields (remark "Orthogonalization is a
 //                        linear operation"), for panels of any height                    (Alg. 1)
-//   k_hr_left<NT>        Q_w = M^T P_hat, one partial per wavefront's row strip          (Alg. 1)
+//   k_hr_left<NT, ..>    Q_w = M^T P_hat, one partial per wavefront's row strip          (Alg. 1)
 //   k_hr_decomp<NT, OM>  Delta' = P_hat Q^T, e' = M - Delta', Delta' stored fp32 or bf16, or folded into the
 //                        momentum / parameter update                                     (Alg. 1, Alg. 2)
 //   k_hr_vec<BFI, BFO>   mean of the vector-shaped tensors                                (Alg. 1 line 1)
@@ -463,7 +463,9 @@ __global__ __launch_bounds__(kBlock) void k_hr_apply(const MatDesc* __restrict__
 // row block is written.
 constexpr int kHrLeftGroups = 2;   // 64-column groups per wavefront (128 columns)
 
-template <int NT>
+// STREAM: M is larger than the memory-side cache: it is read with non-temporal loads, which keeps it from pushing out
+// lines that still wait to be written back
+template <int NT, bool STREAM>
 __global__ __launch_bounds__(kBlock) void k_hr_left(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                     const float* __restrict__ err, const float* __restrict__ p,
                                                     float* __restrict__ ws, float* __restrict__ q, int workers,
@@ -503,7 +505,10 @@ __global__ __launch_bounds__(kBlock) void k_hr_left(const MatDesc* __restrict__ 
             for (int g = 0; g < NG; ++g) {
                 const int col = c0 + 64 * g + 4 * li;
                 a[s][g] = v4f{0.f, 0.f, 0.f, 0.f};
-                if (col < m && col < c0 + t.nvec) a[s][g] = *reinterpret_cast<const v4f*>(e + (int64_t)row_c * m + col);
+                if (col < m && col < c0 + t.nvec) {
+                    const v4f* src = reinterpret_cast<const v4f*>(e + (int64_t)row_c * m + col);
+                    a[s][g] = STREAM ? __builtin_nontemporal_load(src) : *src;
+                }
             }
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
@@ -830,15 +835,19 @@ psgd_status hr_compress(psgd_plan* plan, const void* grad, float* err, float* q,
     HR_MARK(2);
     {
         dim3 grid((unsigned)plan->hr_tiles3.size(), (unsigned)plan->workers);
-        if (nt == 1)
-            hipLaunchKernelGGL((k_hr_left<1>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles3, err, p, ws,
-                               q, plan->workers, plan->sizes.err_stride);
-        else if (nt == 2)
-            hipLaunchKernelGGL((k_hr_left<2>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles3, err, p, ws,
-                               q, plan->workers, plan->sizes.err_stride);
-        else
-            hipLaunchKernelGGL((k_hr_left<4>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles3, err, p, ws,
-                               q, plan->workers, plan->sizes.err_stride);
+#define HR_LAUNCH_LEFT(NTV, STREAMV)                                                                                   \
+    hipLaunchKernelGGL((k_hr_left<NTV, STREAMV>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles3, err, p, ws, \
+                       q, plan->workers, plan->sizes.err_stride)
+        if (plan->stream_hints) {
+            if (nt == 1) HR_LAUNCH_LEFT(1, true);
+            else if (nt == 2) HR_LAUNCH_LEFT(2, true);
+            else HR_LAUNCH_LEFT(4, true);
+        } else {
+            if (nt == 1) HR_LAUNCH_LEFT(1, false);
+            else if (nt == 2) HR_LAUNCH_LEFT(2, false);
+            else HR_LAUNCH_LEFT(4, false);
+        }
+#undef HR_LAUNCH_LEFT
     }
     HR_CHECK("launch k_hr_left");
     HR_MARK(3);

@@ -105,7 +105,9 @@ struct Tuning {
     int64_t hr_k1_cols = 2048;  // matrix-core P = M Q: columns per workgroup (multiple of 64); longer rows are split and their partial P summed
     int64_t k1_mfma = 0;    // 1: P = M Q on the matrix cores when pack * rank <= 16 for every matrix (slower and less
                             // accurate than the vector kernel at these ranks: kept for experiments)
-    int64_t stream_hints = -1;  // streaming path, sweeps 2 and 3: non-temporal loads of M and stores of the error memory.
+    int64_t stream_hints = -1;  // sweeps 2 and 3 of the streaming path: non-temporal loads of M and stores of the error
+                                // memory (and temporal instead of non-temporal stores of Delta'); matrix-core path:
+                                // non-temporal loads of M in sweep 2.
                                 // -1: when M of all workers exceeds kStreamHintBytes; 0: never; 1: always
     int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream
     int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height

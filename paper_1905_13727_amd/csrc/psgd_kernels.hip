@@ -661,7 +661,8 @@ __global__ __launch_bounds__(kBlock) void k_q_reduce(const MatDesc* __restrict__
 
 // ---- k_decomp: Delta' = P_hat Q^T, e_w = M_w - Delta', vectors averaged ---------------------------
 
-// STREAM (see left_tile): M is read with non-temporal loads and the new error memory written with non-temporal stores
+// STREAM (see left_tile): M is read with non-temporal loads and the new error memory written with non-temporal stores;
+// otherwise it is Delta' that is written with non-temporal stores
 template <int R, int V, int NV, bool UPD, bool STREAM>
 __device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, float* __restrict__ e,
                                             const float* __restrict__ p, const float* __restrict__ q,
@@ -736,7 +737,9 @@ __device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, flo
                                     stv<V>(upd.mom + row + col[v], mo[u][v]);
                                     stv<V>(upd.param + row + col[v], pa[u][v]);
                                 } else {
-                                    stv<V>(out + row + col[v], dl);
+                                    // a set that fits the memory-side cache: Delta' goes around it, M and e' stay
+                                    if constexpr (STREAM) stv<V>(out + row + col[v], dl);
+                                    else stv_stream<V>(out + row + col[v], dl);
                                 }
                             }
                         }

@@ -105,7 +105,8 @@ void build_resident(psgd_plan* plan);
 static psgd_status build_hr_tables(psgd_plan* plan) {
     const Tuning& tu = plan->tuning;
     if (tu.hr_k3_rows < 64 || tu.hr_k1_rows < 64 || tu.hr_k1_rows > 256 || tu.hr_k1_rows % 64 != 0 ||
-        tu.hr_k1_cols < 64 || tu.hr_k1_cols % 64 != 0 || tu.hr_k4_rows < 16 || tu.hr_k4_rows > 1024)
+        tu.hr_k1_cols < 64 || tu.hr_k1_cols % 64 != 0 || tu.hr_k4_rows < 16 || tu.hr_k4_rows > 1024 ||
+        tu.stream_hints < -1 || tu.stream_hints > 1 || tu.xcd_order < 0)
         return PSGD_EINVAL;
     const int64_t W = plan->workers;
     const size_t nm = plan->mats.size();
@@ -182,6 +183,8 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
     plan->ws_chol_doubles = cp;
     plan->sizes.workspace_bytes =
         std::max<int64_t>(256, round_up((pp + qp) * (int64_t)sizeof(float), 256) + (gp + cp) * (int64_t)sizeof(double));
+    plan->stream_hints = tu.stream_hints < 0 ? W * plan->sizes.n_mat_elems * (int64_t)sizeof(float) > kStreamHintBytes
+                                             : tu.stream_hints != 0;
     plan->resident_ok = false;
     plan->res_tiles.clear(); plan->res_mats.clear();
     plan->res_ws_floats = 0; plan->res_blocks = 0; plan->res_mail_slots = 0; plan->res_sync_words = 0;

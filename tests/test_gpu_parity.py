@@ -262,6 +262,8 @@ def test_streaming_hints(rank, workers):
         for w in range(workers):
             for x, y in zip(ra["err"][w], rb["err"][w]):
                 assert x is None or np.array_equal(x, y)
+    # matrix-core path: the second sweep reads M that way
+    _run(_workload(TRANSFORMER_SMALL), rank=16, workers=1, steps=2, seed=75, tuning={"stream_hints": 1})
 
 
 def test_between_compress_and_decompress_err_holds_m():
