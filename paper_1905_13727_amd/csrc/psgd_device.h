@@ -230,6 +230,42 @@ __device__ __forceinline__ double wave_sum(double v) {
     return (s0 + s1) + (s2 + s3);
 }
 
+// N sums over the 64 lanes at once: every lane brings N addends x[0..N-1]; on return lane L (L < N) holds the sum
+// over all lanes of x[L].  Within each row of 16 lanes the values are handed over in halves (mirror, half mirror,
+// the two quad swaps): a lane keeps the half whose index bit equals its own lane bit and adds its partner's copy
+// of it, so 16 values per lane shrink to one in 15 exchanges instead of 16 separate reductions; the four rows'
+// results are then added through two cross-lane reads.  Fixed order, the same in every call.
+template <int N>
+__device__ __forceinline__ float lane_sums(const float (&x)[N]) {
+    static_assert(N >= 1 && N <= kWave, "one result per lane");
+    constexpr int G = (N + 15) / 16;
+    const int lane = threadIdx.x & (kWave - 1);
+    const bool b3 = (lane & 8) != 0, b2 = (lane & 4) != 0, b1 = (lane & 2) != 0, b0 = (lane & 1) != 0;
+    float res[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        float a16[16], a8[8], a4[4], a2[2];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) a16[j] = 16 * g + j < N ? x[16 * g + j] : 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a8[j] = (b3 ? a16[j + 8] : a16[j]) + dpp_mov<0x140>(b3 ? a16[j] : a16[j + 8]);   // row_mirror
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a4[j] = (b2 ? a8[j + 4] : a8[j]) + dpp_mov<0x141>(b2 ? a8[j] : a8[j + 4]);       // row_half_mirror
+#pragma unroll
+        for (int j = 0; j < 2; ++j) a2[j] = (b1 ? a4[j + 2] : a4[j]) + dpp_mov<0x1B>(b1 ? a4[j] : a4[j + 2]);        // quad_perm [3,2,1,0]
+        float v = (b0 ? a2[1] : a2[0]) + dpp_mov<0xB1>(b0 ? a2[0] : a2[1]);                                          // quad_perm [1,0,3,2]
+        // lane L now holds, for index 16 g + (L & 15), the sum over its row of 16 lanes
+        v += __int_as_float(__builtin_amdgcn_ds_bpermute((lane ^ 16) << 2, __float_as_int(v)));
+        v += __int_as_float(__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __float_as_int(v)));
+        res[g] = v;
+    }
+    float out = res[0];
+#pragma unroll
+    for (int g = 1; g < G; ++g)
+        if ((lane >> 4) == g) out = res[g];
+    return out;
+}
+
 // rows [*begin, *begin + *count) of a tile's `total` rows that wavefront `wave` of 4 handles
 __device__ __forceinline__ void wave_rows(int total, int wave, int* begin, int* count) {
     const int base = total / kWavesPerBlock, rem = total % kWavesPerBlock;

@@ -112,23 +112,21 @@ __device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, c
                         buf_stv<V>(eres, coff[v] + row_off + (unsigned)(h * RH + i) * (unsigned)d.m * 4u, mv[h * RH + i][v]);
                 }
         }
-        // RS * R dot products, reduced over the wavefront; lane i * R + k keeps the result of (row i, rank k)
-        float mine = 0.f;
+        // RS * R dot products, reduced over the wavefront all at once; lane i * R + k receives the result of
+        // (row i, rank k).  Rows past the strip were read as zeros.
+        float part[RS * R];
 #pragma unroll
-        for (int i = 0; i < RS; ++i) {
-            if (i < rows) {
+        for (int i = 0; i < RS; ++i)
 #pragma unroll
-                for (int k = 0; k < R; ++k) {
-                    float s = 0.f;
+            for (int k = 0; k < R; ++k) {
+                float s = 0.f;
 #pragma unroll
-                    for (int v = 0; v < NV; ++v)
+                for (int v = 0; v < NV; ++v)
 #pragma unroll
-                        for (int x = 0; x < V; ++x) s = fmaf(mv[i][v][x], qr[v][x][k], s);
-                    s = wave_sum(s);
-                    if (lane == i * R + k) mine = s;
-                }
+                    for (int x = 0; x < V; ++x) s = fmaf(mv[i][v][x], qr[v][x][k], s);
+                part[i * R + k] = s;
             }
-        }
+        const float mine = lane_sums<RS * R>(part);
         const int li = lane / R, lk = lane % R;
         if (li < rows && lk < ri)
             ppart[d.ppart_off + ((int64_t)t.part * d.n + i0 + li) * ri + lk] = mine;
