@@ -223,19 +223,37 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
         }
     }
     {
+        // the strip's row dot products: lane i receives row i's (rows past the strip were read as zeros)
         float mine[R];
+        if constexpr (R <= 2) {
+            // rank by rank, all rows of the strip reduced over the wavefront together
 #pragma unroll
-        for (int k = 0; k < R; ++k) mine[k] = 0.f;
+            for (int k = 0; k < R; ++k) {
+                float part[RT];
 #pragma unroll
-        for (int i = 0; i < RT; ++i) {
-            if (i < nrows) {
-#pragma unroll
-                for (int k = 0; k < R; ++k) {
+                for (int i = 0; i < RT; ++i) {
                     float s = 0.f;
 #pragma unroll
                     for (int x = 0; x < V; ++x) s = fmaf(M[i][x], qr[x][k], s);
-                    s = wave_sum(s);
-                    if (lane == i) mine[k] = s;
+                    part[i] = s;
+                }
+                mine[k] = lane_sums<RT>(part);
+            }
+        } else {
+            // the higher ranks have no registers to spare for that: one reduction per row and rank
+#pragma unroll
+            for (int k = 0; k < R; ++k) mine[k] = 0.f;
+#pragma unroll
+            for (int i = 0; i < RT; ++i) {
+                if (i < nrows) {
+#pragma unroll
+                    for (int k = 0; k < R; ++k) {
+                        float s = 0.f;
+#pragma unroll
+                        for (int x = 0; x < V; ++x) s = fmaf(M[i][x], qr[x][k], s);
+                        s = wave_sum(s);
+                        if (lane == i) mine[k] = s;
+                    }
                 }
             }
         }
