@@ -515,7 +515,7 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
                         stv<V>(a.upd.mom + tile_off + (int64_t)i * d.m, mo[u]);
                         stv<V>(a.upd.param + tile_off + (int64_t)i * d.m, pa[u]);
                     } else {
-                        stv<V>(a.out + tile_off + (int64_t)i * d.m, dl);
+                        stv_stream<V>(a.out + tile_off + (int64_t)i * d.m, dl);   // written once: around the caches, which keep e
                     }
                 }
             }
