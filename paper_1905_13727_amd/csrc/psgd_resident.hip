@@ -11,8 +11,8 @@
 //             the wavefront with the first tile of a matrix runs Gram-Schmidt on the n x r panel
 //             (Alg. 1 "orthogonalize") and publishes P_hat
 //   phase B   (needs this strip's rows of P_hat)  Q = M^T P_hat from the registers -> partial Q per
-//             run of strips; the wavefront with the first run of a column chunk adds the runs and
-//             publishes Q
+//             run of strips (consecutive wavefronts of a workgroup with the same column chunk); the
+//             first wavefront of every run adds the chunk's runs and hands Q to its run through LDS
 //   phase C   (needs this chunk's rows of Q)  Delta' = P_hat Q^T (Alg. 1 "decompress"),
 //             e' = M - Delta' (Alg. 2), each stored once
 //
@@ -179,7 +179,6 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
     slot_t* mail_pb = mail_pp + (int64_t)d.n_cchunk * nr; // mean P      [n][r]
     slot_t* mail_ph = mail_pb + nr;                       // P_hat       [n][r]
     slot_t* mail_qp = a.mail + d.qpart_off;               // partial Q   [n_rblock][m][r]
-    slot_t* mail_qb = mail_qp + (int64_t)d.n_rblock * mr; // Q           [m][r]
 
     // ---------------- phase A ----------------
     trace_mark(a, 0);
@@ -399,9 +398,11 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
                 for (int k = 0; k < R; ++k)
                     if (k < ri) post(dst + (int64_t)(x * ri + k) * nvec_m, acc[x][k], epoch);
         }
-        if (t.qpart == 0) {
-            // first run of this column chunk: add the runs' partials in run order and publish Q
-            if (!(t.ppart == 0 && t.row0 == 0)) trace_mark_wave(a, 8);
+        {
+            // Every run of this column chunk adds the chunk's partials itself, in run order (the same sum in each of
+            // them): Q is then one trip through memory away from the partials, not two, and only the runs' first
+            // wavefronts poll.  The chunk's first run also stores Q.
+            if (t.qpart == 0 && !(t.ppart == 0 && t.row0 == 0)) trace_mark_wave(a, 8);
             float s[V][R];
 #pragma unroll
             for (int x = 0; x < V; ++x)
@@ -436,21 +437,26 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
 #pragma unroll
                         for (int k = 0; k < R; ++k)
                             if (p0 + u < t.nqparts) s[x][k] += value_of(w[u][x][k]);
-                if (!(t.ppart == 0 && t.row0 == 0)) trace_mark_wave(a, 9 + min(p0 / PG, 2));
+                if (t.qpart == 0 && !(t.ppart == 0 && t.row0 == 0)) trace_mark_wave(a, 9 + min(p0 / PG, 2));
             }
-            if (valid) {
+            if (t.qpart == 0 && valid) {
 #pragma unroll
                 for (int x = 0; x < V; ++x)
 #pragma unroll
                     for (int k = 0; k < R; ++k)
-                        if (k < ri) {
-                            post(mail_qb + (int64_t)(x * ri + k) * nvec_m + jv, s[x][k], epoch);   // W = 1: mean = sum
-                            a.q[d.q_off + (int64_t)(col + x) * ri + k] = s[x][k];
-                        }
+                        if (k < ri) a.q[d.q_off + (int64_t)(col + x) * ri + k] = s[x][k];   // W = 1: mean = sum
+            }
+            // Q goes to the wavefronts of the run through shared memory (their own sums there have been read above)
+            for (int w2 = 0; w2 < t.qrun_len; ++w2) {
+#pragma unroll
+                for (int x = 0; x < V; ++x)
+#pragma unroll
+                    for (int k = 0; k < R; ++k) lds[(((wave + w2) * V + x) * R + k) * kWave + lane] = s[x][k];
             }
         }
     }
     trace_mark(a, 4);
+    __syncthreads();
 
     // ---------------- phase C ----------------
     float qb[V][R];
@@ -459,25 +465,11 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
 #pragma unroll
         for (int k = 0; k < R; ++k) qb[x][k] = 0.f;
     if (active) {
-        slot_t w[V][R];
-        const int64_t nvec_m = d.m / V;
-        const int64_t jv = t.vec0 + min(lane, t.nvec - 1);
-        await_probed(mail_qb + t.vec0, epoch, [&]() {
-#pragma unroll
-            for (int x = 0; x < V; ++x)
-#pragma unroll
-                for (int k = 0; k < R; ++k) w[x][k] = fetch(mail_qb + (int64_t)(x * ri + min(k, ri - 1)) * nvec_m + jv);
-            bool ok = true;
-#pragma unroll
-            for (int x = 0; x < V; ++x)
-#pragma unroll
-                for (int k = 0; k < R; ++k) ok &= arrived(w[x][k], epoch);
-            return ok;
-        }, err_word);
 #pragma unroll
         for (int x = 0; x < V; ++x)
 #pragma unroll
-            for (int k = 0; k < R; ++k) qb[x][k] = (valid && k < ri) ? value_of(w[x][k]) : 0.f;
+            for (int k = 0; k < R; ++k)
+                qb[x][k] = (valid && k < ri) ? lds[((wave * V + x) * R + k) * kWave + lane] : 0.f;
     }
     trace_mark(a, 5);
     constexpr int CG = UPD ? 4 : 1;   // rows whose momentum / parameter loads are in flight together
