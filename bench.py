@@ -34,8 +34,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 METRIC = "PowerSGD step gradient GB/s + % HBM peak, ResNet18 shapes r=2"   # the headline metric and its workload
 
 MEASURED_TRAFFIC = {
-    # profiles/resident_resnet18_r2.md: 98.4 MB fetched + 93.5 MB written
-    ("resnet18", 2, 1, "k_resident"): 191954115,
+    # profiles/resident_resnet18_r2.md: 107.2 MB fetched + 93.0 MB written
+    ("resnet18", 2, 1, "k_resident"): 200294912,
 }
 
 
