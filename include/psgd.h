@@ -121,7 +121,22 @@ PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, in
                               int64_t* p_off, int64_t* q_off, int32_t* eff_rank);
 
 /* Tuning knob for experiments; must be called before the plan's first GPU call.
- * Unknown keys give PSGD_EINVAL.  Keys are documented in the design notes. */
+ * Unknown keys and values out of range give PSGD_EINVAL.  Keys:
+ *   resident      1 (default): psgd_step keeps M on chip when the model qualifies; 0: always stream
+ *   res_rows      forced strip height of the resident tiling (0: chosen by the planner)
+ *   res_trace     1: the resident kernel records phase timestamps (psgd_plan_read_trace)
+ *   k1_rows, k1_nv / k3_rows, k3_nv / k4_rows, k4_nv
+ *                 rows per workgroup tile and column vectors per lane of the three sweeps of the
+ *                 streaming path (P = M Q; Q = M^T P_hat; decompression)
+ *   k1_mfma       1: matrix-core variant of the first sweep at rank <= 8 (default 0)
+ *   hr_k1_rows, hr_k1_cols, hr_k3_rows, hr_k4_rows   tile shapes of the matrix-core path
+ *   xcd_order     order of the tile lists over the accelerator dies: 0 plain, 1 one contiguous range
+ *                 of the whole list per die, k >= 2 the same within groups of consecutive matrices
+ *                 of at least k tiles (default 2048)
+ *   stream_hints  cache policy of the second and third sweep: -1 (default) by the size of M over all
+ *                 workers (non-temporal accesses to M and the error memory above 320 MB), 0 never,
+ *                 1 always
+ *   q_reduce_elems  accepted, unused */
 PSGD_API psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value);
 
 /* Algorithm 2 "Delta_w <- g_w + e_w" followed by Algorithm 1 compress+aggregate.
