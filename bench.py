@@ -154,9 +154,11 @@ def main():
     tdt = {"f32": torch.float32, "bf16": torch.bfloat16}
     plan = B.Plan(wl.shapes, rank, W, B.PSGD_BF16 if gdt == "bf16" else B.PSGD_F32,
                   B.PSGD_BF16 if odt == "bf16" else B.PSGD_F32)
+    tune = {}
     for kv in args.tune:
         k, v = kv.split("=")
         plan.set_tuning(k, int(v))
+        tune[k] = int(v)
     lay = FlatLayout(plan, wl.shapes)
     s = plan.sizes
 
@@ -284,7 +286,8 @@ def main():
         "config": {"workload": "%s-shaped gradient set, W=%d simulated worker(s), rank %d, gradients %s, output %s"
                                % (wl.name, W, rank, gdt, odt),
                    "mode": "resident (one kernel, M kept in registers)" if resident else
-                           ("matrix cores (one kernel per phase)" if rank > 8 or gdt != "f32" or odt != "f32"
+                           ("matrix cores (one kernel per phase)"
+                            if rank > 8 or ((gdt != "f32" or odt != "f32") and tune.get("bf16_valu", 1) == 0)
                             else "streaming (one kernel per phase)"),
                    "matrices": int(s.n_matrices), "matrix_elems": int(payload_mat), "vector_elems": int(L),
                    "grad_buffers": len(grads), "update": args.update,

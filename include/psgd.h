@@ -127,7 +127,8 @@ PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, in
  *   res_trace     1: the resident kernel records phase timestamps (psgd_plan_read_trace)
  *   k1_rows, k1_nv / k3_rows, k3_nv / k4_rows, k4_nv
  *                 rows per workgroup tile and column vectors per lane of the three sweeps of the
- *                 streaming path (P = M Q; Q = M^T P_hat; decompression)
+ *                 streaming path (P = M Q; Q = M^T P_hat; decompression); rows 0 (default):
+ *                 chosen per matrix by the planner
  *   k1_mfma       1: matrix-core variant of the first sweep at rank <= 8 (default 0)
  *   hr_k1_rows, hr_k1_cols, hr_k3_rows, hr_k4_rows   tile shapes of the matrix-core path
  *   xcd_order     order of the tile lists over the accelerator dies: 0 plain, 1 one contiguous range
@@ -136,6 +137,7 @@ PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, in
  *   stream_hints  cache policy of the second and third sweep: -1 (default) by the size of M over all
  *                 workers (non-temporal accesses to M and the error memory above 320 MB), 0 never,
  *                 1 always
+ *   bf16_valu     bf16 gradients / output at rank <= 8: 1 (default) streaming kernels, 0 matrix-core kernels
  *   q_reduce_elems  accepted, unused */
 PSGD_API psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value);
 

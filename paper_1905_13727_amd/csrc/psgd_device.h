@@ -137,6 +137,55 @@ __device__ __forceinline__ void buf_stv(buf_rsrc r, unsigned off, const float (&
     }
 }
 
+// ---- bf16 gradients and output -----------------------------------------------------------------------------
+typedef unsigned short bf16_t;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float((unsigned)h << 16); }
+
+// fp32 -> bf16, round to nearest even (NaN stays NaN): the conversion instruction of the matrix-core generation
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+    const v2bf y = __builtin_convertvector(v2f{lo, hi}, v2bf);
+    unsigned u;
+    __builtin_memcpy(&u, &y, 4);
+    return u;
+}
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
+
+// V consecutive gradient elements through a descriptor, read once (non-temporal); `off` in bytes.  BF: the
+// gradient is stored as bf16 (4-wide rows only: the planner requires row lengths that are multiples of 4).
+template <int V, bool BF>
+__device__ __forceinline__ void buf_ld_grad(buf_rsrc r, unsigned off, float (&x)[V]) {
+    if constexpr (BF) {
+        static_assert(V == 4, "bf16 gradients are read four at a time");
+        const v2u t = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 2);
+        x[0] = __uint_as_float(t.x << 16); x[1] = __uint_as_float(t.x & 0xffff0000u);
+        x[2] = __uint_as_float(t.y << 16); x[3] = __uint_as_float(t.y & 0xffff0000u);
+    } else {
+        buf_ldv<V>(r, off, x, true);
+    }
+}
+
+// V consecutive elements of the output at element index `at`; BF: stored as bf16 (round to nearest even; 4-wide
+// rows only).  NT: non-temporal.
+template <int V, bool BF, bool NT>
+__device__ __forceinline__ void st_out(void* out, int64_t at, const float (&x)[V]) {
+    if constexpr (BF) {
+        static_assert(V == 4, "bf16 output is written four at a time");
+        typedef unsigned u2 __attribute__((ext_vector_type(2)));
+        u2 t;
+        t.x = pack_bf16x2(x[0], x[1]);
+        t.y = pack_bf16x2(x[2], x[3]);
+        u2* dst = reinterpret_cast<u2*>(static_cast<bf16_t*>(out) + at);
+        if constexpr (NT) __builtin_nontemporal_store(t, dst);
+        else *dst = t;
+    } else {
+        if constexpr (NT) stv_stream<V>(static_cast<float*>(out) + at, x);
+        else stv<V>(static_cast<float*>(out) + at, x);
+    }
+}
+
 // Rows of a factor that belong to V consecutive matrix columns (or rows): the V * ri consecutive floats at
 // `rows` -> f[V][R], zero beyond ri and everything zero when !valid.  With ri == R (the usual case; ri < R
 // only for matrices smaller than the rank) they are fetched with the widest aligned vector loads instead of

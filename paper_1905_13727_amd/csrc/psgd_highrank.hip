@@ -29,21 +29,6 @@
 
 namespace psgd {
 
-typedef unsigned short bf16_t;
-
-__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float((unsigned)h << 16); }
-
-// fp32 -> bf16, round to nearest even (NaN stays NaN): the conversion instruction of the matrix-core generation
-typedef float v2f __attribute__((ext_vector_type(2)));
-typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
-    const v2bf y = __builtin_convertvector(v2f{lo, hi}, v2bf);
-    unsigned u;
-    __builtin_memcpy(&u, &y, 4);
-    return u;
-}
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
-
 // four gradient elements, read once (non-temporal)
 template <bool BF>
 __device__ __forceinline__ v4f buf_load_grad4(buf_rsrc r, unsigned off) {
@@ -857,17 +842,9 @@ psgd_status hr_compress(psgd_plan* plan, const void* grad, float* err, float* q,
     return PSGD_OK;
 }
 
-psgd_status hr_decompress(psgd_plan* plan, const float* p, const float* q, float* err, const void* grad, void* out,
-                          void* stream, const UpdateArgs& upd) {
+// mean over the workers of the vector-shaped tensors (any mix of fp32 / bf16 gradients and output)
+psgd_status launch_vector_mean(psgd_plan* plan, const void* grad, void* out, void* stream, const UpdateArgs& upd) {
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int nt = plan->hr_nt;
-    HR_MARK(5);
-    if (!plan->hr_tiles4.empty()) {
-        if (nt == 1) hr_launch_decomp<1>(plan, err, p, q, out, s, upd);
-        else if (nt == 2) hr_launch_decomp<2>(plan, err, p, q, out, s, upd);
-        else hr_launch_decomp<4>(plan, err, p, q, out, s, upd);
-        HR_CHECK("launch k_hr_decomp");
-    }
     const int64_t L = plan->sizes.n_vec_elems;
     if (L > 0) {
         const unsigned blocks = (unsigned)std::min<int64_t>(1024, (L + kBlock - 1) / kBlock);
@@ -886,6 +863,22 @@ psgd_status hr_decompress(psgd_plan* plan, const float* p, const float* q, float
                                plan->sizes.grad_stride, plan->sizes.n_mat_elems, L, upd);
         HR_CHECK("launch k_hr_vec");
     }
+    return PSGD_OK;
+}
+
+psgd_status hr_decompress(psgd_plan* plan, const float* p, const float* q, float* err, const void* grad, void* out,
+                          void* stream, const UpdateArgs& upd) {
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int nt = plan->hr_nt;
+    HR_MARK(5);
+    if (!plan->hr_tiles4.empty()) {
+        if (nt == 1) hr_launch_decomp<1>(plan, err, p, q, out, s, upd);
+        else if (nt == 2) hr_launch_decomp<2>(plan, err, p, q, out, s, upd);
+        else hr_launch_decomp<4>(plan, err, p, q, out, s, upd);
+        HR_CHECK("launch k_hr_decomp");
+    }
+    psgd_status vs = launch_vector_mean(plan, grad, out, stream, upd);
+    if (vs != PSGD_OK) return vs;
     HR_MARK(6);
     return finish_profiled_step(plan);
 }

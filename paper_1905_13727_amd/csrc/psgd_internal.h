@@ -92,11 +92,12 @@ struct RTile {
 };
 
 struct Tuning {
-    int64_t k1_rows = 32;   // rows per workgroup tile, P = M Q
+    int64_t k1_rows = 0;    // rows per workgroup tile, P = M Q; 0: by the access width of the matrix (16 / 32 / 64; twice
+                            // that for small sets)
     int64_t k1_nv = 2;      // column vectors per lane (<= kMaxVecPerLaneK1)
-    int64_t k3_rows = 128;  // rows per workgroup tile, Q = M^T P
+    int64_t k3_rows = 0;    // rows per workgroup tile, Q = M^T P; 0: 128, or 1024 for matrices >= 2048 x 2048
     int64_t k3_nv = 1;      // column vectors per lane (<= kMaxVecPerLaneK3)
-    int64_t k4_rows = 32;   // rows per workgroup tile, decompress + residual
+    int64_t k4_rows = 0;    // rows per workgroup tile, decompress + residual; 0: 16 (32 for small sets)
     int64_t k4_nv = 1;
     int64_t q_reduce_elems = 1024;  // accepted, unused (the Q reduction works on 64 elements per workgroup)
     int64_t hr_k3_rows = 2048;  // matrix-core Q = M^T P: rows per workgroup (four strips)
@@ -109,6 +110,7 @@ struct Tuning {
                                 // memory (and temporal instead of non-temporal stores of Delta'); matrix-core path:
                                 // non-temporal loads of M in sweep 2.
                                 // -1: when M of all workers exceeds kStreamHintBytes; 0: never; 1: always
+    int64_t bf16_valu = 1;  // bf16 gradients / output at rank <= 8: 1 = the streaming (vector-ALU) kernels, 0 = the matrix-core kernels
     int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream
     int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height
     int64_t res_trace = 0;  // 1: the resident kernel records phase timestamps (diagnostic)
@@ -217,6 +219,7 @@ psgd_status hr_compress(psgd_plan* plan, const void* grad, float* err, float* q,
                         void* stream, bool add);
 psgd_status hr_decompress(psgd_plan* plan, const float* p, const float* q, float* err, const void* grad, void* out,
                           void* stream, const UpdateArgs& upd);
+psgd_status launch_vector_mean(psgd_plan* plan, const void* grad, void* out, void* stream, const UpdateArgs& upd);
 psgd_status check_plan(psgd_plan* plan, void* stream);
 psgd_status read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t* n_written);
 psgd_status resident_check_device(psgd_plan* plan);

@@ -39,10 +39,12 @@ namespace psgd {
 // of different column chunks / workers go to separate slices of the workspace.
 
 // ADD = false: one more subspace iteration on an update that already sits in e (nothing is added, e is not written)
-template <int R, int V, int NV, bool ADD>
-__device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, const float* __restrict__ g,
+// GBF: the gradient is stored as bf16 (M = g + e is an fp32 quantity either way)
+template <int R, int V, int NV, bool ADD, bool GBF>
+__device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, const void* __restrict__ g,
                                               float* __restrict__ e, const float* __restrict__ q,
                                               float* __restrict__ ppart) {
+    constexpr unsigned GS = GBF ? 2u : 4u;   // bytes per gradient element
     // rows per step: all their loads are in flight together; RS * R results fit the 64 lanes
     constexpr int RS = (16 / NV) * R <= kWave ? 16 / NV : 8;
     static_assert(RS * R <= kWave, "one lane per (row, rank) result of a step");
@@ -68,11 +70,14 @@ __device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, c
     // out-of-range offset, a row past the strip lies beyond the range by itself; such loads return zero and
     // such stores are dropped, so no access sits behind a branch and the waits count exactly what is outstanding.
     const int64_t strip = d.off + (int64_t)i_begin * d.m;
-    const buf_rsrc gres = make_rsrc(g + strip, ADD ? (int64_t)rn * d.m * 4 : 0);
+    const buf_rsrc gres = make_rsrc(static_cast<const char*>(g) + strip * GS, ADD ? (int64_t)rn * d.m * GS : 0);
     const buf_rsrc eres = make_rsrc(e + strip, (int64_t)rn * d.m * 4);
-    unsigned coff[NV];
+    unsigned coff[NV], goff[NV];
 #pragma unroll
-    for (int v = 0; v < NV; ++v) coff[v] = valid[v] ? (unsigned)col[v] * 4u : kOutOfRange;
+    for (int v = 0; v < NV; ++v) {
+        coff[v] = valid[v] ? (unsigned)col[v] * 4u : kOutOfRange;
+        goff[v] = valid[v] ? (unsigned)col[v] * GS : kOutOfRange;
+    }
     for (int i0 = i_begin; i0 < i_end; i0 += RS) {
         const int rows = min(RS, i_end - i0);
         const unsigned row_off = (unsigned)(i0 - i_begin) * (unsigned)d.m * 4u;
@@ -83,7 +88,7 @@ __device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, c
             for (int i = 0; i < RS; ++i)
 #pragma unroll
                 for (int v = 0; v < NV; ++v)
-                    buf_ldv<V>(gres, coff[v] + row_off + (unsigned)i * (unsigned)d.m * 4u, mv[i][v], true);
+                    buf_ld_grad<V, GBF>(gres, goff[v] + (row_off / 4u + (unsigned)i * (unsigned)d.m) * GS, mv[i][v]);
         } else {
 #pragma unroll
             for (int i = 0; i < RS; ++i)
@@ -133,20 +138,24 @@ __device__ __forceinline__ void ef_right_tile(const Tile& t, const MatDesc& d, c
     }
 }
 
-template <int R, int NV, bool ADD>
+template <int R, int NV, bool ADD, bool GBF>
 __global__ __launch_bounds__(kBlock) void k_ef_right(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
-                                                     const float* __restrict__ grad, float* __restrict__ err,
+                                                     const void* __restrict__ grad, float* __restrict__ err,
                                                      const float* __restrict__ q, float* __restrict__ ws,
                                                      int64_t gstride, int64_t estride) {
     Tile t = tiles[blockIdx.x];
     const MatDesc d = mats[t.mat];
     const int w = blockIdx.y;
-    const float* g = grad + (int64_t)w * gstride;
+    const void* g = static_cast<const char*>(grad) + (int64_t)w * gstride * (GBF ? 2 : 4);
     float* e = err + (int64_t)w * estride;
     t.part += w * d.n_cchunk;   // partial slices: [worker][column chunk]
-    if (d.vec == 4) ef_right_tile<R, 4, NV, ADD>(t, d, g, e, q, ws);
-    else if (d.vec == 2) ef_right_tile<R, 2, NV, ADD>(t, d, g, e, q, ws);
-    else ef_right_tile<R, 1, NV, ADD>(t, d, g, e, q, ws);
+    if constexpr (GBF) {   // row lengths are multiples of 4 (planner)
+        ef_right_tile<R, 4, NV, ADD, true>(t, d, g, e, q, ws);
+    } else {
+        if (d.vec == 4) ef_right_tile<R, 4, NV, ADD, false>(t, d, g, e, q, ws);
+        else if (d.vec == 2) ef_right_tile<R, 2, NV, ADD, false>(t, d, g, e, q, ws);
+        else ef_right_tile<R, 1, NV, ADD, false>(t, d, g, e, q, ws);
+    }
 }
 
 // ---- k_ef_right_mfma: the same on the matrix cores -------------------------------------------------
@@ -661,10 +670,11 @@ __global__ __launch_bounds__(kBlock) void k_q_reduce(const MatDesc* __restrict__
 
 // STREAM (see left_tile): M is read with non-temporal loads and the new error memory written with non-temporal stores;
 // otherwise it is Delta' that is written with non-temporal stores
-template <int R, int V, int NV, bool UPD, bool STREAM>
+// OBF: Delta' is stored as bf16
+template <int R, int V, int NV, bool UPD, bool STREAM, bool OBF>
 __device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, float* __restrict__ e,
                                             const float* __restrict__ p, const float* __restrict__ q,
-                                            float* __restrict__ out, bool write_out, const UpdateArgs& upd) {
+                                            void* __restrict__ out, bool write_out, const UpdateArgs& upd) {
     constexpr int RU = UPD ? 4 : 8;   // rows whose loads are in flight together (momentum and parameters ride along)
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -736,8 +746,7 @@ __device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, flo
                                     stv<V>(upd.param + row + col[v], pa[u][v]);
                                 } else {
                                     // a set that fits the memory-side cache: Delta' goes around it, M and e' stay
-                                    if constexpr (STREAM) stv<V>(out + row + col[v], dl);
-                                    else stv_stream<V>(out + row + col[v], dl);
+                                    st_out<V, OBF, !STREAM>(out, row + col[v], dl);
                                 }
                             }
                         }
@@ -747,16 +756,19 @@ __device__ __forceinline__ void decomp_tile(const Tile& t, const MatDesc& d, flo
     }
 }
 
-template <int R, int NV, bool UPD, bool STREAM>
+// The slices of the vector region are handled here when gradients and output are fp32 (`grad`, `outv` typed
+// accordingly); with bf16 data a kernel of its own does them and vec_here is 0.
+template <int R, int NV, bool UPD, bool STREAM, bool OBF>
 __global__ __launch_bounds__(kBlock) void k_decomp(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                    float* __restrict__ err, const float* __restrict__ p,
                                                    const float* __restrict__ q, const float* __restrict__ grad,
-                                                   float* __restrict__ out, int workers, int64_t gstride,
-                                                   int64_t estride, int64_t n_mat_elems, UpdateArgs upd) {
+                                                   void* __restrict__ outv, int workers, int64_t gstride,
+                                                   int64_t estride, int64_t n_mat_elems, UpdateArgs upd, int vec_here) {
     const Tile t = tiles[blockIdx.x];
     const int w = blockIdx.y;
     if (t.mat < 0) {
-        if (w != 0) return;
+        if (w != 0 || !vec_here) return;
+        float* out = static_cast<float*>(outv);
         const float inv_w = 1.0f / (float)workers;
         for (int64_t idx = t.elem0 + threadIdx.x; idx < t.elem0 + t.nelem; idx += kBlock) {
             float s = 0.f;
@@ -775,9 +787,13 @@ __global__ __launch_bounds__(kBlock) void k_decomp(const MatDesc* __restrict__ m
     }
     const MatDesc d = mats[t.mat];
     float* e = err + (int64_t)w * estride;
-    if (d.vec == 4) decomp_tile<R, 4, NV, UPD, STREAM>(t, d, e, p, q, out, w == 0, upd);
-    else if (d.vec == 2) decomp_tile<R, 2, NV, UPD, STREAM>(t, d, e, p, q, out, w == 0, upd);
-    else decomp_tile<R, 1, NV, UPD, STREAM>(t, d, e, p, q, out, w == 0, upd);
+    if constexpr (OBF) {   // row lengths are multiples of 4 (planner)
+        decomp_tile<R, 4, NV, UPD, STREAM, true>(t, d, e, p, q, outv, w == 0, upd);
+    } else {
+        if (d.vec == 4) decomp_tile<R, 4, NV, UPD, STREAM, false>(t, d, e, p, q, outv, w == 0, upd);
+        else if (d.vec == 2) decomp_tile<R, 2, NV, UPD, STREAM, false>(t, d, e, p, q, outv, w == 0, upd);
+        else decomp_tile<R, 1, NV, UPD, STREAM, false>(t, d, e, p, q, outv, w == 0, upd);
+    }
 }
 
 // ---- host side ------------------------------------------------------------------------------------
@@ -927,18 +943,21 @@ psgd_status check_plan(psgd_plan* plan, void* stream) {
 }
 
 template <int R>
-static void launch_ef_right(psgd_plan* plan, const float* grad, float* err, const float* q, float* ws,
+static void launch_ef_right(psgd_plan* plan, const void* grad, float* err, const float* q, float* ws,
                             hipStream_t s, bool add) {
     dim3 grid((unsigned)plan->tiles1.size(), (unsigned)plan->workers);
-#define PSGD_LAUNCH_RIGHT(NVV, ADDV)                                                                                     \
-    hipLaunchKernelGGL((k_ef_right<R, NVV, ADDV>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles1, grad, err, \
-                       q, ws, plan->sizes.grad_stride, plan->sizes.err_stride)
-    if (add) {
-        if (plan->tuning.k1_nv == 1) PSGD_LAUNCH_RIGHT(1, true);
-        else PSGD_LAUNCH_RIGHT(2, true);
+#define PSGD_LAUNCH_RIGHT(NVV, ADDV, GBFV)                                                                             \
+    hipLaunchKernelGGL((k_ef_right<R, NVV, ADDV, GBFV>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles1,   \
+                       grad, err, q, ws, plan->sizes.grad_stride, plan->sizes.err_stride)
+    if (!add) {   // the gradient is not read
+        if (plan->tuning.k1_nv == 1) PSGD_LAUNCH_RIGHT(1, false, false);
+        else PSGD_LAUNCH_RIGHT(2, false, false);
+    } else if (plan->grad_dtype == PSGD_BF16) {
+        if (plan->tuning.k1_nv == 1) PSGD_LAUNCH_RIGHT(1, true, true);
+        else PSGD_LAUNCH_RIGHT(2, true, true);
     } else {
-        if (plan->tuning.k1_nv == 1) PSGD_LAUNCH_RIGHT(1, false);
-        else PSGD_LAUNCH_RIGHT(2, false);
+        if (plan->tuning.k1_nv == 1) PSGD_LAUNCH_RIGHT(1, true, false);
+        else PSGD_LAUNCH_RIGHT(2, true, false);
     }
 #undef PSGD_LAUNCH_RIGHT
 }
@@ -960,21 +979,26 @@ static void launch_left(psgd_plan* plan, const float* err, const float* p, float
 }
 
 template <int R>
-static void launch_decomp(psgd_plan* plan, float* err, const float* p, const float* q, const float* grad, float* out,
+static void launch_decomp(psgd_plan* plan, float* err, const float* p, const float* q, const void* grad, void* out,
                           hipStream_t s, const UpdateArgs& upd) {
     dim3 grid((unsigned)plan->tiles4.size(), (unsigned)plan->workers);
-#define PSGD_LAUNCH_DECOMP(NVV, UPDV, STREAMV)                                                                         \
-    hipLaunchKernelGGL((k_decomp<R, NVV, UPDV, STREAMV>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles4,  \
-                       err, p, q, grad, out, plan->workers, plan->sizes.grad_stride, plan->sizes.err_stride,           \
-                       plan->sizes.n_mat_elems, upd)
-#define PSGD_LAUNCH_DECOMP_NV(UPDV, STREAMV)                          \
-    do {                                                              \
-        if (plan->tuning.k4_nv == 1) PSGD_LAUNCH_DECOMP(1, UPDV, STREAMV); \
-        else PSGD_LAUNCH_DECOMP(2, UPDV, STREAMV);                    \
+    // bf16 gradients or output: the vector region has a kernel of its own
+    const int vec_here = plan->grad_dtype == PSGD_F32 && plan->out_dtype == PSGD_F32 ? 1 : 0;
+#define PSGD_LAUNCH_DECOMP(NVV, UPDV, STREAMV, OBFV)                                                                    \
+    hipLaunchKernelGGL((k_decomp<R, NVV, UPDV, STREAMV, OBFV>), grid, dim3(kBlock), 0, s, plan->dev.mats,               \
+                       plan->dev.tiles4, err, p, q, static_cast<const float*>(grad), out, plan->workers,                \
+                       plan->sizes.grad_stride, plan->sizes.err_stride, plan->sizes.n_mat_elems, upd, vec_here)
+#define PSGD_LAUNCH_DECOMP_NV(UPDV, STREAMV)                                     \
+    do {                                                                         \
+        if (plan->tuning.k4_nv == 1) PSGD_LAUNCH_DECOMP(1, UPDV, STREAMV, false); \
+        else PSGD_LAUNCH_DECOMP(2, UPDV, STREAMV, false);                        \
     } while (0)
-    if (upd.mom) {
+    if (upd.mom) {   // Delta' is not stored
         if (plan->stream_hints) PSGD_LAUNCH_DECOMP_NV(true, true);
         else PSGD_LAUNCH_DECOMP_NV(true, false);
+    } else if (plan->out_dtype == PSGD_BF16) {   // one column vector per lane (planner)
+        if (plan->stream_hints) PSGD_LAUNCH_DECOMP(1, false, true, true);
+        else PSGD_LAUNCH_DECOMP(1, false, false, true);
     } else {
         if (plan->stream_hints) PSGD_LAUNCH_DECOMP_NV(false, true);
         else PSGD_LAUNCH_DECOMP_NV(false, false);
@@ -997,7 +1021,6 @@ static void launch_decomp(psgd_plan* plan, float* err, const float* p, const flo
     }
 
 static psgd_status check_ready(psgd_plan* plan) {
-    if (!plan->hr && (plan->grad_dtype != PSGD_F32 || plan->out_dtype != PSGD_F32)) return PSGD_EUNSUPPORTED;
     if (!plan->uploaded) {
         psgd_status st = upload_tables(plan);
         if (st != PSGD_OK) return st;
@@ -1013,13 +1036,13 @@ psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float
     if (!add && plan->k1_on_mfma) return PSGD_EUNSUPPORTED;   // the experimental matrix-core K1 always adds
     hipStream_t s = static_cast<hipStream_t>(stream);
     float* ws = static_cast<float*>(workspace);
-    const float* g = static_cast<const float*>(grad);
+    const void* g = grad;
     if (plan->mats.empty()) return PSGD_OK;
 
     PSGD_MARK(0);
     if (plan->k1_on_mfma) {
         hipLaunchKernelGGL(k_ef_right_mfma, dim3((unsigned)plan->tiles1.size(), (unsigned)plan->workers), dim3(kBlock), 0, s,
-                           plan->dev.mats, plan->dev.tiles1, g, err, q, ws, plan->sizes.grad_stride,
+                           plan->dev.mats, plan->dev.tiles1, static_cast<const float*>(g), err, q, ws, plan->sizes.grad_stride,
                            plan->sizes.err_stride);
     } else {
         PSGD_RANK_SWITCH(launch_ef_right, plan, g, err, q, ws, s, add);
@@ -1078,8 +1101,12 @@ psgd_status launch_decompress(psgd_plan* plan, const float* p, const float* q, f
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (plan->tiles4.empty()) return PSGD_OK;
     PSGD_MARK(5);
-    PSGD_RANK_SWITCH(launch_decomp, plan, err, p, q, static_cast<const float*>(grad), static_cast<float*>(out), s, upd);
+    PSGD_RANK_SWITCH(launch_decomp, plan, err, p, q, grad, out, s, upd);
     PSGD_HIP(hipGetLastError(), "launch k_decomp");
+    if (plan->grad_dtype != PSGD_F32 || plan->out_dtype != PSGD_F32) {
+        psgd_status vs = launch_vector_mean(plan, grad, out, stream, upd);
+        if (vs != PSGD_OK) return vs;
+    }
     PSGD_MARK(6);
     return finish_profiled_step(plan);
 }

@@ -33,12 +33,34 @@ static void col_chunk_range(int64_t nvec, int64_t nchunk, int64_t c, int32_t* ve
     *cnt = (int32_t)(v1 - v0);
 }
 
-static void streaming_tiles(const psgd_plan* plan, int64_t rows_per_tile, int64_t nv, bool by_col_part,
+// Rows per workgroup tile of the three sweeps when the tuning leaves them to the planner (0), from sweeps on the
+// three kinds of sets.  First sweep: a tile of about 8192 elements per column vector a lane owns (16 rows of
+// 4-wide vectors, 32 of 2-wide, 64 of scalars).  Second sweep: 128 rows, but 1024 for matrices that are both tall
+// and wide (>= 2048 each way), where fewer partial Q pay more than more workgroups.  Third sweep: 16 rows.  A small
+// set (under 16 M matrix elements over all workers: each sweep lasts a few tens of microseconds) takes tiles twice
+// as tall in the first and third sweep: fewer, longer-lived workgroups.
+static bool small_set(const psgd_plan* plan) {
+    return (int64_t)plan->workers * plan->sizes.n_mat_elems < (int64_t(16) << 20);
+}
+static int64_t rows_first_sweep(const psgd_plan* plan, const MatDesc& d, int64_t forced) {
+    return forced > 0 ? forced : (small_set(plan) ? 2 : 1) * (64 / d.vec);
+}
+static int64_t rows_second_sweep(const MatDesc& d, int64_t forced) {
+    return forced > 0 ? forced : (d.n >= 2048 && d.m >= 2048 ? 1024 : 128);
+}
+static int64_t rows_third_sweep(const psgd_plan* plan, int64_t forced) {
+    return forced > 0 ? forced : (small_set(plan) ? 32 : 16);
+}
+
+// sweep: 1, 2, 3 (rows per tile by the rules above when rows_forced is 0)
+static void streaming_tiles(const psgd_plan* plan, int sweep, int64_t rows_forced, int64_t nv, bool by_col_part,
                             std::vector<Tile>* out, std::vector<int32_t>* n_rblock,
                             std::vector<int32_t>* n_cchunk) {
     out->clear();
     for (size_t i = 0; i < plan->mats.size(); ++i) {
         const MatDesc& d = plan->mats[i];
+        const int64_t rows_per_tile = sweep == 1 ? rows_first_sweep(plan, d, rows_forced)
+                                      : (sweep == 2 ? rows_second_sweep(d, rows_forced) : rows_third_sweep(plan, rows_forced));
         const int64_t nvec = d.m / d.vec;
         const int64_t ncc = col_chunks(nvec, nv);
         const int64_t nrb = ceil_div(d.n, rows_per_tile);
@@ -202,9 +224,13 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
 }
 
 psgd_status build_tables(psgd_plan* plan) {
-    if (plan->hr) return build_hr_tables(plan);
     const Tuning& tu = plan->tuning;
-    if (tu.k1_rows < 1 || tu.k3_rows < 1 || tu.k4_rows < 1 || tu.k1_nv < 1 ||
+    // ranks above 8 run on the matrix-core kernels; bf16 data at the lower ranks on either (bf16_valu)
+    const bool bf16 = plan->grad_dtype != PSGD_F32 || plan->out_dtype != PSGD_F32;
+    plan->hr = plan->rank > kValuMaxRank || (bf16 && !tu.bf16_valu);
+    if (plan->hr) return build_hr_tables(plan);
+    if (plan->out_dtype != PSGD_F32 && tu.k4_nv != 1) return PSGD_EINVAL;   // bf16 output: one column vector per lane
+    if (tu.k1_rows < 0 || tu.k3_rows < 0 || tu.k4_rows < 0 || tu.k1_nv < 1 ||
         tu.k1_nv > kMaxVecPerLaneK1 || tu.k3_nv < 1 || tu.k3_nv > kMaxVecPerLaneK3 || tu.k4_nv < 1 ||
         tu.k4_nv > kMaxVecPerLaneK3 || tu.q_reduce_elems < 1 || tu.res_rows < 0 || tu.res_rows > kResRows ||
         tu.stream_hints < -1 || tu.stream_hints > 1 || tu.xcd_order < 0)
@@ -213,17 +239,18 @@ psgd_status build_tables(psgd_plan* plan) {
     // k_ef_right and k_left address the rows of a wavefront's strip (a quarter of the tile's rows) with 31-bit
     // byte offsets
     for (const MatDesc& d : plan->mats)
-        if (ceil_div(std::max(tu.k1_rows, tu.k3_rows), kWavesPerBlock) * d.m * 4 >= (int64_t(1) << 31))
+        if (ceil_div(std::max(rows_first_sweep(plan, d, tu.k1_rows), rows_second_sweep(d, tu.k3_rows)), kWavesPerBlock) * d.m * 4 >=
+            (int64_t(1) << 31))
             return PSGD_EUNSUPPORTED;
     std::vector<int32_t> nrb(nm, 0), ncc(nm, 0);
     // P = M Q: matrix-core tiling (16-row steps of super-rows x kMfmaCols columns per wavefront) when every
     // matrix fits pack * rank <= 16, else the vector-ALU tiling
-    plan->k1_on_mfma = tu.k1_mfma != 0;
+    plan->k1_on_mfma = tu.k1_mfma != 0 && plan->grad_dtype == PSGD_F32;
     for (const MatDesc& d : plan->mats)
         if (d.pack * d.r > 16) plan->k1_on_mfma = false;
     if (plan->k1_on_mfma) {
         plan->tiles1.clear();
-        const int64_t rows_per_tile = round_up(std::max<int64_t>(tu.k1_rows, 16), 16);   // super-rows per workgroup
+        const int64_t rows_per_tile = round_up(std::max<int64_t>(tu.k1_rows > 0 ? tu.k1_rows : 32, 16), 16);   // super-rows per workgroup
         for (size_t i = 0; i < nm; ++i) {
             const MatDesc& d = plan->mats[i];
             const int64_t sm = (int64_t)d.pack * d.m, sn = ceil_div(d.n, d.pack);
@@ -242,10 +269,10 @@ psgd_status build_tables(psgd_plan* plan) {
                 }
         }
     } else {
-        streaming_tiles(plan, tu.k1_rows, tu.k1_nv, true, &plan->tiles1, nullptr, &ncc);
+        streaming_tiles(plan, 1, tu.k1_rows, tu.k1_nv, true, &plan->tiles1, nullptr, &ncc);
     }
-    streaming_tiles(plan, tu.k3_rows, tu.k3_nv, false, &plan->tiles3, &nrb, nullptr);
-    streaming_tiles(plan, tu.k4_rows, tu.k4_nv, false, &plan->tiles4, nullptr, nullptr);
+    streaming_tiles(plan, 2, tu.k3_rows, tu.k3_nv, false, &plan->tiles3, &nrb, nullptr);
+    streaming_tiles(plan, 3, tu.k4_rows, tu.k4_nv, false, &plan->tiles4, nullptr, nullptr);
 
     // vector region: slices appended to the decompress work-list
     const int64_t L = plan->sizes.n_vec_elems;
@@ -508,8 +535,8 @@ psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_
         if (shapes[t].rows > INT32_MAX || shapes[t].cols > INT32_MAX) return PSGD_EUNSUPPORTED;
     }
     if (rank > PSGD_MAX_RANK) return PSGD_EUNSUPPORTED;
-    // ranks above 8 and bf16 data run on the matrix-core kernels, which need row lengths that are multiples of 4
-    // and short enough for 32-bit byte offsets within a tile of rows
+    // the matrix-core kernels (ranks above 8) and the bf16 forms of all kernels need row lengths that are multiples
+    // of 4 and short enough for 32-bit byte offsets within a tile of rows
     const bool needs_hr = rank > kValuMaxRank || grad_dtype != PSGD_F32 || out_dtype != PSGD_F32;
     if (needs_hr)
         for (int32_t t = 0; t < n_tensors; ++t)
@@ -522,7 +549,7 @@ psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_
     try {
         plan->rank = rank;
         plan->workers = workers;
-        plan->hr = needs_hr;
+        plan->hr = rank > kValuMaxRank;   // settled in build_tables
         plan->hr_nt = rank <= 16 ? 1 : (rank <= 32 ? 2 : 4);
         plan->grad_dtype = grad_dtype;
         plan->out_dtype = out_dtype;
@@ -642,6 +669,7 @@ psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value
     else if (!strcmp(key, "hr_k1_cols")) tu.hr_k1_cols = value;
     else if (!strcmp(key, "resident")) tu.resident = value;
     else if (!strcmp(key, "stream_hints")) tu.stream_hints = value;
+    else if (!strcmp(key, "bf16_valu")) tu.bf16_valu = value;
     else if (!strcmp(key, "res_rows")) tu.res_rows = value;
     else if (!strcmp(key, "res_trace")) tu.res_trace = value;
     else return PSGD_EINVAL;

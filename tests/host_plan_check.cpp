@@ -370,6 +370,7 @@ int main() {
         {{512, 4608}, {10, 512}, {128, 64}, {9610, 1}},
         {{2600, 650}, {3328, 650}, {33280, 650}, {5000, 3}},
         {{1, 2}, {2, 1}},
+        {{2048, 2048}, {2100, 2052}, {64, 27}, {3000, 1}},   // tall and wide: the taller row blocks of the second sweep
         {{37, 91}, {7, 1}, {50, 650}, {130, 1028}, {5, 3}, {300, 2}, {1, 40}, {1031, 1}, {3, 4700}, {257, 260},
          {512, 36}, {64, 27}},
         {{64, 27}, {64, 576}, {64, 576}, {64, 576}, {64, 576}, {128, 576}, {128, 1152}, {128, 1152}, {128, 1152},

@@ -184,13 +184,28 @@ TRANSFORMER_SMALL = [(1000, 256), (256,), (256, 256), (256, 256), (1024, 256), (
                                                   (64, 1, False, False), (16, 1, True, True), (32, 1, True, False),
                                                   (4, 2, True, True), (2, 1, False, True)])
 def test_matrix_core_path(rank, workers, gbf, obf):
-    """Ranks above 8 and bf16 gradients / output run on the matrix-core kernels: a small
-    transformer-shaped set (ragged row blocks and column chunks, a matrix smaller than the rank,
-    vectors), planted rank 64 with a 1/k spectrum."""
+    """Ranks above 8 run on the matrix-core kernels, with fp32 or bf16 gradients / output; so do bf16 data at
+    rank <= 8 when asked to (`bf16_valu` = 0): a small transformer-shaped set (ragged row blocks and column
+    chunks, a matrix smaller than the rank, vectors), planted rank 64 with a 1/k spectrum."""
     _need_gpu()
     from paper_1905_13727_amd import workloads as WL
     wl = WL.Workload("tr-small", list(TRANSFORMER_SMALL), 64, 1.0 / np.arange(1, 65), 0.001)
-    _run(wl, rank=rank, workers=workers, steps=3, seed=60 + rank, expect_resident=False, grad_bf16=gbf, out_bf16=obf)
+    _run(wl, rank=rank, workers=workers, steps=3, seed=60 + rank, expect_resident=False, grad_bf16=gbf, out_bf16=obf,
+         tuning={"bf16_valu": 0})
+
+
+@pytest.mark.parametrize("rank,workers,gbf,obf", [(4, 2, True, True), (2, 1, False, True), (8, 1, True, False),
+                                                  (3, 3, True, True)])
+def test_streaming_path_bf16(rank, workers, gbf, obf):
+    """bf16 gradients and / or output at rank <= 8 on the streaming kernels (the default for them): the gradient is
+    widened as it is read, Delta' is rounded to nearest even as it is stored, the state stays fp32.  Also with the
+    large-set cache policy forced."""
+    _need_gpu()
+    from paper_1905_13727_amd import workloads as WL
+    wl = WL.Workload("tr-small", list(TRANSFORMER_SMALL), 64, 1.0 / np.arange(1, 65), 0.001)
+    _run(wl, rank=rank, workers=workers, steps=3, seed=80 + rank, expect_resident=False, grad_bf16=gbf, out_bf16=obf)
+    _run(wl, rank=rank, workers=workers, steps=2, seed=90 + rank, expect_resident=False, grad_bf16=gbf, out_bf16=obf,
+         tuning={"stream_hints": 1})
 
 
 @pytest.mark.parametrize("rows,cols", [(64, 64), (256, 192), (128, 4096)])
@@ -470,7 +485,8 @@ def test_fused_update_matrix_cores():
     from paper_1905_13727_amd import workloads as WL
     wl = WL.Workload("tr-small", list(TRANSFORMER_SMALL), 64, 1.0 / np.arange(1, 65), 0.001)
     _run_update(wl, rank=16, workers=2, steps=2, seed=8, expect_resident=False)
-    _run_update(wl, rank=4, workers=1, steps=2, seed=9, grad_bf16=True, expect_resident=False)
+    _run_update(wl, rank=4, workers=1, steps=2, seed=9, grad_bf16=True, expect_resident=False, tuning={"bf16_valu": 0})
+    _run_update(wl, rank=4, workers=1, steps=2, seed=9, grad_bf16=True, expect_resident=False)   # streaming kernels
 
 
 # ---- the 24-layer transformer-shaped set at full size, sampled tensors ---------------------------------
@@ -618,4 +634,5 @@ def test_iterations_matrix_cores():
     from paper_1905_13727_amd import workloads as WL
     wl = WL.Workload("tr-small", list(TRANSFORMER_SMALL), 64, 1.0 / np.arange(1, 65), 0.001)
     _run_iterations(wl, rank=16, workers=1, iterations=3, seed=13)
-    _run_iterations(wl, rank=4, workers=2, iterations=2, seed=14, grad_bf16=True)
+    _run_iterations(wl, rank=4, workers=2, iterations=2, seed=14, grad_bf16=True, tuning={"bf16_valu": 0})
+    _run_iterations(wl, rank=4, workers=2, iterations=2, seed=14, grad_bf16=True)   # streaming kernels
