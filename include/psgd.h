@@ -97,7 +97,7 @@ typedef struct {
  *   out_dtype          dtype of `out`
  * Errors: PSGD_EINVAL for null pointers, n_tensors < 1, rank < 1, workers < 1,
  * a non-positive dimension; PSGD_EUNSUPPORTED for rank > PSGD_MAX_RANK, or,
- * when rank > 8 or a dtype is PSGD_BF16 (the matrix-core kernels), a matrix whose
+ * when rank > 8 (the matrix-core kernels) or a dtype is PSGD_BF16, a matrix whose
  * column count is not a multiple of 4 or exceeds 2^20, or with more than 2^22 rows;
  * on the other kernels for a matrix with more than about 64 M columns (a strip of 8
  * rows is addressed with 31-bit byte offsets); PSGD_ENOMEM. */
