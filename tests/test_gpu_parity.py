@@ -141,6 +141,17 @@ def test_tall_panels(rank, workers):
             assert np.abs(r["err"][0][t]).max() == 0 and np.abs(r["out"][t]).max() == 0
 
 
+@pytest.mark.parametrize("rank,workers,bf16", [(3, 2, False), (4, 1, True)])
+def test_tall_and_wide_matrices(rank, workers, bf16):
+    """Matrices of at least 2048 x 2048 get 1024-row blocks in the second sweep and 16-row tiles in the first and
+    third (the planner's choice for them): one exactly at the limit, one ragged in both directions, next to a
+    small one; fp32 with two workers, and bf16 data."""
+    _need_gpu()
+    shapes = [(2048, 2048), (2100, 2052), (64, 576), (300,)]
+    _run(_workload(shapes), rank=rank, workers=workers, steps=2, seed=50 + rank, expect_resident=False,
+         grad_bf16=bf16, out_bf16=bf16)
+
+
 def _steps(env_name, default):
     """Step count of the long parity runs.  The defaults keep the suite to a few minutes (the fp64 oracle is the
     slow side: 16 workers cost 2.5 s per step); PSGD_PARITY_STEPS_W16 / PSGD_PARITY_STEPS_LSTM change them."""
