@@ -177,7 +177,11 @@ PSGD_API psgd_status psgd_decompress(psgd_plan* plan, const float* p, const floa
  * run.  Otherwise psgd_step is exactly the two calls in sequence.  Resident
  * mode keeps barrier words in plan-owned device memory: do not run two steps
  * of the same plan concurrently on different streams.
- * psgd_plan_check (below) reports whether a resident step ever timed out. */
+ * psgd_plan_check (below) reports whether a resident step ever timed out.
+ * The plan's first GPU call (any entry point) uploads its tables (one device
+ * allocation and copy).  After that this call, psgd_compress and psgd_decompress
+ * only launch kernels on hip_stream: no allocation, no memset, no host
+ * synchronisation, so they may be captured into a HIP graph and replayed. */
 PSGD_API psgd_status psgd_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p,
                       void* out, void* workspace, void* hip_stream);
 

@@ -292,6 +292,74 @@ def test_streaming_hints(rank, workers):
     _run(_workload(TRANSFORMER_SMALL), rank=16, workers=1, steps=2, seed=75, tuning={"stream_hints": 1})
 
 
+@pytest.mark.parametrize("mode", ["resident", "streaming", "streaming_w3_bf16", "matrix_cores"])
+def test_step_replayed_from_a_hip_graph(mode):
+    """psgd_step makes no allocation, no memset and no host synchronisation once the plan's tables are on the device,
+    so it can be captured into a HIP graph.  The graph is replayed several times (new gradients copied into the
+    captured buffer, other GPU work and synchronisations in between); every replay must leave exactly the bits the
+    same steps leave when launched directly."""
+    _need_gpu()
+    from paper_1905_13727_amd import binding as B
+    dev = torch.device("cuda:0")
+    shapes = [(37, 91), (7,), (64, 576), (130, 1028), (5, 3), (300, 4), (512, 36)]
+    rank, workers, gdt, tune = 2, 1, torch.float32, {}
+    if mode == "streaming":
+        tune = {"resident": 0}
+    elif mode == "streaming_w3_bf16":
+        shapes = [(40, 92), (7,), (64, 576), (130, 1028), (300, 4), (2600, 64)]
+        rank, workers, gdt = 4, 3, torch.bfloat16
+    elif mode == "matrix_cores":
+        shapes = [(40, 92), (7,), (64, 576), (130, 1028), (300, 4)]
+        rank = 16
+    dt = B.PSGD_BF16 if gdt == torch.bfloat16 else B.PSGD_F32
+    plan = B.Plan(shapes, rank, workers, dt, dt)
+    for k, v in tune.items():
+        plan.set_tuning(k, v)
+    s = plan.sizes
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(11)
+    grads = [(torch.randn(workers * s.grad_stride, generator=gen) * 0.01).to(gdt).to(dev) for _ in range(4)]
+    q0 = torch.randn(s.q_elems, generator=gen).to(dev)
+
+    def fresh_state():
+        return dict(err=torch.zeros(workers * s.err_stride, device=dev), q=q0.clone(),
+                    p=torch.zeros(s.p_elems, device=dev), out=torch.zeros(s.out_elems, device=dev, dtype=gdt),
+                    ws=torch.zeros(s.workspace_bytes // 4 + 64, device=dev))
+
+    def snapshot(st):
+        torch.cuda.synchronize()
+        return [st[k].clone() for k in ("err", "q", "p", "out")]
+
+    g_in = torch.zeros_like(grads[0])
+    # launched directly (the first call also uploads the plan's tables, which a capture could not)
+    st = fresh_state()
+    want = []
+    for t in range(4):
+        g_in.copy_(grads[t])
+        plan.step(g_in, st["err"], st["q"], st["p"], st["out"], st["ws"], torch.cuda.current_stream().cuda_stream)
+        want.append(snapshot(st))
+    assert plan.check(torch.cuda.current_stream().cuda_stream) == (mode == "resident")
+    # captured once, replayed four times
+    st = fresh_state()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.step(g_in, st["err"], st["q"], st["p"], st["out"], st["ws"], torch.cuda.current_stream().cuda_stream)
+    for k in ("err", "p", "out", "ws"):
+        st[k].zero_()
+    st["q"].copy_(q0)
+    for t in range(4):
+        g_in.copy_(grads[t])
+        graph.replay()
+        noise = (torch.randn(1 << 20, device=dev) * 2).sum()   # unrelated work between the replays
+        got = snapshot(st)
+        assert torch.isfinite(noise)
+        for name, a, b in zip(("err", "q", "p", "out"), got, want[t]):
+            assert torch.equal(a, b), (mode, t, name)
+    plan.check(torch.cuda.current_stream().cuda_stream)
+    plan.destroy()
+
+
 def test_between_compress_and_decompress_err_holds_m():
     _need_gpu()
     from paper_1905_13727_amd import workloads as WL
