@@ -137,6 +137,7 @@ PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, in
  *   stream_hints  cache policy of the second and third sweep: -1 (default) by the size of M over all
  *                 workers (non-temporal accesses to M and the error memory above 320 MB), 0 never,
  *                 1 always
+ *   gram_fused    tall panels: 1 (default) Gram matrices and factorisation in one launch, 0 in two
  *   bf16_valu     bf16 gradients / output at rank <= 8: 1 (default) streaming kernels, 0 matrix-core kernels
  *   q_reduce_elems  accepted, unused */
 PSGD_API psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value);
@@ -175,9 +176,10 @@ PSGD_API psgd_status psgd_decompress(psgd_plan* plan, const float* p, const floa
  * once.  Its sums run in another (fixed) order than the split calls, so the
  * two agree to rounding, not bit for bit; each is reproducible from run to
  * run.  Otherwise psgd_step is exactly the two calls in sequence.  Resident
- * mode keeps barrier words in plan-owned device memory: do not run two steps
- * of the same plan concurrently on different streams.
- * psgd_plan_check (below) reports whether a resident step ever timed out.
+ * mode, and the one-launch factorisation of tall panels (tuning key
+ * gram_fused), keep hand-over words in plan-owned device memory: do not run
+ * two calls of the same plan concurrently on different streams.
+ * psgd_plan_check (below) reports whether a wait inside them ever timed out.
  * The plan's first GPU call (any entry point) uploads its tables (one device
  * allocation and copy).  After that this call, psgd_compress and psgd_decompress
  * only launch kernels on hip_stream: no allocation, no memset, no host
@@ -231,9 +233,10 @@ PSGD_API psgd_status psgd_plan_kernel_times(psgd_plan* plan, double* ms_sum, int
  * kernel trace (prefix of the symbol); NULL if out of range. */
 PSGD_API const char* psgd_kernel_name(int32_t index);
 
-/* Waits for hip_stream, then returns PSGD_EHIP if a resident-mode kernel of this
- * plan gave up waiting at a grid barrier since the last check (its outputs are
- * then invalid; the plan's barrier words are reset), PSGD_OK otherwise.
+/* Waits for hip_stream, then returns PSGD_EHIP if a kernel of this plan whose
+ * workgroups wait for each other (resident mode; the one-launch factorisation
+ * of tall panels) gave up waiting since the last check (its outputs are then
+ * invalid; the plan's hand-over words are reset), PSGD_OK otherwise.
  * is_resident (may be NULL) receives 1 if psgd_step runs in resident mode. */
 PSGD_API psgd_status psgd_plan_check(psgd_plan* plan, void* hip_stream, int32_t* is_resident);
 

@@ -344,6 +344,98 @@ __device__ __forceinline__ unsigned add_dev(unsigned* p, unsigned v) {
     return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// ---- mailbox: values that cross workgroups inside one kernel ---------------------------------------------
+// A slot holds {value, tag} in 64 bits.  The producer writes the float together with the step's epoch in one
+// 8-byte device-scope store, the consumer polls the slot with device-scope loads until the tag equals the
+// epoch: the value is its own arrival flag, and no cache-wide write-back or invalidate is involved.  Every
+// wait is bounded: after a limit of rounds the waiter raises an error word and goes on, so a kernel always ends.
+typedef unsigned long long slot_t;
+constexpr unsigned kSpinLimit = 1u << 21;
+
+__device__ __forceinline__ void post(slot_t* slot, float v, unsigned epoch) {
+    const slot_t w = ((slot_t)epoch << 32) | (slot_t)__float_as_uint(v);
+    __hip_atomic_store(slot, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Polling is written as: issue all loads of an attempt back to back (`fetch`, unconditional, so that
+// no branch forces a wait between them; lanes or slots that are not wanted re-read a wanted one),
+// then look at the tags.
+__device__ __forceinline__ slot_t fetch(const slot_t* slot) {
+    return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool arrived(slot_t w, unsigned epoch) { return (unsigned)(w >> 32) == epoch; }
+__device__ __forceinline__ float value_of(slot_t w) { return __uint_as_float((unsigned)(w & 0xffffffffULL)); }
+
+// Wait for a group of slots: every lane polls the slots it needs (`attempt()` returns true when all of
+// them carry this step's tag) until the whole wavefront has them.  For the few wavefronts that reduce.
+// All lanes of the wavefront call it together.
+template <typename F>
+__device__ __forceinline__ void await(F attempt, unsigned* err_word) {
+    unsigned spins = 0;
+    for (;;) {
+        const bool ok = attempt();
+        if (__all(ok)) break;
+        __builtin_amdgcn_s_sleep(2);
+        if (++spins > kSpinLimit) {
+            st_dev(err_word, 1u);
+            break;
+        }
+    }
+}
+
+// The same for the many wavefronts that wait for a published result: first one lane probes a single
+// slot of the group (`probe`, the same address for the whole wavefront) at a relaxed pace, so that
+// two thousand waiting wavefronts put little load on the memory system; once it carries this step's
+// tag the rest is about to land and every lane polls the slots it needs.
+template <typename F>
+__device__ __forceinline__ void await_probed(const slot_t* probe, unsigned epoch, F attempt, unsigned* err_word) {
+    unsigned spins = 0;
+    for (;;) {
+        unsigned tag = epoch;
+        if ((threadIdx.x & (kWave - 1)) == 0)
+            tag = (unsigned)(__hip_atomic_load(probe, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32);
+        if (__builtin_amdgcn_readfirstlane(tag) == epoch) break;
+        __builtin_amdgcn_s_sleep(6);
+        if (++spins > kSpinLimit) {
+            st_dev(err_word, 1u);
+            return;
+        }
+    }
+    await(attempt, err_word);
+}
+
+// One slot, waited for by this lane alone (other lanes of the wavefront may be waiting for theirs).  Gives up after
+// kTakeSpinLimit rounds, or as soon as another waiter has given up (the error word is looked at now and then), so
+// that a broken hand-over ends the kernel quickly instead of timing out slot after slot.
+constexpr unsigned kTakeSpinLimit = 1u << 18;
+__device__ __forceinline__ unsigned take_bits(const slot_t* slot, slot_t first, unsigned epoch, unsigned* err_word) {
+    slot_t w = first;
+    unsigned spins = 0;
+    while (!arrived(w, epoch)) {
+        __builtin_amdgcn_s_sleep(2);
+        w = fetch(slot);
+        ++spins;
+        if ((spins & 255u) == 0u && (spins > kTakeSpinLimit || ld_dev(err_word) != 0u)) {
+            st_dev(err_word, 1u);
+            break;
+        }
+    }
+    return (unsigned)(w & 0xffffffffULL);
+}
+
+// A double travels as two slots (low word, high word), each with the tag.
+__device__ __forceinline__ void post_double(slot_t* pair, double v, unsigned epoch) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    __hip_atomic_store(pair, ((slot_t)epoch << 32) | (b & 0xffffffffULL), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(pair + 1, ((slot_t)epoch << 32) | (b >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double take_double(const slot_t* pair, slot_t first_lo, slot_t first_hi, unsigned epoch,
+                                              unsigned* err_word) {
+    const unsigned lo = take_bits(pair, first_lo, epoch, err_word);
+    const unsigned hi = take_bits(pair + 1, first_hi, epoch, err_word);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
 // Wait until every memory operation this wavefront has issued is complete (loads returned, stores
 // acknowledged), and keep the compiler from moving memory operations across this point.
 __device__ __forceinline__ void wave_mem_done() {

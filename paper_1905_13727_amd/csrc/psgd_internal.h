@@ -110,6 +110,8 @@ struct Tuning {
                                 // memory (and temporal instead of non-temporal stores of Delta'); matrix-core path:
                                 // non-temporal loads of M in sweep 2.
                                 // -1: when M of all workers exceeds kStreamHintBytes; 0: never; 1: always
+    int64_t gram_fused = 1; // tall panels: 1 = Gram matrices and factorisation in one launch when the device holds a matrix's
+                            // row blocks at once; 0 = always the two launches
     int64_t bf16_valu = 1;  // bf16 gradients / output at rank <= 8: 1 = the streaming (vector-ALU) kernels, 0 = the matrix-core kernels
     int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream
     int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height
@@ -131,6 +133,8 @@ struct DeviceTables {
     Tile* hr_tiles3 = nullptr;
     Tile* hr_tiles4 = nullptr;
     int32_t* small_mats = nullptr;
+    unsigned* gram_sync = nullptr;              // k_gram_chol: error word, epoch, finished-workgroup count
+    unsigned long long* gram_mail = nullptr;    // k_gram_chol: the row blocks' Gram matrices as {value, epoch} slots
     MatDesc* res_mats = nullptr;
     RTile* res_tiles = nullptr;
     unsigned* res_sync = nullptr;  // error word, epoch, finished-workgroup count
@@ -164,6 +168,7 @@ struct psgd_plan {
     std::vector<psgd::Tile> tilesp;         // 64-element slices of the n x r panels (pre-reduction of partial P)
     bool p_pre_reduce = false;              // some matrix has more than kPreReduceParts partial-P slices
     bool stream_hints = false;              // see Tuning::stream_hints
+    bool gram_fused = false;                // tall panels: one launch (k_gram_chol) instead of two (set at upload)
     int32_t max_n = 0;
     int64_t ws_ppart_floats = 0;            // workspace: partial P region (floats)
     int64_t ws_qpart_floats = 0;            // workspace: partial Q region, starts after partial P

@@ -9,8 +9,9 @@
 //                 without the add, one more subspace iteration on a stored M (Appendix G.7)
 //   k_ortho       mean over workers / column chunks, then Gram-Schmidt in LDS, for panels of
 //                 up to 1024 rows                       (Alg. 1 "all reduce mean", "orthogonalize")
-//   k_gram, k_chol_apply   the same orthonormal factor by Cholesky-QR over many workgroups,
-//                 for taller panels                     (Remark "Orthogonalization is a linear operation")
+//   k_gram_chol   the same orthonormal factor by Cholesky-QR over many workgroups, for taller
+//                 panels, in one launch; k_gram, k_chol_apply: the same in two launches
+//                                                       (Remark "Orthogonalization is a linear operation")
 //   k_left        column sums of Q_w = M_w^T P_hat      (Alg. 1 "Q <- M^T P_hat")
 //   k_q_reduce    mean over workers / row blocks        (Alg. 1 second "all reduce mean"); also
 //                 pre-reduces the partial P when there are many
@@ -521,6 +522,165 @@ __global__ __launch_bounds__(kBlock) void k_chol_apply(const MatDesc* __restrict
     }
 }
 
+// ---- k_gram_chol: k_gram and k_chol_apply in one launch ----------------------------------------------------
+//
+// One workgroup per row block (at most kGramRows = kBlock rows, one per thread), as in the pair above, and the same
+// sums in the same order: the results are bit-identical.  The block's Gram matrix goes to a plan-owned mailbox of
+// {value, epoch} slots (two slots per double); the workgroup then collects the Gram matrices of all row blocks
+// of its matrix, factorises the sum and solves for its own rows of P_hat, which never left the registers.  This
+// saves a launch, a drain and refill of the machine, and the second reading of P.  The workgroups of a matrix wait
+// for each other, so they must be co-resident (checked when the tables are uploaded); every wait is bounded.
+template <int R>
+__global__ __launch_bounds__(kBlock) void k_gram_chol(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
+                                                      const float* __restrict__ ws, float* __restrict__ p,
+                                                      slot_t* __restrict__ mail_gram, unsigned* __restrict__ sync,
+                                                      int workers, int pre_reduced) {
+    constexpr int kMaxSlices = 16;
+    constexpr int kAhead = 4;   // slots requested before the first is looked at
+    constexpr int E = kValuMaxRank * kValuMaxRank;
+    __shared__ double red[kWavesPerBlock][E];
+    __shared__ double part[kMaxSlices][E];
+    __shared__ double Rm[kValuMaxRank][kValuMaxRank];
+    __shared__ double rinv[kValuMaxRank];
+    unsigned epoch = 0;
+    if ((threadIdx.x & (kWave - 1)) == 0) epoch = ld_dev(sync + res_sync_epoch());
+    epoch = __builtin_amdgcn_readfirstlane(epoch);
+    unsigned* err_word = sync + res_sync_err();
+    const Tile t = tiles[blockIdx.x];
+    const MatDesc d = mats[t.mat];
+    const int r = d.r, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int64_t nr = (int64_t)d.n * r;
+    const float inv_w = 1.0f / (float)workers;
+    const int nparts = pre_reduced ? 1 : workers * d.n_cchunk;
+    const int i = t.row0 + tid;
+    const bool have = tid < t.nrows;
+
+    float row[R];
+    double g[R][R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        row[k] = 0.f;
+        if (have && k < r) row[k] = sum_parts(ws + d.ppart_off + (int64_t)i * r + k, nparts, nr) * inv_w;
+    }
+#pragma unroll
+    for (int a = 0; a < R; ++a)
+#pragma unroll
+        for (int b = a; b < R; ++b) g[a][b] = (b < r && have) ? (double)row[a] * (double)row[b] : 0.0;
+#pragma unroll
+    for (int a = 0; a < R; ++a)
+#pragma unroll
+        for (int b = a; b < R; ++b)
+            if (b < r) {
+                const double v = wave_sum(g[a][b]);
+                if (lane == 0) red[wave][a * kValuMaxRank + b] = v;
+            }
+    __syncthreads();
+    const int nent = r * r;
+    if (tid < nent) {
+        const int a = tid / r, b = tid % r;
+        double v = 0.0;
+        if (b >= a)
+            for (int wv = 0; wv < kWavesPerBlock; ++wv) v += red[wv][a * kValuMaxRank + b];
+        post_double(mail_gram + 2 * (d.gram_off + (int64_t)t.part * nent + tid), v, epoch);   // upper triangle, zeros below
+    }
+    // sum of all row blocks' matrices: consecutive slices of blocks (one lane per entry and slice), each added in
+    // block order, then the slices in slice order
+    const int per_wave = nent <= 16 ? 4 : (nent <= 32 ? 2 : 1);
+    const int nslices = kWavesPerBlock * per_wave;
+    {
+        const int lanes_per = kWave / per_wave;
+        const int ent = lane % lanes_per, sl = wave * per_wave + lane / lanes_per;
+        if (ent < nent) {
+            const int per = (d.n_gblock + nslices - 1) / nslices;
+            const int b0 = min(d.n_gblock, sl * per), b1 = min(d.n_gblock, b0 + per);
+            const slot_t* src = mail_gram + 2 * (d.gram_off + ent);
+            const int64_t stride = 2 * (int64_t)nent;
+            double v = 0.0;
+            int b = b0;
+            for (; b + kAhead <= b1; b += kAhead) {
+                slot_t lo[kAhead], hi[kAhead];
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    lo[u] = fetch(src + (int64_t)(b + u) * stride);
+                    hi[u] = fetch(src + (int64_t)(b + u) * stride + 1);
+                }
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) v += take_double(src + (int64_t)(b + u) * stride, lo[u], hi[u], epoch, err_word);
+            }
+            for (; b < b1; ++b) {
+                const slot_t* s2 = src + (int64_t)b * stride;
+                v += take_double(s2, fetch(s2), fetch(s2 + 1), epoch, err_word);
+            }
+            part[sl][ent] = v;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double G[R][R];
+#pragma unroll
+        for (int a = 0; a < R; ++a)
+#pragma unroll
+            for (int b = a; b < R; ++b) {
+                double v = 0.0;
+                if (b < r)
+                    for (int sl = 0; sl < nslices; ++sl) v += part[sl][a * r + b];
+                G[a][b] = v;
+            }
+        // Cholesky, row by row of R (upper): R_jj = sqrt(G_jj - sum_k R_kj^2), R_jc = (G_jc - sum_k R_kj R_kc) / R_jj
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            if (j < r) {
+                double piv = G[j][j];
+#pragma unroll
+                for (int k = 0; k < j; ++k) piv -= G[k][j] * G[k][j];
+                const bool dead = piv <= 1e-30;
+                const double rjj = dead ? 0.0 : sqrt(piv);
+                const double rj = dead ? 0.0 : 1.0 / rjj;
+                rinv[j] = rj;
+                G[j][j] = rjj;
+                Rm[j][j] = rjj;
+#pragma unroll
+                for (int c = j + 1; c < R; ++c) {
+                    double v = G[j][c];
+#pragma unroll
+                    for (int k = 0; k < j; ++k) v -= G[k][j] * G[k][c];
+                    v = dead ? 0.0 : v * rj;     // a zero column takes no part in the later ones
+                    G[j][c] = v;
+                    if (c < r) Rm[j][c] = v;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (have) {
+        double ph[R];
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            if (j < r) {
+                double v = (double)row[j];
+#pragma unroll
+                for (int k = 0; k < R; ++k)
+                    if (k < j) v -= ph[k] * Rm[k][j];
+                ph[j] = v * rinv[j];
+            } else {
+                ph[j] = 0.0;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < R; ++j)
+            if (j < r) p[d.p_off + (int64_t)i * r + j] = (float)ph[j];
+    }
+    // the workgroup that finishes last advances the epoch for the next launch
+    __syncthreads();
+    if (tid == 0) {
+        unsigned* done = sync + res_sync_done();
+        if (add_dev(done, 1u) == gridDim.x - 1u) {
+            add_dev(done, 0u - gridDim.x);
+            st_dev(sync + res_sync_epoch(), epoch + 1u);
+        }
+    }
+}
+
 // ---- k_left: Q_w[j,:] = sum_i M[i,j] P_hat[i,:] ---------------------------------------------------
 //
 // A lane owns NV column vectors and keeps their V*R running sums in registers while its
@@ -841,6 +1001,33 @@ void free_tables(psgd_plan* plan) {
     plan->uploaded = false;
 }
 
+// k_gram_chol: the row blocks of a matrix wait for each other.  Workgroups start in index order and a matrix's row
+// blocks are consecutive, so it is enough that the largest matrix's blocks fit the device at once.
+static psgd_status gram_fused_check_device(psgd_plan* plan) {
+    plan->gram_fused = false;
+    if (plan->hr || !plan->tuning.gram_fused || plan->tiles_gram.empty()) return PSGD_OK;
+    int dev = 0, cus = 0, occ = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return PSGD_EHIP;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return PSGD_EHIP;
+    hipError_t e = hipErrorInvalidValue;
+    switch (plan->rank) {
+        case 1: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_gram_chol<1>, kBlock, 0); break;
+        case 2: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_gram_chol<2>, kBlock, 0); break;
+        case 3: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_gram_chol<3>, kBlock, 0); break;
+        case 4: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_gram_chol<4>, kBlock, 0); break;
+        case 5: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_gram_chol<5>, kBlock, 0); break;
+        case 6: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_gram_chol<6>, kBlock, 0); break;
+        case 7: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_gram_chol<7>, kBlock, 0); break;
+        case 8: e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, k_gram_chol<8>, kBlock, 0); break;
+        default: break;
+    }
+    if (e != hipSuccess) return hip_fail(plan, e, "occupancy(k_gram_chol)");
+    int max_blocks = 0;
+    for (const MatDesc& d : plan->mats) max_blocks = std::max(max_blocks, (int)d.n_gblock);
+    plan->gram_fused = (int64_t)cus * occ >= 2 * (int64_t)max_blocks;   // with room to spare
+    return PSGD_OK;
+}
+
 psgd_status upload_tables(psgd_plan* plan) {
     if (plan->uploaded) return PSGD_OK;
     PSGD_HIP(hipGetDevice(&plan->device), "hipGetDevice");
@@ -848,8 +1035,12 @@ psgd_status upload_tables(psgd_plan* plan) {
         psgd_status st = resident_check_device(plan);
         if (st != PSGD_OK) return st;
     }
+    {
+        psgd_status st = gram_fused_check_device(plan);
+        if (st != PSGD_OK) return st;
+    }
     struct Piece { const void* src; size_t bytes; size_t at; };
-    Piece pieces[16] = {
+    Piece pieces[18] = {
         {plan->mats.data(), plan->mats.size() * sizeof(MatDesc), 0},
         {plan->tiles1.data(), plan->tiles1.size() * sizeof(Tile), 0},
         {plan->tiles3.data(), plan->tiles3.size() * sizeof(Tile), 0},
@@ -866,6 +1057,8 @@ psgd_status upload_tables(psgd_plan* plan) {
         {plan->hr_tiles1.data(), plan->hr_tiles1.size() * sizeof(Tile), 0},
         {plan->hr_tiles3.data(), plan->hr_tiles3.size() * sizeof(Tile), 0},
         {plan->hr_tiles4.data(), plan->hr_tiles4.size() * sizeof(Tile), 0},
+        {nullptr, plan->gram_fused ? (size_t)kResSyncWords * sizeof(unsigned) : 0, 0},                   // zero-filled, epoch set below
+        {nullptr, plan->gram_fused ? (size_t)plan->ws_gram_doubles * 2 * sizeof(unsigned long long) : 0, 0},   // zero-filled: tag 0 never matches
     };
     size_t total = 0;
     for (Piece& pc : pieces) {
@@ -879,6 +1072,10 @@ psgd_status upload_tables(psgd_plan* plan) {
     if (plan->res_sync_words) {
         const unsigned one = 1;   // epochs start at 1
         std::memcpy(host.data() + pieces[7].at + res_sync_epoch() * sizeof(unsigned), &one, sizeof(one));
+    }
+    if (plan->gram_fused) {
+        const unsigned one = 1;   // epochs start at 1
+        std::memcpy(host.data() + pieces[16].at + res_sync_epoch() * sizeof(unsigned), &one, sizeof(one));
     }
     void* base = nullptr;
     PSGD_HIP(hipMalloc(&base, total), "hipMalloc(descriptor tables)");
@@ -905,6 +1102,8 @@ psgd_status upload_tables(psgd_plan* plan) {
     plan->dev.hr_tiles1 = reinterpret_cast<Tile*>(b + pieces[13].at);
     plan->dev.hr_tiles3 = reinterpret_cast<Tile*>(b + pieces[14].at);
     plan->dev.hr_tiles4 = reinterpret_cast<Tile*>(b + pieces[15].at);
+    plan->dev.gram_sync = plan->gram_fused ? reinterpret_cast<unsigned*>(b + pieces[16].at) : nullptr;
+    plan->dev.gram_mail = plan->gram_fused ? reinterpret_cast<unsigned long long*>(b + pieces[17].at) : nullptr;
     plan->uploaded = true;
     return PSGD_OK;
 }
@@ -923,6 +1122,22 @@ psgd_status read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t
 psgd_status check_plan(psgd_plan* plan, void* stream) {
     if (!plan->uploaded) return PSGD_OK;
     PSGD_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)), "hipStreamSynchronize");
+    if (plan->gram_fused && plan->dev.gram_sync) {
+        unsigned flag = 0;
+        PSGD_HIP(hipMemcpy(&flag, plan->dev.gram_sync + res_sync_err(), sizeof(flag), hipMemcpyDeviceToHost),
+                 "hipMemcpy(error word)");
+        if (flag) {
+            // start over: empty mailbox, epoch 1, no finished workgroups
+            PSGD_HIP(hipMemset(plan->dev.gram_mail, 0, (size_t)plan->ws_gram_doubles * 2 * sizeof(unsigned long long)),
+                     "hipMemset(mailbox)");
+            PSGD_HIP(hipMemset(plan->dev.gram_sync, 0, (size_t)kResSyncWords * sizeof(unsigned)), "hipMemset(sync words)");
+            const unsigned one = 1;
+            PSGD_HIP(hipMemcpy(plan->dev.gram_sync + res_sync_epoch(), &one, sizeof(one), hipMemcpyHostToDevice),
+                     "hipMemcpy(epoch)");
+            plan->last_error = "k_gram_chol: a wait timed out (row blocks of a matrix not co-resident?)";
+            return PSGD_EHIP;
+        }
+    }
     if (!plan->resident_ok || !plan->res_sync_words) return PSGD_OK;
     unsigned flag = 0;
     PSGD_HIP(hipMemcpy(&flag, plan->dev.res_sync + res_sync_err(), sizeof(flag), hipMemcpyDeviceToHost),
@@ -1061,7 +1276,28 @@ psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float
                            plan->dev.small_mats, ws, p, plan->workers, pre_reduced);
         PSGD_HIP(hipGetLastError(), "launch k_ortho");
     }
-    if (!plan->tiles_gram.empty()) {
+    if (!plan->tiles_gram.empty() && plan->gram_fused) {
+        hipError_t ge = hipSuccess;
+        const dim3 ggrid((unsigned)plan->tiles_gram.size());
+        slot_t* gmail = reinterpret_cast<slot_t*>(plan->dev.gram_mail);
+#define PSGD_LAUNCH_GRAM_CHOL(RR)                                                                                     \
+    hipLaunchKernelGGL((k_gram_chol<RR>), ggrid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles_gram, ws, p, gmail, \
+                       plan->dev.gram_sync, plan->workers, pre_reduced)
+        switch (plan->rank) {
+            case 1: PSGD_LAUNCH_GRAM_CHOL(1); break;
+            case 2: PSGD_LAUNCH_GRAM_CHOL(2); break;
+            case 3: PSGD_LAUNCH_GRAM_CHOL(3); break;
+            case 4: PSGD_LAUNCH_GRAM_CHOL(4); break;
+            case 5: PSGD_LAUNCH_GRAM_CHOL(5); break;
+            case 6: PSGD_LAUNCH_GRAM_CHOL(6); break;
+            case 7: PSGD_LAUNCH_GRAM_CHOL(7); break;
+            case 8: PSGD_LAUNCH_GRAM_CHOL(8); break;
+            default: ge = hipErrorInvalidValue; break;
+        }
+#undef PSGD_LAUNCH_GRAM_CHOL
+        if (ge == hipSuccess) ge = hipGetLastError();
+        PSGD_HIP(ge, "launch k_gram_chol");
+    } else if (!plan->tiles_gram.empty()) {
         const size_t float_bytes = (size_t)(plan->ws_ppart_floats + plan->ws_qpart_floats) * sizeof(float);
         double* gram = reinterpret_cast<double*>(static_cast<char*>(workspace) + (float_bytes + 255) / 256 * 256);
         hipLaunchKernelGGL(k_gram, dim3((unsigned)plan->tiles_gram.size()), dim3(kBlock), 0, s, plan->dev.mats,

@@ -40,10 +40,7 @@
 
 namespace psgd {
 
-constexpr unsigned kSpinLimit = 1u << 21;
 constexpr int kResRowsPerLane = kResMaxN / kWave;   // rows of the Gram-Schmidt panel a lane holds
-
-typedef unsigned long long slot_t;
 
 struct ResArgs {
     const MatDesc* mats;         // resident descriptors: ppart_off / qpart_off are mailbox offsets (slots)
@@ -66,59 +63,6 @@ __device__ __forceinline__ void trace_mark(const ResArgs& a, int point) {
         a.trace[((size_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * kResTracePoints + point] = wall_clock64();
 }
 __device__ __forceinline__ void trace_mark_wave(const ResArgs& a, int point) { trace_mark(a, point); }
-
-// ---- mailbox -----------------------------------------------------------------------------------------
-__device__ __forceinline__ void post(slot_t* slot, float v, unsigned epoch) {
-    const slot_t w = ((slot_t)epoch << 32) | (slot_t)__float_as_uint(v);
-    __hip_atomic_store(slot, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Polling is written as: issue all loads of an attempt back to back (`fetch`, unconditional, so that
-// no branch forces a wait between them; lanes or slots that are not wanted re-read a wanted one),
-// then look at the tags.
-__device__ __forceinline__ slot_t fetch(const slot_t* slot) {
-    return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ bool arrived(slot_t w, unsigned epoch) { return (unsigned)(w >> 32) == epoch; }
-__device__ __forceinline__ float value_of(slot_t w) { return __uint_as_float((unsigned)(w & 0xffffffffULL)); }
-
-// Wait for a group of slots: every lane polls the slots it needs (`attempt()` returns true when all of
-// them carry this step's tag) until the whole wavefront has them.  For the few wavefronts that reduce.
-// All lanes of the wavefront call it together.
-template <typename F>
-__device__ __forceinline__ void await(F attempt, unsigned* err_word) {
-    unsigned spins = 0;
-    for (;;) {
-        const bool ok = attempt();
-        if (__all(ok)) break;
-        __builtin_amdgcn_s_sleep(2);
-        if (++spins > kSpinLimit) {
-            st_dev(err_word, 1u);
-            break;
-        }
-    }
-}
-
-// The same for the many wavefronts that wait for a published result: first one lane probes a single
-// slot of the group (`probe`, the same address for the whole wavefront) at a relaxed pace, so that
-// two thousand waiting wavefronts put little load on the memory system; once it carries this step's
-// tag the rest is about to land and every lane polls the slots it needs.
-template <typename F>
-__device__ __forceinline__ void await_probed(const slot_t* probe, unsigned epoch, F attempt, unsigned* err_word) {
-    unsigned spins = 0;
-    for (;;) {
-        unsigned tag = epoch;
-        if ((threadIdx.x & (kWave - 1)) == 0)
-            tag = (unsigned)(__hip_atomic_load(probe, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32);
-        if (__builtin_amdgcn_readfirstlane(tag) == epoch) break;
-        __builtin_amdgcn_s_sleep(6);
-        if (++spins > kSpinLimit) {
-            st_dev(err_word, 1u);
-            return;
-        }
-    }
-    await(attempt, err_word);
-}
 
 // ---- Gram-Schmidt by one wavefront -------------------------------------------------------------------
 // Rows lane, lane + 64, ... of the n x r panel are held in registers (n <= kResMaxN).  Column by
