@@ -137,7 +137,10 @@ PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, in
  *   stream_hints  cache policy of the second and third sweep: -1 (default) by the size of M over all
  *                 workers (non-temporal accesses to M and the error memory above 320 MB), 0 never,
  *                 1 always
- *   gram_fused    tall panels: 1 (default) Gram matrices and factorisation in one launch, 0 in two
+ *   gram_fused    tall panels: 1 (default) Gram matrices and factorisation in one launch where the
+ *                 device can hold a matrix's row blocks at once, 0 in two launches, 2 in one launch
+ *                 unconditionally (diagnostic: its waits may then time out, see psgd_plan_check)
+ *   gram_spin     polls before a wait in that launch gives up, 1 .. 2^24 (default 2^18)
  *   bf16_valu     bf16 gradients / output at rank <= 8: 1 (default) streaming kernels, 0 matrix-core kernels
  *   q_reduce_elems  accepted, unused */
 PSGD_API psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value);

@@ -405,17 +405,19 @@ __device__ __forceinline__ void await_probed(const slot_t* probe, unsigned epoch
 }
 
 // One slot, waited for by this lane alone (other lanes of the wavefront may be waiting for theirs).  Gives up after
-// kTakeSpinLimit rounds, or as soon as another waiter has given up (the error word is looked at now and then), so
-// that a broken hand-over ends the kernel quickly instead of timing out slot after slot.
+// `limit` rounds (kTakeSpinLimit unless the host asks for less), or as soon as another waiter has given up (the
+// error word is looked at every 16 rounds, far longer than a wait lasts when all is well), so that a broken
+// hand-over ends the kernel quickly instead of timing out slot after slot.
 constexpr unsigned kTakeSpinLimit = 1u << 18;
-__device__ __forceinline__ unsigned take_bits(const slot_t* slot, slot_t first, unsigned epoch, unsigned* err_word) {
+__device__ __forceinline__ unsigned take_bits(const slot_t* slot, slot_t first, unsigned epoch, unsigned* err_word,
+                                              unsigned limit) {
     slot_t w = first;
     unsigned spins = 0;
     while (!arrived(w, epoch)) {
         __builtin_amdgcn_s_sleep(2);
         w = fetch(slot);
         ++spins;
-        if ((spins & 255u) == 0u && (spins > kTakeSpinLimit || ld_dev(err_word) != 0u)) {
+        if ((spins & 15u) == 0u && (spins > limit || ld_dev(err_word) != 0u)) {
             st_dev(err_word, 1u);
             break;
         }
@@ -430,9 +432,9 @@ __device__ __forceinline__ void post_double(slot_t* pair, double v, unsigned epo
     __hip_atomic_store(pair + 1, ((slot_t)epoch << 32) | (b >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ double take_double(const slot_t* pair, slot_t first_lo, slot_t first_hi, unsigned epoch,
-                                              unsigned* err_word) {
-    const unsigned lo = take_bits(pair, first_lo, epoch, err_word);
-    const unsigned hi = take_bits(pair + 1, first_hi, epoch, err_word);
+                                              unsigned* err_word, unsigned limit) {
+    const unsigned lo = take_bits(pair, first_lo, epoch, err_word, limit);
+    const unsigned hi = take_bits(pair + 1, first_hi, epoch, err_word, limit);
     return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
 

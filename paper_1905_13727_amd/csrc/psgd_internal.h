@@ -111,7 +111,9 @@ struct Tuning {
                                 // non-temporal loads of M in sweep 2.
                                 // -1: when M of all workers exceeds kStreamHintBytes; 0: never; 1: always
     int64_t gram_fused = 1; // tall panels: 1 = Gram matrices and factorisation in one launch when the device holds a matrix's
-                            // row blocks at once; 0 = always the two launches
+                            // row blocks at once; 0 = always the two launches; 2 = one launch whatever the device holds
+                            // (diagnostic: the waits may time out, which psgd_plan_check then reports)
+    int64_t gram_spin = 1 << 18;   // polls of one slot in that launch before a wait gives up
     int64_t bf16_valu = 1;  // bf16 gradients / output at rank <= 8: 1 = the streaming (vector-ALU) kernels, 0 = the matrix-core kernels
     int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream
     int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height

@@ -534,7 +534,7 @@ template <int R>
 __global__ __launch_bounds__(kBlock) void k_gram_chol(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                       const float* __restrict__ ws, float* __restrict__ p,
                                                       slot_t* __restrict__ mail_gram, unsigned* __restrict__ sync,
-                                                      int workers, int pre_reduced) {
+                                                      int workers, int pre_reduced, unsigned spin_limit) {
     constexpr int kMaxSlices = 16;
     constexpr int kAhead = 4;   // slots requested before the first is looked at
     constexpr int E = kValuMaxRank * kValuMaxRank;
@@ -605,11 +605,11 @@ __global__ __launch_bounds__(kBlock) void k_gram_chol(const MatDesc* __restrict_
                     hi[u] = fetch(src + (int64_t)(b + u) * stride + 1);
                 }
 #pragma unroll
-                for (int u = 0; u < kAhead; ++u) v += take_double(src + (int64_t)(b + u) * stride, lo[u], hi[u], epoch, err_word);
+                for (int u = 0; u < kAhead; ++u) v += take_double(src + (int64_t)(b + u) * stride, lo[u], hi[u], epoch, err_word, spin_limit);
             }
             for (; b < b1; ++b) {
                 const slot_t* s2 = src + (int64_t)b * stride;
-                v += take_double(s2, fetch(s2), fetch(s2 + 1), epoch, err_word);
+                v += take_double(s2, fetch(s2), fetch(s2 + 1), epoch, err_word, spin_limit);
             }
             part[sl][ent] = v;
         }
@@ -1024,7 +1024,8 @@ static psgd_status gram_fused_check_device(psgd_plan* plan) {
     if (e != hipSuccess) return hip_fail(plan, e, "occupancy(k_gram_chol)");
     int max_blocks = 0;
     for (const MatDesc& d : plan->mats) max_blocks = std::max(max_blocks, (int)d.n_gblock);
-    plan->gram_fused = (int64_t)cus * occ >= 2 * (int64_t)max_blocks;   // with room to spare
+    // with room to spare; gram_fused = 2 skips the test (diagnostic: lets a test see the waits time out)
+    plan->gram_fused = plan->tuning.gram_fused == 2 || (int64_t)cus * occ >= 2 * (int64_t)max_blocks;
     return PSGD_OK;
 }
 
@@ -1282,7 +1283,7 @@ psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float
         slot_t* gmail = reinterpret_cast<slot_t*>(plan->dev.gram_mail);
 #define PSGD_LAUNCH_GRAM_CHOL(RR)                                                                                     \
     hipLaunchKernelGGL((k_gram_chol<RR>), ggrid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.tiles_gram, ws, p, gmail, \
-                       plan->dev.gram_sync, plan->workers, pre_reduced)
+                       plan->dev.gram_sync, plan->workers, pre_reduced, (unsigned)plan->tuning.gram_spin)
         switch (plan->rank) {
             case 1: PSGD_LAUNCH_GRAM_CHOL(1); break;
             case 2: PSGD_LAUNCH_GRAM_CHOL(2); break;

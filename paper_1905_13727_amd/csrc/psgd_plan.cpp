@@ -128,7 +128,8 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
     const Tuning& tu = plan->tuning;
     if (tu.hr_k3_rows < 64 || tu.hr_k1_rows < 64 || tu.hr_k1_rows > 256 || tu.hr_k1_rows % 64 != 0 ||
         tu.hr_k1_cols < 64 || tu.hr_k1_cols % 64 != 0 || tu.hr_k4_rows < 16 || tu.hr_k4_rows > 1024 ||
-        tu.stream_hints < -1 || tu.stream_hints > 1 || tu.xcd_order < 0 || tu.gram_fused < 0 || tu.gram_fused > 1)
+        tu.stream_hints < -1 || tu.stream_hints > 1 || tu.xcd_order < 0 || tu.gram_fused < 0 || tu.gram_fused > 2 || tu.gram_spin < 1 ||
+        tu.gram_spin > (1 << 24))
         return PSGD_EINVAL;
     const int64_t W = plan->workers;
     const size_t nm = plan->mats.size();
@@ -233,7 +234,8 @@ psgd_status build_tables(psgd_plan* plan) {
     if (tu.k1_rows < 0 || tu.k3_rows < 0 || tu.k4_rows < 0 || tu.k1_nv < 1 ||
         tu.k1_nv > kMaxVecPerLaneK1 || tu.k3_nv < 1 || tu.k3_nv > kMaxVecPerLaneK3 || tu.k4_nv < 1 ||
         tu.k4_nv > kMaxVecPerLaneK3 || tu.q_reduce_elems < 1 || tu.res_rows < 0 || tu.res_rows > kResRows ||
-        tu.stream_hints < -1 || tu.stream_hints > 1 || tu.xcd_order < 0 || tu.gram_fused < 0 || tu.gram_fused > 1)
+        tu.stream_hints < -1 || tu.stream_hints > 1 || tu.xcd_order < 0 || tu.gram_fused < 0 || tu.gram_fused > 2 || tu.gram_spin < 1 ||
+        tu.gram_spin > (1 << 24))
         return PSGD_EINVAL;
     const size_t nm = plan->mats.size();
     // k_ef_right and k_left address the rows of a wavefront's strip (a quarter of the tile's rows) with 31-bit
@@ -671,6 +673,7 @@ psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value
     else if (!strcmp(key, "stream_hints")) tu.stream_hints = value;
     else if (!strcmp(key, "bf16_valu")) tu.bf16_valu = value;
     else if (!strcmp(key, "gram_fused")) tu.gram_fused = value;
+    else if (!strcmp(key, "gram_spin")) tu.gram_spin = value;
     else if (!strcmp(key, "res_rows")) tu.res_rows = value;
     else if (!strcmp(key, "res_trace")) tu.res_trace = value;
     else return PSGD_EINVAL;

@@ -170,6 +170,38 @@ def test_tall_panels_in_one_launch_and_in_two(rank, workers):
                 assert x is None or np.array_equal(x, y)
 
 
+def test_one_launch_factorisation_reports_a_wait_that_gives_up():
+    """A panel of 4297 row blocks is more than the device holds at once, so its workgroups cannot all wait for each
+    other: the planner takes the two launches for it (parity below).  Forced into one launch (gram_fused = 2) with
+    a small poll limit, the waits give up, every workgroup still runs to its end, psgd_plan_check reports the
+    failure and clears the slots, and the next call on the plan behaves the same way instead of hanging."""
+    _need_gpu()
+    from paper_1905_13727_amd import binding as B
+    shapes = [(1100000, 8), (300, 40)]
+    _run(_workload(shapes), rank=2, workers=1, steps=1, seed=95, expect_resident=False)
+    dev = torch.device("cuda:0")
+    plan = B.Plan(shapes, 2, 1)
+    for key, value in (("resident", 0), ("gram_fused", 2), ("gram_spin", 256)):
+        plan.set_tuning(key, value)
+    sz = plan.sizes
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(3)
+    grad = (torch.randn(sz.grad_stride, generator=gen) * 0.01).to(dev)
+    err = torch.zeros(sz.err_stride, device=dev)
+    q = torch.randn(sz.q_elems, generator=gen).to(dev)
+    p = torch.zeros(sz.p_elems, device=dev)
+    out = torch.zeros(sz.out_elems, device=dev)
+    ws = torch.zeros(sz.workspace_bytes // 4 + 64, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    for attempt in range(2):
+        print("[timeout] forced one-launch step %d" % attempt, flush=True)
+        plan.step(grad, err, q, p, out, ws, stream)
+        with pytest.raises(B.PsgdError):
+            plan.check(stream)
+        assert "timed out" in plan.last_error()
+    plan.destroy()
+
+
 @pytest.mark.parametrize("rank,workers,bf16", [(3, 2, False), (4, 1, True)])
 def test_tall_and_wide_matrices(rank, workers, bf16):
     """Matrices of at least 2048 x 2048 get 1024-row blocks in the second sweep and 16-row tiles in the first and

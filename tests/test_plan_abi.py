@@ -75,8 +75,11 @@ def test_null_pointers_are_rejected_without_a_gpu():
         plan.set_tuning("stream_hints", 2)
     plan.set_tuning("stream_hints", 1)
     with pytest.raises(B.PsgdError):
-        plan.set_tuning("gram_fused", 2)
+        plan.set_tuning("gram_fused", 3)
+    with pytest.raises(B.PsgdError):
+        plan.set_tuning("gram_spin", 0)
     plan.set_tuning("gram_fused", 0)
+    plan.set_tuning("gram_spin", 1024)
     plan.set_tuning("xcd_order", 0)
     plan.set_tuning("k1_rows", 16)
 
