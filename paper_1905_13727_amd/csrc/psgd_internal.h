@@ -101,7 +101,7 @@ struct Tuning {
     int64_t k4_nv = 1;
     int64_t q_reduce_elems = 1024;  // accepted, unused (the Q reduction works on 64 elements per workgroup)
     int64_t hr_k3_rows = 2048;  // matrix-core Q = M^T P: rows per workgroup (four strips)
-    int64_t hr_k4_rows = 128;   // matrix-core decompression: rows per workgroup (four strips of 16-row steps)
+    int64_t hr_k4_rows = 0;     // matrix-core decompression: rows per workgroup (four strips of 16-row steps); 0 = by rank
     int64_t hr_k1_rows = 128;   // matrix-core P = M Q: rows per workgroup (multiple of 64, at most 256)
     int64_t hr_k1_cols = 2048;  // matrix-core P = M Q: columns per workgroup (multiple of 64); longer rows are split and their partial P summed
     int64_t k1_mfma = 0;    // 1: P = M Q on the matrix cores when pack * rank <= 16 for every matrix (slower and less

@@ -127,7 +127,7 @@ void build_resident(psgd_plan* plan);
 static psgd_status build_hr_tables(psgd_plan* plan) {
     const Tuning& tu = plan->tuning;
     if (tu.hr_k3_rows < 64 || tu.hr_k1_rows < 64 || tu.hr_k1_rows > 256 || tu.hr_k1_rows % 64 != 0 ||
-        tu.hr_k1_cols < 64 || tu.hr_k1_cols % 64 != 0 || tu.hr_k4_rows < 16 || tu.hr_k4_rows > 1024 ||
+        tu.hr_k1_cols < 64 || tu.hr_k1_cols % 64 != 0 || (tu.hr_k4_rows != 0 && (tu.hr_k4_rows < 16 || tu.hr_k4_rows > 1024)) ||
         tu.stream_hints < -1 || tu.stream_hints > 1 || tu.xcd_order < 0 || tu.gram_fused < 0 || tu.gram_fused > 2 || tu.gram_spin < 1 ||
         tu.gram_spin > (1 << 24))
         return PSGD_EINVAL;
@@ -139,7 +139,9 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
     plan->k1_on_mfma = false;
     plan->p_pre_reduce = false;
     const int64_t right_rows = tu.hr_k1_rows;
-    const int64_t decomp_rows = tu.hr_k4_rows;
+    // rows per workgroup of the decompression: measured best on the 24-layer transformer set at ranks 16, 32, 64
+    // (one, two, four rank tiles of 16)
+    const int64_t decomp_rows = tu.hr_k4_rows ? tu.hr_k4_rows : (plan->rank <= 16 ? 128 : (plan->rank <= 32 ? 512 : 256));
     int64_t pp = 0, qp = 0, gp = 0, cp = 0;
     for (size_t i = 0; i < nm; ++i) {
         MatDesc& d = plan->mats[i];
