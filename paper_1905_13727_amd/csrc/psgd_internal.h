@@ -118,9 +118,10 @@ struct Tuning {
     int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream
     int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height
     int64_t res_trace = 0;  // 1: the resident kernel records phase timestamps (diagnostic)
-    int64_t xcd_order = 2048;  // tile lists are ordered so that each accelerator die (own L2) works on one contiguous range of
+    int64_t xcd_order = -1;    // tile lists are ordered so that each accelerator die (own L2) works on one contiguous range of
                                // tiles: 1 = of the whole list; k >= 2 = of each group of consecutive matrices, a group being
-                               // closed once it holds k tiles (a large matrix is then spread over all dies by itself); 0 = off
+                               // closed once it holds k tiles (a large matrix is then spread over all dies by itself); 0 = off;
+                               // -1 = the planner's choice (groups sized by the worker count)
 };
 
 struct DeviceTables {

@@ -237,7 +237,7 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
     }
     CHECK(psgd_plan_set_tuning(plan, "res_rows", 0) == PSGD_OK);
     check_p_tiling(plan);
-    for (int64_t xo : {0, 1, 2, 100, 2048}) {   // every ordering of the tile lists for the dies covers the same elements
+    for (int64_t xo : {0, 1, 2, 100, 2048, -1}) {   // every ordering of the tile lists for the dies covers the same elements
         CHECK(psgd_plan_set_tuning(plan, "xcd_order", xo) == PSGD_OK);
         check_cover(plan, plan->tiles1, (int)plan->tuning.k1_nv, 1);
         check_cover(plan, plan->tiles3, (int)plan->tuning.k3_nv, 2);

@@ -80,6 +80,9 @@ def test_null_pointers_are_rejected_without_a_gpu():
         plan.set_tuning("gram_spin", 0)
     plan.set_tuning("gram_fused", 0)
     plan.set_tuning("gram_spin", 1024)
+    with pytest.raises(B.PsgdError):
+        plan.set_tuning("xcd_order", -2)
+    plan.set_tuning("xcd_order", -1)
     plan.set_tuning("xcd_order", 0)
     plan.set_tuning("k1_rows", 16)
 
