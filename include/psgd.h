@@ -135,7 +135,7 @@ PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, in
  *   xcd_order     order of the tile lists over the accelerator dies: 0 plain, 1 one contiguous range
  *                 of the whole list per die, k >= 2 the same within groups of consecutive matrices
  *                 of at least k tiles, -1 (default) the planner's choice: groups of 4096 / workers
- *                 tiles (128 .. 2048)
+ *                 tiles (128 .. 2048); the whole list for one worker and a set beyond the cache
  *   stream_hints  cache policy of the second and third sweep: -1 (default) by the size of M over all
  *                 workers (non-temporal accesses to M and the error memory above 320 MB), 0 never,
  *                 1 always

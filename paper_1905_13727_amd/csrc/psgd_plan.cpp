@@ -374,7 +374,11 @@ psgd_status build_tables(psgd_plan* plan) {
     build_resident(plan);
     plan->sizes.workspace_bytes =
         std::max<int64_t>(plan->sizes.workspace_bytes, plan->res_ws_floats * (int64_t)sizeof(float));
-    const int64_t order = tu.xcd_order < 0 ? group_tiles(plan) : tu.xcd_order;
+    // The planner's own choice: groups; for one worker and a set beyond the memory-side cache the whole list instead
+    // (24-layer transformer set, rank 4: k_left 880 -> 842 us, k_decomp 2186 -> 2143 us, k_ef_right 2203 -> 2217 us,
+    // the step 5.34 -> 5.28 ms; with the first sweep alone left in groups the second sweep's gain is lost; at 16
+    // workers whole-list order loses 1-3 % in every sweep).
+    const int64_t order = tu.xcd_order >= 0 ? tu.xcd_order : (W == 1 && plan->stream_hints ? 1 : group_tiles(plan));
     order_tiles(plan->tiles1, order);
     order_tiles(plan->tiles3, order);
     order_tiles(plan->tiles4, order);
