@@ -129,6 +129,7 @@ struct DeviceTables {
     Tile* tiles1 = nullptr;
     Tile* tiles3 = nullptr;
     Tile* tiles4 = nullptr;
+    Tile* tiles4u = nullptr;   // decompression fused with the update: tiles of its own, or null (then tiles4)
     Tile* tilesq = nullptr;
     Tile* tiles_gram = nullptr;
     Tile* tilesp = nullptr;
@@ -159,6 +160,7 @@ struct psgd_plan {
     std::vector<int32_t> tensor_mat;        // per tensor: matrix index or -1
     std::vector<psgd::MatDesc> mats;
     std::vector<psgd::Tile> tiles1, tiles3, tiles4, tilesq;
+    std::vector<psgd::Tile> tiles4u;        // third sweep when fused with the update, if its tiles differ (else empty)
     std::vector<psgd::Tile> tiles_gram;     // row blocks of tall panels (Cholesky-QR)
     std::vector<int32_t> small_mats;        // matrices orthogonalised by one workgroup (Gram-Schmidt in LDS)
     int64_t ws_gram_doubles = 0;            // workspace: Gram partials, after the float regions

@@ -1041,7 +1041,7 @@ psgd_status upload_tables(psgd_plan* plan) {
         if (st != PSGD_OK) return st;
     }
     struct Piece { const void* src; size_t bytes; size_t at; };
-    Piece pieces[18] = {
+    Piece pieces[19] = {
         {plan->mats.data(), plan->mats.size() * sizeof(MatDesc), 0},
         {plan->tiles1.data(), plan->tiles1.size() * sizeof(Tile), 0},
         {plan->tiles3.data(), plan->tiles3.size() * sizeof(Tile), 0},
@@ -1060,6 +1060,7 @@ psgd_status upload_tables(psgd_plan* plan) {
         {plan->hr_tiles4.data(), plan->hr_tiles4.size() * sizeof(Tile), 0},
         {nullptr, plan->gram_fused ? (size_t)kResSyncWords * sizeof(unsigned) : 0, 0},                   // zero-filled, epoch set below
         {nullptr, plan->gram_fused ? (size_t)plan->ws_gram_doubles * 2 * sizeof(unsigned long long) : 0, 0},   // zero-filled: tag 0 never matches
+        {plan->tiles4u.data(), plan->tiles4u.size() * sizeof(Tile), 0},
     };
     size_t total = 0;
     for (Piece& pc : pieces) {
@@ -1105,6 +1106,7 @@ psgd_status upload_tables(psgd_plan* plan) {
     plan->dev.hr_tiles4 = reinterpret_cast<Tile*>(b + pieces[15].at);
     plan->dev.gram_sync = plan->gram_fused ? reinterpret_cast<unsigned*>(b + pieces[16].at) : nullptr;
     plan->dev.gram_mail = plan->gram_fused ? reinterpret_cast<unsigned long long*>(b + pieces[17].at) : nullptr;
+    plan->dev.tiles4u = plan->tiles4u.empty() ? nullptr : reinterpret_cast<Tile*>(b + pieces[18].at);
     plan->uploaded = true;
     return PSGD_OK;
 }
@@ -1197,12 +1199,15 @@ static void launch_left(psgd_plan* plan, const float* err, const float* p, float
 template <int R>
 static void launch_decomp(psgd_plan* plan, float* err, const float* p, const float* q, const void* grad, void* out,
                           hipStream_t s, const UpdateArgs& upd) {
-    dim3 grid((unsigned)plan->tiles4.size(), (unsigned)plan->workers);
+    // fused with the update: tiles of its own where the planner made some
+    const bool own_tiles = upd.mom && plan->dev.tiles4u;
+    const Tile* tiles = own_tiles ? plan->dev.tiles4u : plan->dev.tiles4;
+    dim3 grid((unsigned)(own_tiles ? plan->tiles4u.size() : plan->tiles4.size()), (unsigned)plan->workers);
     // bf16 gradients or output: the vector region has a kernel of its own
     const int vec_here = plan->grad_dtype == PSGD_F32 && plan->out_dtype == PSGD_F32 ? 1 : 0;
 #define PSGD_LAUNCH_DECOMP(NVV, UPDV, STREAMV, OBFV)                                                                    \
     hipLaunchKernelGGL((k_decomp<R, NVV, UPDV, STREAMV, OBFV>), grid, dim3(kBlock), 0, s, plan->dev.mats,               \
-                       plan->dev.tiles4, err, p, q, static_cast<const float*>(grad), out, plan->workers,                \
+                       tiles, err, p, q, static_cast<const float*>(grad), out, plan->workers,                           \
                        plan->sizes.grad_stride, plan->sizes.err_stride, plan->sizes.n_mat_elems, upd, vec_here)
 #define PSGD_LAUNCH_DECOMP_NV(UPDV, STREAMV)                                     \
     do {                                                                         \

@@ -147,7 +147,7 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
         return PSGD_EINVAL;
     const int64_t W = plan->workers;
     const size_t nm = plan->mats.size();
-    plan->tiles1.clear(); plan->tiles3.clear(); plan->tiles4.clear(); plan->tilesp.clear();
+    plan->tiles1.clear(); plan->tiles3.clear(); plan->tiles4.clear(); plan->tiles4u.clear(); plan->tilesp.clear();
     plan->small_mats.clear(); plan->tiles_gram.clear(); plan->tilesq.clear();
     plan->hr_tiles1.clear(); plan->hr_tiles3.clear(); plan->hr_tiles4.clear();
     plan->k1_on_mfma = false;
@@ -289,6 +289,14 @@ psgd_status build_tables(psgd_plan* plan) {
     streaming_tiles(plan, 2, tu.k3_rows, tu.k3_nv, false, &plan->tiles3, &nrb, nullptr);
     streaming_tiles(plan, 3, tu.k4_rows, tu.k4_nv, false, &plan->tiles4, nullptr, nullptr);
 
+    // The pass fused with the momentum / parameter update moves 20 bytes per element where the plain one moves 12 and
+    // wants taller tiles on a mid-sized single-worker set (LSTM-shaped set, rank 4: 163 -> 155 us with 64 rows; the
+    // ResNet18-shaped sets at 1 and 16 workers are at their optimum with the plain pass's tiles).
+    plan->tiles4u.clear();
+    if (tu.k4_rows == 0 && plan->workers == 1 && !small_set(plan) &&
+        plan->sizes.n_mat_elems * (int64_t)sizeof(float) <= kStreamHintBytes)
+        streaming_tiles(plan, 3, 64, tu.k4_nv, false, &plan->tiles4u, nullptr, nullptr);
+
     // vector region: slices appended to the decompress work-list
     const int64_t L = plan->sizes.n_vec_elems;
     const int64_t vec_slice = (int64_t)kBlock * 4 * 4;
@@ -298,6 +306,7 @@ psgd_status build_tables(psgd_plan* plan) {
         t.elem0 = e;
         t.nelem = std::min(vec_slice, L - e);
         plan->tiles4.push_back(t);
+        if (!plan->tiles4u.empty()) plan->tiles4u.push_back(t);
     }
 
     // workspace: partial P of every matrix ([W * n_cchunk][n][r] each), then partial Q
@@ -382,6 +391,7 @@ psgd_status build_tables(psgd_plan* plan) {
     order_tiles(plan->tiles1, order);
     order_tiles(plan->tiles3, order);
     order_tiles(plan->tiles4, order);
+    order_tiles(plan->tiles4u, order);
     plan->tables_built = true;
     return PSGD_OK;
 }

@@ -242,6 +242,7 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
         check_cover(plan, plan->tiles1, (int)plan->tuning.k1_nv, 1);
         check_cover(plan, plan->tiles3, (int)plan->tuning.k3_nv, 2);
         check_cover(plan, plan->tiles4, (int)plan->tuning.k4_nv, 0);
+        if (!plan->tiles4u.empty()) check_cover(plan, plan->tiles4u, (int)plan->tuning.k4_nv, 0);   // fused-update pass
     }
     check_cover(plan, plan->tiles3, (int)plan->tuning.k3_nv, 2);
     check_cover(plan, plan->tiles4, (int)plan->tuning.k4_nv, 0);

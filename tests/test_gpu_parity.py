@@ -620,6 +620,19 @@ def test_fused_update_streaming():
                 expect_resident=False)
 
 
+def test_fused_update_streaming_tiles_of_its_own():
+    """A single-worker set of 16 M elements or more that fits the memory-side cache gets taller tiles for the fused
+    pass than for the plain decompression (ragged last row blocks, a tall panel, vectors): parity of the fused
+    step, and psgd_step on the same plan still at parity (it keeps the plain pass's tiles)."""
+    _need_gpu()
+    shapes = [(2600, 650), (33, ), (3333, 2700), (1031, 7), (9001, 650), (70, 4100), (129, )]
+    assert sum(int(np.prod(s)) for s in shapes if len(s) == 2) >= (1 << 24)
+    wl = _workload(shapes)
+    _run_update(wl, rank=4, workers=1, steps=2, seed=11, expect_resident=False)
+    _run_update(wl, rank=2, workers=1, steps=2, seed=12, split=True, expect_resident=False)
+    _run(wl, rank=4, workers=1, steps=2, seed=13, expect_resident=False)
+
+
 def test_fused_update_matrix_cores():
     _need_gpu()
     from paper_1905_13727_amd import workloads as WL
