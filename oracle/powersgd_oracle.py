@@ -16,6 +16,8 @@ Every function follows the paper's steps in the paper's order and notation:
                the decompressed *aggregate*, eq. (ef-sgd) last line
   Appendix G.7 ("Best-approximation PowerSGD"): several subspace iterations,
                no reuse of the previous step
+  Appendix G   ("Random Block compression", "Random K compression"): the two
+               linear baselines that run inside the same error-feedback loop
 
 Readings taken where the paper is silent (listed again in the design notes):
   * Gram-Schmidt is the modified variant, columns left to right, one pass.
@@ -34,7 +36,11 @@ least-squares projection for P_hat / Q / decompressed result, hand-derived
 2x2 and 3x2 cases, exact reconstruction at full rank, the subspace-iteration
 limit sum_{i>r} sigma_i^2, W-worker == 1-worker on the mean, triangular
 invariance of the warm start, r = 1 power iteration, the compression ratios
-the paper prints for ResNet18 and the LSTM.  No function here is unpinned.
+the paper prints for ResNet18 and the LSTM; for the Appendix G baselines
+hand-worked 2x3 cases, a per-element brute force, conservation, the
+W-worker == 1-worker lemma, Random K on a contiguous index range == Random
+Block, and the paper's ratios again (their budget is PowerSGD's).  No
+function here is unpinned.
 """
 from __future__ import annotations
 
@@ -207,3 +213,88 @@ def uncompressed_floats(shapes):
 
 def compression_ratio(shapes, rank):
     return uncompressed_floats(shapes) / compressed_floats(shapes, rank)
+
+
+# --- Appendix G: the two linear baseline compressors that share the error-feedback loop -----------------
+#
+# "Random Block" and "Random K" (Appendix G, first two algorithms) plug into Algorithm 2 in the place
+# of Algorithm 1: the update matrix M_w = g_w + e_w is seen as a vector of length n*m, every worker keeps
+# the same b = (n + m) r entries of it (the budget of rank-r PowerSGD), the kept values are averaged over
+# the workers, the decompressed matrix is zero elsewhere, and e_w <- M_w - decompressed.  The random draws
+# (the block's start s, the index set I) are the same on all workers; here they are arguments.
+#
+# Readings where the appendix is silent:
+#   * b is capped at n*m (tiny matrices);
+#   * a block that would run past the end of the vector stops there (no wrap-around): the slice
+#     M(s : s+b) holds min(b, n*m - s) entries; the packed values are zero beyond them;
+#   * vector-shaped tensors are averaged uncompressed, as in Algorithm 1.
+
+def kept_count(n, m, rank):
+    """Entries a matrix keeps: b = (m + n) r, "to match rank-r PowerSGD", at most n*m."""
+    return min((int(n) + int(m)) * int(rank), int(n) * int(m))
+
+
+def _sparse_step(grads, errs, rank, positions_of):
+    """Algorithm 2 up to the momentum update with a keep-these-positions compressor.
+    positions_of(t, n, m, b) -> integer array of the kept positions of tensor t (length <= b)."""
+    W = len(grads)
+    T = len(grads[0])
+    out = {"values": [None] * T, "out": [None] * T, "err": [[None] * T for _ in range(W)]}
+    for t in range(T):
+        view = matrix_view(np.shape(grads[0][t]))
+        if view is None:
+            acc = np.zeros(np.shape(grads[0][t]), dtype=np.float64)
+            for w in range(W):
+                acc = acc + np.asarray(grads[w][t], dtype=np.float64)
+            out["out"][t] = acc / W
+            continue
+        n, m = view
+        b = kept_count(n, m, rank)
+        pos = np.asarray(positions_of(t, n, m, b), dtype=np.int64)
+        # Delta_w <- g_w + e_w, treated as a vector of length n m
+        Ms = []
+        for w in range(W):
+            g = np.asarray(grads[w][t], dtype=np.float64).reshape(n * m)
+            e = np.asarray(errs[w][t], dtype=np.float64).reshape(n * m)
+            Ms.append(g + e)
+        # compress: S_w = M_w(positions) ; aggregate: mean over the workers
+        S = np.zeros(len(pos), dtype=np.float64)
+        for w in range(W):
+            S = S + Ms[w][pos]
+        S = S / W
+        # decompress: zero matrix with the averaged values put back
+        M_hat = np.zeros(n * m, dtype=np.float64)
+        M_hat[pos] = S
+        vals = np.zeros(b, dtype=np.float64)
+        vals[: len(pos)] = S
+        out["values"][t] = vals
+        out["out"][t] = M_hat.reshape(n, m)
+        # e_w <- Delta_w - Delta'
+        for w in range(W):
+            out["err"][w][t] = (Ms[w] - M_hat).reshape(n, m)
+    return out
+
+
+def random_block_step(grads, errs, starts, rank):
+    """Appendix G, "Random Block compression", inside Algorithm 2.
+
+    starts[t]  the sampled index s in [0, n m) of matrix tensor t (same on all workers); ignored for 1-D
+    Returns 'values'[t] (the b averaged slice entries, zero past the end of the vector), 'out'[t]
+    (Delta'), 'err'[w][t]."""
+    def positions(t, n, m, b):
+        s = int(starts[t])
+        assert 0 <= s < n * m
+        return np.arange(s, min(s + b, n * m))
+    return _sparse_step(grads, errs, rank, positions)
+
+
+def random_k_step(grads, errs, indices, rank):
+    """Appendix G, "Random K compression", inside Algorithm 2.
+
+    indices[t]  the b sampled positions of matrix tensor t, without repetition (same on all workers)
+    Returns 'values'[t] (the averaged looked-up values, in the order of indices[t]), 'out'[t], 'err'[w][t]."""
+    def positions(t, n, m, b):
+        idx = np.asarray(indices[t], dtype=np.int64)
+        assert idx.shape == (b,) and len(np.unique(idx)) == b and idx.min() >= 0 and idx.max() < n * m
+        return idx
+    return _sparse_step(grads, errs, rank, positions)

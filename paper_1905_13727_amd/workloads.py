@@ -226,6 +226,37 @@ def initial_q(wl: Workload, rank: int, seed: int, only=None):
     return out
 
 
+def kept_count(shape, rank: int) -> int:
+    """Entries per matrix that the Random Block / Random K baselines keep: (n + m) r, at most n m."""
+    n, m = shape
+    return min((n + m) * rank, n * m)
+
+
+def block_starts(wl: Workload, rank: int, seed: int, step: int):
+    """The draw of the Random Block baseline: per matrix one start index uniform in [0, n m), the same on every
+    worker (it depends on the seed and the step only); None for vectors."""
+    out = []
+    for i, s in enumerate(wl.shapes):
+        if len(s) < 2:
+            out.append(None)
+            continue
+        out.append(int(_rng(seed, 4000003, i, step).integers(0, s[0] * s[1])))
+    return out
+
+
+def random_indices(wl: Workload, rank: int, seed: int, step: int):
+    """The draw of the Random K baseline: per matrix kept_count positions in [0, n m) without repetition, the same
+    on every worker; int64 arrays, None for vectors."""
+    out = []
+    for i, s in enumerate(wl.shapes):
+        if len(s) < 2:
+            out.append(None)
+            continue
+        out.append(_rng(seed, 5000003, i, step).choice(s[0] * s[1], size=kept_count(s, rank), replace=False)
+                   .astype(np.int64))
+    return out
+
+
 def bf16_round(a: np.ndarray) -> np.ndarray:
     """Round float32 to the nearest bfloat16 (ties to even), returned as
     float32 holding exactly representable values.  Input conditioning for the

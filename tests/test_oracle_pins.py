@@ -307,3 +307,127 @@ def test_best_approximation_matches_truncated_svd():
     assert np.linalg.norm(O.decompress(P_hat, Q) - best) < 2e-3 * np.linalg.norm(best)
     P1, Q1 = O.best_approx_compress([M], Q0, 1)
     assert np.linalg.norm(O.decompress(P1, Q1) - best) > np.linalg.norm(O.decompress(P_hat, Q) - best)
+
+
+# -- Appendix G baselines: Random Block and Random K -------------------------------------
+
+def _brute_sparse(Ms, keep, W):
+    """Per-element loops: what 'keep these positions, average them, zero the rest' means."""
+    n, m = Ms[0].shape
+    M_hat = [[0.0] * m for _ in range(n)]
+    for pos in keep:
+        i, j = divmod(int(pos), m)
+        acc = 0.0
+        for w in range(W):
+            acc += float(Ms[w][i, j])
+        M_hat[i][j] = acc / W
+    errs = [[[float(Ms[w][i, j]) - M_hat[i][j] for j in range(m)] for i in range(n)] for w in range(W)]
+    return np.array(M_hat), [np.array(e) for e in errs]
+
+
+def test_random_block_by_hand():
+    # Appendix G, "Random Block compression": n = 2, m = 3, r = 1 -> b = (3 + 2) * 1 = 5
+    G = np.array([[1.0, 2.0, 3.0], [4.0, 5.0, 6.0]])
+    Z = np.zeros((2, 3))
+    assert O.kept_count(2, 3, 1) == 5
+    r = O.random_block_step([[G]], [[Z]], [1], 1)       # slice M(1:6) = [2,3,4,5,6]
+    assert np.array_equal(r["values"][0], [2, 3, 4, 5, 6])
+    assert np.array_equal(r["out"][0], [[0, 2, 3], [4, 5, 6]])
+    assert np.array_equal(r["err"][0][0], [[1, 0, 0], [0, 0, 0]])
+    # the carried error comes back in the next step (Algorithm 2): M = G + e = [[2,2,3],[4,5,6]], block at 0
+    r2 = O.random_block_step([[G]], [r["err"][0]], [0], 1)
+    assert np.array_equal(r2["out"][0], [[2, 2, 3], [4, 5, 0]])
+    assert np.array_equal(r2["err"][0][0], [[0, 0, 0], [0, 0, 6]])
+    # a block that starts near the end stops at the end (no wrap-around): M(4:9) -> [5, 6]
+    r3 = O.random_block_step([[G]], [[Z]], [4], 1)
+    assert np.array_equal(r3["values"][0], [5, 6, 0, 0, 0])
+    assert np.array_equal(r3["out"][0], [[0, 0, 0], [0, 5, 6]])
+    # two workers: the kept entries are the mean, each worker keeps its own deviation
+    G2 = np.array([[3.0, 0.0, 1.0], [0.0, 1.0, 2.0]])
+    r4 = O.random_block_step([[G], [G2]], [[Z], [Z]], [1], 1)
+    assert np.array_equal(r4["out"][0], [[0, 1, 2], [2, 3, 4]])
+    assert np.array_equal(r4["err"][0][0], [[1, 1, 1], [2, 2, 2]])
+    assert np.array_equal(r4["err"][1][0], [[3, -1, -1], [-2, -2, -2]])
+
+
+def test_random_k_by_hand():
+    # Appendix G, "Random K compression": the same 2 x 3 case, I = (5, 0, 3, 2, 1) -> all but position 4
+    G = np.array([[1.0, 2.0, 3.0], [4.0, 5.0, 6.0]])
+    Z = np.zeros((2, 3))
+    r = O.random_k_step([[G]], [[Z]], [np.array([5, 0, 3, 2, 1])], 1)
+    assert np.array_equal(r["values"][0], [6, 1, 4, 3, 2])          # in the order of I
+    assert np.array_equal(r["out"][0], [[1, 2, 3], [4, 0, 6]])
+    assert np.array_equal(r["err"][0][0], [[0, 0, 0], [0, 5, 0]])
+
+
+@pytest.mark.parametrize("W", [1, 3])
+def test_baselines_against_per_element_brute_force(W):
+    g = rng(200 + W)
+    shapes = [(7, 5), (4,), (3, 11)]
+    rank = 2
+    grads = [[g.standard_normal(s) for s in shapes] for _ in range(W)]
+    errs = [[None if len(s) == 1 else g.standard_normal(s) for s in shapes] for _ in range(W)]
+    starts = [9, None, 30]                                      # the second block runs past the end (3*11 = 33)
+    idx = [g.permutation(35)[: O.kept_count(7, 5, rank)], None, g.permutation(33)[: O.kept_count(3, 11, rank)]]
+    rb = O.random_block_step(grads, errs, starts, rank)
+    rk = O.random_k_step(grads, errs, idx, rank)
+    for t, s in enumerate(shapes):
+        if len(s) == 1:
+            mean = sum(grads[w][t] for w in range(W)) / W
+            assert np.allclose(rb["out"][t], mean, atol=1e-15) and np.allclose(rk["out"][t], mean, atol=1e-15)
+            assert rb["err"][0][t] is None and rb["values"][t] is None
+            continue
+        n, m = s
+        b = O.kept_count(n, m, rank)
+        Ms = [grads[w][t] + errs[w][t] for w in range(W)]
+        for res, keep in ((rb, range(starts[t], min(starts[t] + b, n * m))), (rk, idx[t])):
+            M_hat, e = _brute_sparse(Ms, keep, W)
+            assert np.allclose(res["out"][t], M_hat, atol=1e-14)
+            for w in range(W):
+                assert np.allclose(res["err"][w][t], e[w], atol=1e-14)
+                # Algorithm 2: what is not sent stays in the memory, exactly
+                assert np.allclose(res["out"][t] + res["err"][w][t], Ms[w], atol=1e-14)
+            assert np.count_nonzero(res["out"][t]) == len(list(keep))
+
+
+def test_random_k_on_a_contiguous_range_is_random_block():
+    g = rng(210)
+    G, E = g.standard_normal((6, 9)), g.standard_normal((6, 9))
+    b = O.kept_count(6, 9, 2)
+    rb = O.random_block_step([[G]], [[E]], [7], 2)
+    rk = O.random_k_step([[G]], [[E]], [np.arange(7, 7 + b)], 2)
+    for key in ("values", "out"):
+        assert np.array_equal(rb[key][0], rk[key][0])
+    assert np.array_equal(rb["err"][0][0], rk["err"][0][0])
+    # keeping every position sends the whole update: nothing is left in the memory (W = 1)
+    full = O.random_k_step([[G]], [[E]], [g.permutation(54)], 99)
+    assert O.kept_count(6, 9, 99) == 54
+    assert np.array_equal(full["out"][0], G + E) and not full["err"][0][0].any()
+
+
+def test_baselines_single_multi_worker_equivalence():
+    """Appendix A.3: for a linear compressor W workers equal one worker on the mean update."""
+    g = rng(220)
+    W, s, rank = 4, (8, 6), 1
+    grads = [[g.standard_normal(s)] for _ in range(W)]
+    errs = [[g.standard_normal(s)] for _ in range(W)]
+    gm = [sum(grads[w][0] for w in range(W)) / W]
+    em = [sum(errs[w][0] for w in range(W)) / W]
+    idx = [g.permutation(48)[: O.kept_count(8, 6, rank)]]
+    for many, one in ((O.random_block_step(grads, errs, [20], rank), O.random_block_step([gm], [em], [20], rank)),
+                      (O.random_k_step(grads, errs, idx, rank), O.random_k_step([gm], [em], idx, rank))):
+        assert np.allclose(many["out"][0], one["out"][0], atol=1e-14)
+        assert np.allclose(many["values"][0], one["values"][0], atol=1e-14)
+        assert np.allclose(sum(many["err"][w][0] for w in range(W)) / W, one["err"][0][0], atol=1e-14)
+
+
+def test_baseline_budget_is_the_papers_compression_ratio():
+    """b = (n + m) r "to match rank-r PowerSGD": with the vectors sent whole, the two baselines exchange exactly
+    what the paper's tables count for PowerSGD (243x / 136x / 72x, 310x / 203x / 120x)."""
+    from paper_1905_13727_amd import workloads as WL
+    _, totals = _golden()
+    shapes = {"resnet18": WL.resnet18_shapes(), "lstm": WL.lstm_shapes(vocab=28869)}
+    for model, r, ratio in totals:
+        sent = sum(int(np.prod(s)) if len(s) == 1 else O.kept_count(s[0], int(np.prod(s[1:])), r) for s in shapes[model])
+        assert abs(O.uncompressed_floats(shapes[model]) / sent - ratio) <= 0.5, (model, r)
+    assert O.kept_count(10, 3, 4) == 30          # capped at n m
