@@ -122,14 +122,20 @@ PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, in
 
 /* Tuning knob for experiments; must be called before the plan's first GPU call.
  * Unknown keys and values out of range give PSGD_EINVAL.  Keys:
- *   resident      1 (default): psgd_step keeps M on chip when the model qualifies; 0: always stream
+ *   resident      1 (default): psgd_step keeps M on chip when the model qualifies; 0: always stream;
+ *                 2 (TEST ONLY): as 1, but the grid is not checked against what the device holds at once
  *   res_rows      forced strip height of the resident tiling (0: chosen by the planner)
  *   res_trace     1: the resident kernel records phase timestamps (psgd_plan_read_trace)
+ *   res_spin      polls before a wait of the resident kernel gives up, 1 .. 2^30 (default 2^21)
+ *   res_max_blocks  TEST ONLY: most workgroups the resident tiling may use (0, the default: what the device
+ *                 holds at once, found when the plan's tables are uploaded)
+ *   res_order     order of the matrices in the resident tile list: 1 (default) largest first, 0 model order
+ *   res_groups, res_stagger   the resident tile list is cut into res_groups parts of about equal size (1 .. 8)
+ *                 and the wavefronts of part g start loading g * res_stagger units of 512 clocks late
  *   k1_rows, k1_nv / k3_rows, k3_nv / k4_rows, k4_nv
  *                 rows per workgroup tile and column vectors per lane of the three sweeps of the
  *                 streaming path (P = M Q; Q = M^T P_hat; decompression); rows 0 (default):
  *                 chosen per matrix by the planner
- *   k1_mfma       1: matrix-core variant of the first sweep at rank <= 8 (default 0)
  *   hr_k1_rows, hr_k1_cols, hr_k3_rows, hr_k4_rows   tile shapes of the matrix-core path
  *                 (hr_k4_rows 0, the default: 128, 512 or 256 rows by rank <= 16, <= 32, <= 64)
  *   xcd_order     order of the tile lists over the accelerator dies: 0 plain, 1 one contiguous range
@@ -140,11 +146,10 @@ PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, in
  *                 workers (non-temporal accesses to M and the error memory above 320 MB), 0 never,
  *                 1 always
  *   gram_fused    tall panels: 1 (default) Gram matrices and factorisation in one launch where the
- *                 device can hold a matrix's row blocks at once, 0 in two launches, 2 in one launch
- *                 unconditionally (diagnostic: its waits may then time out, see psgd_plan_check)
+ *                 device holds all row blocks of the launch at once, 0 in two launches, 2 (TEST ONLY) in one
+ *                 launch unconditionally: its waits may then time out, see psgd_plan_check
  *   gram_spin     polls before a wait in that launch gives up, 1 .. 2^24 (default 2^18)
- *   bf16_valu     bf16 gradients / output at rank <= 8: 1 (default) streaming kernels, 0 matrix-core kernels
- *   q_reduce_elems  accepted, unused */
+ *   bf16_valu     bf16 gradients / output at rank <= 8: 1 (default) streaming kernels, 0 matrix-core kernels */
 PSGD_API psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value);
 
 /* Algorithm 2 "Delta_w <- g_w + e_w" followed by Algorithm 1 compress+aggregate.
@@ -183,8 +188,15 @@ PSGD_API psgd_status psgd_decompress(psgd_plan* plan, const float* p, const floa
  * run.  Otherwise psgd_step is exactly the two calls in sequence.  Resident
  * mode, and the one-launch factorisation of tall panels (tuning key
  * gram_fused), keep hand-over words in plan-owned device memory: do not run
- * two calls of the same plan concurrently on different streams.
- * psgd_plan_check (below) reports whether a wait inside them ever timed out.
+ * two calls of the same plan concurrently on different streams.  Both are
+ * kernels whose workgroups wait for each other inside one ordinary launch:
+ * THEY NEED THE GPU TO THEMSELVES for the length of the kernel (no other
+ * stream or process holding compute units).  Their waits are bounded; if one
+ * gives up (the GPU was shared), the kernel still ends, that step's outputs -
+ * err and q included, which are updated in place - are invalid, and
+ * psgd_plan_check (below) reports it and moves the plan to the kernels that
+ * need no co-residency.  A caller that may share the GPU checks every step,
+ * or sets the tuning keys resident = 0 and gram_fused = 0.
  * The plan's first GPU call (any entry point) uploads its tables (one device
  * allocation and copy).  After that this call, psgd_compress and psgd_decompress
  * only launch kernels on hip_stream: no allocation, no memset, no host
@@ -198,11 +210,21 @@ PSGD_API psgd_status psgd_step(psgd_plan* plan, const void* grad, float* err, fl
  * psgd_compress followed by k-1 calls of psgd_iterate, then psgd_decompress, is the
  * compressor with k iterations per step of Appendix G.7 ("best approximation" as k
  * grows; started from a fresh random Q it is the variant without warm start of
- * Table 2).  Always the streaming or matrix-core kernels (no resident mode).
+ * Table 2).  Always the streaming or matrix-core kernels; psgd_step_iterations is the
+ * one-call form that can stay on chip.
  *   err (device, const in effect)  M_w  [W][N] float
  *   q   (device, in/out), p (device, out), workspace, hip_stream: as psgd_compress */
 PSGD_API psgd_status psgd_iterate(psgd_plan* plan, float* err, float* q, float* p, void* workspace,
                          void* hip_stream);
+
+/* One whole step with `iterations` subspace iterations (Appendix G.7, "best-approximation PowerSGD"; Table 2):
+ * the same quantities as psgd_compress, iterations - 1 calls of psgd_iterate, psgd_decompress.  iterations = 1 is
+ * psgd_step.  A plan in resident mode (see psgd_step) keeps M on chip through all the iterations: one kernel, each
+ * element of g, e read once and of e', Delta' written once whatever the count; otherwise the calls above in
+ * sequence.  Start it from a fresh random Q for the variants without warm start.
+ * Errors: PSGD_EINVAL also for iterations outside 1 .. 64. */
+PSGD_API psgd_status psgd_step_iterations(psgd_plan* plan, const void* grad, float* err, float* q, float* p,
+                                          void* out, void* workspace, void* hip_stream, int32_t iterations);
 
 /* The step fused with the last two lines of Algorithm 2 (error-feedback SGD with
  * momentum): m <- lambda m + Delta' ; x <- x - gamma (Delta' + m).  Delta' is not
@@ -238,11 +260,17 @@ PSGD_API psgd_status psgd_plan_kernel_times(psgd_plan* plan, double* ms_sum, int
  * kernel trace (prefix of the symbol); NULL if out of range. */
 PSGD_API const char* psgd_kernel_name(int32_t index);
 
-/* Waits for hip_stream, then returns PSGD_EHIP if a kernel of this plan whose
+/* A plan that has made no GPU call yet: uploads its tables (the plan's one device allocation) and returns.
+ * Otherwise waits for hip_stream, then returns PSGD_EHIP if a kernel of this plan whose
  * workgroups wait for each other (resident mode; the one-launch factorisation
- * of tall panels) gave up waiting since the last check (its outputs are then
- * invalid; the plan's hand-over words are reset), PSGD_OK otherwise.
- * is_resident (may be NULL) receives 1 if psgd_step runs in resident mode. */
+ * of tall panels) gave up waiting since the last check, PSGD_OK otherwise.
+ * After PSGD_EHIP the outputs of the steps since the last check are invalid
+ * (restore err and q from a copy, or restart them), the plan's hand-over words
+ * are reset, and the mode that failed is switched off for this plan: later
+ * steps run on the streaming kernels / the two-launch factorisation.
+ * is_resident (may be NULL) receives 1 if psgd_step runs in resident mode (a
+ * plan that has made no GPU call yet answers with the planner's provisional
+ * choice; the device's capacity is known once its tables are uploaded). */
 PSGD_API psgd_status psgd_plan_check(psgd_plan* plan, void* hip_stream, int32_t* is_resident);
 
 /* Diagnostic.  After psgd_plan_set_tuning(plan, "res_trace", 1), every resident

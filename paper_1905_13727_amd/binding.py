@@ -67,6 +67,8 @@ def load_library(path: Optional[str] = None):
     lib.psgd_decompress.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psgd_step.restype = C.c_int
     lib.psgd_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.psgd_step_iterations.restype = C.c_int
+    lib.psgd_step_iterations.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32]
     lib.psgd_plan_set_profiling.restype = C.c_int
     lib.psgd_iterate.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.psgd_iterate.restype = C.c_int
@@ -172,6 +174,11 @@ class Plan:
         self._check(self._lib.psgd_step(self._h, _ptr(grad), _ptr(err), _ptr(q), _ptr(p), _ptr(out),
                                         _ptr(workspace), _ptr(stream)), "psgd_step")
 
+    def step_iterations(self, grad, err, q, p, out, workspace, iterations, stream=None):
+        self._check(self._lib.psgd_step_iterations(self._h, _ptr(grad), _ptr(err), _ptr(q), _ptr(p), _ptr(out),
+                                                   _ptr(workspace), _ptr(stream), int(iterations)),
+                    "psgd_step_iterations")
+
     def iterate(self, err, q, p, workspace, stream=None):
         self._check(self._lib.psgd_iterate(self._h, _ptr(err), _ptr(q), _ptr(p), _ptr(workspace), _ptr(stream)),
                     "psgd_iterate")
@@ -198,8 +205,8 @@ class Plan:
         return dict(zip(names, list(ms))), steps.value
 
     def check(self, stream=None) -> bool:
-        """Synchronises the stream, raises if a resident step timed out; returns True if the plan's
-        psgd_step runs in resident mode."""
+        """Uploads the plan's tables if no GPU call has done so yet; synchronises the stream, raises if a kernel
+        whose workgroups wait for each other gave up; returns True if the plan's psgd_step runs in resident mode."""
         r = C.c_int32()
         self._check(self._lib.psgd_plan_check(self._h, _ptr(stream), C.byref(r)), "psgd_plan_check")
         return bool(r.value)

@@ -348,9 +348,12 @@ __device__ __forceinline__ unsigned add_dev(unsigned* p, unsigned v) {
 // A slot holds {value, tag} in 64 bits.  The producer writes the float together with the step's epoch in one
 // 8-byte device-scope store, the consumer polls the slot with device-scope loads until the tag equals the
 // epoch: the value is its own arrival flag, and no cache-wide write-back or invalidate is involved.  Every
-// wait is bounded: after a limit of rounds the waiter raises an error word and goes on, so a kernel always ends.
+// wait is bounded: after a limit of rounds the waiter writes the launch's epoch into an error word and goes on,
+// so a kernel always ends.  The error word is only ever compared with the epoch of the running launch (a waiter
+// that sees it gives up at once instead of timing out slot after slot): what an earlier launch left there does
+// not shorten any wait of a later one.  The host reads the word as "some launch since the last check gave up".
 typedef unsigned long long slot_t;
-constexpr unsigned kSpinLimit = 1u << 21;
+constexpr unsigned kSpinLimit = 1u << 21;   // default poll limit of the resident kernel's waits
 
 __device__ __forceinline__ void post(slot_t* slot, float v, unsigned epoch) {
     const slot_t w = ((slot_t)epoch << 32) | (slot_t)__float_as_uint(v);
@@ -366,18 +369,28 @@ __device__ __forceinline__ slot_t fetch(const slot_t* slot) {
 __device__ __forceinline__ bool arrived(slot_t w, unsigned epoch) { return (unsigned)(w >> 32) == epoch; }
 __device__ __forceinline__ float value_of(slot_t w) { return __uint_as_float((unsigned)(w & 0xffffffffULL)); }
 
+// true when the wait should be abandoned: the limit is reached, or (looked at every 16 rounds, far longer than
+// a wait lasts when all is well) another waiter of this launch has given up.  Uniform over the wavefront.
+__device__ __forceinline__ bool give_up(unsigned spins, unsigned limit, const unsigned* err_word, unsigned epoch) {
+    if (spins > limit) return true;
+    if ((spins & 15u) != 0u) return false;
+    unsigned seen = 0;
+    if ((threadIdx.x & (kWave - 1)) == 0) seen = ld_dev(err_word);
+    return __builtin_amdgcn_readfirstlane(seen) == epoch;
+}
+
 // Wait for a group of slots: every lane polls the slots it needs (`attempt()` returns true when all of
 // them carry this step's tag) until the whole wavefront has them.  For the few wavefronts that reduce.
 // All lanes of the wavefront call it together.
 template <typename F>
-__device__ __forceinline__ void await(F attempt, unsigned* err_word) {
+__device__ __forceinline__ void await(F attempt, unsigned* err_word, unsigned epoch, unsigned limit) {
     unsigned spins = 0;
     for (;;) {
         const bool ok = attempt();
         if (__all(ok)) break;
         __builtin_amdgcn_s_sleep(2);
-        if (++spins > kSpinLimit) {
-            st_dev(err_word, 1u);
+        if (give_up(++spins, limit, err_word, epoch)) {
+            st_dev(err_word, epoch);
             break;
         }
     }
@@ -388,7 +401,8 @@ __device__ __forceinline__ void await(F attempt, unsigned* err_word) {
 // two thousand waiting wavefronts put little load on the memory system; once it carries this step's
 // tag the rest is about to land and every lane polls the slots it needs.
 template <typename F>
-__device__ __forceinline__ void await_probed(const slot_t* probe, unsigned epoch, F attempt, unsigned* err_word) {
+__device__ __forceinline__ void await_probed(const slot_t* probe, unsigned epoch, F attempt, unsigned* err_word,
+                                             unsigned limit) {
     unsigned spins = 0;
     for (;;) {
         unsigned tag = epoch;
@@ -396,19 +410,17 @@ __device__ __forceinline__ void await_probed(const slot_t* probe, unsigned epoch
             tag = (unsigned)(__hip_atomic_load(probe, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32);
         if (__builtin_amdgcn_readfirstlane(tag) == epoch) break;
         __builtin_amdgcn_s_sleep(6);
-        if (++spins > kSpinLimit) {
-            st_dev(err_word, 1u);
+        if (give_up(++spins, limit, err_word, epoch)) {
+            st_dev(err_word, epoch);
             return;
         }
     }
-    await(attempt, err_word);
+    await(attempt, err_word, epoch, limit);
 }
 
 // One slot, waited for by this lane alone (other lanes of the wavefront may be waiting for theirs).  Gives up after
-// `limit` rounds (kTakeSpinLimit unless the host asks for less), or as soon as another waiter has given up (the
-// error word is looked at every 16 rounds, far longer than a wait lasts when all is well), so that a broken
-// hand-over ends the kernel quickly instead of timing out slot after slot.
-constexpr unsigned kTakeSpinLimit = 1u << 18;
+// `limit` rounds, or as soon as another waiter of this launch has given up (the error word is looked at every 16
+// rounds), so that a broken hand-over ends the kernel quickly.
 __device__ __forceinline__ unsigned take_bits(const slot_t* slot, slot_t first, unsigned epoch, unsigned* err_word,
                                               unsigned limit) {
     slot_t w = first;
@@ -417,8 +429,8 @@ __device__ __forceinline__ unsigned take_bits(const slot_t* slot, slot_t first, 
         __builtin_amdgcn_s_sleep(2);
         w = fetch(slot);
         ++spins;
-        if ((spins & 15u) == 0u && (spins > limit || ld_dev(err_word) != 0u)) {
-            st_dev(err_word, 1u);
+        if ((spins & 15u) == 0u && (spins > limit || ld_dev(err_word) == epoch)) {
+            st_dev(err_word, epoch);
             break;
         }
     }

@@ -790,6 +790,7 @@ psgd_status hr_compress(psgd_plan* plan, const void* grad, float* err, float* q,
     if (plan->mats.empty()) return PSGD_OK;
     const int nt = plan->hr_nt;
     HR_MARK(0);
+    plan->compress_marked = plan->profiling;
     if (nt == 1) hr_launch_right<1>(plan, grad, err, q, ws, s, add);
     else if (nt == 2) hr_launch_right<2>(plan, grad, err, q, ws, s, add);
     else hr_launch_right<4>(plan, grad, err, q, ws, s, add);

@@ -29,7 +29,6 @@ constexpr int64_t kHrMaxRows = 1 << 22;   // matrix-core path: tallest matrix (a
 constexpr int64_t kHrMaxCols = 1 << 20;   // matrix-core path: longest row (tiles of <= 256 rows are addressed with 31-bit byte offsets)
 constexpr int64_t kStreamHintBytes = int64_t(320) << 20;   // update matrices of all workers above this (the 256 MB memory-side
                                                            // cache and a margin): the sweeps after the first treat M as a stream
-constexpr int kMfmaCols = 128;     // super-row columns a wavefront covers per 16-row step in the matrix-core P = M Q kernel
 
 // One matrix of the model.
 struct MatDesc {
@@ -45,8 +44,7 @@ struct MatDesc {
     int32_t n_rblock;   // row blocks of the Q = M^T P kernel (partials to sum)
     int32_t tensor;     // index in the caller's shape list
     int32_t n_gblock;   // tall panels: row blocks of the Gram / apply kernels; 0 = panel fits one workgroup's LDS
-    int32_t pack;       // rows fused into one "super-row" so that its length pack*m is a multiple of 4 (1, 2 or 4)
-    int32_t pad_;
+    int32_t pad_[2];
     int64_t chol_off;   // matrix-core path: offset (in doubles) of this matrix's Cholesky factor, r*r + r values
 };
 
@@ -69,7 +67,8 @@ constexpr int res_rows_for_rank(int r) { return r <= 2 ? 32 : 24; }   // ... few
 constexpr int kResMinRows = 8;       // strips are not made thinner than this
 constexpr int kResMaxN = 512;        // tallest matrix the single-wavefront Gram-Schmidt handles (8 rows per lane)
 constexpr int kResMaxRank = 4;
-constexpr int kResCUs = 256;         // MI355X compute units
+constexpr int kResCUs = 256;         // MI355X compute units: the planner's provisional figure (it runs without a device); the
+                                     // tiling is laid out again for the device's own count when the tables are uploaded
 constexpr int kResBlocksPerCU = 2;   // 256-thread workgroups per compute unit (8 wavefronts, 2 per SIMD)
 constexpr int kResTracePoints = 16;  // diagnostic timestamps per workgroup of the resident kernel
 
@@ -88,6 +87,7 @@ struct RTile {
     int32_t nqparts;     // partial-Q slots of this column chunk
     int32_t cntq;        // running index of this column chunk over the model
     int32_t cnts;        // running index of this strip over the model
+    int32_t delay;       // units of 512 clocks this wavefront sleeps before its first load (later load groups)
     int64_t elem0, nelem;  // vector tiles: slice of the vector region
 };
 
@@ -99,13 +99,10 @@ struct Tuning {
     int64_t k3_nv = 1;      // column vectors per lane (<= kMaxVecPerLaneK3)
     int64_t k4_rows = 0;    // rows per workgroup tile, decompress + residual; 0: 16 (32 for small sets)
     int64_t k4_nv = 1;
-    int64_t q_reduce_elems = 1024;  // accepted, unused (the Q reduction works on 64 elements per workgroup)
     int64_t hr_k3_rows = 2048;  // matrix-core Q = M^T P: rows per workgroup (four strips)
     int64_t hr_k4_rows = 0;     // matrix-core decompression: rows per workgroup (four strips of 16-row steps); 0 = by rank
     int64_t hr_k1_rows = 128;   // matrix-core P = M Q: rows per workgroup (multiple of 64, at most 256)
     int64_t hr_k1_cols = 2048;  // matrix-core P = M Q: columns per workgroup (multiple of 64); longer rows are split and their partial P summed
-    int64_t k1_mfma = 0;    // 1: P = M Q on the matrix cores when pack * rank <= 16 for every matrix (slower and less
-                            // accurate than the vector kernel at these ranks: kept for experiments)
     int64_t stream_hints = -1;  // sweeps 2 and 3 of the streaming path: non-temporal loads of M and stores of the error
                                 // memory (and temporal instead of non-temporal stores of Delta'); matrix-core path:
                                 // non-temporal loads of M in sweep 2.
@@ -115,7 +112,13 @@ struct Tuning {
                             // (diagnostic: the waits may time out, which psgd_plan_check then reports)
     int64_t gram_spin = 1 << 18;   // polls of one slot in that launch before a wait gives up
     int64_t bf16_valu = 1;  // bf16 gradients / output at rank <= 8: 1 = the streaming (vector-ALU) kernels, 0 = the matrix-core kernels
-    int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream
+    int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream; 2: as 1 without the check
+                            // against the device at upload (diagnostic, with res_max_blocks: lets a test see the waits give up)
+    int64_t res_spin = 1 << 21;      // polls before a wait of the resident kernel gives up
+    int64_t res_max_blocks = 0;      // 0: the device's capacity; else the most workgroups the resident tiling may use (diagnostic)
+    int64_t res_order = 1;           // order of the matrices in the resident tile list: 0 model order, 1 largest first
+    int64_t res_groups = 1;          // load groups: the tile list is cut into this many parts of about equal bytes ...
+    int64_t res_stagger = 0;         // ... and part g starts its loads g * res_stagger units of 512 clocks late
     int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height
     int64_t res_trace = 0;  // 1: the resident kernel records phase timestamps (diagnostic)
     int64_t xcd_order = -1;    // tile lists are ordered so that each accelerator die (own L2) works on one contiguous range of
@@ -164,7 +167,6 @@ struct psgd_plan {
     std::vector<psgd::Tile> tiles_gram;     // row blocks of tall panels (Cholesky-QR)
     std::vector<int32_t> small_mats;        // matrices orthogonalised by one workgroup (Gram-Schmidt in LDS)
     int64_t ws_gram_doubles = 0;            // workspace: Gram partials, after the float regions
-    bool k1_on_mfma = false;                // tiles1 are laid out for the matrix-core kernel
     // matrix-core path (rank > 8, or bf16 gradients / output)
     bool hr = false;
     int32_t hr_nt = 1;                      // 16-wide rank tiles
@@ -197,6 +199,7 @@ struct psgd_plan {
     std::string last_error;
     // per-kernel timing (benchmarks only)
     bool profiling = false;
+    bool compress_marked = false;            // a compress call has recorded its events since profiling was switched on
     void* events[PSGD_N_KERNELS + 2] = {};   // hipEvent_t: before/after each kernel
     double kernel_ms[PSGD_N_KERNELS] = {};
     int64_t profiled_steps = 0;
@@ -213,6 +216,8 @@ struct UpdateArgs {
 };
 // host planner (psgd_plan.cpp)
 psgd_status build_tables(psgd_plan* plan);
+// lays the resident tiling out for a device that holds `max_blocks` workgroups at once (sets plan->resident_ok)
+void build_resident(psgd_plan* plan, int64_t max_blocks);
 // device side (psgd_kernels.hip)
 psgd_status upload_tables(psgd_plan* plan);
 void free_tables(psgd_plan* plan);
@@ -234,7 +239,7 @@ psgd_status check_plan(psgd_plan* plan, void* stream);
 psgd_status read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t* n_written);
 psgd_status resident_check_device(psgd_plan* plan);
 psgd_status launch_resident_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,
-                                 void* workspace, void* stream, const UpdateArgs& upd = UpdateArgs());
+                                 void* workspace, void* stream, const UpdateArgs& upd = UpdateArgs(), int iterations = 1);
 // The resident kernel's synchronisation words (units of unsigned), one 256-byte line each: an error word
 // (a wait gave up), the epoch that tags this step's mailbox slots, the count of finished workgroups.
 constexpr int kSyncLineWords = 64;

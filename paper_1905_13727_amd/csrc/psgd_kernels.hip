@@ -159,110 +159,6 @@ __global__ __launch_bounds__(kBlock) void k_ef_right(const MatDesc* __restrict__
     }
 }
 
-// ---- k_ef_right_mfma: the same on the matrix cores -------------------------------------------------
-//
-// P = M Q is a product with a tiny inner shape (n x m times m x r, r <= 16): written for the vector
-// ALUs, most instructions are the cross-lane sums of the row dot products.  v_mfma_f32_16x16x4_f32
-// does the multiply and the sum over columns in one instruction: A = a 16 x 4 block of M (lane l
-// supplies row l % 16, column 4 (l / 16) + c of a 16-column group, taken from the c-th component
-// of one 16-byte load), B = the matching 4 x 16 block of Q, padded with zeros beyond the rank.
-// fp32 in, fp32 accumulate.  Rows whose length is not a multiple of 4 are fused in pairs / fours
-// into "super-rows" of length pack * m (a multiple of 4, so every 16-byte load is aligned); the rank
-// axis then carries one block of r outputs per fused row: B'[c'][s r + j] = Q[c' - s m][j] for
-// columns c' of sub-row s, so that a load that straddles two rows feeds both dot products.
-//
-// A wavefront walks a strip of super-rows 16 at a time over a chunk of kMfmaCols columns, keeping
-// the B blocks of the chunk in registers; M = g + e is written back as it goes.
-
-typedef float v4f __attribute__((ext_vector_type(4)));
-
-__global__ __launch_bounds__(kBlock) void k_ef_right_mfma(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
-                                                          const float* __restrict__ grad, float* __restrict__ err,
-                                                          const float* __restrict__ q, float* __restrict__ ws,
-                                                          int64_t gstride, int64_t estride) {
-    constexpr int NG = kMfmaCols / 16;   // 16-column groups per chunk
-    const Tile t = tiles[blockIdx.x];
-    const MatDesc d = mats[t.mat];
-    const int w = blockIdx.y;
-    const float* g = grad + (int64_t)w * gstride + d.off;
-    float* e = err + (int64_t)w * estride + d.off;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int ri = d.r, pack = d.pack, m = d.m, n = d.n;
-    const int sm = pack * m;                       // super-row length
-    const int li = lane & 15, kb = lane >> 4;
-    const int c_end = t.vec0 + t.nvec;             // first column after the chunk
-
-    // B blocks of the chunk: lane holds, for group u and component c, B'[col'][j] with
-    // col' = vec0 + 16 u + 4 kb + c and j = li
-    float bq[NG][4];
-    {
-        const int s_j = li / ri, jj = li % ri;     // fused-row block and rank index of this lane's output column
-#pragma unroll
-        for (int u = 0; u < NG; ++u)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int colp = t.vec0 + 16 * u + 4 * kb + c;
-                float v = 0.f;
-                if (colp < c_end && s_j < pack) {
-                    const int s = colp / m, col = colp - s * m;
-                    if (s == s_j) v = q[d.q_off + (int64_t)col * ri + jj];
-                }
-                bq[u][c] = v;
-            }
-    }
-
-    // the four wavefronts take 16-row steps of the tile's super-rows in turn
-    const int nsteps = (t.nrows + 15) / 16;
-    for (int step = wave; step < nsteps; step += kWavesPerBlock) {
-        const int srow = t.row0 + 16 * step + li;                  // this lane's super-row
-        const int rows_here = min(pack, n - pack * srow);          // real rows in it (<= 0: none)
-        const int valid_len = rows_here > 0 ? rows_here * m : 0;   // valid prefix of the super-row
-        const int64_t base = (int64_t)srow * sm;
-        v4f gv[NG], ev[NG];
-#pragma unroll
-        for (int u = 0; u < NG; ++u) {
-            const int colp = t.vec0 + 16 * u + 4 * kb;
-            gv[u] = v4f{0.f, 0.f, 0.f, 0.f};
-            ev[u] = v4f{0.f, 0.f, 0.f, 0.f};
-            if (colp < c_end && colp < valid_len) {
-                gv[u] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(g + base + colp));
-                ev[u] = *reinterpret_cast<const v4f*>(e + base + colp);
-            }
-        }
-        v4f acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int u = 0; u < NG; ++u) {
-            const int colp = t.vec0 + 16 * u + 4 * kb;
-            v4f mv = gv[u] + ev[u];
-            if (colp < c_end && colp < valid_len) {
-                if (colp + 4 <= valid_len) {
-                    *reinterpret_cast<v4f*>(e + base + colp) = mv;
-                } else {
-                    // the last real row ends inside this vector: what follows is not part of the matrix
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        if (colp + c < valid_len) e[base + colp + c] = mv[c];
-                        else mv[c] = 0.f;
-                    }
-                }
-            }
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(mv[c], bq[u][c], acc, 0, 0, 0);
-        }
-        // acc[v] = P'[super-row 16 step + 4 kb + v][li]: fused row li / ri, rank li % ri
-        const int s_j = li / ri, jj = li % ri;
-        if (s_j < pack) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int row = pack * (t.row0 + 16 * step + 4 * kb + v) + s_j;
-                if (16 * step + 4 * kb + v < t.nrows && row < n)
-                    ws[d.ppart_off + ((int64_t)(w * d.n_cchunk + t.part) * n + row) * ri + jj] = acc[v];
-            }
-        }
-    }
-}
-
 // sum of `nparts` partial slices (stride `stride` floats) at `src`, in slice order, eight loads in flight
 __device__ __forceinline__ float sum_parts(const float* __restrict__ src, int nparts, int64_t stride) {
     float s = 0.f;
@@ -984,6 +880,7 @@ psgd_status set_profiling(psgd_plan* plan, bool enable) {
         }
     }
     plan->profiling = enable;
+    plan->compress_marked = false;
     return PSGD_OK;
 }
 
@@ -1001,8 +898,8 @@ void free_tables(psgd_plan* plan) {
     plan->uploaded = false;
 }
 
-// k_gram_chol: the row blocks of a matrix wait for each other.  Workgroups start in index order and a matrix's row
-// blocks are consecutive, so it is enough that the largest matrix's blocks fit the device at once.
+// k_gram_chol: the row blocks of a matrix wait for each other, so the one-launch form is taken only when the whole
+// grid fits the device at once (no assumption about the order in which workgroups are started).
 static psgd_status gram_fused_check_device(psgd_plan* plan) {
     plan->gram_fused = false;
     if (plan->hr || !plan->tuning.gram_fused || plan->tiles_gram.empty()) return PSGD_OK;
@@ -1022,17 +919,15 @@ static psgd_status gram_fused_check_device(psgd_plan* plan) {
         default: break;
     }
     if (e != hipSuccess) return hip_fail(plan, e, "occupancy(k_gram_chol)");
-    int max_blocks = 0;
-    for (const MatDesc& d : plan->mats) max_blocks = std::max(max_blocks, (int)d.n_gblock);
-    // with room to spare; gram_fused = 2 skips the test (diagnostic: lets a test see the waits time out)
-    plan->gram_fused = plan->tuning.gram_fused == 2 || (int64_t)cus * occ >= 2 * (int64_t)max_blocks;
+    // gram_fused = 2 skips the test (diagnostic: lets a test see the waits time out)
+    plan->gram_fused = plan->tuning.gram_fused == 2 || (int64_t)cus * occ >= (int64_t)plan->tiles_gram.size();
     return PSGD_OK;
 }
 
 psgd_status upload_tables(psgd_plan* plan) {
     if (plan->uploaded) return PSGD_OK;
     PSGD_HIP(hipGetDevice(&plan->device), "hipGetDevice");
-    if (plan->resident_ok) {
+    if (!plan->hr && plan->tuning.resident) {   // lays the resident tiling out for this device
         psgd_status st = resident_check_device(plan);
         if (st != PSGD_OK) return st;
     }
@@ -1121,9 +1016,11 @@ psgd_status read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t
     return PSGD_OK;
 }
 
-// Waits for the stream; reports and clears a barrier time-out of the resident kernel.
+// Waits for the stream; reports a wait that gave up in one of the kernels whose workgroups wait for each other,
+// resets that kernel's hand-over words and switches its mode off for the rest of the plan's life: the step then
+// runs on the kernels that need no co-residency (streaming sweeps; Gram matrices and factorisation in two launches).
 psgd_status check_plan(psgd_plan* plan, void* stream) {
-    if (!plan->uploaded) return PSGD_OK;
+    if (!plan->uploaded) return upload_tables(plan);   // nothing has run yet: just bring the tables to the device
     PSGD_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)), "hipStreamSynchronize");
     if (plan->gram_fused && plan->dev.gram_sync) {
         unsigned flag = 0;
@@ -1137,7 +1034,9 @@ psgd_status check_plan(psgd_plan* plan, void* stream) {
             const unsigned one = 1;
             PSGD_HIP(hipMemcpy(plan->dev.gram_sync + res_sync_epoch(), &one, sizeof(one), hipMemcpyHostToDevice),
                      "hipMemcpy(epoch)");
-            plan->last_error = "k_gram_chol: a wait timed out (row blocks of a matrix not co-resident?)";
+            if (plan->tuning.gram_fused != 2) plan->gram_fused = false;   // 2: the diagnostic setting keeps the mode
+            plan->last_error = "k_gram_chol: a wait timed out (row blocks not co-resident: is the GPU shared?); "
+                               "the plan continues with the two-launch factorisation";
             return PSGD_EHIP;
         }
     }
@@ -1154,7 +1053,9 @@ psgd_status check_plan(psgd_plan* plan, void* stream) {
         const unsigned one = 1;
         PSGD_HIP(hipMemcpy(plan->dev.res_sync + res_sync_epoch(), &one, sizeof(one), hipMemcpyHostToDevice),
                  "hipMemcpy(epoch)");
-        plan->last_error = "resident kernel: a wait timed out (grid not co-resident?)";
+        plan->resident_ok = false;
+        plan->last_error = "resident kernel: a wait timed out (grid not co-resident: is the GPU shared?); "
+                           "the plan continues on the streaming kernels";
         return PSGD_EHIP;
     }
     return PSGD_OK;
@@ -1254,20 +1155,14 @@ psgd_status launch_compress(psgd_plan* plan, const void* grad, float* err, float
     psgd_status st = check_ready(plan);
     if (st != PSGD_OK) return st;
     if (plan->hr) return hr_compress(plan, grad, err, q, p, workspace, stream, add);
-    if (!add && plan->k1_on_mfma) return PSGD_EUNSUPPORTED;   // the experimental matrix-core K1 always adds
     hipStream_t s = static_cast<hipStream_t>(stream);
     float* ws = static_cast<float*>(workspace);
     const void* g = grad;
     if (plan->mats.empty()) return PSGD_OK;
 
     PSGD_MARK(0);
-    if (plan->k1_on_mfma) {
-        hipLaunchKernelGGL(k_ef_right_mfma, dim3((unsigned)plan->tiles1.size(), (unsigned)plan->workers), dim3(kBlock), 0, s,
-                           plan->dev.mats, plan->dev.tiles1, static_cast<const float*>(g), err, q, ws, plan->sizes.grad_stride,
-                           plan->sizes.err_stride);
-    } else {
-        PSGD_RANK_SWITCH(launch_ef_right, plan, g, err, q, ws, s, add);
-    }
+    plan->compress_marked = plan->profiling;
+    PSGD_RANK_SWITCH(launch_ef_right, plan, g, err, q, ws, s, add);
     PSGD_HIP(hipGetLastError(), "launch k_ef_right");
     PSGD_MARK(1);
 
@@ -1356,6 +1251,7 @@ psgd_status launch_decompress(psgd_plan* plan, const float* p, const float* q, f
 // measurement mode: wait for the step, then add its per-kernel times (compress must have run first)
 psgd_status finish_profiled_step(psgd_plan* plan) {
     if (!plan->profiling) return PSGD_OK;
+    if (!plan->compress_marked) return PSGD_OK;   // no psgd_compress recorded its events since profiling was switched on
     PSGD_HIP(hipEventSynchronize(static_cast<hipEvent_t>(plan->events[6])), "hipEventSynchronize");
     static const int first[5] = {0, 1, 2, 3, 5};
     for (int k = 0; k < 5; ++k) {

@@ -135,7 +135,6 @@ static int64_t group_tiles(const psgd_plan* plan) {
     return std::min<int64_t>(2048, std::max<int64_t>(128, 4096 / plan->workers));
 }
 
-void build_resident(psgd_plan* plan);
 
 // Matrix-core path: its own tilings and workspace layout.
 static psgd_status build_hr_tables(psgd_plan* plan) {
@@ -150,7 +149,6 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
     plan->tiles1.clear(); plan->tiles3.clear(); plan->tiles4.clear(); plan->tiles4u.clear(); plan->tilesp.clear();
     plan->small_mats.clear(); plan->tiles_gram.clear(); plan->tilesq.clear();
     plan->hr_tiles1.clear(); plan->hr_tiles3.clear(); plan->hr_tiles4.clear();
-    plan->k1_on_mfma = false;
     plan->p_pre_reduce = false;
     const int64_t right_rows = tu.hr_k1_rows;
     // rows per workgroup of the decompression: measured best on the 24-layer transformer set at ranks 16, 32, 64
@@ -246,7 +244,10 @@ psgd_status build_tables(psgd_plan* plan) {
     if (plan->out_dtype != PSGD_F32 && tu.k4_nv != 1) return PSGD_EINVAL;   // bf16 output: one column vector per lane
     if (tu.k1_rows < 0 || tu.k3_rows < 0 || tu.k4_rows < 0 || tu.k1_nv < 1 ||
         tu.k1_nv > kMaxVecPerLaneK1 || tu.k3_nv < 1 || tu.k3_nv > kMaxVecPerLaneK3 || tu.k4_nv < 1 ||
-        tu.k4_nv > kMaxVecPerLaneK3 || tu.q_reduce_elems < 1 || tu.res_rows < 0 || tu.res_rows > kResRows ||
+        tu.k4_nv > kMaxVecPerLaneK3 || tu.res_rows < 0 || tu.res_rows > kResRows || tu.resident < 0 || tu.resident > 2 ||
+        tu.res_spin < 1 || tu.res_spin > (int64_t(1) << 30) || tu.res_max_blocks < 0 || tu.res_max_blocks > 65535 ||
+        tu.res_order < 0 || tu.res_order > 1 || tu.res_groups < 1 || tu.res_groups > 8 || tu.res_stagger < 0 ||
+        tu.res_stagger > 1024 ||
         tu.stream_hints < -1 || tu.stream_hints > 1 || tu.xcd_order < -1 || tu.gram_fused < 0 || tu.gram_fused > 2 || tu.gram_spin < 1 ||
         tu.gram_spin > (1 << 24))
         return PSGD_EINVAL;
@@ -258,34 +259,7 @@ psgd_status build_tables(psgd_plan* plan) {
             (int64_t(1) << 31))
             return PSGD_EUNSUPPORTED;
     std::vector<int32_t> nrb(nm, 0), ncc(nm, 0);
-    // P = M Q: matrix-core tiling (16-row steps of super-rows x kMfmaCols columns per wavefront) when every
-    // matrix fits pack * rank <= 16, else the vector-ALU tiling
-    plan->k1_on_mfma = tu.k1_mfma != 0 && plan->grad_dtype == PSGD_F32;
-    for (const MatDesc& d : plan->mats)
-        if (d.pack * d.r > 16) plan->k1_on_mfma = false;
-    if (plan->k1_on_mfma) {
-        plan->tiles1.clear();
-        const int64_t rows_per_tile = round_up(std::max<int64_t>(tu.k1_rows > 0 ? tu.k1_rows : 32, 16), 16);   // super-rows per workgroup
-        for (size_t i = 0; i < nm; ++i) {
-            const MatDesc& d = plan->mats[i];
-            const int64_t sm = (int64_t)d.pack * d.m, sn = ceil_div(d.n, d.pack);
-            const int64_t nchunk = ceil_div(sm, kMfmaCols);
-            ncc[i] = (int32_t)nchunk;
-            for (int64_t r0 = 0; r0 < sn; r0 += rows_per_tile)
-                for (int64_t c = 0; c < nchunk; ++c) {
-                    Tile t{};
-                    t.mat = (int32_t)i;
-                    t.row0 = (int32_t)r0;                                        // first super-row
-                    t.nrows = (int32_t)std::min<int64_t>(rows_per_tile, sn - r0); // super-rows
-                    t.vec0 = (int32_t)(c * kMfmaCols);                           // first super-row column
-                    t.nvec = (int32_t)std::min<int64_t>(kMfmaCols, sm - c * kMfmaCols);   // columns
-                    t.part = (int32_t)c;
-                    plan->tiles1.push_back(t);
-                }
-        }
-    } else {
-        streaming_tiles(plan, 1, tu.k1_rows, tu.k1_nv, true, &plan->tiles1, nullptr, &ncc);
-    }
+    streaming_tiles(plan, 1, tu.k1_rows, tu.k1_nv, true, &plan->tiles1, nullptr, &ncc);
     streaming_tiles(plan, 2, tu.k3_rows, tu.k3_nv, false, &plan->tiles3, &nrb, nullptr);
     streaming_tiles(plan, 3, tu.k4_rows, tu.k4_nv, false, &plan->tiles4, nullptr, nullptr);
 
@@ -380,7 +354,7 @@ psgd_status build_tables(psgd_plan* plan) {
     }
     plan->stream_hints = tu.stream_hints < 0 ? W * plan->sizes.n_mat_elems * (int64_t)sizeof(float) > kStreamHintBytes
                                              : tu.stream_hints != 0;
-    build_resident(plan);
+    build_resident(plan, (int64_t)kResCUs * kResBlocksPerCU);
     plan->sizes.workspace_bytes =
         std::max<int64_t>(plan->sizes.workspace_bytes, plan->res_ws_floats * (int64_t)sizeof(float));
     // The planner's own choice: groups; for one worker and a set beyond the memory-side cache the whole list instead
@@ -405,7 +379,7 @@ static int64_t resident_tiles_for(const psgd_plan* plan, int h) {
     return total;
 }
 
-void build_resident(psgd_plan* plan) {
+void build_resident(psgd_plan* plan, int64_t device_blocks) {
     plan->resident_ok = false;
     plan->res_tiles.clear();
     plan->res_mats.clear();
@@ -416,10 +390,22 @@ void build_resident(psgd_plan* plan) {
     if (plan->grad_dtype != PSGD_F32 || plan->out_dtype != PSGD_F32) return;
     for (const MatDesc& d : plan->mats)
         if (d.n > kResMaxN) return;
-    const int64_t max_blocks = (int64_t)kResCUs * kResBlocksPerCU;
+    const int64_t max_blocks = tu.res_max_blocks > 0 ? tu.res_max_blocks : device_blocks;
     const int64_t L = plan->sizes.n_vec_elems;
     const int64_t vec_slice = (int64_t)kWave * 4 * 8;   // elements of the vector region per wavefront
     const int64_t vec_tiles = ceil_div(L, vec_slice);
+
+    // Order of the matrices in the tile list.  Largest first: the matrices with the longest dependency chains
+    // (most strips and column chunks) sit in the first workgroups, whose loads are issued and served first.
+    std::vector<size_t> order(plan->mats.size());
+    for (size_t i = 0; i < order.size(); ++i) order[i] = i;
+    if (tu.res_order == 1)
+        std::stable_sort(order.begin(), order.end(), [&](size_t x, size_t y) {
+            const MatDesc& a = plan->mats[x];
+            const MatDesc& b = plan->mats[y];
+            if (a.vec != b.vec) return a.vec > b.vec;   // one access width per workgroup: keep the widths together
+            return (int64_t)a.n * a.m > (int64_t)b.n * b.m;
+        });
 
     auto layout = [&](int h, std::vector<RTile>* tiles, std::vector<MatDesc>* mats, int32_t* n_cntq,
                       int32_t* n_cnts) -> int64_t {
@@ -427,13 +413,15 @@ void build_resident(psgd_plan* plan) {
         int64_t slots = 0;            // wavefront slots used so far (multiple of 4 at block boundaries)
         int32_t cntq = 0, cnts = 0;
         int cur_vec = 0;
+        if (mats) mats->assign(plan->mats.size(), MatDesc{});
         auto pad_block = [&]() {
             while (slots % kWavesPerBlock) {
                 if (tiles) { RTile t{}; t.mat = -2; tiles->push_back(t); }
                 ++slots;
             }
         };
-        for (size_t i = 0; i < plan->mats.size(); ++i) {
+        for (size_t oi = 0; oi < order.size(); ++oi) {
+            const size_t i = order[oi];
             const MatDesc& d0 = plan->mats[i];
             if (d0.vec != cur_vec) { pad_block(); cur_vec = d0.vec; }
             const int64_t nvec = d0.m / d0.vec;
@@ -482,7 +470,7 @@ void build_resident(psgd_plan* plan) {
                 MatDesc d = d0;
                 d.n_cchunk = (int32_t)nchunk;
                 d.n_rblock = max_runs;
-                mats->push_back(d);
+                (*mats)[i] = d;
             }
             cnts += (int32_t)nstrip;
         }
@@ -523,6 +511,22 @@ void build_resident(psgd_plan* plan) {
     plan->res_blocks = (int32_t)blocks;
     plan->res_n_cntq = n_cntq;
     plan->res_n_cnts = n_cnts;
+    // Load groups: whole matrices in list order, a group closed once it holds its share of the elements; the
+    // wavefronts of group g start their loads g * res_stagger units late.
+    if (tu.res_groups > 1 && tu.res_stagger > 0) {
+        int64_t total = 0, seen = 0;
+        for (const MatDesc& d : plan->mats) total += (int64_t)d.n * d.m;
+        std::vector<int32_t> group_of(plan->mats.size(), 0);
+        for (size_t oi = 0; oi < order.size(); ++oi) {
+            const MatDesc& d = plan->mats[order[oi]];
+            // the group in which the middle of this matrix falls
+            const int64_t mid = seen + (int64_t)d.n * d.m / 2;
+            group_of[order[oi]] = (int32_t)std::min<int64_t>(tu.res_groups - 1, mid * tu.res_groups / std::max<int64_t>(total, 1));
+            seen += (int64_t)d.n * d.m;
+        }
+        for (RTile& t : plan->res_tiles)
+            t.delay = t.mat >= 0 ? group_of[t.mat] * (int32_t)tu.res_stagger : (t.mat == -1 ? (int32_t)((tu.res_groups - 1) * tu.res_stagger) : 0);
+    }
     // mailbox of the resident kernel (64-bit slots): per matrix [partial P | mean P | P_hat], then per
     // matrix [partial Q | Q]; the offsets are kept in res_mats
     int64_t off = 0;
@@ -592,7 +596,6 @@ psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_
             d.m = (int32_t)shapes[t].cols;
             d.r = std::min<int32_t>(rank, std::min(d.n, d.m));
             d.vec = (d.m % 4 == 0) ? 4 : (d.m % 2 == 0 ? 2 : 1);
-            d.pack = 4 / d.vec;
             d.off = N;
             d.p_off = P;
             d.q_off = Q;
@@ -684,8 +687,6 @@ psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value
     else if (!strcmp(key, "k3_nv")) tu.k3_nv = value;
     else if (!strcmp(key, "k4_rows")) tu.k4_rows = value;
     else if (!strcmp(key, "k4_nv")) tu.k4_nv = value;
-    else if (!strcmp(key, "q_reduce_elems")) tu.q_reduce_elems = value;
-    else if (!strcmp(key, "k1_mfma")) tu.k1_mfma = value;
     else if (!strcmp(key, "hr_k3_rows")) tu.hr_k3_rows = value;
     else if (!strcmp(key, "xcd_order")) tu.xcd_order = value;
     else if (!strcmp(key, "hr_k4_rows")) tu.hr_k4_rows = value;
@@ -698,6 +699,11 @@ psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value
     else if (!strcmp(key, "gram_spin")) tu.gram_spin = value;
     else if (!strcmp(key, "res_rows")) tu.res_rows = value;
     else if (!strcmp(key, "res_trace")) tu.res_trace = value;
+    else if (!strcmp(key, "res_spin")) tu.res_spin = value;
+    else if (!strcmp(key, "res_max_blocks")) tu.res_max_blocks = value;
+    else if (!strcmp(key, "res_order")) tu.res_order = value;
+    else if (!strcmp(key, "res_groups")) tu.res_groups = value;
+    else if (!strcmp(key, "res_stagger")) tu.res_stagger = value;
     else return PSGD_EINVAL;
     Tuning old = plan->tuning;
     plan->tuning = tu;
@@ -734,6 +740,17 @@ psgd_status psgd_step(psgd_plan* plan, const void* grad, float* err, float* q, f
     if (!plan || bad_ptrs(grad, err, q, p, workspace) || !out) return PSGD_EINVAL;
     if (plan->resident_ok) return launch_resident_step(plan, grad, err, q, p, out, workspace, hip_stream);
     psgd_status st = launch_compress(plan, grad, err, q, p, workspace, hip_stream);
+    if (st != PSGD_OK) return st;
+    return launch_decompress(plan, p, q, err, grad, out, workspace, hip_stream);
+}
+
+psgd_status psgd_step_iterations(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,
+                                 void* workspace, void* hip_stream, int32_t iterations) {
+    if (!plan || bad_ptrs(grad, err, q, p, workspace) || !out || iterations < 1 || iterations > 64) return PSGD_EINVAL;
+    if (plan->resident_ok) return launch_resident_step(plan, grad, err, q, p, out, workspace, hip_stream, UpdateArgs(), iterations);
+    psgd_status st = launch_compress(plan, grad, err, q, p, workspace, hip_stream);
+    for (int32_t it = 1; it < iterations && st == PSGD_OK; ++it)
+        st = launch_compress(plan, err, err, q, p, workspace, hip_stream, false);
     if (st != PSGD_OK) return st;
     return launch_decompress(plan, p, q, err, grad, out, workspace, hip_stream);
 }

@@ -32,6 +32,7 @@
 // kernel always terminates.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 
@@ -55,6 +56,8 @@ struct ResArgs {
     int32_t nblocks;
     int64_t n_mat_elems;
     unsigned long long* trace;   // diagnostic: kResTracePoints timestamps per workgroup, or nullptr
+    unsigned spin;               // polls before a wait gives up
+    int32_t iters;               // subspace iterations per step (ITER kernels; 1 otherwise)
     UpdateArgs upd;              // UPD kernels: momentum / parameter buffers and step sizes (Algorithm 2's last lines)
 };
 
@@ -104,10 +107,13 @@ __device__ __forceinline__ void gram_schmidt_rows(float (&P)[kResRowsPerLane][R]
 }
 
 // ---- the step, for a workgroup whose tiles use V-wide row accesses ---------------------------------------
-template <int R, int V, bool UPD>
-__device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, float* lds, unsigned epoch) {
+// ITER: several subspace iterations on the resident tile (Appendix G.7): P = M Q, orthogonalise, Q = M^T P_hat
+// repeated a.iters times before the decompression, each round under its own mailbox tag epoch0 + round.
+template <int R, int V, bool UPD, bool ITER>
+__device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, float* lds, unsigned epoch0) {
     constexpr int RT = res_rows_for_rank(R);
-    const int lane = threadIdx.x & (kWave - 1);
+    const int lane_id = threadIdx.x & (kWave - 1);
+    const int lane = lane_id;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const bool active = t.mat >= 0;
     const MatDesc d = a.mats[active ? t.mat : 0];
@@ -119,10 +125,11 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
     unsigned* err_word = a.sync + res_sync_err();
     // mailbox regions of this matrix (slots)
     const int64_t nr = (int64_t)d.n * ri, mr = (int64_t)d.m * ri;
-    slot_t* mail_pp = a.mail + d.ppart_off;               // partial P   [n_cchunk][n][r]
-    slot_t* mail_pb = mail_pp + (int64_t)d.n_cchunk * nr; // mean P      [n][r]
-    slot_t* mail_ph = mail_pb + nr;                       // P_hat       [n][r]
-    slot_t* mail_qp = a.mail + d.qpart_off;               // partial Q   [n_rblock][m][r]
+    slot_t* mail_base = a.mail;
+
+    // A wavefront of a later load group lets the earlier groups' requests reach the memory system first, so that
+    // their dependency chains run under this group's loads and their stores under this group's chains.
+    for (int dl = 0; dl < t.delay; ++dl) __builtin_amdgcn_s_sleep(8);
 
     // ---------------- phase A ----------------
     trace_mark(a, 0);
@@ -165,6 +172,21 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
                 for (int x = 0; x < V; ++x) M[i][x] += e[i][x];
         }
     }
+    const int iters = ITER ? a.iters : 1;
+    float pr[R];
+    for (int it = 0; it < iters; ++it) {
+    const unsigned epoch = epoch0 + (unsigned)it;
+    int lane = lane_id;
+    if constexpr (ITER) {
+        // the slot addresses are formed anew in every round: computed once before the loop they would all be held
+        // in registers across it, which the tile of M leaves no room for
+        asm volatile("" : "+s"(mail_base));
+        asm volatile("" : "+v"(lane));
+    }
+    slot_t* mail_pp = mail_base + d.ppart_off;            // partial P   [n_cchunk][n][r]
+    slot_t* mail_pb = mail_pp + (int64_t)d.n_cchunk * nr; // mean P      [n][r]
+    slot_t* mail_ph = mail_pb + nr;                       // P_hat       [n][r]
+    slot_t* mail_qp = mail_base + d.qpart_off;            // partial Q   [n_rblock][m][r]
     {
         // the strip's row dot products: lane i receives row i's (rows past the strip were read as zeros)
         float mine[R];
@@ -232,7 +254,7 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
 #pragma unroll
                     for (int cc = 0; cc < CG; ++cc) ok &= arrived(w[cc], epoch);
                     return ok;
-                }, err_word);
+                }, err_word, epoch, a.spin);
 #pragma unroll
                 for (int cc = 0; cc < CG; ++cc)
                     if (c0 + cc < d.n_cchunk) s += value_of(w[cc]);
@@ -257,7 +279,7 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
 #pragma unroll
                         for (int k = 0; k < R; ++k) ok &= arrived(w[j][k], epoch);
                     return ok;
-                }, err_word);
+                }, err_word, epoch, a.spin);
 #pragma unroll
                 for (int j = 0; j < kResRowsPerLane; ++j)
 #pragma unroll
@@ -285,7 +307,6 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
     trace_mark(a, 2);
 
     // ---------------- phase B ----------------
-    float pr[R];
 #pragma unroll
     for (int k = 0; k < R; ++k) pr[k] = 0.f;
     if (active) {
@@ -298,7 +319,7 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
 #pragma unroll
             for (int k = 0; k < R; ++k) ok &= arrived(w[k], epoch);
             return ok;
-        }, err_word);
+        }, err_word, a.spin);
 #pragma unroll
         for (int k = 0; k < R; ++k) pr[k] = (lane < nrows && k < ri) ? value_of(w[k]) : 0.f;
     }
@@ -373,7 +394,7 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
 #pragma unroll
                             for (int k = 0; k < R; ++k) ok &= arrived(w[u][x][k], epoch);
                     return ok;
-                }, err_word);
+                }, err_word, epoch, a.spin);
 #pragma unroll
                 for (int u = 0; u < PG; ++u)
 #pragma unroll
@@ -402,19 +423,25 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
     trace_mark(a, 4);
     __syncthreads();
 
-    // ---------------- phase C ----------------
-    float qb[V][R];
+    // this chunk's rows of Q, for the decompression or the next round's P = M Q
 #pragma unroll
     for (int x = 0; x < V; ++x)
 #pragma unroll
-        for (int k = 0; k < R; ++k) qb[x][k] = 0.f;
+        for (int k = 0; k < R; ++k) qr[x][k] = 0.f;
     if (active) {
 #pragma unroll
         for (int x = 0; x < V; ++x)
 #pragma unroll
             for (int k = 0; k < R; ++k)
-                qb[x][k] = (valid && k < ri) ? lds[((wave * V + x) * R + k) * kWave + lane] : 0.f;
+                qr[x][k] = (valid && k < ri) ? lds[((wave * V + x) * R + k) * kWave + lane] : 0.f;
     }
+    if constexpr (ITER) {
+        if (it + 1 < iters) __syncthreads();   // shared memory is written again in the next round
+    }
+    }   // rounds
+
+    // ---------------- phase C ----------------
+    float (&qb)[V][R] = qr;
     trace_mark(a, 5);
     constexpr int CG = UPD ? 4 : 1;   // rows whose momentum / parameter loads are in flight together
 #pragma unroll
@@ -474,7 +501,7 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
     trace_mark(a, 6);
 }
 
-template <int R, bool UPD>
+template <int R, bool UPD, bool ITER>
 __global__ __launch_bounds__(kBlock, 2) void k_resident(ResArgs a) {
     __shared__ float lds[kWavesPerBlock * 4 * R * kWave];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -486,16 +513,16 @@ __global__ __launch_bounds__(kBlock, 2) void k_resident(ResArgs a) {
     // all tiles of a workgroup use the same access width; the first slot is never idle
     const RTile t0 = a.tiles[blockIdx.x * kWavesPerBlock];
     const int vec = t0.mat >= 0 ? a.mats[t0.mat].vec : 4;
-    if (vec == 4) resident_body<R, 4, UPD>(a, t, lds, epoch);
-    else if (vec == 2) resident_body<R, 2, UPD>(a, t, lds, epoch);
-    else resident_body<R, 1, UPD>(a, t, lds, epoch);
+    if (vec == 4) resident_body<R, 4, UPD, ITER>(a, t, lds, epoch);
+    else if (vec == 2) resident_body<R, 2, UPD, ITER>(a, t, lds, epoch);
+    else resident_body<R, 1, UPD, ITER>(a, t, lds, epoch);
     // the workgroup that finishes last advances the epoch for the next launch
     __syncthreads();
     if (threadIdx.x == 0) {
         unsigned* done = a.sync + res_sync_done();
         if (add_dev(done, 1u) == (unsigned)a.nblocks - 1u) {
             add_dev(done, 0u - (unsigned)a.nblocks);
-            st_dev(a.sync + res_sync_epoch(), epoch + 1u);
+            st_dev(a.sync + res_sync_epoch(), epoch + (ITER ? (unsigned)a.iters : 1u));   // one tag per round
         }
     }
 }
@@ -505,16 +532,20 @@ __global__ __launch_bounds__(kBlock, 2) void k_resident(ResArgs a) {
 template <int R>
 static hipError_t launch_k_resident(const ResArgs& a, int blocks, hipStream_t s, int* max_blocks_per_cu) {
     if (max_blocks_per_cu) {
-        int plain = 0, fused = 0;   // both variants must be co-resident
-        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&plain, k_resident<R, false>, kBlock, 0);
+        // every variant must be co-resident
+        int occ[3] = {0, 0, 0};
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ[0], k_resident<R, false, false>, kBlock, 0);
         if (e != hipSuccess) return e;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&fused, k_resident<R, true>, kBlock, 0);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ[1], k_resident<R, true, false>, kBlock, 0);
         if (e != hipSuccess) return e;
-        *max_blocks_per_cu = plain < fused ? plain : fused;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ[2], k_resident<R, false, true>, kBlock, 0);
+        if (e != hipSuccess) return e;
+        *max_blocks_per_cu = std::min(occ[0], std::min(occ[1], occ[2]));
         return hipSuccess;
     }
-    if (a.upd.mom) hipLaunchKernelGGL((k_resident<R, true>), dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
-    else hipLaunchKernelGGL((k_resident<R, false>), dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
+    if (a.upd.mom) hipLaunchKernelGGL((k_resident<R, true, false>), dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
+    else if (a.iters > 1) hipLaunchKernelGGL((k_resident<R, false, true>), dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
+    else hipLaunchKernelGGL((k_resident<R, false, false>), dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
     return hipGetLastError();
 }
 
@@ -528,30 +559,38 @@ static hipError_t dispatch_resident(int rank, const ResArgs& a, int blocks, hipS
     }
 }
 
-// Checks, once per plan, that the resident grid fits the device all at once.
+// Once per plan, when its tables are uploaded: the resident tiling is laid out again for the number of workgroups
+// THIS device holds at once (compute units x workgroups per unit of the kernel); the planner's own figure is a
+// provisional one, since it runs without a device.  A model that does not fit streams instead.
 psgd_status resident_check_device(psgd_plan* plan) {
     int dev = 0, cus = 0, occ = 0;
     if (hipGetDevice(&dev) != hipSuccess) return PSGD_EHIP;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return PSGD_EHIP;
     ResArgs dummy{};
     if (dispatch_resident(plan->rank, dummy, 0, nullptr, &occ) != hipSuccess) return PSGD_EHIP;
-    if ((int64_t)cus * occ < plan->res_blocks) {
-        plan->resident_ok = false;   // not co-resident on this device: the streaming path takes over
-    }
+    if (plan->tuning.resident == 2) return PSGD_OK;   // diagnostic: keep the planner's grid whatever the device holds
+    build_resident(plan, (int64_t)cus * std::min(occ, kResBlocksPerCU));
     return PSGD_OK;
 }
 
+// The step on the streaming kernels: what a plan without (or no longer with) a resident tiling runs.
+static psgd_status streamed_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,
+                                 void* workspace, void* stream, const UpdateArgs& upd, int iterations) {
+    psgd_status st = launch_compress(plan, grad, err, q, p, workspace, stream);
+    for (int it = 1; it < iterations && st == PSGD_OK; ++it)
+        st = launch_compress(plan, err, err, q, p, workspace, stream, false);
+    if (st != PSGD_OK) return st;
+    return launch_decompress(plan, p, q, err, grad, out, workspace, stream, upd);
+}
+
 psgd_status launch_resident_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,
-                                 void* workspace, void* stream, const UpdateArgs& upd) {
+                                 void* workspace, void* stream, const UpdateArgs& upd, int iterations) {
     if (!plan->uploaded) {
         psgd_status st = upload_tables(plan);
         if (st != PSGD_OK) return st;
-        if (!plan->resident_ok) {   // upload found that the grid does not fit this device
-            st = launch_compress(plan, grad, err, q, p, workspace, stream);
-            if (st != PSGD_OK) return st;
-            return launch_decompress(plan, p, q, err, grad, out, workspace, stream, upd);
-        }
     }
+    // the upload may have found that the grid does not fit this device; a wait that gave up switches the mode off
+    if (!plan->resident_ok) return streamed_step(plan, grad, err, q, p, out, workspace, stream, upd, iterations);
     hipStream_t s = static_cast<hipStream_t>(stream);
     ResArgs a{};
     a.upd = upd;
@@ -562,12 +601,13 @@ psgd_status launch_resident_step(psgd_plan* plan, const void* grad, float* err, 
     a.q = q;
     a.p = p;
     a.out = static_cast<float*>(out);
-    (void)workspace;   // the resident kernel communicates through the plan-owned mailbox
     a.mail = reinterpret_cast<slot_t*>(plan->dev.res_mail);
     a.sync = plan->dev.res_sync;
     a.nblocks = plan->res_blocks;
     a.n_mat_elems = plan->sizes.n_mat_elems;
     a.trace = plan->dev.res_trace;
+    a.spin = (unsigned)plan->tuning.res_spin;
+    a.iters = iterations;
     if (plan->profiling) {
         hipError_t e = hipEventRecord(static_cast<hipEvent_t>(plan->events[0]), s);
         if (e != hipSuccess) { plan->last_error = hipGetErrorString(e); return PSGD_EHIP; }

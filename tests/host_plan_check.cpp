@@ -16,7 +16,7 @@ void free_tables(psgd_plan*) {}
 psgd_status set_profiling(psgd_plan*, bool) { return PSGD_EHIP; }
 psgd_status check_plan(psgd_plan*, void*) { return PSGD_EHIP; }
 psgd_status read_trace(psgd_plan*, uint64_t*, int64_t, int64_t*) { return PSGD_EHIP; }
-psgd_status launch_resident_step(psgd_plan*, const void*, float*, float*, float*, void*, void*, void*, const UpdateArgs&) {
+psgd_status launch_resident_step(psgd_plan*, const void*, float*, float*, float*, void*, void*, void*, const UpdateArgs&, int) {
     return PSGD_EHIP;
 }
 psgd_status launch_compress(psgd_plan*, const void*, float*, float*, float*, void*, void*, bool) { return PSGD_EHIP; }
@@ -176,39 +176,7 @@ static void check_resident(const psgd_plan* plan) {
     }
 }
 
-static void check_p_tiling(const psgd_plan* plan) {
-    if (plan->k1_on_mfma) {
-        // matrix-core tiling of P = M Q: tiles are (super-rows x super-row columns); every element once
-        std::vector<std::vector<unsigned char>> seen(plan->mats.size());
-        for (size_t i = 0; i < plan->mats.size(); ++i) seen[i].assign((size_t)plan->mats[i].n * plan->mats[i].m, 0);
-        for (const Tile& t : plan->tiles1) {
-            CHECK(t.mat >= 0 && t.mat < (int)plan->mats.size());
-            const MatDesc& d = plan->mats[t.mat];
-            const int64_t sm = (int64_t)d.pack * d.m, sn = (d.n + d.pack - 1) / d.pack;
-            CHECK(d.pack * d.r <= 16 && sm % 4 == 0 && d.off % 4 == 0);
-            CHECK(t.row0 >= 0 && t.nrows > 0 && t.row0 + t.nrows <= sn && t.row0 % 16 == 0);
-            CHECK(t.vec0 >= 0 && t.vec0 % kMfmaCols == 0 && t.nvec > 0 && t.nvec <= kMfmaCols && t.vec0 + t.nvec <= sm);
-            CHECK(t.part >= 0 && t.part < d.n_cchunk && t.part == t.vec0 / kMfmaCols);
-            for (int64_t I = t.row0; I < t.row0 + t.nrows; ++I)
-                for (int64_t c = t.vec0; c < t.vec0 + t.nvec; ++c) {
-                    const int64_t row = I * d.pack + c / d.m, col = c % d.m;
-                    if (row >= d.n) continue;
-                    unsigned char& sf = seen[t.mat][(size_t)row * d.m + col];
-                    CHECK(sf == 0);
-                    sf = 1;
-                }
-        }
-        for (auto& v : seen)
-            for (unsigned char sf : v) CHECK(sf == 1);
-        // a 16-byte load that starts on a valid element ends inside the matrix's padded extent
-        for (const MatDesc& d : plan->mats) {
-            const int64_t padded = ((int64_t)d.n * d.m + kAlignElems - 1) / kAlignElems * kAlignElems;
-            CHECK(((int64_t)d.n * d.m + 3) / 4 * 4 <= padded);
-        }
-    } else {
-        check_cover(plan, plan->tiles1, (int)plan->tuning.k1_nv, 1);
-    }
-}
+static void check_p_tiling(const psgd_plan* plan) { check_cover(plan, plan->tiles1, (int)plan->tuning.k1_nv, 1); }
 
 static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int workers, const Tuning* tu) {
     psgd_plan* plan = nullptr;
@@ -220,16 +188,8 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
         CHECK(psgd_plan_set_tuning(plan, "k3_nv", tu->k3_nv) == PSGD_OK);
         CHECK(psgd_plan_set_tuning(plan, "k4_rows", tu->k4_rows) == PSGD_OK);
         CHECK(psgd_plan_set_tuning(plan, "k4_nv", tu->k4_nv) == PSGD_OK);
-        CHECK(psgd_plan_set_tuning(plan, "q_reduce_elems", tu->q_reduce_elems) == PSGD_OK);
     }
     check_resident(plan);
-    {
-        // both tilings of P = M Q are checked (check_cover below sees whichever is active; flip and check the other)
-        const int64_t was = plan->tuning.k1_mfma;
-        CHECK(psgd_plan_set_tuning(plan, "k1_mfma", was ? 0 : 1) == PSGD_OK);
-        check_p_tiling(plan);
-        CHECK(psgd_plan_set_tuning(plan, "k1_mfma", was) == PSGD_OK);
-    }
     for (int64_t rr : {5, 8, 13, 24, 32}) {
         CHECK(psgd_plan_set_tuning(plan, "res_rows", rr) == PSGD_OK);
         if (rr > res_rows_for_rank(rank)) CHECK(!plan->resident_ok);
@@ -380,7 +340,6 @@ int main() {
     };
     Tuning small;
     small.k1_rows = 8; small.k1_nv = 1; small.k3_rows = 16; small.k3_nv = 1; small.k4_rows = 8; small.k4_nv = 1;
-    small.q_reduce_elems = 256;
     Tuning big;
     big.k1_rows = 64; big.k1_nv = 2; big.k3_rows = 300; big.k3_nv = 2; big.k4_rows = 300; big.k4_nv = 2;
     for (auto& s : sets)
