@@ -563,6 +563,7 @@ static hipError_t dispatch_resident(int rank, const ResArgs& a, int blocks, hipS
 // THIS device holds at once (compute units x workgroups per unit of the kernel); the planner's own figure is a
 // provisional one, since it runs without a device.  A model that does not fit streams instead.
 psgd_status resident_check_device(psgd_plan* plan) {
+    if (plan->rank > kResMaxRank || plan->workers != 1) return PSGD_OK;   // never resident: nothing to lay out
     int dev = 0, cus = 0, occ = 0;
     if (hipGetDevice(&dev) != hipSuccess) return PSGD_EHIP;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return PSGD_EHIP;
