@@ -217,6 +217,20 @@ PSGD_API psgd_status psgd_step(psgd_plan* plan, const void* grad, float* err, fl
 PSGD_API psgd_status psgd_iterate(psgd_plan* plan, float* err, float* q, float* p, void* workspace,
                          void* hip_stream);
 
+/* psgd_step for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the workspace is not an argument but an array the library itself holds on
+ * every GPU it is loaded on (PSGD_STATIC_WORKSPACE_BYTES, part of the code object, kept until the process
+ * ends).  The call allocates and frees nothing and otherwise behaves exactly like psgd_step with that workspace.
+ * Conditions: the plan's tables are on the device already (psgd_plan_check, or any earlier GPU call on the plan,
+ * puts them there; that upload is the one allocation a plan makes) - else PSGD_EINVAL; the plan's
+ * workspace_bytes fit - else PSGD_EUNSUPPORTED (the ResNet18-shaped set up to 16 workers and the LSTM-shaped set
+ * fit, the 24-layer transformer-shaped set does not); the current device is the plan's.  All plans on a GPU share
+ * the one array and it keeps whatever the last call left there (the kernels read nothing of it that they have
+ * not written in the same call): calls that overlap in time on one GPU, from any plan or stream, race. */
+#define PSGD_STATIC_WORKSPACE_BYTES (32u << 20)
+PSGD_API psgd_status psgd_step_static(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,
+                                      void* hip_stream);
+
 /* One whole step with `iterations` subspace iterations (Appendix G.7, "best-approximation PowerSGD"; Table 2):
  * the same quantities as psgd_compress, iterations - 1 calls of psgd_iterate, psgd_decompress.  iterations = 1 is
  * psgd_step.  A plan in resident mode (see psgd_step) keeps M on chip through all the iterations: one kernel, each

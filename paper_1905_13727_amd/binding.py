@@ -69,6 +69,8 @@ def load_library(path: Optional[str] = None):
     lib.psgd_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psgd_step_iterations.restype = C.c_int
     lib.psgd_step_iterations.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32]
+    lib.psgd_step_static.restype = C.c_int
+    lib.psgd_step_static.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.psgd_plan_set_profiling.restype = C.c_int
     lib.psgd_iterate.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.psgd_iterate.restype = C.c_int
@@ -178,6 +180,10 @@ class Plan:
         self._check(self._lib.psgd_step_iterations(self._h, _ptr(grad), _ptr(err), _ptr(q), _ptr(p), _ptr(out),
                                                    _ptr(workspace), _ptr(stream), int(iterations)),
                     "psgd_step_iterations")
+
+    def step_static(self, grad, err, q, p, out, stream=None):
+        self._check(self._lib.psgd_step_static(self._h, _ptr(grad), _ptr(err), _ptr(q), _ptr(p), _ptr(out),
+                                               _ptr(stream)), "psgd_step_static")
 
     def iterate(self, err, q, p, workspace, stream=None):
         self._check(self._lib.psgd_iterate(self._h, _ptr(err), _ptr(q), _ptr(p), _ptr(workspace), _ptr(stream)),

@@ -195,6 +195,7 @@ struct psgd_plan {
     bool tables_built = false;
     bool uploaded = false;
     int device = -1;
+    void* static_ws = nullptr;              // the library-owned workspace on that device (psgd_step_static)
     psgd::DeviceTables dev;
     std::string last_error;
     // per-kernel timing (benchmarks only)
@@ -236,6 +237,7 @@ psgd_status hr_decompress(psgd_plan* plan, const float* p, const float* q, float
                           void* stream, const UpdateArgs& upd);
 psgd_status launch_vector_mean(psgd_plan* plan, const void* grad, void* out, void* stream, const UpdateArgs& upd);
 psgd_status check_plan(psgd_plan* plan, void* stream);
+psgd_status static_workspace(psgd_plan* plan, void** ws);
 psgd_status read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t* n_written);
 psgd_status resident_check_device(psgd_plan* plan);
 psgd_status launch_resident_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,

@@ -26,6 +26,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "psgd_device.h"
 #include "psgd_internal.h"
@@ -854,6 +855,29 @@ __global__ __launch_bounds__(kBlock) void k_decomp(const MatDesc* __restrict__ m
 
 // ---- host side ------------------------------------------------------------------------------------
 
+// Workspace owned by the library, for callers that cannot allocate (psgd_step_static): one array per GPU, part of
+// the loaded code object, held until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; its device address differs from GPU to GPU and is looked up once per device, with that
+// device current, when a plan's tables are uploaded there.
+static __device__ __align__(256) unsigned char scratch[PSGD_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each GPU (nullptr: not looked up yet)
+static std::mutex g_scratch_mutex;
+
+static hipError_t scratch_address(int device, void** out) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));   // the current device's copy
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
 static psgd_status hip_fail(psgd_plan* plan, hipError_t err, const char* what) {
     plan->last_error = std::string(what) + ": " + hipGetErrorString(err);
     return err == hipErrorOutOfMemory ? PSGD_ENOMEM : PSGD_EHIP;
@@ -927,6 +951,7 @@ static psgd_status gram_fused_check_device(psgd_plan* plan) {
 psgd_status upload_tables(psgd_plan* plan) {
     if (plan->uploaded) return PSGD_OK;
     PSGD_HIP(hipGetDevice(&plan->device), "hipGetDevice");
+    PSGD_HIP(scratch_address(plan->device, &plan->static_ws), "hipGetSymbolAddress(static workspace)");
     if (!plan->hr && plan->tuning.resident) {   // lays the resident tiling out for this device
         psgd_status st = resident_check_device(plan);
         if (st != PSGD_OK) return st;
@@ -1013,6 +1038,30 @@ psgd_status read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t
     PSGD_HIP(hipDeviceSynchronize(), "hipDeviceSynchronize");
     PSGD_HIP(hipMemcpy(out, plan->dev.res_trace, (size_t)n * sizeof(uint64_t), hipMemcpyDeviceToHost), "hipMemcpy(trace)");
     *n_written = n;
+    return PSGD_OK;
+}
+
+// The library-owned workspace of the device the plan lives on, for a plan whose tables are there already and whose
+// workspace fits it; nothing is allocated here.
+psgd_status static_workspace(psgd_plan* plan, void** ws) {
+    if (!plan->uploaded || !plan->static_ws) {
+        plan->last_error = "psgd_step_static: the plan's tables are not on the device yet (psgd_plan_check, or any "
+                           "other GPU call on the plan, uploads them; that first call allocates)";
+        return PSGD_EINVAL;
+    }
+    if (plan->sizes.workspace_bytes > (int64_t)PSGD_STATIC_WORKSPACE_BYTES) {
+        plan->last_error = "psgd_step_static: the plan needs " + std::to_string(plan->sizes.workspace_bytes) +
+                           " bytes of workspace, the library-owned one holds " +
+                           std::to_string((long long)PSGD_STATIC_WORKSPACE_BYTES);
+        return PSGD_EUNSUPPORTED;
+    }
+    int dev = -1;
+    PSGD_HIP(hipGetDevice(&dev), "hipGetDevice");
+    if (dev != plan->device) {
+        plan->last_error = "psgd_step_static: the current device is not the one the plan's tables were uploaded to";
+        return PSGD_EINVAL;
+    }
+    *ws = plan->static_ws;
     return PSGD_OK;
 }
 

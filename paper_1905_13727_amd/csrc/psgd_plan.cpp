@@ -744,6 +744,15 @@ psgd_status psgd_step(psgd_plan* plan, const void* grad, float* err, float* q, f
     return launch_decompress(plan, p, q, err, grad, out, workspace, hip_stream);
 }
 
+psgd_status psgd_step_static(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,
+                             void* hip_stream) {
+    if (!plan || !grad || !err || !q || !p || !out) return PSGD_EINVAL;
+    void* ws = nullptr;
+    psgd_status st = static_workspace(plan, &ws);
+    if (st != PSGD_OK) return st;
+    return psgd_step(plan, grad, err, q, p, out, ws, hip_stream);
+}
+
 psgd_status psgd_step_iterations(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,
                                  void* workspace, void* hip_stream, int32_t iterations) {
     if (!plan || bad_ptrs(grad, err, q, p, workspace) || !out || iterations < 1 || iterations > 64) return PSGD_EINVAL;

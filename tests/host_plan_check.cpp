@@ -15,6 +15,7 @@ namespace psgd {
 void free_tables(psgd_plan*) {}
 psgd_status set_profiling(psgd_plan*, bool) { return PSGD_EHIP; }
 psgd_status check_plan(psgd_plan*, void*) { return PSGD_EHIP; }
+psgd_status static_workspace(psgd_plan*, void**) { return PSGD_EHIP; }
 psgd_status read_trace(psgd_plan*, uint64_t*, int64_t, int64_t*) { return PSGD_EHIP; }
 psgd_status launch_resident_step(psgd_plan*, const void*, float*, float*, float*, void*, void*, void*, const UpdateArgs&, int) {
     return PSGD_EHIP;
