@@ -125,10 +125,28 @@ def cpu_baseline(wl, rank, workers, budget_s):
         if spent >= budget_s or steps >= 50:
             break
     gbs = workers * n_elems * 4 / (spent / steps) / 1e9
-    return {"value": round(gbs, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
-            "ms_per_step": round(1e3 * spent / steps, 3),
-            "sample": "%d full steps of the %s workload (W=%d, r=%d), numpy fp64, same gradient each step"
-                      % (steps, wl.name, workers, rank)}
+    rec = {"value": round(gbs, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+           "ms_per_step": round(1e3 * spent / steps, 3),
+           "sample": "%d full steps of the %s workload (W=%d, r=%d), numpy fp64, same gradient each step"
+                     % (steps, wl.name, workers, rank)}
+    # the same with the numerical library held to one thread (a few steps, at most a fifth of the budget again)
+    try:
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=1):
+            n1, spent1 = 0, 0.0
+            while True:
+                t0 = time.perf_counter()
+                res = O.powersgd_step(grads, errs, q, rank)
+                spent1 += time.perf_counter() - t0
+                q, errs = res["Q"], res["err"]
+                n1 += 1
+                if spent1 >= budget_s / 5 or n1 >= 10:
+                    break
+        rec["single_thread"] = {"value": round(workers * n_elems * 4 / (spent1 / n1) / 1e9, 4), "unit": "GB/s",
+                                "ms_per_step": round(1e3 * spent1 / n1, 3), "steps": n1}
+    except Exception:
+        rec["single_thread"] = None
+    return rec
 
 
 def main():
@@ -180,11 +198,8 @@ def main():
             return 2
 
     def step(i):
-        if args.iterations > 1:   # Appendix G.7: several subspace iterations per step (split calls, never resident)
-            plan.compress(grads[i % len(grads)], err, q, p, ws, sh)
-            for _ in range(args.iterations - 1):
-                plan.iterate(err, q, p, ws, sh)
-            plan.decompress(p, q, err, grads[i % len(grads)], out, ws, sh)
+        if args.iterations > 1:   # Appendix G.7: several subspace iterations per step (on chip when the plan is resident)
+            plan.step_iterations(grads[i % len(grads)], err, q, p, out, ws, args.iterations, sh)
             return
         if args.update == "fused":
             plan.step_update(grads[i % len(grads)], err, q, p, mom, par, 0.01, 0.9, ws, sh)
@@ -230,7 +245,7 @@ def main():
     # A resident step is one launch, so the events around the timed region give that kernel's average launch
     # duration directly (back to back, as timed); the per-launch event pairs of the profiling pass add about 3 us
     # each and stay in `kernel_ms` for reference.  Multi-kernel steps keep the per-kernel pairs.
-    if resident and args.update == "none" and args.iterations == 1:
+    if resident and args.update != "separate":
         kavg_events = dict(kavg)
         kavg = {k: 0.0 for k in kavg}
         kavg["k_resident"] = event_ms_per_step
@@ -253,6 +268,20 @@ def main():
         cold_ms = {"median": round(ts[len(ts) // 2], 4), "min": round(ts[0], 4)}
         del flush
 
+    # the dominant kernel's duration in the cold pass: a resident step is that one kernel; a multi-kernel step
+    # gets the per-kernel event pairs again, with the caches flushed before every step
+    cold_kavg = None
+    if cold_ms is not None and not (resident and args.update != "separate") and args.profile_steps > 0:
+        flush = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device=dev)
+        plan.set_profiling(True)
+        for i in range(args.cold_steps):
+            flush.fill_(float(i))
+            step(i)
+        ckms, csteps = plan.kernel_times()
+        plan.set_profiling(False)
+        cold_kavg = {k: v / max(1, csteps) for k, v in ckms.items()}
+        del flush
+
     payload_mat = s.payload_elems - s.n_vec_elems
     L = s.n_vec_elems
     # algorithmic bytes per launch of each kernel (fp32): what the kernel itself has to move
@@ -263,11 +292,24 @@ def main():
         "k_decomp": payload_mat * (W * 8 + osz) + L * (W * gsz + osz),      # read M, write e', write Delta' once
         "k_resident": int(s.bytes_min),                           # read g, e; write e', Delta': each once
     }
+    if args.update == "fused":   # Delta' is not stored; momentum and parameters are read and written instead
+        extra = (payload_mat + L) * (16 - osz)
+        kernel_bytes["k_resident"] += extra
+        kernel_bytes["k_decomp"] += extra
+    if args.iterations > 1:      # the library's event pairs then hold the last round, whose P = M Q only reads M
+        kernel_bytes["k_ef_right"] = payload_mat * W * 4
     dom = max(kernel_bytes, key=lambda k: kavg.get(k, 0.0))
     achieved = kernel_bytes[dom] / (kavg[dom] * 1e-3) / 1e9 if kavg[dom] > 0 else 0.0
     grad_bytes = W * (payload_mat + L) * gsz
     value = grad_bytes / (ms_per_step * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC.get((wl.name, rank, W, dom))
+    if args.update != "none" or args.iterations != 1 or tune:
+        traffic = None   # the counters were taken on the plain step with the planner's own choices
+    if resident and args.update != "separate":
+        cold_dom_ms = cold_ms["median"] if cold_ms else None
+    else:
+        cold_dom_ms = cold_kavg[dom] if cold_kavg and cold_kavg.get(dom, 0.0) > 0 else None
+    achieved_cold = kernel_bytes[dom] / (cold_dom_ms * 1e-3) / 1e9 if cold_dom_ms else None
 
     rec = {
         "metric": METRIC if (wl.name, rank, W) == ("resnet18", 2, 1) and gdt == "f32" and odt == "f32"
@@ -292,21 +334,38 @@ def main():
                    "matrices": int(s.n_matrices), "matrix_elems": int(payload_mat), "vector_elems": int(L),
                    "grad_buffers": len(grads), "update": args.update,
                    "iterations": args.iterations},
-        "stream_model": {"bytes_per_step": int(s.bytes_stream),
-                         "GBps": round(s.bytes_stream / (ms_per_step * 1e-3) / 1e9, 2),
-                         "frac_of_hbm_peak": round(s.bytes_stream / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        # Byte models of the whole step over the timed (warm, back-to-back) steps.  min_model: every element of g, e
+        # read once and of e', Delta' written once - what a resident step moves.  stream_model: the same plus the two
+        # re-reads of M that the method's two global reductions force on kernels that cannot keep M on chip - what a
+        # streaming or matrix-core step moves; a resident step does not move these bytes, so the model is not
+        # reported for it.
         "min_model": {"bytes_per_step": int(s.bytes_min),
                       "GBps": round(s.bytes_min / (ms_per_step * 1e-3) / 1e9, 2),
                       "frac_of_hbm_peak": round(s.bytes_min / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "stream_model": None if resident else {
+            "bytes_per_step": int(s.bytes_stream),
+            "GBps": round(s.bytes_stream / (ms_per_step * 1e-3) / 1e9, 2),
+            "frac_of_hbm_peak": round(s.bytes_stream / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        # cold: caches flushed before every step, outside the timing - gradients and error memory come from HBM as
+        # they would after a real backward pass.  The primary regime; `value` and `roofline.frac` are the timed
+        # region's (warm), the cold fractions stand beside them.
         "cold_ms_per_step": cold_ms,
-        "cold_stream_model_frac_of_hbm_peak": (round(s.bytes_stream / (cold_ms["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-                                               if cold_ms else None),
+        "cold": None if not cold_ms else {
+            "value": round(grad_bytes / (cold_ms["median"] * 1e-3) / 1e9, 3), "unit": "GB/s",
+            "min_model_frac_of_hbm_peak": round(s.bytes_min / (cold_ms["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "stream_model_frac_of_hbm_peak": None if resident else
+                round(s.bytes_stream / (cold_ms["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "event_ms_per_step": round(event_ms_per_step, 5),
         "kernel_ms": {k: round(v, 5) for k, v in kavg_events.items()},
+        "cold_kernel_ms": None if not cold_kavg else {k: round(v, 5) for k, v in cold_kavg.items()},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": int(kernel_bytes[dom]),
-                     "avg_launch_ms": round(kavg[dom], 5)},
+                     "avg_launch_ms": round(kavg[dom], 5),
+                     "regime": "warm (the timed region: steps back to back)",
+                     "achieved_cold": None if achieved_cold is None else round(achieved_cold, 2),
+                     "frac_cold": None if achieved_cold is None else round(achieved_cold / HBM_PEAK_GBS, 4),
+                     "avg_launch_ms_cold": None if cold_dom_ms is None else round(cold_dom_ms, 5)},
     }
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(wl, rank, W, args.cpu_seconds)

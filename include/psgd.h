@@ -129,7 +129,7 @@ PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, in
  *   res_spin      polls before a wait of the resident kernel gives up, 1 .. 2^30 (default 2^21)
  *   res_max_blocks  TEST ONLY: most workgroups the resident tiling may use (0, the default: what the device
  *                 holds at once, found when the plan's tables are uploaded)
- *   res_order     order of the matrices in the resident tile list: 1 (default) largest first, 0 model order
+ *   res_order     order of the matrices in the resident tile list: 0 (default) model order, 1 largest first
  *   res_groups, res_stagger   the resident tile list is cut into res_groups parts of about equal size (1 .. 8)
  *                 and the wavefronts of part g start loading g * res_stagger units of 512 clocks late
  *   k1_rows, k1_nv / k3_rows, k3_nv / k4_rows, k4_nv
@@ -288,11 +288,13 @@ PSGD_API const char* psgd_kernel_name(int32_t index);
 PSGD_API psgd_status psgd_plan_check(psgd_plan* plan, void* hip_stream, int32_t* is_resident);
 
 /* Diagnostic.  After psgd_plan_set_tuning(plan, "res_trace", 1), every resident
- * step records 16 device timestamps (100 MHz clock) per wavefront: start, partial
- * P posted, reducer work done, P_hat received, partial Q posted, Q received, end;
- * 7..11 are written by a wavefront that orthogonalises (own partial posted,
- * strip sum posted, mean P received, Gram-Schmidt done, P_hat posted); the rest
- * is unused.  Synchronises the device and copies at most
+ * step records 16 values per wavefront: device timestamps (100 MHz clock) of start,
+ * partial P posted, reducer work done, P_hat received, partial Q posted, Q received,
+ * end; 7..11 are written by a wavefront that orthogonalises (own partial posted,
+ * strip sum posted, mean P received, Gram-Schmidt done, P_hat posted); 12..15 name
+ * the tile: matrix, column chunk (upper half: the hardware id register of the
+ * wavefront), first row (upper half: accelerator die), partial-Q slot or -1.
+ * Synchronises the device and copies at most
  * `capacity` values of the last step to `out` (host); *n_written = count. */
 PSGD_API psgd_status psgd_plan_read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t* n_written);
 

@@ -116,7 +116,7 @@ struct Tuning {
                             // against the device at upload (diagnostic, with res_max_blocks: lets a test see the waits give up)
     int64_t res_spin = 1 << 21;      // polls before a wait of the resident kernel gives up
     int64_t res_max_blocks = 0;      // 0: the device's capacity; else the most workgroups the resident tiling may use (diagnostic)
-    int64_t res_order = 1;           // order of the matrices in the resident tile list: 0 model order, 1 largest first
+    int64_t res_order = 0;           // order of the matrices in the resident tile list: 0 model order, 1 largest first
     int64_t res_groups = 1;          // load groups: the tile list is cut into this many parts of about equal bytes ...
     int64_t res_stagger = 0;         // ... and part g starts its loads g * res_stagger units of 512 clocks late
     int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height

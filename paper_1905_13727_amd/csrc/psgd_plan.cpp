@@ -395,8 +395,9 @@ void build_resident(psgd_plan* plan, int64_t device_blocks) {
     const int64_t vec_slice = (int64_t)kWave * 4 * 8;   // elements of the vector region per wavefront
     const int64_t vec_tiles = ceil_div(L, vec_slice);
 
-    // Order of the matrices in the tile list.  Largest first: the matrices with the longest dependency chains
-    // (most strips and column chunks) sit in the first workgroups, whose loads are issued and served first.
+    // Order of the matrices in the tile list: model order, or largest first (the matrices with the most strips and
+    // column chunks then sit in the first workgroups, whose loads are issued and served first; measured on the
+    // ResNet18-shaped set it is 1 % slower than model order, which therefore stays the default).
     std::vector<size_t> order(plan->mats.size());
     for (size_t i = 0; i < order.size(); ++i) order[i] = i;
     if (tu.res_order == 1)

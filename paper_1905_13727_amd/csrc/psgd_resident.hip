@@ -136,8 +136,12 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
     if (a.trace && lane == 0) {
         unsigned long long* tr = a.trace + ((size_t)blockIdx.x * kWavesPerBlock + wave) * kResTracePoints;
         tr[12] = (unsigned long long)(long long)t.mat;
-        tr[13] = (unsigned long long)t.ppart;
-        tr[14] = (unsigned long long)t.row0;
+        // with the wavefront's place on the chip in the upper halves: hardware id (compute unit, shader array and
+        // engine, SIMD, slot) and accelerator die
+        const unsigned long long hw_id = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_ID, all 32 bits
+        const unsigned long long xcc_id = __builtin_amdgcn_s_getreg((31 << 11) | 20);  // XCC_ID, all 32 bits
+        tr[13] = (unsigned long long)(unsigned)t.ppart | (hw_id << 32);
+        tr[14] = (unsigned long long)(unsigned)t.row0 | (xcc_id << 32);
         tr[15] = (unsigned long long)(t.qrun_len > 0 ? t.qpart : -1);
     }
     float M[RT][V];
@@ -152,15 +156,18 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
 #pragma unroll
         for (int i = 0; i < RT; ++i) buf_ldv<V>(gres, coff + (unsigned)i * (unsigned)d.m * 4u, M[i], true);
         if constexpr (RT > 24) {
-            // the tallest strips: e row by row behind the arrival of g (no room for a second tile of registers)
+            // the tallest strips have no room for a second whole tile of registers: e in two halves, all loads of a
+            // half in flight together (row by row behind single loads the phase is bound by their latency)
+            constexpr int H = RT / 2;
 #pragma unroll
-            for (int i = 0; i < RT; ++i) {
-                if (i < nrows && valid) {
-                    float e[V];
-                    ldv<V>(a.err + tile_off + (int64_t)i * d.m, e);
+            for (int h = 0; h < 2; ++h) {
+                float e[H][V];
 #pragma unroll
-                    for (int x = 0; x < V; ++x) M[i][x] += e[x];
-                }
+                for (int i = 0; i < H; ++i) buf_ldv<V>(eres, coff + (unsigned)(h * H + i) * (unsigned)d.m * 4u, e[i]);
+#pragma unroll
+                for (int i = 0; i < H; ++i)
+#pragma unroll
+                    for (int x = 0; x < V; ++x) M[h * H + i][x] += e[i][x];
             }
         } else {
             float e[RT][V];
