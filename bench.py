@@ -59,6 +59,9 @@ def parse():
                          "(psgd_step_update) or as separate elementwise kernels after psgd_step")
     ap.add_argument("--iterations", type=int, default=1,
                     help="subspace iterations per step (psgd_compress, then psgd_iterate, then psgd_decompress)")
+    ap.add_argument("--compressor", choices=["powersgd", "random_block", "random_k"], default="powersgd",
+                    help="powersgd (the headline), or one of the linear baselines of Appendix G run in the same "
+                         "error-feedback loop (their random draws are made before the timed region)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing")
     ap.add_argument("--tune", action="append", default=[], help="key=value planner tuning (experiments)")
@@ -101,10 +104,12 @@ def device_gradients(wl, lay, plan, workers, seed, torch, dev, dtype=None):
     return grad
 
 
-def cpu_baseline(wl, rank, workers, budget_s):
+def cpu_baseline(wl, rank, workers, budget_s, compressor="powersgd"):
     """The oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
     from oracle import powersgd_oracle as O
     from paper_1905_13727_amd import workloads as WL
+    if compressor != "powersgd":
+        return cpu_baseline_sparse(wl, rank, workers, budget_s, compressor)
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
@@ -147,6 +152,30 @@ def cpu_baseline(wl, rank, workers, budget_s):
     except Exception:
         rec["single_thread"] = None
     return rec
+
+
+def cpu_baseline_sparse(wl, rank, workers, budget_s, compressor):
+    """The oracle's Random Block / Random K step on the same workload (numpy fp64; the draws are not timed)."""
+    from oracle import powersgd_oracle as O
+    from paper_1905_13727_amd import workloads as WL
+    factors = WL.planted_factors(wl, 0)
+    errs = [[None if len(s) == 1 else np.zeros(s) for s in wl.shapes] for _ in range(workers)]
+    grads = [WL.gradients(wl, factors, 0, 0, w) for w in range(workers)]
+    n_elems = sum(int(np.prod(s)) for s in wl.shapes)
+    steps, spent = 0, 0.0
+    while True:
+        draw = WL.block_starts(wl, rank, 0, steps) if compressor == "random_block" else WL.random_indices(wl, rank, 0, steps)
+        t0 = time.perf_counter()
+        res = (O.random_block_step if compressor == "random_block" else O.random_k_step)(grads, errs, draw, rank)
+        spent += time.perf_counter() - t0
+        errs = res["err"]
+        steps += 1
+        if spent >= budget_s or steps >= 50:
+            break
+    return {"value": round(workers * n_elems * 4 / (spent / steps) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "ms_per_step": round(1e3 * spent / steps, 3),
+            "sample": "%d full %s steps of the %s workload (W=%d, r=%d), numpy fp64 elementwise (one thread), same "
+                      "gradient each step, draws not timed" % (steps, compressor, wl.name, workers, rank)}
 
 
 def main():
@@ -197,7 +226,37 @@ def main():
             print("bench.py: --update separate needs an f32 output", file=sys.stderr)
             return 2
 
+    sparse = args.compressor != "powersgd"
+    if sparse:
+        if gdt != "f32" or odt != "f32" or args.update != "none" or args.iterations != 1:
+            print("bench.py: the baselines run in fp32, without fused update or iterations", file=sys.stderr)
+            return 2
+        vals = torch.zeros(max(1, s.kept_elems), dtype=torch.float32, device=dev)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(7)
+        draws = []
+        for _ in range(len(grads)):      # one draw per gradient batch, made before the timed region
+            if args.compressor == "random_block":
+                st = torch.zeros(len(wl.shapes), dtype=torch.int64, device=dev)
+                for t, shp in enumerate(wl.shapes):
+                    if len(shp) == 2:
+                        st[t] = int(torch.randint(0, shp[0] * shp[1], (1,), generator=gen, device=dev))
+                draws.append(st)
+            else:
+                ix = torch.zeros(max(1, s.kept_elems), dtype=torch.int64, device=dev)
+                for t, shp in enumerate(wl.shapes):
+                    if len(shp) == 2:
+                        off, n = plan.kept(t)
+                        ix[off: off + n] = torch.randperm(shp[0] * shp[1], generator=gen, device=dev)[:n]
+                draws.append(ix)
+
     def step(i):
+        if sparse:
+            if args.compressor == "random_block":
+                plan.random_block_step(grads[i % len(grads)], err, draws[i % len(draws)], vals, out, sh)
+            else:
+                plan.random_k_step(grads[i % len(grads)], err, draws[i % len(draws)], vals, out, sh)
+            return
         if args.iterations > 1:   # Appendix G.7: several subspace iterations per step (on chip when the plan is resident)
             plan.step_iterations(grads[i % len(grads)], err, q, p, out, ws, args.iterations, sh)
             return
@@ -245,12 +304,19 @@ def main():
     # A resident step is one launch, so the events around the timed region give that kernel's average launch
     # duration directly (back to back, as timed); the per-launch event pairs of the profiling pass add about 3 us
     # each and stay in `kernel_ms` for reference.  Multi-kernel steps keep the per-kernel pairs.
+    if sparse:
+        resident = False
+    kavg_events = dict(kavg)
     if resident and args.update != "separate":
-        kavg_events = dict(kavg)
         kavg = {k: 0.0 for k in kavg}
         kavg["k_resident"] = event_ms_per_step
-    else:
-        kavg_events = kavg
+    elif args.update != "separate" and sum(kavg.values()) > 0:
+        # Multi-kernel steps: the pass above waits for the stream after every step, so each of its event pairs also
+        # holds the start-up of a kernel launched onto an idle GPU (the pairs add up to 10-40 % more than a step of
+        # the timed region takes).  A kernel's launch duration over the timed region is therefore taken as the
+        # region's time per step (events around the K back-to-back steps) times that kernel's share of the pairs.
+        total = sum(kavg.values())
+        kavg = {k: event_ms_per_step * v / total for k, v in kavg.items()}
 
     # cold-cache pass: a 1 GiB fill between steps evicts L2 and the memory-side cache
     cold_ms = None
@@ -280,6 +346,9 @@ def main():
         ckms, csteps = plan.kernel_times()
         plan.set_profiling(False)
         cold_kavg = {k: v / max(1, csteps) for k, v in ckms.items()}
+        ctotal = sum(cold_kavg.values())
+        if ctotal > 0:   # the same apportioning, of the cold pass's own time per step
+            cold_kavg = {k: cold_ms["median"] * v / ctotal for k, v in cold_kavg.items()}
         del flush
 
     payload_mat = s.payload_elems - s.n_vec_elems
@@ -291,6 +360,8 @@ def main():
         "k_left": payload_mat * W * 4,                                      # read M
         "k_decomp": payload_mat * (W * 8 + osz) + L * (W * gsz + osz),      # read M, write e', write Delta' once
         "k_resident": int(s.bytes_min),                           # read g, e; write e', Delta': each once
+        "k_ef_add_zero": int(s.bytes_min),                        # baselines: read g, e; write M; write Delta' = 0 once
+        "k_kept_entries": int(s.kept_elems) * (W * 8 + 8),        # read, write M at the kept entries; Delta', values
     }
     if args.update == "fused":   # Delta' is not stored; momentum and parameters are read and written instead
         extra = (payload_mat + L) * (16 - osz)
@@ -303,6 +374,7 @@ def main():
     grad_bytes = W * (payload_mat + L) * gsz
     value = grad_bytes / (ms_per_step * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC.get((wl.name, rank, W, dom))
+    compressor_label = {"powersgd": "PowerSGD", "random_block": "Random Block", "random_k": "Random K"}[args.compressor]
     if args.update != "none" or args.iterations != 1 or tune:
         traffic = None   # the counters were taken on the plain step with the planner's own choices
     if resident and args.update != "separate":
@@ -312,8 +384,8 @@ def main():
     achieved_cold = kernel_bytes[dom] / (cold_dom_ms * 1e-3) / 1e9 if cold_dom_ms else None
 
     rec = {
-        "metric": METRIC if (wl.name, rank, W) == ("resnet18", 2, 1) and gdt == "f32" and odt == "f32"
-                  else "PowerSGD step gradient GB/s + %% HBM peak, %s shapes W=%d r=%d" % (wl.name, W, rank),
+        "metric": METRIC if (wl.name, rank, W) == ("resnet18", 2, 1) and gdt == "f32" and odt == "f32" and not sparse
+                  else "%s step gradient GB/s + %% HBM peak, %s shapes W=%d r=%d" % (compressor_label, wl.name, W, rank),
         "value": round(value, 3),
         "unit": "GB/s",
         "n_gpus": 1,
@@ -327,7 +399,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s-shaped gradient set, W=%d simulated worker(s), rank %d, gradients %s, output %s"
                                % (wl.name, W, rank, gdt, odt),
-                   "mode": "resident (one kernel, M kept in registers)" if resident else
+                   "compressor": args.compressor,
+                   "mode": "elementwise sweep + kept entries (two kernels)" if sparse else
+                           "resident (one kernel, M kept in registers)" if resident else
                            ("matrix cores (one kernel per phase)"
                             if rank > 8 or ((gdt != "f32" or odt != "f32") and tune.get("bf16_valu", 1) == 0)
                             else "streaming (one kernel per phase)"),
@@ -342,7 +416,7 @@ def main():
         "min_model": {"bytes_per_step": int(s.bytes_min),
                       "GBps": round(s.bytes_min / (ms_per_step * 1e-3) / 1e9, 2),
                       "frac_of_hbm_peak": round(s.bytes_min / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
-        "stream_model": None if resident else {
+        "stream_model": None if (resident or sparse) else {
             "bytes_per_step": int(s.bytes_stream),
             "GBps": round(s.bytes_stream / (ms_per_step * 1e-3) / 1e9, 2),
             "frac_of_hbm_peak": round(s.bytes_stream / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
@@ -353,10 +427,11 @@ def main():
         "cold": None if not cold_ms else {
             "value": round(grad_bytes / (cold_ms["median"] * 1e-3) / 1e9, 3), "unit": "GB/s",
             "min_model_frac_of_hbm_peak": round(s.bytes_min / (cold_ms["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-            "stream_model_frac_of_hbm_peak": None if resident else
+            "stream_model_frac_of_hbm_peak": None if (resident or sparse) else
                 round(s.bytes_stream / (cold_ms["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "event_ms_per_step": round(event_ms_per_step, 5),
-        "kernel_ms": {k: round(v, 5) for k, v in kavg_events.items()},
+        "kernel_ms": {k: round(v, 5) for k, v in kavg.items()},
+        "kernel_ms_event_pairs": {k: round(v, 5) for k, v in kavg_events.items()},
         "cold_kernel_ms": None if not cold_kavg else {k: round(v, 5) for k, v in cold_kavg.items()},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
@@ -368,7 +443,7 @@ def main():
                      "avg_launch_ms_cold": None if cold_dom_ms is None else round(cold_dom_ms, 5)},
     }
     if not args.no_cpu_baseline:
-        rec["cpu_baseline"] = cpu_baseline(wl, rank, W, args.cpu_seconds)
+        rec["cpu_baseline"] = cpu_baseline(wl, rank, W, args.cpu_seconds, args.compressor)
     print(json.dumps(rec), flush=True)
     return 0
 

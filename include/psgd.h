@@ -85,6 +85,8 @@ typedef struct {
                                 read g, read e, write e' per worker, write Delta' once */
     int64_t bytes_stream;    /* same with the two extra reads of M forced by the two global
                                 reductions (after P, after Q) */
+    int64_t kept_elems;      /* Random Block / Random K baselines (Appendix G): sum over the matrices of
+                                min((n_i + m_i) * rank, n_i * m_i), the length of their packed value / index buffers */
 } psgd_sizes;
 
 /* Build a plan.  Host only: makes no HIP call, so it works without a GPU.
@@ -258,6 +260,36 @@ PSGD_API psgd_status psgd_decompress_update(psgd_plan* plan, const float* p, con
                                    const void* grad, float* mom, float* param, float lr, float momentum,
                                    void* workspace, void* hip_stream);
 
+/* ---- The two linear baselines of Appendix G that share the error-feedback loop of Algorithm 2 -------------
+ *
+ * "Random Block compression" and "Random K compression": the update M_w = g_w + e_w of a matrix is seen as a
+ * vector of length n m; every worker keeps the same b = (n + m) rank entries of it (PowerSGD's budget; at most
+ * n m): a contiguous block M(s : s+b) from a sampled start s, or a sampled set I of b distinct positions.  The
+ * kept values are averaged over the workers, Delta' is zero everywhere else, and e_w <- M_w - Delta'.  The
+ * library draws nothing: the samples are arguments (the appendix samples them on the CPU with the same seed on
+ * every worker).  A block that would run past the end of the vector stops there.  Vector-shaped tensors are
+ * averaged uncompressed, as in psgd_step.  fp32 plans only (else PSGD_EUNSUPPORTED); the plan's workspace and
+ * its P / Q buffers are not used.
+ *
+ *   grad   (device, const)   as psgd_step
+ *   err    (device, in/out)  in: e_w ; out: e_w <- g_w + e_w - Delta'
+ *   starts (device, const)   Random Block: int64 [n_tensors], starts[t] = s of tensor t in [0, n m) (values
+ *                            outside are clamped into the range; entries of vector tensors are ignored)
+ *   indices (device, const)  Random K: int64 [kept_elems], the positions of matrix i at kept_off_i .. + kept_i
+ *                            (psgd_plan_kept), each in [0, n m) and distinct within a matrix; a position outside
+ *                            the range is skipped (its value slot is zero); repeated positions race
+ *   vals   (device, out)     [kept_elems] float: the averaged kept values in block / index order (what the
+ *                            workers would all-reduce); zero past the end of a block cut short
+ *   out    (device, out)     [N+L] float: Delta'
+ * Enqueued on hip_stream; no allocation (after the plan's first GPU call), no synchronisation. */
+PSGD_API psgd_status psgd_random_block_step(psgd_plan* plan, const void* grad, float* err, const int64_t* starts,
+                                            float* vals, void* out, void* hip_stream);
+PSGD_API psgd_status psgd_random_k_step(psgd_plan* plan, const void* grad, float* err, const int64_t* indices,
+                                        float* vals, void* out, void* hip_stream);
+/* Placement of tensor `tensor` in the packed value / index buffers of the baselines: offset and count
+ * (-1 and 0 for vector tensors).  Either output may be NULL. */
+PSGD_API psgd_status psgd_plan_kept(const psgd_plan* plan, int32_t tensor, int64_t* kept_off, int64_t* kept);
+
 /* Per-kernel timing for benchmarks.  With profiling enabled, psgd_compress and
  * psgd_decompress record HIP events on the caller's stream around each of their
  * kernels, and psgd_decompress (hence psgd_step) WAITS for the stream at its
@@ -265,9 +297,13 @@ PSGD_API psgd_status psgd_decompress_update(psgd_plan* plan, const float* p, con
  * psgd_plan_kernel_times copies the accumulated milliseconds per kernel (array
  * of PSGD_N_KERNELS doubles, order given by psgd_kernel_name) and the number of
  * accumulated steps, then clears the accumulators.  A plan in resident mode
- * (see psgd_step) runs one kernel per step, index PSGD_KERNEL_RESIDENT. */
-#define PSGD_N_KERNELS 6
+ * (see psgd_step) runs one kernel per step, index PSGD_KERNEL_RESIDENT; the
+ * baseline steps (psgd_random_block_step, psgd_random_k_step) fill the last two
+ * entries and wait for the stream at their end like psgd_decompress. */
+#define PSGD_N_KERNELS 8
 #define PSGD_KERNEL_RESIDENT 5
+#define PSGD_KERNEL_EF_ADD_ZERO 6   /* the two launches of the Appendix G baselines */
+#define PSGD_KERNEL_KEPT_ENTRIES 7
 PSGD_API psgd_status psgd_plan_set_profiling(psgd_plan* plan, int32_t enable);
 PSGD_API psgd_status psgd_plan_kernel_times(psgd_plan* plan, double* ms_sum, int64_t* steps);
 /* Name of kernel `index` in [0, PSGD_N_KERNELS) as it appears in a profiler's

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(HERE, "libpsgd.so")
 PSGD_OK, PSGD_EINVAL, PSGD_ENOMEM, PSGD_EHIP, PSGD_EUNSUPPORTED = range(5)
 PSGD_F32, PSGD_BF16 = 0, 1
 PSGD_MAX_RANK = 64
-PSGD_N_KERNELS = 6
+PSGD_N_KERNELS = 8
 
 
 class psgd_shape(C.Structure):
@@ -25,7 +25,7 @@ class psgd_sizes(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "n_mat_elems", "n_vec_elems", "grad_stride", "err_stride", "out_elems", "p_elems", "q_elems",
         "workspace_bytes", "n_matrices", "n_vectors", "payload_elems", "compressed_elems",
-        "bytes_min", "bytes_stream")]
+        "bytes_min", "bytes_stream", "kept_elems")]
 
 
 class PsgdError(RuntimeError):
@@ -69,6 +69,12 @@ def load_library(path: Optional[str] = None):
     lib.psgd_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psgd_step_iterations.restype = C.c_int
     lib.psgd_step_iterations.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32]
+    lib.psgd_random_block_step.restype = C.c_int
+    lib.psgd_random_block_step.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.psgd_random_k_step.restype = C.c_int
+    lib.psgd_random_k_step.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.psgd_plan_kept.restype = C.c_int
+    lib.psgd_plan_kept.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(i64)]
     lib.psgd_step_static.restype = C.c_int
     lib.psgd_step_static.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.psgd_plan_set_profiling.restype = C.c_int
@@ -180,6 +186,19 @@ class Plan:
         self._check(self._lib.psgd_step_iterations(self._h, _ptr(grad), _ptr(err), _ptr(q), _ptr(p), _ptr(out),
                                                    _ptr(workspace), _ptr(stream), int(iterations)),
                     "psgd_step_iterations")
+
+    def random_block_step(self, grad, err, starts, vals, out, stream=None):
+        self._check(self._lib.psgd_random_block_step(self._h, _ptr(grad), _ptr(err), _ptr(starts), _ptr(vals), _ptr(out),
+                                                     _ptr(stream)), "psgd_random_block_step")
+
+    def random_k_step(self, grad, err, indices, vals, out, stream=None):
+        self._check(self._lib.psgd_random_k_step(self._h, _ptr(grad), _ptr(err), _ptr(indices), _ptr(vals), _ptr(out),
+                                                 _ptr(stream)), "psgd_random_k_step")
+
+    def kept(self, tensor: int):
+        off, n = C.c_int64(), C.c_int64()
+        self._check(self._lib.psgd_plan_kept(self._h, int(tensor), C.byref(off), C.byref(n)), "psgd_plan_kept")
+        return off.value, n.value
 
     def step_static(self, grad, err, q, p, out, stream=None):
         self._check(self._lib.psgd_step_static(self._h, _ptr(grad), _ptr(err), _ptr(q), _ptr(p), _ptr(out),

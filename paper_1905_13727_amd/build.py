@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libpsgd.so")
-SOURCES = ["psgd_plan.cpp", "psgd_kernels.hip", "psgd_resident.hip", "psgd_highrank.hip"]
+SOURCES = ["psgd_plan.cpp", "psgd_kernels.hip", "psgd_resident.hip", "psgd_highrank.hip", "psgd_sparse.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

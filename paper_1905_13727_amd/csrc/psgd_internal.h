@@ -23,6 +23,7 @@ constexpr int kPanelFloats = 12288;  // n*r up to this: Gram-Schmidt by one work
 constexpr int kGramRows = 256;     // rows per workgroup of the tall-panel Gram / apply kernels
 constexpr int kPreReduceParts = 16; // more partial-P slices than this: a reduction kernel runs before the orthogonalisation
 constexpr int kOrthoMaxRows = 1024; // panels with more rows take the multi-workgroup route
+constexpr int kFlatTileElems = 8192;        // baselines: elements of a flattened matrix per workgroup of the elementwise sweep
 constexpr int kFactorAlignElems = 4;        // P and Q of a matrix start at multiples of 4 floats (vector loads of factor rows)
 constexpr int kHrGramTileRows = 128;       // matrix-core path: rows per workgroup of the mean-P / Gram / apply kernels
 constexpr int64_t kHrMaxRows = 1 << 22;   // matrix-core path: tallest matrix (an n x 64 factor is addressed with 31-bit byte offsets)
@@ -46,6 +47,8 @@ struct MatDesc {
     int32_t n_gblock;   // tall panels: row blocks of the Gram / apply kernels; 0 = panel fits one workgroup's LDS
     int32_t pad_[2];
     int64_t chol_off;   // matrix-core path: offset (in doubles) of this matrix's Cholesky factor, r*r + r values
+    int64_t kept_off;   // Random Block / Random K baselines: offset of this matrix's kept values (and indices) in their packed buffers
+    int64_t kept;       // ... and their number, min((n + m) * rank, n * m)
 };
 
 // One workgroup's share of a streaming kernel.
@@ -139,6 +142,10 @@ struct DeviceTables {
     Tile* hr_tiles1 = nullptr;
     Tile* hr_tiles3 = nullptr;
     Tile* hr_tiles4 = nullptr;
+    Tile* tiles_flat = nullptr;    // baselines: slices of the flattened matrices (elem0, nelem), then of the vector region
+    int32_t* kept_slice_mat = nullptr;     // baselines: per slice of kBlock kept entries, its matrix ...
+    int64_t* kept_slice_first = nullptr;   // ... and its first entry within that matrix
+    int32_t* mat_tensor = nullptr;         // per matrix: index in the caller's tensor list
     int32_t* small_mats = nullptr;
     unsigned* gram_sync = nullptr;              // k_gram_chol: error word, epoch, finished-workgroup count
     unsigned long long* gram_mail = nullptr;    // k_gram_chol: the row blocks' Gram matrices as {value, epoch} slots
@@ -165,6 +172,11 @@ struct psgd_plan {
     std::vector<psgd::Tile> tiles1, tiles3, tiles4, tilesq;
     std::vector<psgd::Tile> tiles4u;        // third sweep when fused with the update, if its tiles differ (else empty)
     std::vector<psgd::Tile> tiles_gram;     // row blocks of tall panels (Cholesky-QR)
+    std::vector<psgd::Tile> tiles_flat;     // baselines (Appendix G): slices of the flattened matrices and of the vector region
+    std::vector<int32_t> kept_slice_mat;    // baselines: slices of kBlock kept entries (matrix, first entry)
+    std::vector<int64_t> kept_slice_first;
+    std::vector<int32_t> mat_tensor;
+    int64_t kept_slices = 0;
     std::vector<int32_t> small_mats;        // matrices orthogonalised by one workgroup (Gram-Schmidt in LDS)
     int64_t ws_gram_doubles = 0;            // workspace: Gram partials, after the float regions
     // matrix-core path (rank > 8, or bf16 gradients / output)
@@ -238,6 +250,9 @@ psgd_status hr_decompress(psgd_plan* plan, const float* p, const float* q, float
 psgd_status launch_vector_mean(psgd_plan* plan, const void* grad, void* out, void* stream, const UpdateArgs& upd);
 psgd_status check_plan(psgd_plan* plan, void* stream);
 psgd_status static_workspace(psgd_plan* plan, void** ws);
+// Appendix G baselines (psgd_sparse.hip): starts != nullptr: Random Block, else Random K with `indices`
+psgd_status launch_sparse_step(psgd_plan* plan, const void* grad, float* err, const int64_t* starts,
+                               const int64_t* indices, float* vals, void* out, void* stream);
 psgd_status read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t* n_written);
 psgd_status resident_check_device(psgd_plan* plan);
 psgd_status launch_resident_step(psgd_plan* plan, const void* grad, float* err, float* q, float* p, void* out,

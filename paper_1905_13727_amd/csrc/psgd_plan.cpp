@@ -588,7 +588,7 @@ psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_
 
         const int64_t gsz = grad_dtype == PSGD_BF16 ? 2 : 4;
         const int64_t osz = out_dtype == PSGD_BF16 ? 2 : 4;
-        int64_t N = 0, P = 0, Q = 0, payload = 0, compressed = 0;
+        int64_t N = 0, P = 0, Q = 0, payload = 0, compressed = 0, kept_total = 0;
         // matrices first
         for (int32_t t = 0; t < n_tensors; ++t) {
             if (shapes[t].cols == 1) continue;
@@ -602,10 +602,28 @@ psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_
             d.q_off = Q;
             d.tensor = t;
             plan->tensor_flat_off[t] = N;
-            plan->tensor_mat[t] = (int32_t)plan->mats.size();
-            plan->mats.push_back(d);
+            const int32_t mi = (int32_t)plan->mats.size();
+            plan->tensor_mat[t] = mi;
             plan->max_n = std::max(plan->max_n, d.n);
             const int64_t elems = (int64_t)d.n * d.m;
+            // Appendix G baselines: b = (n + m) r entries per matrix "to match rank-r PowerSGD", at most all of them
+            d.kept = std::min(((int64_t)d.n + d.m) * rank, elems);
+            d.kept_off = kept_total;
+            kept_total += d.kept;
+            plan->mats.push_back(d);
+            for (int64_t j0 = 0; j0 < d.kept; j0 += kBlock) {
+                plan->kept_slice_mat.push_back(mi);
+                plan->kept_slice_first.push_back(j0);
+            }
+            plan->mat_tensor.push_back(t);
+            // slices of the flattened matrix for their elementwise sweep
+            for (int64_t e0 = 0; e0 < elems; e0 += kFlatTileElems) {
+                Tile ft{};
+                ft.mat = mi;
+                ft.elem0 = e0;
+                ft.nelem = std::min<int64_t>(kFlatTileElems, elems - e0);
+                plan->tiles_flat.push_back(ft);
+            }
             N += round_up(elems, kAlignElems);
             P += round_up((int64_t)d.n * d.r, kFactorAlignElems);   // every factor starts 16-byte aligned
             Q += round_up((int64_t)d.m * d.r, kFactorAlignElems);
@@ -620,7 +638,16 @@ psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_
             L += shapes[t].rows;
             ++nvec_t;
         }
+        for (int64_t e0 = 0; e0 < L; e0 += kFlatTileElems) {
+            Tile ft{};
+            ft.mat = -1;
+            ft.elem0 = e0;
+            ft.nelem = std::min<int64_t>(kFlatTileElems, L - e0);
+            plan->tiles_flat.push_back(ft);
+        }
         psgd_sizes& s = plan->sizes;
+        s.kept_elems = kept_total;
+        plan->kept_slices = (int64_t)plan->kept_slice_mat.size();
         s.n_mat_elems = N;
         s.n_vec_elems = L;
         s.grad_stride = round_up(N + L, kAlignElems);
@@ -676,6 +703,28 @@ psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, int64_t* fl
         if (eff_rank) *eff_rank = d.r;
     }
     return PSGD_OK;
+}
+
+psgd_status psgd_plan_kept(const psgd_plan* plan, int32_t tensor, int64_t* kept_off, int64_t* kept) {
+    if (!plan || tensor < 0 || tensor >= (int32_t)plan->shapes.size()) return PSGD_EINVAL;
+    const int32_t mi = plan->tensor_mat[tensor];
+    if (kept_off) *kept_off = mi < 0 ? -1 : plan->mats[mi].kept_off;
+    if (kept) *kept = mi < 0 ? 0 : plan->mats[mi].kept;
+    return PSGD_OK;
+}
+
+psgd_status psgd_random_block_step(psgd_plan* plan, const void* grad, float* err, const int64_t* starts, float* vals,
+                                   void* out, void* hip_stream) {
+    if (!plan || !grad || !err || !starts || !vals || !out) return PSGD_EINVAL;
+    if (plan->grad_dtype != PSGD_F32 || plan->out_dtype != PSGD_F32) return PSGD_EUNSUPPORTED;
+    return launch_sparse_step(plan, grad, err, starts, nullptr, vals, out, hip_stream);
+}
+
+psgd_status psgd_random_k_step(psgd_plan* plan, const void* grad, float* err, const int64_t* indices, float* vals,
+                               void* out, void* hip_stream) {
+    if (!plan || !grad || !err || !indices || !vals || !out) return PSGD_EINVAL;
+    if (plan->grad_dtype != PSGD_F32 || plan->out_dtype != PSGD_F32) return PSGD_EUNSUPPORTED;
+    return launch_sparse_step(plan, grad, err, nullptr, indices, vals, out, hip_stream);
 }
 
 psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value) {
@@ -818,8 +867,8 @@ psgd_status psgd_plan_kernel_times(psgd_plan* plan, double* ms_sum, int64_t* ste
 }
 
 const char* psgd_kernel_name(int32_t index) {
-    static const char* const names[PSGD_N_KERNELS] = {"k_ef_right", "k_ortho",  "k_left",
-                                                      "k_q_reduce", "k_decomp", "k_resident"};
+    static const char* const names[PSGD_N_KERNELS] = {"k_ef_right", "k_ortho",    "k_left",        "k_q_reduce",
+                                                      "k_decomp",   "k_resident", "k_ef_add_zero", "k_kept_entries"};
     return (index >= 0 && index < PSGD_N_KERNELS) ? names[index] : nullptr;
 }
 

@@ -15,6 +15,9 @@ namespace psgd {
 void free_tables(psgd_plan*) {}
 psgd_status set_profiling(psgd_plan*, bool) { return PSGD_EHIP; }
 psgd_status check_plan(psgd_plan*, void*) { return PSGD_EHIP; }
+psgd_status launch_sparse_step(psgd_plan*, const void*, float*, const int64_t*, const int64_t*, float*, void*, void*) {
+    return PSGD_EHIP;
+}
 psgd_status static_workspace(psgd_plan*, void**) { return PSGD_EHIP; }
 psgd_status read_trace(psgd_plan*, uint64_t*, int64_t, int64_t*) { return PSGD_EHIP; }
 psgd_status launch_resident_step(psgd_plan*, const void*, float*, float*, float*, void*, void*, void*, const UpdateArgs&, int) {
@@ -179,6 +182,36 @@ static void check_resident(const psgd_plan* plan) {
 
 static void check_p_tiling(const psgd_plan* plan) { check_cover(plan, plan->tiles1, (int)plan->tuning.k1_nv, 1); }
 
+// Appendix G baselines: the slices of the flattened matrices (16-byte accesses: aligned starts), of the vector region
+// and of the kept entries each cover their range exactly once; the packed value offsets are back to back.
+static void check_baseline_tables(const psgd_plan* plan, int rank) {
+    std::vector<int64_t> flat(plan->mats.size(), 0), kept(plan->mats.size(), 0);
+    int64_t vec = 0, kept_total = 0;
+    for (const Tile& t : plan->tiles_flat) {
+        CHECK(t.nelem > 0 && t.nelem <= kFlatTileElems);
+        if (t.mat < 0) { CHECK(t.elem0 == vec); vec += t.nelem; continue; }
+        CHECK(t.mat < (int)plan->mats.size() && t.elem0 == flat[t.mat] && t.elem0 % 4 == 0);
+        flat[t.mat] += t.nelem;
+    }
+    CHECK(vec == plan->sizes.n_vec_elems);
+    CHECK((int64_t)plan->kept_slice_mat.size() == plan->kept_slices && plan->kept_slice_first.size() == plan->kept_slice_mat.size());
+    for (size_t k = 0; k < plan->kept_slice_mat.size(); ++k) {
+        const int32_t mi = plan->kept_slice_mat[k];
+        CHECK(mi >= 0 && mi < (int)plan->mats.size() && plan->kept_slice_first[k] == kept[mi]);
+        kept[mi] += std::min<int64_t>(kBlock, plan->mats[mi].kept - kept[mi]);
+    }
+    CHECK(plan->mat_tensor.size() == plan->mats.size());
+    for (size_t i = 0; i < plan->mats.size(); ++i) {
+        const MatDesc& d = plan->mats[i];
+        const int64_t nm = (int64_t)d.n * d.m;
+        CHECK(flat[i] == nm && d.off % 4 == 0);
+        CHECK(d.kept == std::min<int64_t>(((int64_t)d.n + d.m) * rank, nm) && kept[i] == d.kept && d.kept_off == kept_total);
+        CHECK(plan->mat_tensor[i] == d.tensor);
+        kept_total += d.kept;
+    }
+    CHECK(kept_total == plan->sizes.kept_elems);
+}
+
 static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int workers, const Tuning* tu) {
     psgd_plan* plan = nullptr;
     CHECK(psgd_plan_create(shapes.data(), (int)shapes.size(), rank, workers, PSGD_F32, PSGD_F32, &plan) == PSGD_OK);
@@ -259,6 +292,7 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
         covered_p[t.mat] += t.nelem;
     }
     for (size_t i = 0; i < plan->mats.size(); ++i) CHECK(covered_p[i] == (int64_t)plan->mats[i].n * plan->mats[i].r);
+    check_baseline_tables(plan, rank);
     psgd_plan_destroy(plan);
 }
 
