@@ -478,14 +478,14 @@ __global__ __launch_bounds__(kBlock) void k_hr_left(const MatDesc* __restrict__ 
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) acc[g][c][nt] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    for (int r0 = r_begin; r0 < r_end; r0 += 16) {
-        v4f a[4][NG];
-        float b[4][NT];
+    // the 16 rows of a step: four loads of M per column group and the lane's P_hat entries.  Rows past the strip read
+    // a real row (the strip's last) whose product is switched off through B = 0.
+    auto load_step = [&](int r0, v4f (&a)[4][NG], float (&b)[4][NT]) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int row = r0 + 4 * s + kb;
             const bool ok = row < r_end;
-            const int row_c = ok ? row : r_end - 1;     // a real row: its product is switched off through B
+            const int row_c = ok ? row : r_end - 1;
 #pragma unroll
             for (int g = 0; g < NG; ++g) {
                 const int col = c0 + 64 * g + 4 * li;
@@ -501,6 +501,22 @@ __global__ __launch_bounds__(kBlock) void k_hr_left(const MatDesc* __restrict__ 
                 b[s][nt] = (ok && j < ri) ? p[d.p_off + (int64_t)row * ri + j] : 0.f;
             }
         }
+    };
+    // the next step's loads are in flight while the current step is multiplied
+    v4f an[4][NG];
+    float bn[4][NT];
+    if (r_begin < r_end) load_step(r_begin, an, bn);
+    for (int r0 = r_begin; r0 < r_end; r0 += 16) {
+        v4f a[4][NG];
+        float b[4][NT];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+#pragma unroll
+            for (int g = 0; g < NG; ++g) a[s][g] = an[s][g];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) b[s][nt] = bn[s][nt];
+        }
+        if (r0 + 16 < r_end) load_step(r0 + 16, an, bn);
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
