@@ -318,20 +318,34 @@ def main():
         total = sum(kavg.values())
         kavg = {k: event_ms_per_step * v / total for k, v in kavg.items()}
 
-    # cold-cache pass: a 1 GiB fill between steps evicts L2 and the memory-side cache
-    cold_ms = None
+    # Cold-cache passes: before every step (outside its timing) 1 GiB of other data is pushed through L2 and the
+    # memory-side cache, so that gradients and error memory come from HBM as after a real backward pass.  Two
+    # variants: the caches are left full of DIRTY foreign lines (a 1 GiB fill; the step's own traffic then also
+    # pays for their write-back: the harsher figure, reported as `cold`), or of CLEAN ones (a read-only sum over
+    # the same 1 GiB: `cold_clean`).
+    cold_ms = cold_clean_ms = None
     if args.cold_steps > 0:
         flush = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device=dev)
-        ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.cold_steps)]
-        ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.cold_steps)]
-        for i in range(args.cold_steps):
-            flush.fill_(float(i))
-            ev0[i].record(stream)
-            step(i)
-            ev1[i].record(stream)
-        torch.cuda.synchronize(dev)
-        ts = sorted(a.elapsed_time(b) for a, b in zip(ev0, ev1))
-        cold_ms = {"median": round(ts[len(ts) // 2], 4), "min": round(ts[0], 4)}
+        flush.fill_(1.0)
+        sink = torch.zeros(1, dtype=torch.float32, device=dev)
+        for dirty in (True, False):
+            ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.cold_steps)]
+            ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.cold_steps)]
+            for i in range(args.cold_steps):
+                if dirty:
+                    flush.fill_(float(i))
+                else:
+                    sink += flush.sum()
+                ev0[i].record(stream)
+                step(i)
+                ev1[i].record(stream)
+            torch.cuda.synchronize(dev)
+            ts = sorted(a.elapsed_time(b) for a, b in zip(ev0, ev1))
+            res = {"median": round(ts[len(ts) // 2], 4), "min": round(ts[0], 4)}
+            if dirty:
+                cold_ms = res
+            else:
+                cold_clean_ms = res
         del flush
 
     # the dominant kernel's duration in the cold pass: a resident step is that one kernel; a multi-kernel step
@@ -424,6 +438,7 @@ def main():
         # they would after a real backward pass.  The primary regime; `value` and `roofline.frac` are the timed
         # region's (warm), the cold fractions stand beside them.
         "cold_ms_per_step": cold_ms,
+        "cold_clean_ms_per_step": cold_clean_ms,
         "cold": None if not cold_ms else {
             "value": round(grad_bytes / (cold_ms["median"] * 1e-3) / 1e9, 3), "unit": "GB/s",
             "min_model_frac_of_hbm_peak": round(s.bytes_min / (cold_ms["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
@@ -440,7 +455,9 @@ def main():
                      "regime": "warm (the timed region: steps back to back)",
                      "achieved_cold": None if achieved_cold is None else round(achieved_cold, 2),
                      "frac_cold": None if achieved_cold is None else round(achieved_cold / HBM_PEAK_GBS, 4),
-                     "avg_launch_ms_cold": None if cold_dom_ms is None else round(cold_dom_ms, 5)},
+                     "avg_launch_ms_cold": None if cold_dom_ms is None else round(cold_dom_ms, 5),
+                     "frac_cold_clean": None if not (resident and cold_clean_ms and args.update != "separate") else
+                         round(kernel_bytes[dom] / (cold_clean_ms["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
     }
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(wl, rank, W, args.cpu_seconds, args.compressor)

@@ -99,10 +99,10 @@ typedef struct {
  *   out_dtype          dtype of `out`
  * Errors: PSGD_EINVAL for null pointers, n_tensors < 1, rank < 1, workers < 1,
  * a non-positive dimension; PSGD_EUNSUPPORTED for rank > PSGD_MAX_RANK, or,
- * when rank > 8 (the matrix-core kernels) or a dtype is PSGD_BF16, a matrix whose
- * column count is not a multiple of 4 or exceeds 2^20, or with more than 2^22 rows;
- * on the other kernels for a matrix with more than about 64 M columns (a strip of 8
- * rows is addressed with 31-bit byte offsets); PSGD_ENOMEM. */
+ * when rank > 8 (the matrix-core kernels), a matrix whose column count is not a
+ * multiple of 4 or exceeds 2^20, or with more than 2^22 rows; on the other kernels
+ * (rank <= 8, fp32 or bf16 data, any row length) for a matrix with more than about
+ * 64 M columns (a strip of 8 rows is addressed with 31-bit byte offsets); PSGD_ENOMEM. */
 #define PSGD_MAX_RANK 64
 PSGD_API psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_t rank,
                              int32_t workers, psgd_dtype grad_dtype, psgd_dtype out_dtype,
@@ -151,7 +151,8 @@ PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, in
  *                 device holds all row blocks of the launch at once, 0 in two launches, 2 (TEST ONLY) in one
  *                 launch unconditionally: its waits may then time out, see psgd_plan_check
  *   gram_spin     polls before a wait in that launch gives up, 1 .. 2^24 (default 2^18)
- *   bf16_valu     bf16 gradients / output at rank <= 8: 1 (default) streaming kernels, 0 matrix-core kernels */
+ *   bf16_valu     bf16 gradients / output at rank <= 8: 1 (default) streaming kernels, 0 matrix-core kernels
+ *                 (then every row length must be a multiple of 4, else PSGD_EUNSUPPORTED) */
 PSGD_API psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value);
 
 /* Algorithm 2 "Delta_w <- g_w + e_w" followed by Algorithm 1 compress+aggregate.

@@ -154,32 +154,50 @@ __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
 
 // V consecutive gradient elements through a descriptor, read once (non-temporal); `off` in bytes.  BF: the
-// gradient is stored as bf16 (4-wide rows only: the planner requires row lengths that are multiples of 4).
+// gradient is stored as bf16: 8-, 4- or 2-byte loads of four, two or one value, widened exactly.
 template <int V, bool BF>
 __device__ __forceinline__ void buf_ld_grad(buf_rsrc r, unsigned off, float (&x)[V]) {
     if constexpr (BF) {
-        static_assert(V == 4, "bf16 gradients are read four at a time");
-        const v2u t = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 2);
-        x[0] = __uint_as_float(t.x << 16); x[1] = __uint_as_float(t.x & 0xffff0000u);
-        x[2] = __uint_as_float(t.y << 16); x[3] = __uint_as_float(t.y & 0xffff0000u);
+        if constexpr (V == 4) {
+            const v2u t = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 2);
+            x[0] = __uint_as_float(t.x << 16); x[1] = __uint_as_float(t.x & 0xffff0000u);
+            x[2] = __uint_as_float(t.y << 16); x[3] = __uint_as_float(t.y & 0xffff0000u);
+        } else if constexpr (V == 2) {
+            const unsigned t = __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 2);
+            x[0] = __uint_as_float(t << 16); x[1] = __uint_as_float(t & 0xffff0000u);
+        } else {
+            const unsigned t = (unsigned)(unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, (int)off, 0, 2);
+            x[0] = __uint_as_float(t << 16);
+        }
     } else {
         buf_ldv<V>(r, off, x, true);
     }
 }
 
-// V consecutive elements of the output at element index `at`; BF: stored as bf16 (round to nearest even; 4-wide
-// rows only).  NT: non-temporal.
+// V consecutive elements of the output at element index `at`; BF: stored as bf16 (round to nearest even).
+// NT: non-temporal.
 template <int V, bool BF, bool NT>
 __device__ __forceinline__ void st_out(void* out, int64_t at, const float (&x)[V]) {
     if constexpr (BF) {
-        static_assert(V == 4, "bf16 output is written four at a time");
-        typedef unsigned u2 __attribute__((ext_vector_type(2)));
-        u2 t;
-        t.x = pack_bf16x2(x[0], x[1]);
-        t.y = pack_bf16x2(x[2], x[3]);
-        u2* dst = reinterpret_cast<u2*>(static_cast<bf16_t*>(out) + at);
-        if constexpr (NT) __builtin_nontemporal_store(t, dst);
-        else *dst = t;
+        bf16_t* base = static_cast<bf16_t*>(out) + at;
+        if constexpr (V == 4) {
+            typedef unsigned u2 __attribute__((ext_vector_type(2)));
+            u2 t;
+            t.x = pack_bf16x2(x[0], x[1]);
+            t.y = pack_bf16x2(x[2], x[3]);
+            u2* dst = reinterpret_cast<u2*>(base);
+            if constexpr (NT) __builtin_nontemporal_store(t, dst);
+            else *dst = t;
+        } else if constexpr (V == 2) {
+            const unsigned t = pack_bf16x2(x[0], x[1]);
+            unsigned* dst = reinterpret_cast<unsigned*>(base);
+            if constexpr (NT) __builtin_nontemporal_store(t, dst);
+            else *dst = t;
+        } else {
+            const bf16_t t = f32_to_bf16(x[0]);
+            if constexpr (NT) __builtin_nontemporal_store(t, base);
+            else *base = t;
+        }
     } else {
         if constexpr (NT) stv_stream<V>(static_cast<float*>(out) + at, x);
         else stv<V>(static_cast<float*>(out) + at, x);

@@ -151,13 +151,9 @@ __global__ __launch_bounds__(kBlock) void k_ef_right(const MatDesc* __restrict__
     const void* g = static_cast<const char*>(grad) + (int64_t)w * gstride * (GBF ? 2 : 4);
     float* e = err + (int64_t)w * estride;
     t.part += w * d.n_cchunk;   // partial slices: [worker][column chunk]
-    if constexpr (GBF) {   // row lengths are multiples of 4 (planner)
-        ef_right_tile<R, 4, NV, ADD, true>(t, d, g, e, q, ws);
-    } else {
-        if (d.vec == 4) ef_right_tile<R, 4, NV, ADD, false>(t, d, g, e, q, ws);
-        else if (d.vec == 2) ef_right_tile<R, 2, NV, ADD, false>(t, d, g, e, q, ws);
-        else ef_right_tile<R, 1, NV, ADD, false>(t, d, g, e, q, ws);
-    }
+    if (d.vec == 4) ef_right_tile<R, 4, NV, ADD, GBF>(t, d, g, e, q, ws);
+    else if (d.vec == 2) ef_right_tile<R, 2, NV, ADD, GBF>(t, d, g, e, q, ws);
+    else ef_right_tile<R, 1, NV, ADD, GBF>(t, d, g, e, q, ws);
 }
 
 // sum of `nparts` partial slices (stride `stride` floats) at `src`, in slice order, eight loads in flight
@@ -844,13 +840,9 @@ __global__ __launch_bounds__(kBlock) void k_decomp(const MatDesc* __restrict__ m
     }
     const MatDesc d = mats[t.mat];
     float* e = err + (int64_t)w * estride;
-    if constexpr (OBF) {   // row lengths are multiples of 4 (planner)
-        decomp_tile<R, 4, NV, UPD, STREAM, true>(t, d, e, p, q, outv, w == 0, upd);
-    } else {
-        if (d.vec == 4) decomp_tile<R, 4, NV, UPD, STREAM, false>(t, d, e, p, q, outv, w == 0, upd);
-        else if (d.vec == 2) decomp_tile<R, 2, NV, UPD, STREAM, false>(t, d, e, p, q, outv, w == 0, upd);
-        else decomp_tile<R, 1, NV, UPD, STREAM, false>(t, d, e, p, q, outv, w == 0, upd);
-    }
+    if (d.vec == 4) decomp_tile<R, 4, NV, UPD, STREAM, OBF>(t, d, e, p, q, outv, w == 0, upd);
+    else if (d.vec == 2) decomp_tile<R, 2, NV, UPD, STREAM, OBF>(t, d, e, p, q, outv, w == 0, upd);
+    else decomp_tile<R, 1, NV, UPD, STREAM, OBF>(t, d, e, p, q, outv, w == 0, upd);
 }
 
 // ---- host side ------------------------------------------------------------------------------------

@@ -144,6 +144,8 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
         tu.stream_hints < -1 || tu.stream_hints > 1 || tu.xcd_order < -1 || tu.gram_fused < 0 || tu.gram_fused > 2 || tu.gram_spin < 1 ||
         tu.gram_spin > (1 << 24))
         return PSGD_EINVAL;
+    for (const MatDesc& d : plan->mats)   // 16-byte accesses along the rows, 31-bit byte offsets within a tile
+        if (d.m % 4 != 0 || d.m > kHrMaxCols || d.n > kHrMaxRows) return PSGD_EUNSUPPORTED;
     const int64_t W = plan->workers;
     const size_t nm = plan->mats.size();
     plan->tiles1.clear(); plan->tiles3.clear(); plan->tiles4.clear(); plan->tiles4u.clear(); plan->tilesp.clear();
@@ -564,9 +566,9 @@ psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_
         if (shapes[t].rows > INT32_MAX || shapes[t].cols > INT32_MAX) return PSGD_EUNSUPPORTED;
     }
     if (rank > PSGD_MAX_RANK) return PSGD_EUNSUPPORTED;
-    // the matrix-core kernels (ranks above 8) and the bf16 forms of all kernels need row lengths that are multiples
-    // of 4 and short enough for 32-bit byte offsets within a tile of rows
-    const bool needs_hr = rank > kValuMaxRank || grad_dtype != PSGD_F32 || out_dtype != PSGD_F32;
+    // the matrix-core kernels (ranks above 8) need row lengths that are multiples of 4 and short enough for 32-bit
+    // byte offsets within a tile of rows
+    const bool needs_hr = rank > kValuMaxRank;
     if (needs_hr)
         for (int32_t t = 0; t < n_tensors; ++t)
             if (shapes[t].cols != 1 && (shapes[t].cols % 4 != 0 || shapes[t].cols > kHrMaxCols ||

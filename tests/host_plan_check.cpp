@@ -393,7 +393,11 @@ int main() {
         std::vector<psgd_shape> odd = {{64, 650}};
         psgd_plan* plan = nullptr;
         CHECK(psgd_plan_create(odd.data(), 1, 16, 1, PSGD_F32, PSGD_F32, &plan) == PSGD_EUNSUPPORTED);
-        CHECK(psgd_plan_create(odd.data(), 1, 4, 1, PSGD_BF16, PSGD_F32, &plan) == PSGD_EUNSUPPORTED);
+        // bf16 data at rank <= 8 run on the streaming kernels at any row length; the matrix-core kernels refuse it
+        CHECK(psgd_plan_create(odd.data(), 1, 4, 1, PSGD_BF16, PSGD_F32, &plan) == PSGD_OK);
+        CHECK(psgd_plan_set_tuning(plan, "bf16_valu", 0) == PSGD_EUNSUPPORTED);
+        CHECK(!plan->hr);
+        psgd_plan_destroy(plan);
     }
     std::printf("OK\n");
     return 0;

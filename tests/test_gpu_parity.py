@@ -328,6 +328,21 @@ def test_streaming_path_bf16(rank, workers, gbf, obf):
          tuning={"stream_hints": 1})
 
 
+@pytest.mark.parametrize("rank,workers,gbf,obf", [(4, 2, True, True), (1, 1, True, False), (8, 1, False, True),
+                                                  (3, 3, True, True)])
+def test_streaming_path_bf16_any_row_length(rank, workers, gbf, obf):
+    """bf16 gradients / output on matrices whose row length is odd or even but not a multiple of 4 (the LSTM's rows
+    of 650 among them): 2- and 4-byte accesses to the bf16 buffers instead of 8-byte ones."""
+    _need_gpu()
+    shapes = [(37, 91), (7,), (50, 650), (130, 1028), (5, 3), (300, 2), (1, 40), (1031,), (3, 4700), (257, 262),
+              (2600, 650)]
+    _run(_workload(shapes), rank=rank, workers=workers, steps=3, seed=110 + rank, expect_resident=False, grad_bf16=gbf,
+         out_bf16=obf)
+    if rank == 4:
+        _run_update(_workload(shapes), rank=rank, workers=workers, steps=2, seed=115, grad_bf16=True,
+                    expect_resident=False)
+
+
 @pytest.mark.parametrize("rows,cols", [(64, 64), (256, 192), (128, 4096)])
 def test_matrix_core_tilings(rows, cols):
     """P = M Q on the matrix cores with rows split into many column ranges (partials summed in

@@ -37,9 +37,8 @@ def test_status_strings():
     (dict(shapes=[], rank=2), B.PSGD_EINVAL),
     (dict(shapes=[(4, 4)], rank=B.PSGD_MAX_RANK + 1), B.PSGD_EUNSUPPORTED),
     (dict(shapes=[(4, 4)], rank=2, grad_dtype=7), B.PSGD_EINVAL),
-    # the matrix-core kernels (rank > 8 or bf16) need row lengths that are multiples of 4, at most 2^20
+    # the matrix-core kernels (rank > 8) need row lengths that are multiples of 4, at most 2^20
     (dict(shapes=[(64, 650)], rank=16), B.PSGD_EUNSUPPORTED),
-    (dict(shapes=[(64, 650)], rank=2, grad_dtype=B.PSGD_BF16), B.PSGD_EUNSUPPORTED),
     (dict(shapes=[(8, (1 << 20) + 4)], rank=16), B.PSGD_EUNSUPPORTED),
     # vector-ALU kernels: a strip of 8 rows must stay below 2^31 bytes
     (dict(shapes=[(4, 68_000_000)], rank=2), B.PSGD_EUNSUPPORTED),
