@@ -34,8 +34,24 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 METRIC = "PowerSGD step gradient GB/s + % HBM peak, ResNet18 shapes r=2"   # the headline metric and its workload
 
 MEASURED_TRAFFIC = {
-    # profiles/resident_resnet18_r2.md: 107.2 MB fetched + 93.0 MB written
-    ("resnet18", 2, 1, "k_resident"): 200294912,
+    # (workload, rank, workers, kernel slot of kernel_ms): FETCH_SIZE + WRITE_SIZE, scaled, bytes per launch
+    ("resnet18", 2, 1, "k_resident"): 200288882,      # profiles/resident_resnet18_r2.md
+    ("lstm", 4, 1, "k_ef_right"): 391861304,          # profiles/streaming_lstm_r4.md
+    ("lstm", 4, 1, "k_left"): 132708464,
+    ("lstm", 4, 1, "k_decomp"): 400277868,
+    ("resnet18", 2, 16, "k_ef_right"): 2169944560,    # profiles/streaming_resnet18_w16_r2.md
+    ("resnet18", 2, 16, "k_left"): 726187447,
+    ("resnet18", 2, 16, "k_decomp"): 1479682475,
+    ("resnet18", 2, 1, "k_ef_add_zero"): 179024126,   # profiles/baseline_random_*_resnet18_r2.md
+}
+# The 24-layer transformer-shaped set: the counter runs end in a crash of the profiler once the process holds
+# several GB of device memory, so the counters were taken on the embedding + 4 layers (same kernels and tiles,
+# profiles/transformer_4layers_bf16_r*_counters.md); here: measured traffic / algorithmic bytes of that subset,
+# applied to the full set's algorithmic bytes.
+TRANSFORMER_TRAFFIC_RATIO = {
+    (4, "k_ef_right"): 3183900381 / 3043491840, (4, "k_left"): 1273797976 / 1217396736, (4, "k_decomp"): 3182370412 / 3043934208,
+    (16, "k_ef_right"): 3192048669 / 3043491840, (16, "k_left"): 1285844555 / 1217396736, (16, "k_decomp"): 3230931164 / 3043934208,
+    (32, "k_ef_right"): 3257299928 / 3043491840, (32, "k_left"): 1305106500 / 1217396736, (32, "k_decomp"): 3255200543 / 3043934208,
 }
 
 
@@ -388,9 +404,16 @@ def main():
     grad_bytes = W * (payload_mat + L) * gsz
     value = grad_bytes / (ms_per_step * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC.get((wl.name, rank, W, dom))
+    traffic_source = "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this configuration (profiles/)" if traffic else None
+    if wl.name.startswith("transformer") and gdt == "bf16" and odt == "bf16" and W == 1 and (rank, dom) in TRANSFORMER_TRAFFIC_RATIO:
+        traffic = int(TRANSFORMER_TRAFFIC_RATIO[(rank, dom)] * kernel_bytes[dom])
+        traffic_source = ("counters of the embedding + 4 layers subset (profiles/transformer_4layers_bf16_r%d_counters.md), "
+                          "traffic / algorithmic bytes applied to this set" % rank)
+    if (sparse and dom != "k_ef_add_zero") or (not sparse and dom == "k_ef_add_zero"):
+        traffic = None
     compressor_label = {"powersgd": "PowerSGD", "random_block": "Random Block", "random_k": "Random K"}[args.compressor]
     if args.update != "none" or args.iterations != 1 or tune:
-        traffic = None   # the counters were taken on the plain step with the planner's own choices
+        traffic, traffic_source = None, None   # the counters were taken on the plain step with the planner's own choices
     if resident and args.update != "separate":
         cold_dom_ms = cold_ms["median"] if cold_ms else None
     else:
@@ -450,6 +473,7 @@ def main():
         "cold_kernel_ms": None if not cold_kavg else {k: round(v, 5) for k, v in cold_kavg.items()},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "traffic_source": traffic_source,
                      "algorithmic_bytes_per_launch": int(kernel_bytes[dom]),
                      "avg_launch_ms": round(kavg[dom], 5),
                      "regime": "warm (the timed region: steps back to back)",

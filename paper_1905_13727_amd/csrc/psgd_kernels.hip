@@ -973,7 +973,7 @@ psgd_status upload_tables(psgd_plan* plan) {
         {nullptr, plan->gram_fused ? (size_t)kResSyncWords * sizeof(unsigned) : 0, 0},                   // zero-filled, epoch set below
         {nullptr, plan->gram_fused ? (size_t)plan->ws_gram_doubles * 2 * sizeof(unsigned long long) : 0, 0},   // zero-filled: tag 0 never matches
         {plan->tiles4u.data(), plan->tiles4u.size() * sizeof(Tile), 0},
-        {plan->tiles_flat.data(), plan->tiles_flat.size() * sizeof(Tile), 0},
+        {plan->flat_first.data(), plan->flat_first.size() * sizeof(int64_t), 0},
         {plan->kept_slice_mat.data(), plan->kept_slice_mat.size() * sizeof(int32_t), 0},
         {plan->kept_slice_first.data(), plan->kept_slice_first.size() * sizeof(int64_t), 0},
         {plan->mat_tensor.data(), plan->mat_tensor.size() * sizeof(int32_t), 0},
@@ -1023,7 +1023,7 @@ psgd_status upload_tables(psgd_plan* plan) {
     plan->dev.gram_sync = plan->gram_fused ? reinterpret_cast<unsigned*>(b + pieces[16].at) : nullptr;
     plan->dev.gram_mail = plan->gram_fused ? reinterpret_cast<unsigned long long*>(b + pieces[17].at) : nullptr;
     plan->dev.tiles4u = plan->tiles4u.empty() ? nullptr : reinterpret_cast<Tile*>(b + pieces[18].at);
-    plan->dev.tiles_flat = reinterpret_cast<Tile*>(b + pieces[19].at);
+    plan->dev.flat_first = reinterpret_cast<int64_t*>(b + pieces[19].at);
     plan->dev.kept_slice_mat = reinterpret_cast<int32_t*>(b + pieces[20].at);
     plan->dev.kept_slice_first = reinterpret_cast<int64_t*>(b + pieces[21].at);
     plan->dev.mat_tensor = reinterpret_cast<int32_t*>(b + pieces[22].at);

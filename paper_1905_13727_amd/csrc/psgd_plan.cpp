@@ -618,14 +618,10 @@ psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_
                 plan->kept_slice_first.push_back(j0);
             }
             plan->mat_tensor.push_back(t);
-            // slices of the flattened matrix for their elementwise sweep
-            for (int64_t e0 = 0; e0 < elems; e0 += kFlatTileElems) {
-                Tile ft{};
-                ft.mat = mi;
-                ft.elem0 = e0;
-                ft.nelem = std::min<int64_t>(kFlatTileElems, elems - e0);
-                plan->tiles_flat.push_back(ft);
-            }
+            // slices of the flattened matrix for their elementwise sweep: only their running count is kept (the
+            // kernel finds its matrix by bisection), not a table of a million entries for a large model
+            plan->flat_first.push_back(plan->flat_tiles);
+            plan->flat_tiles += ceil_div(elems, kFlatTileElems);
             N += round_up(elems, kAlignElems);
             P += round_up((int64_t)d.n * d.r, kFactorAlignElems);   // every factor starts 16-byte aligned
             Q += round_up((int64_t)d.m * d.r, kFactorAlignElems);
@@ -640,13 +636,8 @@ psgd_status psgd_plan_create(const psgd_shape* shapes, int32_t n_tensors, int32_
             L += shapes[t].rows;
             ++nvec_t;
         }
-        for (int64_t e0 = 0; e0 < L; e0 += kFlatTileElems) {
-            Tile ft{};
-            ft.mat = -1;
-            ft.elem0 = e0;
-            ft.nelem = std::min<int64_t>(kFlatTileElems, L - e0);
-            plan->tiles_flat.push_back(ft);
-        }
+        plan->flat_first.push_back(plan->flat_tiles);   // one past the last matrix: where the vector region's slices start
+        plan->flat_vec_tiles = ceil_div(L, kFlatTileElems);
         psgd_sizes& s = plan->sizes;
         s.kept_elems = kept_total;
         plan->kept_slices = (int64_t)plan->kept_slice_mat.size();

@@ -22,56 +22,57 @@
 
 namespace psgd {
 
-constexpr int kFlatUnroll = 4;   // 16-byte accesses a lane has in flight per array
+static_assert(kFlatTileElems == kBlock * 4, "one 16-byte access per lane and array");
 
-__global__ __launch_bounds__(kBlock) void k_ef_add_zero(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
-                                                        const float* __restrict__ grad, float* __restrict__ err,
-                                                        float* __restrict__ out, int workers, int64_t gstride,
-                                                        int64_t estride, int64_t n_mat_elems) {
-    const Tile t = tiles[blockIdx.x];
+// blockIdx.x: slice of kFlatTileElems elements; slices [first[i], first[i+1]) belong to matrix i, those from
+// first[n_mats] on to the vector region.  blockIdx.y: worker.
+__global__ __launch_bounds__(kBlock) void k_ef_add_zero(const MatDesc* __restrict__ mats, const int64_t* __restrict__ first,
+                                                        int n_mats, const float* __restrict__ grad,
+                                                        float* __restrict__ err, float* __restrict__ out, int workers,
+                                                        int64_t gstride, int64_t estride, int64_t n_mat_elems,
+                                                        int64_t n_vec_elems) {
+    const int64_t slice = blockIdx.x;
     const int w = blockIdx.y;
-    if (t.mat < 0) {
+    if (slice >= first[n_mats]) {
         // vector-shaped tensors: aggregated uncompressed (mean over the workers), no error memory
         if (w != 0) return;
         const float inv_w = 1.0f / (float)workers;
-        for (int64_t idx = t.elem0 + threadIdx.x; idx < t.elem0 + t.nelem; idx += kBlock) {
+        const int64_t e0 = (slice - first[n_mats]) * kFlatTileElems;
+        const int64_t e1 = e0 + kFlatTileElems < n_vec_elems ? e0 + kFlatTileElems : n_vec_elems;
+        for (int64_t idx = e0 + threadIdx.x; idx < e1; idx += kBlock) {
             float s = 0.f;
             for (int ww = 0; ww < workers; ++ww) s += grad[(int64_t)ww * gstride + n_mat_elems + idx];
             out[n_mat_elems + idx] = s * inv_w;
         }
         return;
     }
-    const MatDesc d = mats[t.mat];
-    const float* g = grad + (int64_t)w * gstride + d.off + t.elem0;
-    float* e = err + (int64_t)w * estride + d.off + t.elem0;
-    float* o = out + d.off + t.elem0;
-    // matrices start on multiples of 64 elements and slices on multiples of kFlatTileElems: 16-byte accesses
-    // are aligned; a slice's last few elements (n m not a multiple of 4) go one by one
-    const int nvec = (int)(t.nelem / 4);
-    for (int v0 = threadIdx.x; v0 < nvec; v0 += kBlock * kFlatUnroll) {
-        f4 gv[kFlatUnroll], ev[kFlatUnroll];
-#pragma unroll
-        for (int u = 0; u < kFlatUnroll; ++u) {
-            const int v = v0 + u * kBlock;
-            if (v < nvec) {
-                gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g) + v);   // read once
-                ev[u] = reinterpret_cast<const f4*>(e)[v];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < kFlatUnroll; ++u) {
-            const int v = v0 + u * kBlock;
-            if (v < nvec) {
-                reinterpret_cast<f4*>(e)[v] = gv[u] + ev[u];
-                if (w == 0) __builtin_nontemporal_store(f4{0.f, 0.f, 0.f, 0.f}, reinterpret_cast<f4*>(o) + v);
-            }
-        }
+    // the matrix this slice belongs to: the last i with first[i] <= slice (the same in every lane)
+    int lo = 0, hi = n_mats - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (first[mid] <= slice) lo = mid;
+        else hi = mid - 1;
     }
-    const int tail = (int)(t.nelem - (int64_t)nvec * 4);
-    if ((int)threadIdx.x < tail) {
-        const int i = nvec * 4 + threadIdx.x;
-        e[i] = g[i] + e[i];
-        if (w == 0) o[i] = 0.f;
+    const MatDesc d = mats[lo];
+    const int64_t nm = (int64_t)d.n * d.m;
+    const int64_t e0 = (slice - first[lo]) * kFlatTileElems;
+    const int nelem = (int)(nm - e0 < kFlatTileElems ? nm - e0 : kFlatTileElems);
+    const float* g = grad + (int64_t)w * gstride + d.off + e0;
+    float* e = err + (int64_t)w * estride + d.off + e0;
+    float* o = out + d.off + e0;
+    // matrices start on multiples of 64 elements and slices on multiples of kFlatTileElems: the 16-byte accesses
+    // are aligned; a matrix's last few elements (n m not a multiple of 4) go one by one
+    const int v = threadIdx.x;
+    if (4 * v + 4 <= nelem) {
+        const f4 gv = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g) + v);   // read once
+        const f4 ev = reinterpret_cast<const f4*>(e)[v];
+        reinterpret_cast<f4*>(e)[v] = gv + ev;
+        if (w == 0) __builtin_nontemporal_store(f4{0.f, 0.f, 0.f, 0.f}, reinterpret_cast<f4*>(o) + v);
+    } else {
+        for (int i = 4 * v; i < nelem; ++i) {
+            e[i] = g[i] + e[i];
+            if (w == 0) o[i] = 0.f;
+        }
     }
 }
 
@@ -124,11 +125,16 @@ psgd_status launch_sparse_step(psgd_plan* plan, const void* grad, float* err, co
         return e == hipSuccess;
     };
     if (!mark(0)) return PSGD_EHIP;
-    if (!plan->tiles_flat.empty()) {
-        hipLaunchKernelGGL(k_ef_add_zero, dim3((unsigned)plan->tiles_flat.size(), (unsigned)plan->workers), dim3(kBlock), 0, s,
-                           plan->dev.mats, plan->dev.tiles_flat, static_cast<const float*>(grad), err,
+    const int64_t slices = plan->flat_tiles + plan->flat_vec_tiles;
+    if (slices > 0x7fffffffLL) {
+        plan->last_error = "baseline step: more than 2^31 slices of 1024 elements";
+        return PSGD_EUNSUPPORTED;
+    }
+    if (slices > 0) {
+        hipLaunchKernelGGL(k_ef_add_zero, dim3((unsigned)slices, (unsigned)plan->workers), dim3(kBlock), 0, s,
+                           plan->dev.mats, plan->dev.flat_first, (int)plan->mats.size(), static_cast<const float*>(grad), err,
                            static_cast<float*>(out), plan->workers, plan->sizes.grad_stride, plan->sizes.err_stride,
-                           plan->sizes.n_mat_elems);
+                           plan->sizes.n_mat_elems, plan->sizes.n_vec_elems);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) { plan->last_error = std::string("launch k_ef_add_zero: ") + hipGetErrorString(e); return PSGD_EHIP; }
     }

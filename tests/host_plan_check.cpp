@@ -185,15 +185,15 @@ static void check_p_tiling(const psgd_plan* plan) { check_cover(plan, plan->tile
 // Appendix G baselines: the slices of the flattened matrices (16-byte accesses: aligned starts), of the vector region
 // and of the kept entries each cover their range exactly once; the packed value offsets are back to back.
 static void check_baseline_tables(const psgd_plan* plan, int rank) {
-    std::vector<int64_t> flat(plan->mats.size(), 0), kept(plan->mats.size(), 0);
-    int64_t vec = 0, kept_total = 0;
-    for (const Tile& t : plan->tiles_flat) {
-        CHECK(t.nelem > 0 && t.nelem <= kFlatTileElems);
-        if (t.mat < 0) { CHECK(t.elem0 == vec); vec += t.nelem; continue; }
-        CHECK(t.mat < (int)plan->mats.size() && t.elem0 == flat[t.mat] && t.elem0 % 4 == 0);
-        flat[t.mat] += t.nelem;
+    std::vector<int64_t> kept(plan->mats.size(), 0);
+    int64_t kept_total = 0;
+    // running slice counts: matrix i owns slices [first[i], first[i+1]), enough to cover its n m elements
+    CHECK(plan->flat_first.size() == plan->mats.size() + 1 && plan->flat_first.back() == plan->flat_tiles);
+    for (size_t i = 0; i < plan->mats.size(); ++i) {
+        const int64_t nm = (int64_t)plan->mats[i].n * plan->mats[i].m;
+        CHECK(plan->flat_first[i + 1] - plan->flat_first[i] == (nm + kFlatTileElems - 1) / kFlatTileElems);
     }
-    CHECK(vec == plan->sizes.n_vec_elems);
+    CHECK(plan->flat_vec_tiles == (plan->sizes.n_vec_elems + kFlatTileElems - 1) / kFlatTileElems);
     CHECK((int64_t)plan->kept_slice_mat.size() == plan->kept_slices && plan->kept_slice_first.size() == plan->kept_slice_mat.size());
     for (size_t k = 0; k < plan->kept_slice_mat.size(); ++k) {
         const int32_t mi = plan->kept_slice_mat[k];
@@ -204,7 +204,7 @@ static void check_baseline_tables(const psgd_plan* plan, int rank) {
     for (size_t i = 0; i < plan->mats.size(); ++i) {
         const MatDesc& d = plan->mats[i];
         const int64_t nm = (int64_t)d.n * d.m;
-        CHECK(flat[i] == nm && d.off % 4 == 0);
+        CHECK(d.off % 4 == 0 && nm > 0);
         CHECK(d.kept == std::min<int64_t>(((int64_t)d.n + d.m) * rank, nm) && kept[i] == d.kept && d.kept_off == kept_total);
         CHECK(plan->mat_tensor[i] == d.tensor);
         kept_total += d.kept;
