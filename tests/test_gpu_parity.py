@@ -15,11 +15,13 @@ the fp64 trajectory at the same rate.  Holding 1e-5 over 100 free-running steps
 is therefore not a property an fp32 state can have.  The long runs are
 free-running in windows of RESYNC steps: at a window boundary the oracle's state
 is rounded to fp32 (the paper's storage precision) and the GPU is restarted from
-those bits.  RESYNC = 8 comes from measurement on the full ResNet18-shaped set at
-rank 2: the fp64 oracle whose state alone is kept in fp32 is 5e-7 away from the
-exact one after 8 steps and 1e-6 after 11; the GPU path, which also computes in
-fp32, starts a window at 1.3e-7 and is at 7e-6 after 8 steps, at 1.04e-5 after 10
-and at 5e-5 after 20 (first window of the run, the fastest growing one).  Short runs (the 10-step Tiny configuration) are free-running
+those bits.  RESYNC = 6 comes from measurement on the full ResNet18-shaped set:
+the fp64 oracle whose state alone is kept in fp32 is 2.4e-7 away from the exact one
+after 6 steps, 6.5e-7 after 8 and 1e-6 after 11 (rank 2); the GPU path, which also
+computes in fp32, starts a window at 1.3e-7 and, in the first window of a run (the
+fastest growing one), is at 1-2e-6 after 6 steps at every rank, at 6e-6 to 1.3e-5
+after 8 depending on rank and seed, and at 5e-5 after 20: six is the longest window
+that keeps a factor of five under the bar.  Short runs (the 10-step Tiny configuration) are free-running
 throughout.  A separate 100-step run never re-synchronised checks what stays
 well defined on a diverging trajectory: orthonormality, conservation of
 g + e = Delta' + e', and that the compression quality ||e'|| / ||M|| follows
@@ -34,7 +36,7 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 TOL = 1e-5
-RESYNC = 8
+RESYNC = 6
 
 
 def _need_gpu():
