@@ -131,9 +131,6 @@ PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, in
  *   res_spin      polls before a wait of the resident kernel gives up, 1 .. 2^30 (default 2^21)
  *   res_max_blocks  TEST ONLY: most workgroups the resident tiling may use (0, the default: what the device
  *                 holds at once, found when the plan's tables are uploaded)
- *   res_order     order of the matrices in the resident tile list: 0 (default) model order, 1 largest first
- *   res_groups, res_stagger   the resident tile list is cut into res_groups parts of about equal size (1 .. 8)
- *                 and the wavefronts of part g start loading g * res_stagger units of 512 clocks late
  *   k1_rows, k1_nv / k3_rows, k3_nv / k4_rows, k4_nv
  *                 rows per workgroup tile and column vectors per lane of the three sweeps of the
  *                 streaming path (P = M Q; Q = M^T P_hat; decompression); rows 0 (default):

@@ -91,7 +91,7 @@ struct RTile {
     int32_t nqparts;     // partial-Q slots of this column chunk
     int32_t cntq;        // running index of this column chunk over the model
     int32_t cnts;        // running index of this strip over the model
-    int32_t delay;       // units of 512 clocks this wavefront sleeps before its first load (later load groups)
+    int32_t pad_;
     int64_t elem0, nelem;  // vector tiles: slice of the vector region
 };
 
@@ -120,9 +120,6 @@ struct Tuning {
                             // against the device at upload (diagnostic, with res_max_blocks: lets a test see the waits give up)
     int64_t res_spin = 1 << 21;      // polls before a wait of the resident kernel gives up
     int64_t res_max_blocks = 0;      // 0: the device's capacity; else the most workgroups the resident tiling may use (diagnostic)
-    int64_t res_order = 0;           // order of the matrices in the resident tile list: 0 model order, 1 largest first
-    int64_t res_groups = 1;          // load groups: the tile list is cut into this many parts of about equal bytes ...
-    int64_t res_stagger = 0;         // ... and part g starts its loads g * res_stagger units of 512 clocks late
     int64_t res_rows = 0;   // 0: smallest strip height that fits; else forced strip height
     int64_t res_trace = 0;  // 1: the resident kernel records phase timestamps (diagnostic)
     int64_t xcd_order = -1;    // tile lists are ordered so that each accelerator die (own L2) works on one contiguous range of

@@ -248,8 +248,6 @@ psgd_status build_tables(psgd_plan* plan) {
         tu.k1_nv > kMaxVecPerLaneK1 || tu.k3_nv < 1 || tu.k3_nv > kMaxVecPerLaneK3 || tu.k4_nv < 1 ||
         tu.k4_nv > kMaxVecPerLaneK3 || tu.res_rows < 0 || tu.res_rows > kResRows || tu.resident < 0 || tu.resident > 2 ||
         tu.res_spin < 1 || tu.res_spin > (int64_t(1) << 30) || tu.res_max_blocks < 0 || tu.res_max_blocks > 65535 ||
-        tu.res_order < 0 || tu.res_order > 1 || tu.res_groups < 1 || tu.res_groups > 8 || tu.res_stagger < 0 ||
-        tu.res_stagger > 1024 ||
         tu.stream_hints < -1 || tu.stream_hints > 1 || tu.xcd_order < -1 || tu.gram_fused < 0 || tu.gram_fused > 2 || tu.gram_spin < 1 ||
         tu.gram_spin > (1 << 24))
         return PSGD_EINVAL;
@@ -397,19 +395,8 @@ void build_resident(psgd_plan* plan, int64_t device_blocks) {
     const int64_t vec_slice = (int64_t)kWave * 4 * 8;   // elements of the vector region per wavefront
     const int64_t vec_tiles = ceil_div(L, vec_slice);
 
-    // Order of the matrices in the tile list: model order, or largest first (the matrices with the most strips and
-    // column chunks then sit in the first workgroups, whose loads are issued and served first; measured on the
-    // ResNet18-shaped set it is 1 % slower than model order, which therefore stays the default).
-    std::vector<size_t> order(plan->mats.size());
-    for (size_t i = 0; i < order.size(); ++i) order[i] = i;
-    if (tu.res_order == 1)
-        std::stable_sort(order.begin(), order.end(), [&](size_t x, size_t y) {
-            const MatDesc& a = plan->mats[x];
-            const MatDesc& b = plan->mats[y];
-            if (a.vec != b.vec) return a.vec > b.vec;   // one access width per workgroup: keep the widths together
-            return (int64_t)a.n * a.m > (int64_t)b.n * b.m;
-        });
-
+    // The matrices keep model order in the tile list (largest first, so that the matrices with the most strips and
+    // column chunks sit in the first workgroups, was 1 % slower on the ResNet18-shaped set).
     auto layout = [&](int h, std::vector<RTile>* tiles, std::vector<MatDesc>* mats, int32_t* n_cntq,
                       int32_t* n_cnts) -> int64_t {
         // returns the number of workgroups, fills the tables when tiles != nullptr
@@ -423,8 +410,7 @@ void build_resident(psgd_plan* plan, int64_t device_blocks) {
                 ++slots;
             }
         };
-        for (size_t oi = 0; oi < order.size(); ++oi) {
-            const size_t i = order[oi];
+        for (size_t i = 0; i < plan->mats.size(); ++i) {
             const MatDesc& d0 = plan->mats[i];
             if (d0.vec != cur_vec) { pad_block(); cur_vec = d0.vec; }
             const int64_t nvec = d0.m / d0.vec;
@@ -514,22 +500,6 @@ void build_resident(psgd_plan* plan, int64_t device_blocks) {
     plan->res_blocks = (int32_t)blocks;
     plan->res_n_cntq = n_cntq;
     plan->res_n_cnts = n_cnts;
-    // Load groups: whole matrices in list order, a group closed once it holds its share of the elements; the
-    // wavefronts of group g start their loads g * res_stagger units late.
-    if (tu.res_groups > 1 && tu.res_stagger > 0) {
-        int64_t total = 0, seen = 0;
-        for (const MatDesc& d : plan->mats) total += (int64_t)d.n * d.m;
-        std::vector<int32_t> group_of(plan->mats.size(), 0);
-        for (size_t oi = 0; oi < order.size(); ++oi) {
-            const MatDesc& d = plan->mats[order[oi]];
-            // the group in which the middle of this matrix falls
-            const int64_t mid = seen + (int64_t)d.n * d.m / 2;
-            group_of[order[oi]] = (int32_t)std::min<int64_t>(tu.res_groups - 1, mid * tu.res_groups / std::max<int64_t>(total, 1));
-            seen += (int64_t)d.n * d.m;
-        }
-        for (RTile& t : plan->res_tiles)
-            t.delay = t.mat >= 0 ? group_of[t.mat] * (int32_t)tu.res_stagger : (t.mat == -1 ? (int32_t)((tu.res_groups - 1) * tu.res_stagger) : 0);
-    }
     // mailbox of the resident kernel (64-bit slots): per matrix [partial P | mean P | P_hat], then per
     // matrix [partial Q | Q]; the offsets are kept in res_mats
     int64_t off = 0;
@@ -744,9 +714,6 @@ psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value
     else if (!strcmp(key, "res_trace")) tu.res_trace = value;
     else if (!strcmp(key, "res_spin")) tu.res_spin = value;
     else if (!strcmp(key, "res_max_blocks")) tu.res_max_blocks = value;
-    else if (!strcmp(key, "res_order")) tu.res_order = value;
-    else if (!strcmp(key, "res_groups")) tu.res_groups = value;
-    else if (!strcmp(key, "res_stagger")) tu.res_stagger = value;
     else return PSGD_EINVAL;
     Tuning old = plan->tuning;
     plan->tuning = tu;

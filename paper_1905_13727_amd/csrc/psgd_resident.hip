@@ -127,10 +127,6 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
     const int64_t nr = (int64_t)d.n * ri, mr = (int64_t)d.m * ri;
     slot_t* mail_base = a.mail;
 
-    // A wavefront of a later load group lets the earlier groups' requests reach the memory system first, so that
-    // their dependency chains run under this group's loads and their stores under this group's chains.
-    for (int dl = 0; dl < t.delay; ++dl) __builtin_amdgcn_s_sleep(8);
-
     // ---------------- phase A ----------------
     trace_mark(a, 0);
     if (a.trace && lane == 0) {

@@ -63,6 +63,15 @@ def test_null_pointers_are_rejected_without_a_gpu():
     assert lib.psgd_step_update(plan._h, 1, 1, 1, 1, None, 1, 0.1, 0.9, 1, None) == B.PSGD_EINVAL     # no momentum buffer
     assert lib.psgd_step_update(plan._h, 1, 1, 1, 1, 1, 1, float("nan"), 0.9, 1, None) == B.PSGD_EINVAL  # NaN step size
     assert lib.psgd_decompress_update(plan._h, 1, 1, 1, 1, 1, None, 0.1, 0.9, 1, None) == B.PSGD_EINVAL
+    # the one-call form of several iterations: a count outside 1 .. 64 is refused
+    assert lib.psgd_step_iterations(plan._h, 1, 1, 1, 1, 1, 1, None, 0) == B.PSGD_EINVAL
+    assert lib.psgd_step_iterations(plan._h, 1, 1, 1, 1, 1, 1, None, 65) == B.PSGD_EINVAL
+    assert lib.psgd_step_iterations(plan._h, 1, 1, 1, 1, None, 1, None, 2) == B.PSGD_EINVAL
+    # the step without allocation refuses a plan whose tables are not on a device yet (no GPU call is made for that)
+    assert lib.psgd_step_static(plan._h, 1, 1, 1, 1, 1, None) == B.PSGD_EINVAL
+    assert b"not on the device" in lib.psgd_plan_last_error(plan._h)
+    assert lib.psgd_step_static(plan._h, 1, None, 1, 1, 1, None) == B.PSGD_EINVAL
+    assert lib.psgd_plan_kept(plan._h, 3, None, None) == B.PSGD_EINVAL and lib.psgd_plan_kept(plan._h, 0, None, None) == B.PSGD_OK
     assert lib.psgd_plan_sizes(plan._h, None) == B.PSGD_EINVAL
     assert lib.psgd_plan_offsets(plan._h, 5, None, None, None, None) == B.PSGD_EINVAL
     lib.psgd_plan_destroy(None)
@@ -77,6 +86,10 @@ def test_null_pointers_are_rejected_without_a_gpu():
         plan.set_tuning("gram_fused", 3)
     with pytest.raises(B.PsgdError):
         plan.set_tuning("gram_spin", 0)
+    for key, bad in (("resident", 3), ("res_spin", 0), ("res_max_blocks", -1), ("q_reduce_elems", 1), ("k1_mfma", 1)):
+        with pytest.raises(B.PsgdError):     # out of range, or a key that no longer exists
+            plan.set_tuning(key, bad)
+    plan.set_tuning("res_spin", 1 << 10)
     plan.set_tuning("gram_fused", 0)
     plan.set_tuning("gram_spin", 1024)
     with pytest.raises(B.PsgdError):
