@@ -423,22 +423,25 @@ __device__ __forceinline__ void await(F attempt, unsigned* err_word, unsigned ep
 // slot of the group (`probe`, the same address for the whole wavefront) at a relaxed pace, so that
 // two thousand waiting wavefronts put little load on the memory system; once it carries this step's
 // tag the rest is about to land and every lane polls the slots it needs.
-template <typename F>
-__device__ __forceinline__ void await_probed(const slot_t* probe, unsigned epoch, F attempt, unsigned* err_word,
-                                             unsigned limit) {
+// the probing alone: false when the wait was given up
+__device__ __forceinline__ bool await_tag(const slot_t* probe, unsigned epoch, unsigned* err_word, unsigned limit) {
     unsigned spins = 0;
     for (;;) {
         unsigned tag = epoch;
         if ((threadIdx.x & (kWave - 1)) == 0)
             tag = (unsigned)(__hip_atomic_load(probe, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32);
-        if (__builtin_amdgcn_readfirstlane(tag) == epoch) break;
+        if (__builtin_amdgcn_readfirstlane(tag) == epoch) return true;
         __builtin_amdgcn_s_sleep(6);
         if (give_up(++spins, limit, err_word, epoch)) {
             st_dev(err_word, epoch);
-            return;
+            return false;
         }
     }
-    await(attempt, err_word, epoch, limit);
+}
+template <typename F>
+__device__ __forceinline__ void await_probed(const slot_t* probe, unsigned epoch, F attempt, unsigned* err_word,
+                                             unsigned limit) {
+    if (await_tag(probe, epoch, err_word, limit)) await(attempt, err_word, epoch, limit);
 }
 
 // One slot, waited for by this lane alone (other lanes of the wavefront may be waiting for theirs).  Gives up after

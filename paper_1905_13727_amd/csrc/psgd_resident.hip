@@ -207,6 +207,10 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
         trace_mark_wave(a, 7);
         const int nval = nrows * ri;   // <= 128
         float sv[2] = {0.f, 0.f};
+        // The strip's last column chunk sits furthest down the tile list and tends to deliver last: one lane watches
+        // its slot before all lanes poll all chunks.  (A wavefront that polls everything for microseconds fills its
+        // compute unit's memory pipeline, and the loads of the other workgroup on that unit land 2-3 us late.)
+        await_tag(mail_pp + (int64_t)(d.n_cchunk - 1) * nr + t.row0, epoch, err_word, a.spin);
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             if (u * kWave < nval) {

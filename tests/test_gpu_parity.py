@@ -211,7 +211,8 @@ def test_one_launch_factorisation_reports_a_wait_that_gives_up():
 def test_resident_wait_that_gives_up_is_reported_and_the_plan_streams_on():
     """The resident kernel's workgroups wait for each other, so all of them must be on the chip at once; the planner
     sizes the grid for that.  Here the check is switched off (resident = 2) and the ResNet18-shaped set is cut into
-    8-row strips: four times more workgroups than the device holds.  With a small poll limit the waits give up,
+    8-row strips: four times more workgroups than the device holds.  With a poll limit of two rounds (far less than
+    the time until a workgroup that is not yet on the chip has delivered) waits give up,
     every workgroup still runs to its end, psgd_plan_check reports the failure and moves the plan to the streaming
     kernels, and the next step on the same plan (state restored) is at parity."""
     _need_gpu()
@@ -221,7 +222,7 @@ def test_resident_wait_that_gives_up_is_reported_and_the_plan_streams_on():
     rank, seed = 2, 7
     factors = WL.planted_factors(wl, seed)
     q0 = WL.initial_q(wl, rank, seed)
-    gpu = GpuRun(wl.shapes, rank, 1, q0, {"resident": 2, "res_max_blocks": 4096, "res_rows": 8, "res_spin": 64})
+    gpu = GpuRun(wl.shapes, rank, 1, q0, {"resident": 2, "res_max_blocks": 4096, "res_rows": 8, "res_spin": 2})
     ora = OracleRun(wl.shapes, rank, 1, q0)
     grads = [WL.gradients(wl, factors, seed, 0, 0)]
     print("[resident give-up] oversubscribed launch", flush=True)
