@@ -35,23 +35,23 @@ METRIC = "PowerSGD step gradient GB/s + % HBM peak, ResNet18 shapes r=2"   # the
 
 MEASURED_TRAFFIC = {
     # (workload, rank, workers, kernel slot of kernel_ms): FETCH_SIZE + WRITE_SIZE, scaled, bytes per launch
-    ("resnet18", 2, 1, "k_resident"): 200288882,      # profiles/resident_resnet18_r2.md
-    ("lstm", 4, 1, "k_ef_right"): 391861304,          # profiles/streaming_lstm_r4.md
-    ("lstm", 4, 1, "k_left"): 132708464,
-    ("lstm", 4, 1, "k_decomp"): 400277868,
-    ("resnet18", 2, 16, "k_ef_right"): 2169944560,    # profiles/streaming_resnet18_w16_r2.md
-    ("resnet18", 2, 16, "k_left"): 726187447,
-    ("resnet18", 2, 16, "k_decomp"): 1479682475,
-    ("resnet18", 2, 1, "k_ef_add_zero"): 179024126,   # profiles/baseline_random_*_resnet18_r2.md
+    ("resnet18", 2, 1, "k_resident"): 200118894,      # profiles/resident_resnet18_r2.md
+    ("lstm", 4, 1, "k_ef_right"): 391863557,          # profiles/streaming_lstm_r4.md
+    ("lstm", 4, 1, "k_left"): 132707849,
+    ("lstm", 4, 1, "k_decomp"): 400357535,
+    ("resnet18", 2, 16, "k_ef_right"): 2169944030,    # profiles/streaming_resnet18_w16_r2.md
+    ("resnet18", 2, 16, "k_left"): 726187992,
+    ("resnet18", 2, 16, "k_decomp"): 1479685687,
+    ("resnet18", 2, 1, "k_ef_add_zero"): 178776239,   # profiles/baseline_random_*_resnet18_r2.md
 }
 # The 24-layer transformer-shaped set: the counter runs end in a crash of the profiler once the process holds
 # several GB of device memory, so the counters were taken on the embedding + 4 layers (same kernels and tiles,
 # profiles/transformer_4layers_bf16_r*_counters.md); here: measured traffic / algorithmic bytes of that subset,
 # applied to the full set's algorithmic bytes.
 TRANSFORMER_TRAFFIC_RATIO = {
-    (4, "k_ef_right"): 3183900381 / 3043491840, (4, "k_left"): 1273797976 / 1217396736, (4, "k_decomp"): 3182370412 / 3043934208,
-    (16, "k_ef_right"): 3192048669 / 3043491840, (16, "k_left"): 1285844555 / 1217396736, (16, "k_decomp"): 3230931164 / 3043934208,
-    (32, "k_ef_right"): 3257299928 / 3043491840, (32, "k_left"): 1305106500 / 1217396736, (32, "k_decomp"): 3255200543 / 3043934208,
+    (4, "k_ef_right"): 3183901020 / 3043491840, (4, "k_left"): 1273799574 / 1217396736, (4, "k_decomp"): 3182413765 / 3043934208,
+    (16, "k_ef_right"): 3192121738 / 3043491840, (16, "k_left"): 1285844662 / 1217396736, (16, "k_decomp"): 3230979309 / 3043934208,
+    (32, "k_ef_right"): 3257136164 / 3043491840, (32, "k_left"): 1305107626 / 1217396736, (32, "k_decomp"): 3255566005 / 3043934208,
 }
 
 

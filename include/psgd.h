@@ -322,12 +322,10 @@ PSGD_API const char* psgd_kernel_name(int32_t index);
 PSGD_API psgd_status psgd_plan_check(psgd_plan* plan, void* hip_stream, int32_t* is_resident);
 
 /* Diagnostic.  After psgd_plan_set_tuning(plan, "res_trace", 1), every resident
- * step records 16 values per wavefront: device timestamps (100 MHz clock) of 0 start,
- * 1 partial P posted, 3 own rows of P_hat computed, 4 own part in the sum of Q done,
- * 5 Q received, 6 end, 11 Gram matrices of all strips received; 7..9 are written by a
- * wavefront that adds a strip's column chunks (begin, chunks added, rows of P and Gram
- * matrix posted), 10 and 2 by the first wavefront of a column chunk's first run
- * (partial Q posted, first batch of the chunk's partials fetched); 12..15 name
+ * step records 16 values per wavefront: device timestamps (100 MHz clock) of start,
+ * partial P posted, reducer work done, P_hat received, partial Q posted, Q received,
+ * end; 7..11 are written by a wavefront that orthogonalises (own partial posted,
+ * strip sum posted, mean P received, Gram-Schmidt done, P_hat posted); 12..15 name
  * the tile: matrix, column chunk (upper half: the hardware id register of the
  * wavefront), first row (upper half: accelerator die), partial-Q slot or -1.
  * Synchronises the device and copies at most

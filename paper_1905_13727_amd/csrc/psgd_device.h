@@ -256,11 +256,6 @@ __device__ __forceinline__ float lane_bcast(float v, int src_lane) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
 }
 
-// every lane reads the value of a lane of its own choice
-__device__ __forceinline__ float lane_gather(float v, int src_lane) {
-    return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane << 2, __float_as_int(v)));
-}
-
 template <int CTRL>
 __device__ __forceinline__ float dpp_mov(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
@@ -474,13 +469,6 @@ __device__ __forceinline__ double take_double(const slot_t* pair, slot_t first_l
     const unsigned lo = take_bits(pair, first_lo, epoch, err_word, limit);
     const unsigned hi = take_bits(pair + 1, first_hi, epoch, err_word, limit);
     return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
-}
-
-// Shared memory written by lanes of this wavefront is read by other lanes of the same wavefront (or the reverse)
-// across this point: the wavefront's LDS operations complete in order, the compiler must not move them.
-__device__ __forceinline__ void wave_lds_done() {
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
 }
 
 // Wait until every memory operation this wavefront has issued is complete (loads returned, stores

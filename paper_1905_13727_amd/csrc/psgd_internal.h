@@ -69,8 +69,7 @@ struct Tile {
 constexpr int kResRows = 32;         // most rows of a resident tile (registers: rows * vec floats per lane) ...
 constexpr int res_rows_for_rank(int r) { return r <= 2 ? 32 : 24; }   // ... fewer when the rank needs the registers
 constexpr int kResMinRows = 8;       // strips are not made thinner than this
-constexpr int kResMaxN = 512;        // taller matrices are streamed (the planner's policy: the resident tiling is tuned on
-                                     // convolution-shaped sets, whose matrices have at most 512 rows)
+constexpr int kResMaxN = 512;        // tallest matrix the single-wavefront Gram-Schmidt handles (8 rows per lane)
 constexpr int kResMaxRank = 4;
 constexpr int kResCUs = 256;         // MI355X compute units: the planner's provisional figure (it runs without a device); the
                                      // tiling is laid out again for the device's own count when the tables are uploaded
@@ -83,15 +82,15 @@ struct RTile {
     int32_t row0, nrows; // strip of rows (nrows <= kResRows)
     int32_t vec0, nvec;  // column vectors (nvec <= 64)
     int32_t ppart;       // column-chunk index = slice of partial P this tile writes; the wavefront with
-                         // ppart == 0 adds the chunks of its strip and reduces the strip's Gram matrix
+                         // ppart == 0 adds the chunks of its strip, the one that also has row0 == 0
+                         // orthogonalises the matrix
     int32_t nstrips_mat; // strips of this matrix
     int32_t qrun_len;    // > 0: first of a run of consecutive wavefronts of the workgroup that hold strips of
                          // the same column chunk; it adds the run's sums in LDS and writes one partial Q
-    int32_t qpart;       // slot of that partial; the run with qpart == 0 also stores Q
+    int32_t qpart;       // slot of that partial; the run with qpart == 0 adds the chunk's partials
     int32_t nqparts;     // partial-Q slots of this column chunk
     int32_t cntq;        // running index of this column chunk over the model
     int32_t cnts;        // running index of this strip over the model
-    int32_t strip;       // index of this strip within its matrix
     int32_t pad_;
     int64_t elem0, nelem;  // vector tiles: slice of the vector region
 };

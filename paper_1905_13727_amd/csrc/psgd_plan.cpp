@@ -436,7 +436,6 @@ void build_resident(psgd_plan* plan, int64_t device_blocks) {
                         t.ppart = (int32_t)c;
                         t.cntq = cntq;
                         t.cnts = cnts + (int32_t)sidx;
-                        t.strip = (int32_t)sidx;
                         if (new_run) {
                             run_leader = tiles->size();
                             t.qrun_len = 1;
@@ -501,13 +500,12 @@ void build_resident(psgd_plan* plan, int64_t device_blocks) {
     plan->res_blocks = (int32_t)blocks;
     plan->res_n_cntq = n_cntq;
     plan->res_n_cnts = n_cnts;
-    // mailbox of the resident kernel (64-bit slots): per matrix [partial P | mean P | the strips' Gram matrices:
-    // upper triangle, two slots per fp64 entry], then per matrix [partial Q | Q]; the offsets are kept in res_mats
-    const int64_t gram_slots = (int64_t)plan->rank * (plan->rank + 1);
+    // mailbox of the resident kernel (64-bit slots): per matrix [partial P | mean P | P_hat], then per
+    // matrix [partial Q | Q]; the offsets are kept in res_mats
     int64_t off = 0;
     for (MatDesc& d : plan->res_mats) {
         d.ppart_off = off;
-        off += round_up(((int64_t)d.n_cchunk + 1) * d.n * d.r + ceil_div(d.n, h) * gram_slots, kAlignElems);
+        off += round_up(((int64_t)d.n_cchunk + 2) * d.n * d.r, kAlignElems);
     }
     for (MatDesc& d : plan->res_mats) {
         d.qpart_off = off;

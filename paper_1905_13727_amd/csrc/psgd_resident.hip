@@ -7,19 +7,17 @@
 // store, so that HBM sees each matrix element exactly once in (g, e) and once out (e', Delta'):
 //
 //   phase A   load g, e; M = g + e (Alg. 2);  row dot products of P = M Q (Alg. 1) -> partial P per
-//             column chunk; the wavefront with the first chunk of a strip adds the strip's chunks,
-//             publishes the strip's rows of P and the strip's share of the r x r Gram matrix P^T P (fp64)
-//   phase B   (needs this strip's rows of P and every strip's Gram matrix)  P_hat = P R^-1, R the Cholesky
-//             factor of the Gram matrix: the orthonormal factor Gram-Schmidt computes (Alg. 1
-//             "orthogonalize"), worked out by every wavefront for its own rows, so that no wavefront
-//             orthogonalises for the others;  Q = M^T P_hat from the registers -> partial Q per
+//             column chunk; the wavefront with the first chunk of a strip adds the strip's chunks;
+//             the wavefront with the first tile of a matrix runs Gram-Schmidt on the n x r panel
+//             (Alg. 1 "orthogonalize") and publishes P_hat
+//   phase B   (needs this strip's rows of P_hat)  Q = M^T P_hat from the registers -> partial Q per
 //             run of strips (consecutive wavefronts of a workgroup with the same column chunk); the
 //             first wavefront of every run adds the chunk's runs and hands Q to its run through LDS
 //   phase C   (needs this chunk's rows of Q)  Delta' = P_hat Q^T (Alg. 1 "decompress"),
 //             e' = M - Delta' (Alg. 2), each stored once
 //
 // The two "needs" are the two global dependencies of the method (all of P before P_hat, all of Q
-// before P_hat Q^T), taken per matrix and per column chunk instead of as grid-wide barriers.
+// before P_hat Q^T), taken per strip and per column chunk instead of as grid-wide barriers.
 //
 // Everything that crosses wavefronts travels through a plan-owned MAILBOX of 64-bit slots
 // {value, tag}: the producer writes the float together with the step's epoch in one 8-byte
@@ -43,7 +41,7 @@
 
 namespace psgd {
 
-constexpr int kGramBatch = 4;   // slots of the strips' Gram matrices a lane fetches together
+constexpr int kResRowsPerLane = kResMaxN / kWave;   // rows of the Gram-Schmidt panel a lane holds
 
 struct ResArgs {
     const MatDesc* mats;         // resident descriptors: ppart_off / qpart_off are mailbox offsets (slots)
@@ -69,14 +67,51 @@ __device__ __forceinline__ void trace_mark(const ResArgs& a, int point) {
 }
 __device__ __forceinline__ void trace_mark_wave(const ResArgs& a, int point) { trace_mark(a, point); }
 
+// ---- Gram-Schmidt by one wavefront -------------------------------------------------------------------
+// Rows lane, lane + 64, ... of the n x r panel are held in registers (n <= kResMaxN).  Column by
+// column, left to right: squared norm and dot products with the columns to the right in fp64, reduced
+// over the wavefront; normalise; remove the component from the columns to the right (modified
+// Gram-Schmidt).  A column whose squared norm is <= 1e-30 at its turn becomes zero.
+template <int R>
+__device__ __forceinline__ void gram_schmidt_rows(float (&P)[kResRowsPerLane][R], int ri) {
+#pragma unroll
+    for (int c = 0; c < R; ++c) {
+        if (c < ri) {
+            double s[R];
+#pragma unroll
+            for (int k = 0; k < R; ++k) s[k] = 0.0;
+#pragma unroll
+            for (int j = 0; j < kResRowsPerLane; ++j) {
+                const double pc = (double)P[j][c];
+#pragma unroll
+                for (int k = c; k < R; ++k) s[k] += pc * (double)P[j][k];
+            }
+#pragma unroll
+            for (int k = c; k < R; ++k) s[k] = wave_sum(s[k]);
+            const double scc = s[c];
+            if (scc <= 1e-30) {
+#pragma unroll
+                for (int j = 0; j < kResRowsPerLane; ++j) P[j][c] = 0.f;
+            } else {
+                const double inv = 1.0 / sqrt(scc);
+#pragma unroll
+                for (int j = 0; j < kResRowsPerLane; ++j) {
+                    const double pc = (double)P[j][c];
+                    P[j][c] = (float)(pc * inv);
+#pragma unroll
+                    for (int k = c + 1; k < R; ++k) P[j][k] = (float)((double)P[j][k] - (s[k] / scc) * pc);
+                }
+            }
+        }
+    }
+}
+
 // ---- the step, for a workgroup whose tiles use V-wide row accesses ---------------------------------------
 // ITER: several subspace iterations on the resident tile (Appendix G.7): P = M Q, orthogonalise, Q = M^T P_hat
 // repeated a.iters times before the decompression, each round under its own mailbox tag epoch0 + round.
 template <int R, int V, bool UPD, bool ITER>
-__device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, float* lds, unsigned* gl,
-                                              unsigned epoch0) {
+__device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, float* lds, unsigned epoch0) {
     constexpr int RT = res_rows_for_rank(R);
-    constexpr int NE = R * (R + 1) / 2;   // entries of the upper triangle of the r x r Gram matrix
     const int lane_id = threadIdx.x & (kWave - 1);
     const int lane = lane_id;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -153,7 +188,7 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
     }
     slot_t* mail_pp = mail_base + d.ppart_off;            // partial P   [n_cchunk][n][r]
     slot_t* mail_pb = mail_pp + (int64_t)d.n_cchunk * nr; // mean P      [n][r]
-    slot_t* mail_g = mail_pb + nr;                        // Gram matrices of the strips [strip][entry][low, high]
+    slot_t* mail_ph = mail_pb + nr;                       // P_hat       [n][r]
     slot_t* mail_qp = mail_base + d.qpart_off;            // partial Q   [n_rblock][m][r]
     {
         // the strip's row dot products: lane i receives row i's (rows past the strip were read as zeros)
@@ -200,157 +235,100 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
         }
     }
     trace_mark(a, 1);
+    if (active && t.ppart == 0 && t.row0 == 0) trace_mark_wave(a, 7);
     if (active && t.ppart == 0) {
         // This wavefront holds the first column chunk of its strip: it adds the strip's chunks in chunk
-        // order into the rows of the mean P (W = 1: the mean over workers is the value itself), publishes them,
-        // and publishes the strip's share of the Gram matrix P^T P (fp64, upper triangle).
-        trace_mark_wave(a, 7);
+        // order into the rows of the mean P (W = 1: the mean over workers is the value itself).
         const int nval = nrows * ri;   // <= 128
-        float sv[2] = {0.f, 0.f};
         // The strip's last column chunk sits furthest down the tile list and tends to deliver last: one lane watches
         // its slot before all lanes poll all chunks.  (A wavefront that polls everything for microseconds fills its
         // compute unit's memory pipeline, and the loads of the other workgroup on that unit land 2-3 us late.)
         await_tag(mail_pp + (int64_t)(d.n_cchunk - 1) * nr + t.row0, epoch, err_word, a.spin);
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            if (u * kWave < nval) {
-                const int idx = lane + kWave * u;
-                const bool mine = idx < nval;
-                const int idx_c = mine ? idx : nval - 1;
-                const int64_t at = (int64_t)(idx_c / nrows) * d.n + t.row0 + idx_c % nrows;   // [k][row]
-                float s = 0.f;
-                constexpr int CG = 20;   // chunk partials polled together
-                for (int c0 = 0; c0 < d.n_cchunk; c0 += CG) {
-                    slot_t w[CG];
-                    await([&]() {
-#pragma unroll
-                        for (int cc = 0; cc < CG; ++cc)
-                            w[cc] = fetch(mail_pp + (int64_t)min(c0 + cc, d.n_cchunk - 1) * nr + at);
-                        bool ok = true;
-#pragma unroll
-                        for (int cc = 0; cc < CG; ++cc) ok &= arrived(w[cc], epoch);
-                        return ok;
-                    }, err_word, epoch, a.spin);
+        for (int u = 0; u * kWave < nval; ++u) {
+            const int idx = lane + kWave * u;
+            const bool mine = idx < nval;
+            const int idx_c = mine ? idx : nval - 1;
+            const int64_t at = (int64_t)(idx_c / nrows) * d.n + t.row0 + idx_c % nrows;   // [k][row]
+            float s = 0.f;
+            constexpr int CG = 20;   // chunk partials polled together
+            for (int c0 = 0; c0 < d.n_cchunk; c0 += CG) {
+                slot_t w[CG];
+                await([&]() {
 #pragma unroll
                     for (int cc = 0; cc < CG; ++cc)
-                        if (c0 + cc < d.n_cchunk) s += value_of(w[cc]);
-                }
-                if (mine) post(mail_pb + at, s, epoch);
-                sv[u] = mine ? s : 0.f;
+                        w[cc] = fetch(mail_pp + (int64_t)min(c0 + cc, d.n_cchunk - 1) * nr + at);
+                    bool ok = true;
+#pragma unroll
+                    for (int cc = 0; cc < CG; ++cc) ok &= arrived(w[cc], epoch);
+                    return ok;
+                }, err_word, epoch, a.spin);
+#pragma unroll
+                for (int cc = 0; cc < CG; ++cc)
+                    if (c0 + cc < d.n_cchunk) s += value_of(w[cc]);
             }
+            if (mine) post(mail_pb + at, s, epoch);
         }
-        trace_mark_wave(a, 8);
-        // lane i takes row i of the strip (value k * nrows + i of the sums above, for every k)
-        float prow[R];
+        if (t.row0 == 0) {
+            // ... and this one also holds the first strip: it orthogonalises the matrix's panel.
+            trace_mark_wave(a, 8);
+            float P[kResRowsPerLane][R];
+            {
+                slot_t w[kResRowsPerLane][R];
+                await([&]() {
 #pragma unroll
-        for (int k = 0; k < R; ++k) {
-            const int idx = k * nrows + lane;
-            const float v0 = lane_gather(sv[0], idx & (kWave - 1)), v1 = lane_gather(sv[1], idx & (kWave - 1));
-            prow[k] = (lane < nrows && k < ri) ? (idx >= kWave ? v1 : v0) : 0.f;
-        }
-        unsigned word = 0;
-        {
-            int e = 0;
+                    for (int j = 0; j < kResRowsPerLane; ++j)
 #pragma unroll
-            for (int x = 0; x < R; ++x)
+                        for (int k = 0; k < R; ++k)
+                            w[j][k] = fetch(mail_pb + (int64_t)min(k, ri - 1) * d.n + min(lane + kWave * j, d.n - 1));
+                    bool ok = true;
 #pragma unroll
-                for (int y = x; y < R; ++y, ++e) {
-                    const unsigned long long b =
-                        (unsigned long long)__double_as_longlong(wave_sum((double)prow[x] * (double)prow[y]));
-                    if ((lane >> 1) == e) word = (lane & 1) ? (unsigned)(b >> 32) : (unsigned)(b & 0xffffffffULL);
+                    for (int j = 0; j < kResRowsPerLane; ++j)
+#pragma unroll
+                        for (int k = 0; k < R; ++k) ok &= arrived(w[j][k], epoch);
+                    return ok;
+                }, err_word, epoch, a.spin);
+#pragma unroll
+                for (int j = 0; j < kResRowsPerLane; ++j)
+#pragma unroll
+                    for (int k = 0; k < R; ++k)
+                        P[j][k] = (lane + kWave * j < d.n && k < ri) ? value_of(w[j][k]) : 0.f;
+            }
+            trace_mark_wave(a, 9);
+            gram_schmidt_rows<R>(P, ri);
+            trace_mark_wave(a, 10);
+#pragma unroll
+            for (int j = 0; j < kResRowsPerLane; ++j) {
+                const int row = lane + kWave * j;
+                if (row < d.n) {
+#pragma unroll
+                    for (int k = 0; k < R; ++k)
+                        if (k < ri) {
+                            post(mail_ph + (int64_t)k * d.n + row, P[j][k], epoch);
+                            a.p[d.p_off + (int64_t)row * ri + k] = P[j][k];
+                        }
                 }
+            }
+            trace_mark_wave(a, 11);
         }
-        // a double travels as two slots (low word, high word)
-        if (lane < 2 * NE) post(mail_g + (int64_t)t.strip * (2 * NE) + lane, __uint_as_float(word), epoch);
-        trace_mark_wave(a, 9);
     }
+    trace_mark(a, 2);
 
     // ---------------- phase B ----------------
-    // This strip's rows of P_hat = P R^-1, R the Cholesky factor of the Gram matrix (what Gram-Schmidt computes:
-    // "orthogonalize" of Alg. 1): every wavefront adds the strips' Gram matrices in strip order, factorises
-    // (fp64) and solves for its own rows, so P_hat is one trip through memory behind the last strip's sums.
 #pragma unroll
     for (int k = 0; k < R; ++k) pr[k] = 0.f;
     if (active) {
-        slot_t wp[R];
+        slot_t w[R];
         const int64_t my_row = t.row0 + min(lane, nrows - 1);
-        const int nst = t.nstrips_mat;
-        constexpr int SB = (kGramBatch * kWave / 2) / NE;   // strips whose Gram matrices are fetched together
-        double part = 0.0;                                  // lane e < NE: entry e, summed over the strips
-        unsigned* gw = gl + wave * (kGramBatch * kWave);
-        for (int s0 = 0; s0 < nst; s0 += SB) {
-            const int ns = min(SB, nst - s0);
-            const int cnt = ns * 2 * NE;
-            const slot_t* src = mail_g + (int64_t)s0 * (2 * NE);
-            slot_t w[kGramBatch];
-            auto attempt = [&]() {
+        await_probed(mail_ph + t.row0, epoch, [&]() {
 #pragma unroll
-                for (int v = 0; v < kGramBatch; ++v) w[v] = fetch(src + min(lane + kWave * v, cnt - 1));
-                bool ok = true;
-                if (s0 == 0) {
+            for (int k = 0; k < R; ++k) w[k] = fetch(mail_ph + (int64_t)min(k, ri - 1) * d.n + my_row);
+            bool ok = true;
 #pragma unroll
-                    for (int k = 0; k < R; ++k) wp[k] = fetch(mail_pb + (int64_t)min(k, ri - 1) * d.n + my_row);
+            for (int k = 0; k < R; ++k) ok &= arrived(w[k], epoch);
+            return ok;
+        }, err_word, a.spin);
 #pragma unroll
-                    for (int k = 0; k < R; ++k) ok &= arrived(wp[k], epoch);
-                }
-#pragma unroll
-                for (int v = 0; v < kGramBatch; ++v) ok &= arrived(w[v], epoch);
-                return ok;
-            };
-            if (s0 == 0) await_probed(mail_pb + t.row0, epoch, attempt, err_word, a.spin);
-            else await(attempt, err_word, epoch, a.spin);
-#pragma unroll
-            for (int v = 0; v < kGramBatch; ++v) gw[lane + kWave * v] = (unsigned)(w[v] & 0xffffffffULL);
-            wave_lds_done();
-            if (lane < NE)
-                for (int s = 0; s < ns; ++s) {
-                    const unsigned lo = gw[(s * NE + lane) * 2], hi = gw[(s * NE + lane) * 2 + 1];
-                    part += __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
-                }
-            wave_lds_done();
-        }
-        trace_mark(a, 11);
-        float prow[R];
-#pragma unroll
-        for (int k = 0; k < R; ++k) prow[k] = (lane < nrows && k < ri) ? value_of(wp[k]) : 0.f;
-        // upper triangular factor U (U^T U = Gram matrix), row by row; a pivot <= 1e-30 (the squared norm
-        // Gram-Schmidt would find for that column at its turn) gives a zero column
-        double U[R][R], rinv[R], ph[R];
-        {
-            int e = 0;
-#pragma unroll
-            for (int x = 0; x < R; ++x)
-#pragma unroll
-                for (int y = x; y < R; ++y, ++e) U[x][y] = lane_bcast(part, e);
-        }
-#pragma unroll
-        for (int c = 0; c < R; ++c) {
-            double piv = U[c][c];
-#pragma unroll
-            for (int k = 0; k < c; ++k) piv -= U[k][c] * U[k][c];
-            const bool zero = !(piv > 1e-30);
-            rinv[c] = zero ? 0.0 : 1.0 / sqrt(piv);
-#pragma unroll
-            for (int j = c + 1; j < R; ++j) {
-                double s = U[c][j];
-#pragma unroll
-                for (int k = 0; k < c; ++k) s -= U[k][c] * U[k][j];
-                U[c][j] = s * rinv[c];
-            }
-        }
-#pragma unroll
-        for (int c = 0; c < R; ++c) {
-            double s = (double)prow[c];
-#pragma unroll
-            for (int k = 0; k < c; ++k) s -= ph[k] * U[k][c];
-            ph[c] = s * rinv[c];
-            pr[c] = (float)ph[c];
-        }
-        if (t.ppart == 0 && lane < nrows) {
-#pragma unroll
-            for (int k = 0; k < R; ++k)
-                if (k < ri) a.p[d.p_off + (int64_t)(t.row0 + lane) * ri + k] = pr[k];
-        }
+        for (int k = 0; k < R; ++k) pr[k] = (lane < nrows && k < ri) ? value_of(w[k]) : 0.f;
     }
     trace_mark(a, 3);
     float acc[V][R];
@@ -396,7 +374,7 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
             // Every run of this column chunk adds the chunk's partials itself, in run order (the same sum in each of
             // them): Q is then one trip through memory away from the partials, not two, and only the runs' first
             // wavefronts poll.  The chunk's first run also stores Q.
-            if (t.qpart == 0 && t.ppart != 0) trace_mark_wave(a, 10);
+            if (t.qpart == 0 && !(t.ppart == 0 && t.row0 == 0)) trace_mark_wave(a, 8);
             float s[V][R];
 #pragma unroll
             for (int x = 0; x < V; ++x)
@@ -431,7 +409,7 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
 #pragma unroll
                         for (int k = 0; k < R; ++k)
                             if (p0 + u < t.nqparts) s[x][k] += value_of(w[u][x][k]);
-                if (t.qpart == 0 && t.ppart != 0 && p0 == 0) trace_mark_wave(a, 2);
+                if (t.qpart == 0 && !(t.ppart == 0 && t.row0 == 0)) trace_mark_wave(a, 9 + min(p0 / PG, 2));
             }
             if (t.qpart == 0 && valid) {
 #pragma unroll
@@ -533,7 +511,6 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
 template <int R, bool UPD, bool ITER>
 __global__ __launch_bounds__(kBlock, 2) void k_resident(ResArgs a) {
     __shared__ float lds[kWavesPerBlock * 4 * R * kWave];
-    __shared__ unsigned gl[kWavesPerBlock * kGramBatch * kWave];   // per wavefront: a batch of Gram-matrix words
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // the epoch cannot change before every workgroup of this launch has finished
     unsigned epoch = 0;
@@ -543,9 +520,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_resident(ResArgs a) {
     // all tiles of a workgroup use the same access width; the first slot is never idle
     const RTile t0 = a.tiles[blockIdx.x * kWavesPerBlock];
     const int vec = t0.mat >= 0 ? a.mats[t0.mat].vec : 4;
-    if (vec == 4) resident_body<R, 4, UPD, ITER>(a, t, lds, gl, epoch);
-    else if (vec == 2) resident_body<R, 2, UPD, ITER>(a, t, lds, gl, epoch);
-    else resident_body<R, 1, UPD, ITER>(a, t, lds, gl, epoch);
+    if (vec == 4) resident_body<R, 4, UPD, ITER>(a, t, lds, epoch);
+    else if (vec == 2) resident_body<R, 2, UPD, ITER>(a, t, lds, epoch);
+    else resident_body<R, 1, UPD, ITER>(a, t, lds, epoch);
     // the workgroup that finishes last advances the epoch for the next launch
     __syncthreads();
     if (threadIdx.x == 0) {

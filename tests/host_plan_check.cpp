@@ -143,16 +143,10 @@ static void check_resident(const psgd_plan* plan) {
             CHECK(t.nrows * d.r <= 2 * kWave);
         }
     {
-        // mailbox regions: [partial P | mean P | Gram matrices of the strips, two slots per entry of the upper
-        // triangle] and [partial Q | Q] per matrix, disjoint, inside the mailbox
+        // mailbox regions: [partial P | mean P | P_hat] and [partial Q | Q] per matrix, disjoint, inside the mailbox
         std::vector<std::pair<int64_t, int64_t>> regions;
-        std::vector<int64_t> strips_of(plan->res_mats.size(), 0);
-        for (const RTile& t : plan->res_tiles)
-            if (t.mat >= 0) strips_of[t.mat] = t.nstrips_mat;
-        for (size_t i = 0; i < plan->res_mats.size(); ++i) {
-            const MatDesc& d = plan->res_mats[i];
-            regions.push_back({d.ppart_off, d.ppart_off + ((int64_t)d.n_cchunk + 1) * d.n * d.r +
-                                                strips_of[i] * plan->rank * (plan->rank + 1)});
+        for (const MatDesc& d : plan->res_mats) {
+            regions.push_back({d.ppart_off, d.ppart_off + ((int64_t)d.n_cchunk + 2) * d.n * d.r});
             regions.push_back({d.qpart_off, d.qpart_off + ((int64_t)d.n_rblock + 1) * d.m * d.r});
         }
         std::sort(regions.begin(), regions.end());
@@ -163,22 +157,18 @@ static void check_resident(const psgd_plan* plan) {
         }
     }
     CHECK(plan->res_sync_words == kResSyncWords);
-    // exactly one strip reducer per strip (each writing its own Gram-matrix slots: the strip indices of a matrix
-    // are 0 .. strips - 1, the same for all column chunks of a strip), one chunk reducer per column chunk
+    // exactly one strip reducer per strip, one orthogonaliser per matrix, one chunk reducer per column chunk
     {
-        std::vector<int> strip_red(plan->res_n_cnts, 0), chunk_red(plan->res_n_cntq, 0);
-        std::vector<int> first_cnts(plan->mats.size(), 1 << 30);
-        for (const RTile& t : plan->res_tiles)
-            if (t.mat >= 0) first_cnts[t.mat] = std::min(first_cnts[t.mat], t.cnts);
+        std::vector<int> strip_red(plan->res_n_cnts, 0), chunk_red(plan->res_n_cntq, 0), ortho(plan->mats.size(), 0);
         for (const RTile& t : plan->res_tiles) {
             if (t.mat < 0) continue;
-            CHECK(t.strip >= 0 && t.strip < t.nstrips_mat);
-            CHECK(t.strip == t.cnts - first_cnts[t.mat]);
             if (t.ppart == 0) strip_red[t.cnts] += 1;
+            if (t.ppart == 0 && t.row0 == 0) ortho[t.mat] += 1;
             if (t.qrun_len > 0 && t.qpart == 0) chunk_red[t.cntq] += 1;
         }
         for (int v : strip_red) CHECK(v == 1);
         for (int v : chunk_red) CHECK(v == 1);
+        for (int v : ortho) CHECK(v == 1);
     }
     // every strip counter is shared by exactly the column chunks of one strip
     {
