@@ -273,6 +273,8 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
             trace_mark_wave(a, 8);
             float P[kResRowsPerLane][R];
             {
+                // again one lane first, on the matrix's last row (its last strip is furthest down the tile list)
+                await_tag(mail_pb + (d.n - 1), epoch, err_word, a.spin);
                 slot_t w[kResRowsPerLane][R];
                 await([&]() {
 #pragma unroll
