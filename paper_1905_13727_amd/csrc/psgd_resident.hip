@@ -318,17 +318,22 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
     // ---------------- phase B ----------------
 #pragma unroll
     for (int k = 0; k < R; ++k) pr[k] = 0.f;
+    // The workgroup's first wavefront watches for P_hat (one lane, one slot); the others wait for it at a barrier,
+    // which costs no memory traffic.  Its strips are mostly consecutive strips of one matrix and get their rows at
+    // the same time; they meet at the barrier of the sum of Q a moment later anyway.
+    if (active && wave == 0) await_tag(mail_ph + t.row0, epoch, err_word, a.spin);
+    __syncthreads();
     if (active) {
         slot_t w[R];
         const int64_t my_row = t.row0 + min(lane, nrows - 1);
-        await_probed(mail_ph + t.row0, epoch, [&]() {
+        await([&]() {
 #pragma unroll
             for (int k = 0; k < R; ++k) w[k] = fetch(mail_ph + (int64_t)min(k, ri - 1) * d.n + my_row);
             bool ok = true;
 #pragma unroll
             for (int k = 0; k < R; ++k) ok &= arrived(w[k], epoch);
             return ok;
-        }, err_word, a.spin);
+        }, err_word, epoch, a.spin);
 #pragma unroll
         for (int k = 0; k < R; ++k) pr[k] = (lane < nrows && k < ri) ? value_of(w[k]) : 0.f;
     }
