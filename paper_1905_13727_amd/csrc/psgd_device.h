@@ -104,6 +104,17 @@ __device__ __forceinline__ v4f buf_load_v4f(buf_rsrc r, unsigned off) {
     const v4u x = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
     return v4f{__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w)};
 }
+// the same two with a cache policy word (0: none, 2: non-temporal)
+template <int AUX>
+__device__ __forceinline__ v4f buf_load_v4f_policy(buf_rsrc r, unsigned off) {
+    const v4u x = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, AUX);
+    return v4f{__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w)};
+}
+template <int AUX>
+__device__ __forceinline__ void buf_store_v4f_policy(buf_rsrc r, unsigned off, v4f v) {
+    const v4u x{__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
+    __builtin_amdgcn_raw_buffer_store_b128(x, r, (int)off, 0, AUX);
+}
 __device__ __forceinline__ void buf_store_v4f(buf_rsrc r, unsigned off, v4f v) {
     const v4u x{__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
     __builtin_amdgcn_raw_buffer_store_b128(x, r, (int)off, 0, 0);

@@ -64,7 +64,7 @@ constexpr int kHrAStride = kHrChunk + 4;   // floats per LDS row of an A tile (b
 
 typedef double v4d __attribute__((ext_vector_type(4)));
 
-template <int NT, bool BF, bool F64>
+template <int NT, bool BF, bool F64, bool STREAM>
 __global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                         const void* __restrict__ grad, float* __restrict__ err,
                                                         const float* __restrict__ q, float* __restrict__ ws,
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatD
             for (int i = 0; i < 4; ++i) {
                 const unsigned el = voff[i] + (unsigned)(16 * s * m + c0);
                 gv[i] = buf_load_grad4<BF>(gr, col_ok ? el * GS : kOutOfRange);
-                ev[i] = buf_load_v4f(er, col_ok ? el * 4u : kOutOfRange);
+                ev[i] = buf_load_v4f_policy<STREAM ? 2 : 0>(er, col_ok ? el * 4u : kOutOfRange);
             }
         };
 
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatD
                     for (int i = 0; i < 4; ++i) {
                         const v4f mv = gn[i] + en[i];
                         const unsigned el = voff[i] + (unsigned)(16 * s * m + c0);
-                        buf_store_v4f(esto, col_ok ? el * 4u : kOutOfRange, mv);
+                        buf_store_v4f_policy<STREAM ? 2 : 0>(esto, col_ok ? el * 4u : kOutOfRange, mv);
                         *reinterpret_cast<v4f*>(&at[4 * i + lr][lc]) = mv;
                     }
                 }
@@ -773,11 +773,19 @@ static void hr_launch_right(psgd_plan* plan, const void* grad, float* err, const
     dim3 grid((unsigned)plan->hr_tiles1.size(), (unsigned)plan->workers);
     // fp64 accumulation at every rank of this path: it costs nothing next to the loads (2.88 against 2.92 ms on
     // the transformer set) and at rank 4 fp32 accumulation left P_hat up to 8e-6 off after two steps
-#define HR_RIGHT(BFV)                                                                                             \
-    hipLaunchKernelGGL((k_hr_right<NT, BFV, true>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles1, \
+    // Sets beyond the memory-side cache: e is read and M written around the caches (non-temporal), as the streaming
+    // path does (transformer subset, rank 16: k_hr_right -3 %, and k_hr_left, which then finds less of its M pushed
+    // out by lines nobody reads again, -7 %).  The same hint on k_hr_decomp's 64-byte pieces costs 40 %.
+#define HR_RIGHT(BFV, STREAMV)                                                                                             \
+    hipLaunchKernelGGL((k_hr_right<NT, BFV, true, STREAMV>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles1, \
                        grad, err, q, ws, plan->sizes.grad_stride, plan->sizes.err_stride, add ? 1 : 0)
-    if (plan->grad_dtype == PSGD_BF16) HR_RIGHT(true);
-    else HR_RIGHT(false);
+    if (plan->stream_hints) {
+        if (plan->grad_dtype == PSGD_BF16) HR_RIGHT(true, true);
+        else HR_RIGHT(false, true);
+    } else {
+        if (plan->grad_dtype == PSGD_BF16) HR_RIGHT(true, false);
+        else HR_RIGHT(false, false);
+    }
 #undef HR_RIGHT
 }
 
