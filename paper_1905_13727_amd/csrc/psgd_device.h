@@ -482,6 +482,13 @@ __device__ __forceinline__ double take_double(const slot_t* pair, slot_t first_l
     return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
 
+// Shared memory written by lanes of this wavefront is read by other lanes of the same wavefront (or the reverse)
+// across this point: the wavefront's LDS operations complete in order, the compiler must not move them.
+__device__ __forceinline__ void wave_lds_done() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // Wait until every memory operation this wavefront has issued is complete (loads returned, stores
 // acknowledged), and keep the compiler from moving memory operations across this point.
 __device__ __forceinline__ void wave_mem_done() {

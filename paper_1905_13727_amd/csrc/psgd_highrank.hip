@@ -29,23 +29,25 @@
 
 namespace psgd {
 
-// four gradient elements, read once (non-temporal)
+// four gradient elements, read once (non-temporal): as they come (8 or 16 bytes, kept that way while in flight), and widened
 template <bool BF>
-__device__ __forceinline__ v4f buf_load_grad4(buf_rsrc r, unsigned off) {
-    if constexpr (BF) {
-        const v2u x = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 2);
-        return v4f{__uint_as_float(x.x << 16), __uint_as_float(x.x & 0xffff0000u), __uint_as_float(x.y << 16),
-                   __uint_as_float(x.y & 0xffff0000u)};
-    } else {
-        const v4u x = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 2);
-        return v4f{__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w)};
-    }
+struct grad4 { typedef typename std::conditional<BF, v2u, v4u>::type raw; };
+template <bool BF>
+__device__ __forceinline__ typename grad4<BF>::raw buf_load_grad4_raw(buf_rsrc r, unsigned off) {
+    if constexpr (BF) return __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 2);
+    else return __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 2);
+}
+__device__ __forceinline__ v4f grad4_widen(v2u x) {
+    return v4f{__uint_as_float(x.x << 16), __uint_as_float(x.x & 0xffff0000u), __uint_as_float(x.y << 16),
+               __uint_as_float(x.y & 0xffff0000u)};
+}
+__device__ __forceinline__ v4f grad4_widen(v4u x) {
+    return v4f{__uint_as_float(x.x), __uint_as_float(x.y), __uint_as_float(x.z), __uint_as_float(x.w)};
 }
 
 // ---- k_hr_right: P_w = M Q ------------------------------------------------------------------------------
-// A workgroup owns a block of rows and walks the whole row in chunks of 64 columns.  Global memory is
-// touched in row-contiguous pieces only (a load instruction covers 4 rows x 64 columns: 256-byte runs of
-// e, 128- or 256-byte runs of g); M = g + e goes back over e in the same shape and into a 16 x 64 tile in
+// A workgroup owns a block of rows and walks the whole row in chunks of 128 or 64 columns.  Global memory is
+// touched in row-contiguous pieces only (a load instruction covers 2 rows x 128 or 4 rows x 64 columns); M = g + e goes back over e in the same shape and into a 16 x chunk tile in
 // LDS private to the wavefront, from which the lanes fetch their A operands (row li, columns
 // 16 u + 4 kb ..+3).  The Q rows of the chunk (B operands) are staged in LDS once per workgroup, double
 // buffered, one barrier per chunk.  g and e of the next 16-row step are in flight while the current
@@ -59,24 +61,31 @@ __device__ __forceinline__ v4f buf_load_grad4(buf_rsrc r, unsigned off) {
 // largest column is not small against the smallest.  fp32 accumulation leaves P_hat 2-3e-5 off at
 // r = 16 on a 1/k spectrum; fp64 accumulation (one rounding to fp32 at the end) keeps it at 1e-6.
 // The fp64 output tile is D[4 v + kb][li] (fp32: D[4 kb + v][li]).
-constexpr int kHrChunk = 64;          // columns per chunk
-constexpr int kHrAStride = kHrChunk + 4;   // floats per LDS row of an A tile (b128 reads of 16 rows spread over the banks)
+// columns per chunk: 128 (a load instruction covers 2 rows x 128 columns: 512-byte runs of e, 256-byte runs of bf16 g;
+// a plain pass over g, e, M with that shape moves 5.9 TB/s here, with 4 rows x 64 columns 5.0) where the staged Q
+// chunks leave room for two workgroups per compute unit, 64 at three and four rank tiles
+constexpr int hr_chunk(int nt) { return nt <= 2 ? 128 : 64; }
 
 typedef double v4d __attribute__((ext_vector_type(4)));
 
 template <int NT, bool BF, bool F64, bool STREAM>
-__global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
+__global__ __launch_bounds__(kBlock, 2) void k_hr_right(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                         const void* __restrict__ grad, float* __restrict__ err,
                                                         const float* __restrict__ q, float* __restrict__ ws,
                                                         int64_t gstride, int64_t estride, int add) {
     constexpr int STEPS = 2;                          // 16-row steps per wavefront and pass: 128 rows per workgroup and pass
     constexpr int RP = 16 * NT;                       // padded rank
     constexpr int BST = RP + 4;                       // floats per LDS row of the staged Q chunk
-    constexpr int BPT = kHrChunk * RP / kBlock;       // staged Q elements per thread
+    constexpr int CH = hr_chunk(NT);                  // columns per chunk
+    constexpr int AST = CH + 4;                       // floats per LDS row of an A tile (b128 reads of 16 rows spread over the banks)
+    constexpr int LPR = CH / 4;                       // loader lanes per row
+    constexpr int RPI = kWave / LPR;                  // rows per load instruction
+    constexpr int NI = 16 / RPI;                      // load instructions per 16-row step
+    constexpr int BPT = CH * RP / kBlock;             // staged Q elements per thread
     typedef typename std::conditional<F64, v4d, v4f>::type acc_t;
     typedef typename std::conditional<F64, double, float>::type b_t;
-    __shared__ float Bs[2][kHrChunk][BST];
-    __shared__ __attribute__((aligned(16))) float As[kWavesPerBlock][16][kHrAStride];
+    __shared__ float Bs[2][CH][BST];
+    __shared__ __attribute__((aligned(16))) float As[kWavesPerBlock][16][AST];
 
     const Tile t = tiles[blockIdx.x];
     const MatDesc d = mats[t.mat];
@@ -85,34 +94,32 @@ __global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatD
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, kb = lane >> 4;      // matrix-core roles
-    const int lr = lane >> 4, lc = 4 * (lane & 15);   // loader roles: row within a group of 4, first column
+    const int lr = lane / LPR, lc = 4 * (lane % LPR);   // loader roles: row within the rows of an instruction, first column
     const int ri = d.r, m = d.m, n = d.n;
     constexpr int GS = BF ? 2 : 4;                  // bytes per gradient element
     const char* gmat = static_cast<const char*>(grad) + ((int64_t)w * gstride + d.off) * GS;
     float* emat = err + (int64_t)w * estride + d.off;
     const int row_end = min(n, t.row0 + t.nrows);
     const int col0 = t.vec0;   // first of this workgroup's columns (a multiple of 64); they end with the row or at a multiple of 64
-    const int nchunks = (t.nvec + kHrChunk - 1) / kHrChunk;
+    const int col_end = min(m, col0 + t.nvec);
+    const int nchunks = (t.nvec + CH - 1) / CH;
     const int part = w * d.n_cchunk + t.part;
-    float (*at)[kHrAStride] = As[wave];
+    float (*at)[AST] = As[wave];
 
-    // Q rows of a chunk: element idx of the 64 x RP block is Q[c0 + idx / RP][idx % RP]; rows past the
+    // Q rows of a chunk: element idx of the CH x RP block is Q[c0 + idx / RP][idx % RP]; rows past the
     // matrix fall outside the buffer (zero), padded rank columns get the out-of-range offset themselves
     const buf_rsrc qres = make_rsrc(q + d.q_off, (int64_t)m * ri * 4);
-    unsigned qoff[BPT];
-#pragma unroll
-    for (int k = 0; k < BPT; ++k) {
-        const int idx = tid + k * kBlock;
-        const int j = idx % RP;
-        qoff[k] = j < ri ? (unsigned)((idx / RP) * ri + j) * 4u : kOutOfRange;
-    }
+    // (thread tid stages elements tid + k * 256: the same rank column tid % RP in rows 256 / RP apart)
+    const unsigned qoff0 = tid % RP < ri ? (unsigned)((tid / RP) * ri + tid % RP) * 4u : kOutOfRange;
+    const unsigned qstep = (unsigned)((kBlock / RP) * ri * 4);
     // an unwanted request (past the last chunk) goes through a descriptor with an empty range: nothing is fetched,
     // and no branch surrounds the request, so the waits count exactly what is outstanding
     const buf_rsrc nores = make_rsrc(q + d.q_off, 0);
     auto stage_load = [&](int c0, bool wanted, float (&br)[BPT]) {
         const buf_rsrc res = wanted ? qres : nores;
 #pragma unroll
-        for (int k = 0; k < BPT; ++k) br[k] = buf_load_f32(res, qoff[k] + (unsigned)(c0 * ri * 4));
+        for (int k = 0; k < BPT; ++k)
+            br[k] = buf_load_f32(res, qoff0 == kOutOfRange ? kOutOfRange : qoff0 + (unsigned)k * qstep + (unsigned)(c0 * ri * 4));
     };
     auto stage_store = [&](int buf, const float (&br)[BPT]) {
 #pragma unroll
@@ -141,18 +148,19 @@ __global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatD
         const buf_rsrc eres = make_rsrc(emat + base_w, (int64_t)rows_w * m * 4);
         const buf_rsrc esto = make_rsrc(emat + base_w, add ? (int64_t)rows_w * m * 4 : 0);
         const buf_rsrc gres = make_rsrc(gmat + base_w * GS, add ? (int64_t)rows_w * m * GS : 0);
-        unsigned voff[4];
+        unsigned voff[NI];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) voff[i] = (unsigned)(4 * i + lr) * (unsigned)m + (unsigned)lc;
+        for (int i = 0; i < NI; ++i) voff[i] = (unsigned)(RPI * i + lr) * (unsigned)m + (unsigned)lc;
         // a step s starts 16 s rows further down: added to the lane offset (the range check looks at the lane
         // offset only)
-        auto data_load = [&](int c0, int s, bool wanted, v4f (&gv)[4], v4f (&ev)[4]) {
-            const bool col_ok = c0 + lc < m;
+        typedef typename grad4<BF>::raw graw_t;
+        auto data_load = [&](int c0, int s, bool wanted, graw_t (&gv)[NI], v4f (&ev)[NI]) {
+            const bool col_ok = c0 + lc < col_end;   // the workgroup's columns may end inside a chunk
             const buf_rsrc gr = wanted ? gres : nores, er = wanted ? eres : nores;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < NI; ++i) {
                 const unsigned el = voff[i] + (unsigned)(16 * s * m + c0);
-                gv[i] = buf_load_grad4<BF>(gr, col_ok ? el * GS : kOutOfRange);
+                gv[i] = buf_load_grad4_raw<BF>(gr, col_ok ? el * GS : kOutOfRange);
                 ev[i] = buf_load_v4f_policy<STREAM ? 2 : 0>(er, col_ok ? el * 4u : kOutOfRange);
             }
         };
@@ -161,36 +169,37 @@ __global__ __launch_bounds__(kBlock, NT <= 2 ? 3 : 2) void k_hr_right(const MatD
         __syncthreads();   // the previous pass has finished with Bs
         stage_load(col0, true, br);
         stage_store(0, br);
-        v4f gn[4], en[4];
+        graw_t gn[NI];
+        v4f en[NI];
         data_load(col0, 0, true, gn, en);
         for (int ch = 0; ch < nchunks; ++ch) {
-            const int c0 = col0 + ch * kHrChunk;
+            const int c0 = col0 + ch * CH;
             const int buf = ch & 1;
             __syncthreads();   // Bs[buf] is complete; Bs[buf ^ 1] is no longer read
             // requests past the last chunk are sent out of range (nothing is fetched): no branch around a request,
             // so the waits below count exactly what is outstanding
             const bool more = ch + 1 < nchunks;
-            stage_load(c0 + kHrChunk, more, br);
+            stage_load(c0 + CH, more, br);
 #pragma unroll
             for (int s = 0; s < STEPS; ++s) {
                 {
-                    const bool col_ok = c0 + lc < m;
+                    const bool col_ok = c0 + lc < col_end;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const v4f mv = gn[i] + en[i];
+                    for (int i = 0; i < NI; ++i) {
+                        const v4f mv = grad4_widen(gn[i]) + en[i];
                         const unsigned el = voff[i] + (unsigned)(16 * s * m + c0);
                         buf_store_v4f_policy<STREAM ? 2 : 0>(esto, col_ok ? el * 4u : kOutOfRange, mv);
-                        *reinterpret_cast<v4f*>(&at[4 * i + lr][lc]) = mv;
+                        *reinterpret_cast<v4f*>(&at[RPI * i + lr][lc]) = mv;
                     }
                 }
                 // g and e of the next step (or of the next chunk's first step)
                 if (s + 1 < STEPS) data_load(c0, s + 1, true, gn, en);
-                else data_load(c0 + kHrChunk, 0, more, gn, en);
+                else data_load(c0 + CH, 0, more, gn, en);
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < CH / 16; ++u) {
                     const v4f a = *reinterpret_cast<const v4f*>(&at[li][16 * u + 4 * kb]);
 #pragma unroll
                     for (int c = 0; c < 4; ++c)
@@ -576,27 +585,32 @@ __global__ __launch_bounds__(kBlock) void k_hr_left(const MatDesc* __restrict__ 
 // ---- k_hr_decomp: Delta' = P_hat Q^T, e' = M - Delta' -------------------------------------------------------
 // The product is formed transposed, (Q block 16 x K) (P_hat^T K x 16): A[li][kb] = Q[col0 + li][4 kk + kb],
 // B[kb][li] = P_hat[row0 + li][4 kk + kb], so that lane (kb, li) ends up with Delta'[row0 + li][col0 + 4 kb + v],
-// v = 0..3: four consecutive columns of one row, the same 16 bytes it loads of M and stores of e' and Delta'
-// (the eight column blocks of a step cover 512 contiguous bytes of each row).  The Q rows of the workgroup's
-// 128 columns are staged in LDS once; M and P_hat of the next 16-row step are in flight while the current one
-// is multiplied.  Buffer addressing: each wavefront's descriptors end with its last row.
+// v = 0..3: four consecutive columns of one row.  A 16 x 16 block is then 16 rows of 64 bytes, too short a run for
+// the memory system (a plain pass with that shape reads and writes 5.0 TB/s here, with runs of 512 bytes 5.8), so
+// the eight blocks of a 16-row step go through a tile in LDS private to the wavefront and memory is touched in a
+// second lane layout: lane (h, j) holds row 2 i + h, columns 4 j .. 4 j + 3 of the step's 16 x 128 piece, i = 0..7,
+// i.e. every load and store instruction covers two runs of 512 bytes.  The Q rows of the workgroup's 128 columns
+// are staged in LDS once; M and P_hat of the next 16-row step are in flight while the current one is multiplied.
+// Buffer addressing: each wavefront's descriptors end with its last row.  STREAM: sets beyond the memory-side
+// cache read M and write e' and Delta' around the caches.
 constexpr int kHrDecompBlocks = 8;   // 16-column blocks per wavefront (128 columns)
+constexpr int kHrDecompStride = 16 * kHrDecompBlocks + 4;   // floats per row of the wavefront's tile in LDS
 
-template <bool BF>
+template <bool BF, int AUX>
 __device__ __forceinline__ void buf_store_out4(buf_rsrc r, unsigned off, v4f v) {
     if constexpr (BF) {
         v2u x;
         x.x = pack_bf16x2(v.x, v.y);
         x.y = pack_bf16x2(v.z, v.w);
-        __builtin_amdgcn_raw_buffer_store_b64(x, r, (int)off, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b64(x, r, (int)off, 0, AUX);
     } else {
-        buf_store_v4f(r, off, v);
+        buf_store_v4f_policy<AUX>(r, off, v);
     }
 }
 
 // OM: what becomes of Delta': 0 stored as fp32, 1 stored as bf16, 2 not stored but folded into the momentum and
 // parameter buffers (Algorithm 2's last two lines)
-template <int NT, int OM>
+template <int NT, int OM, bool STREAM>
 __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restrict__ mats, const Tile* __restrict__ tiles,
                                                          float* __restrict__ err, const float* __restrict__ p,
                                                          const float* __restrict__ q, void* __restrict__ out,
@@ -608,7 +622,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restri
     constexpr int RP = 16 * NT;
     constexpr int QST = RP + 4;  // floats per LDS row of the staged Q block
     constexpr int OS = BF ? 2 : 4;
+    constexpr int AUX = STREAM ? 2 : 0;
     __shared__ float Qs[16 * CB][QST];
+    __shared__ __attribute__((aligned(16))) float Ds[kWavesPerBlock][16][kHrDecompStride];
     const Tile t = tiles[blockIdx.x];
     const MatDesc d = mats[t.mat];
     const int w = blockIdx.y;
@@ -652,12 +668,10 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restri
     const buf_rsrc pres = make_rsrc(p + d.p_off + (int64_t)r_begin * ri, (int64_t)rn * ri * 4);
     // lane offsets in elements, relative to the first row of the strip; out of range where the column (of M) or
     // the rank index (of P_hat) does not exist
-    unsigned eo[CB], po[KK];
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb) {
-        const int col = c0 + 16 * cb + 4 * kb;
-        eo[cb] = col < c_end ? (unsigned)(li * m + col) : kOutOfRange;
-    }
+    const int h = lane >> 5, j = lane & 31;
+    const int mcol = c0 + 4 * j;
+    const unsigned eo = mcol < c_end ? (unsigned)(h * m + mcol) : kOutOfRange;   // row h of the step, this lane's columns
+    unsigned po[KK];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
         const int k = 4 * kk + kb;
@@ -665,17 +679,18 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restri
     }
     // an out-of-range marker stays out of range after scaling and stepping: the element offsets below are
     // under 2^26, so it is kept apart by using byte offsets only at the access
-    auto e_off = [&](int cb, int step_el, int bytes) -> unsigned {
-        return eo[cb] == kOutOfRange ? kOutOfRange : (eo[cb] + (unsigned)step_el) * (unsigned)bytes;
+    auto e_off = [&](int i, int step_el, int bytes) -> unsigned {
+        return eo == kOutOfRange ? kOutOfRange : (eo + (unsigned)(2 * i * m) + (unsigned)step_el) * (unsigned)bytes;
     };
     auto load_step = [&](int r_rel, v4f (&mv)[CB], float (&bp)[KK]) {
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk)
             bp[kk] = buf_load_f32(pres, po[kk] == kOutOfRange ? kOutOfRange : (po[kk] + (unsigned)(r_rel * ri)) * 4u);
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) mv[cb] = buf_load_v4f(eres, e_off(cb, r_rel * m, 4));
+        for (int i = 0; i < CB; ++i) mv[i] = buf_load_v4f_policy<AUX>(eres, e_off(i, r_rel * m, 4));
     };
 
+    float (*dt)[kHrDecompStride] = Ds[wave];
     v4f mvn[CB];
     float bpn[KK];
     load_step(0, mvn, bpn);
@@ -683,7 +698,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restri
         v4f mv[CB];
         float bp[KK];
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) mv[cb] = mvn[cb];
+        for (int i = 0; i < CB; ++i) mv[i] = mvn[i];
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) bp[kk] = bpn[kk];
         load_step(r_rel + 16, mvn, bpn);   // past the strip's last row: out of range, nothing is fetched
@@ -692,9 +707,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restri
         v4f mo[UPD ? CB : 1], pa[UPD ? CB : 1];
         if constexpr (UPD) {   // momentum and parameters of this step: requested before the products are issued
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
-                mo[cb] = buf_load_v4f(mres, e_off(cb, r_rel * m, 4));
-                pa[cb] = buf_load_v4f(xres, e_off(cb, r_rel * m, 4));
+            for (int i = 0; i < CB; ++i) {
+                mo[i] = buf_load_v4f(mres, e_off(i, r_rel * m, 4));
+                pa[i] = buf_load_v4f(xres, e_off(i, r_rel * m, 4));
             }
         }
         if constexpr (NT >= 2) asm volatile("" ::: "memory");
@@ -704,17 +719,24 @@ __global__ __launch_bounds__(kBlock, 2) void k_hr_decomp(const MatDesc* __restri
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk)
                 acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Qs[16 * cb + li][4 * kk + kb], bp[kk], acc, 0, 0, 0);
-            buf_store_v4f(eres, e_off(cb, r_rel * m, 4), mv[cb] - acc);
+            *reinterpret_cast<v4f*>(&dt[li][16 * cb + 4 * kb]) = acc;
+        }
+        wave_lds_done();
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+            const v4f acc = *reinterpret_cast<const v4f*>(&dt[2 * i + h][4 * j]);
+            buf_store_v4f_policy<AUX>(eres, e_off(i, r_rel * m, 4), mv[i] - acc);
             if constexpr (UPD) {
-                float m4[4] = {mo[cb].x, mo[cb].y, mo[cb].z, mo[cb].w}, x4[4] = {pa[cb].x, pa[cb].y, pa[cb].z, pa[cb].w};
+                float m4[4] = {mo[i].x, mo[i].y, mo[i].z, mo[i].w}, x4[4] = {pa[i].x, pa[i].y, pa[i].z, pa[i].w};
                 const float d4[4] = {acc.x, acc.y, acc.z, acc.w};
                 momentum_step<4>(m4, x4, d4, upd.lr, upd.lam);
-                buf_store_v4f(mres, e_off(cb, r_rel * m, 4), v4f{m4[0], m4[1], m4[2], m4[3]});
-                buf_store_v4f(xres, e_off(cb, r_rel * m, 4), v4f{x4[0], x4[1], x4[2], x4[3]});
+                buf_store_v4f(mres, e_off(i, r_rel * m, 4), v4f{m4[0], m4[1], m4[2], m4[3]});
+                buf_store_v4f(xres, e_off(i, r_rel * m, 4), v4f{x4[0], x4[1], x4[2], x4[3]});
             } else {
-                buf_store_out4<BF>(ores, e_off(cb, r_rel * m, OS), acc);   // dropped for workers other than the first (empty range)
+                buf_store_out4<BF, AUX>(ores, e_off(i, r_rel * m, OS), acc);   // dropped for workers other than the first (empty range)
             }
         }
+        wave_lds_done();   // the tile is written again in the next step
     }
 }
 
@@ -793,12 +815,18 @@ template <int NT>
 static void hr_launch_decomp(psgd_plan* plan, float* err, const float* p, const float* q, void* out, hipStream_t s,
                              const UpdateArgs& upd) {
     dim3 grid((unsigned)plan->hr_tiles4.size(), (unsigned)plan->workers);
-#define HR_DECOMP(OMV)                                                                                                \
-    hipLaunchKernelGGL((k_hr_decomp<NT, OMV>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles4, err, p, q, \
+#define HR_DECOMP(OMV, STREAMV)                                                                                                \
+    hipLaunchKernelGGL((k_hr_decomp<NT, OMV, STREAMV>), grid, dim3(kBlock), 0, s, plan->dev.mats, plan->dev.hr_tiles4, err, p, q, \
                        out, plan->sizes.err_stride, upd)
-    if (upd.mom) HR_DECOMP(2);
-    else if (plan->out_dtype == PSGD_BF16) HR_DECOMP(1);
-    else HR_DECOMP(0);
+    if (plan->stream_hints) {
+        if (upd.mom) HR_DECOMP(2, true);
+        else if (plan->out_dtype == PSGD_BF16) HR_DECOMP(1, true);
+        else HR_DECOMP(0, true);
+    } else {
+        if (upd.mom) HR_DECOMP(2, false);
+        else if (plan->out_dtype == PSGD_BF16) HR_DECOMP(1, false);
+        else HR_DECOMP(0, false);
+    }
 #undef HR_DECOMP
 }
 
