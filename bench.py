@@ -50,8 +50,8 @@ MEASURED_TRAFFIC = {
 # applied to the full set's algorithmic bytes.
 TRANSFORMER_TRAFFIC_RATIO = {
     (4, "k_ef_right"): 3183901020 / 3043491840, (4, "k_left"): 1273799574 / 1217396736, (4, "k_decomp"): 3182413765 / 3043934208,
-    (16, "k_ef_right"): 3192121738 / 3043491840, (16, "k_left"): 1285844662 / 1217396736, (16, "k_decomp"): 3230979309 / 3043934208,
-    (32, "k_ef_right"): 3257136164 / 3043491840, (32, "k_left"): 1305107626 / 1217396736, (32, "k_decomp"): 3255566005 / 3043934208,
+    (16, "k_ef_right"): 3183009566 / 3043491840, (16, "k_left"): 1285829804 / 1217396736, (16, "k_decomp"): 3191912143 / 3043934208,
+    (32, "k_ef_right"): 3222841127 / 3043491840, (32, "k_left"): 1305105648 / 1217396736, (32, "k_decomp"): 3200086304 / 3043934208,
 }
 
 
