@@ -136,7 +136,7 @@ PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, in
  *                 streaming path (P = M Q; Q = M^T P_hat; decompression); rows 0 (default):
  *                 chosen per matrix by the planner
  *   hr_k1_rows, hr_k1_cols, hr_k3_rows, hr_k4_rows   tile shapes of the matrix-core path
- *                 (hr_k4_rows 0, the default: 128, 512 or 256 rows by rank <= 16, <= 32, <= 64)
+ *                 (hr_k4_rows 0, the default: 64, 256 or 512 rows by rank <= 16, <= 32, <= 64)
  *   xcd_order     order of the tile lists over the accelerator dies: 0 plain, 1 one contiguous range
  *                 of the whole list per die, k >= 2 the same within groups of consecutive matrices
  *                 of at least k tiles, -1 (default) the planner's choice: groups of 4096 / workers

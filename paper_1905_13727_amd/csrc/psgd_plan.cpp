@@ -155,7 +155,9 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
     const int64_t right_rows = tu.hr_k1_rows;
     // rows per workgroup of the decompression: measured best on the 24-layer transformer set at ranks 16, 32, 64
     // (one, two, four rank tiles of 16)
-    const int64_t decomp_rows = tu.hr_k4_rows ? tu.hr_k4_rows : (plan->rank <= 16 ? 128 : (plan->rank <= 32 ? 512 : 256));
+    // measured on the 24-layer transformer-shaped set (k_hr_decomp, ms): rank 16: 2.16 at 64 rows, 2.22 at 128, 2.25 at
+    // 256; rank 32: 2.54 at 64, 2.28 at 128...256, 2.36 at 512; rank 64: 3.04 at 128, 2.62 at 256, 2.48 at 512
+    const int64_t decomp_rows = tu.hr_k4_rows ? tu.hr_k4_rows : (plan->rank <= 16 ? 64 : (plan->rank <= 32 ? 256 : 512));
     int64_t pp = 0, qp = 0, gp = 0, cp = 0;
     for (size_t i = 0; i < nm; ++i) {
         MatDesc& d = plan->mats[i];
