@@ -425,11 +425,11 @@ __device__ __forceinline__ void await(F attempt, unsigned* err_word, unsigned ep
     }
 }
 
-// The same for the many wavefronts that wait for a published result: first one lane probes a single
-// slot of the group (`probe`, the same address for the whole wavefront) at a relaxed pace, so that
-// two thousand waiting wavefronts put little load on the memory system; once it carries this step's
-// tag the rest is about to land and every lane polls the slots it needs.
-// the probing alone: false when the wait was given up
+// Before a long wait: one lane watches a single slot (`probe`, the same address for the whole wavefront) at a
+// relaxed pace, so that the waiting wavefronts put little load on the memory system (a wavefront that polls all its
+// slots with all lanes also delays the loads of the other workgroup on its compute unit); once the slot carries this
+// step's tag the rest is about to land and the caller polls the slots it needs with await().  False when the wait
+// was given up.
 __device__ __forceinline__ bool await_tag(const slot_t* probe, unsigned epoch, unsigned* err_word, unsigned limit) {
     unsigned spins = 0;
     for (;;) {
@@ -443,11 +443,6 @@ __device__ __forceinline__ bool await_tag(const slot_t* probe, unsigned epoch, u
             return false;
         }
     }
-}
-template <typename F>
-__device__ __forceinline__ void await_probed(const slot_t* probe, unsigned epoch, F attempt, unsigned* err_word,
-                                             unsigned limit) {
-    if (await_tag(probe, epoch, err_word, limit)) await(attempt, err_word, epoch, limit);
 }
 
 // One slot, waited for by this lane alone (other lanes of the wavefront may be waiting for theirs).  Gives up after
