@@ -349,12 +349,16 @@ def test_streaming_path_bf16_any_row_length(rank, workers, gbf, obf):
 @pytest.mark.parametrize("rows,cols", [(64, 64), (256, 192), (128, 4096)])
 def test_matrix_core_tilings(rows, cols):
     """P = M Q on the matrix cores with rows split into many column ranges (partials summed in
-    index order), one range only, and the tallest workgroup tile."""
+    index order; ranges of 192 columns end inside a 128-column chunk), one range only, and the tallest workgroup
+    tile; at one and two rank tiles; the decompression with workgroups of 48 rows (wavefront strips of 12: every
+    16-row step is ragged)."""
     _need_gpu()
     from paper_1905_13727_amd import workloads as WL
     wl = WL.Workload("tr-small", list(TRANSFORMER_SMALL), 64, 1.0 / np.arange(1, 65), 0.001)
     tuning = {"hr_k1_rows": rows, "hr_k1_cols": cols}
     _run(wl, rank=16, workers=2, steps=2, seed=77, expect_resident=False, tuning=tuning)
+    _run(wl, rank=32, workers=1, steps=2, seed=79, expect_resident=False, tuning=dict(tuning, hr_k4_rows=48),
+         grad_bf16=True, out_bf16=True)
     _run(wl, rank=4, workers=1, steps=2, seed=78, expect_resident=False, tuning=tuning, grad_bf16=True)
 
 
