@@ -1,9 +1,12 @@
 """Builds libpsgd.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree."""
 from __future__ import annotations
 
+import concurrent.futures
 import os
+import shutil
 import subprocess
 import sys
+import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -22,17 +25,33 @@ FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every source for gfx950 and link libpsgd.so next to this file."""
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = [HIPCC] + FLAGS + ["-x", "hip"] + srcs + ["-o", LIB_PATH]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout)
-    if verbose and res.stdout.strip():
-        print(res.stdout)
+    return res.stdout
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile every source for gfx950 (one hipcc process per source, side by side) and link libpsgd.so next to
+    this file.  The objects live in a temporary folder outside the tree."""
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+    tmp = tempfile.mkdtemp(prefix="psgd_build_")
+    try:
+        objs = [os.path.join(tmp, os.path.splitext(s)[0] + ".o") for s in SOURCES]
+        cmds = [[HIPCC] + compile_flags + ["-c", "-x", "hip", os.path.join(CSRC, s), "-o", o]
+                for s, o in zip(SOURCES, objs)]
+        with concurrent.futures.ThreadPoolExecutor(max_workers=min(len(cmds), os.cpu_count() or 1)) as pool:
+            outs = list(pool.map(lambda c: _run(c, verbose), cmds))
+        outs.append(_run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950"] + objs + ["-o", LIB_PATH], verbose))
+        if verbose:
+            for o in outs:
+                if o.strip():
+                    print(o)
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
     return LIB_PATH
 
 
