@@ -193,37 +193,19 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
     {
         // the strip's row dot products: lane i receives row i's (rows past the strip were read as zeros)
         float mine[R];
-        if constexpr (R <= 2) {
-            // rank by rank, all rows of the strip reduced over the wavefront together
+        // rank by rank, all rows of the strip reduced over the wavefront together (one reduction per row and rank
+        // instead: +1.5 us at rank 3, +0.9 us at rank 4)
 #pragma unroll
-            for (int k = 0; k < R; ++k) {
-                float part[RT];
-#pragma unroll
-                for (int i = 0; i < RT; ++i) {
-                    float s = 0.f;
-#pragma unroll
-                    for (int x = 0; x < V; ++x) s = fmaf(M[i][x], qr[x][k], s);
-                    part[i] = s;
-                }
-                mine[k] = lane_sums<RT>(part);
-            }
-        } else {
-            // the higher ranks have no registers to spare for that: one reduction per row and rank
-#pragma unroll
-            for (int k = 0; k < R; ++k) mine[k] = 0.f;
+        for (int k = 0; k < R; ++k) {
+            float part[RT];
 #pragma unroll
             for (int i = 0; i < RT; ++i) {
-                if (i < nrows) {
+                float s = 0.f;
 #pragma unroll
-                    for (int k = 0; k < R; ++k) {
-                        float s = 0.f;
-#pragma unroll
-                        for (int x = 0; x < V; ++x) s = fmaf(M[i][x], qr[x][k], s);
-                        s = wave_sum(s);
-                        if (lane == i) mine[k] = s;
-                    }
-                }
+                for (int x = 0; x < V; ++x) s = fmaf(M[i][x], qr[x][k], s);
+                part[i] = s;
             }
+            mine[k] = lane_sums<RT>(part);
         }
         if (lane < nrows) {
             // mailbox layouts are [..][k][row] (and [..][x][k][column vector] for Q): consecutive lanes
@@ -344,14 +326,12 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
 #pragma unroll
         for (int k = 0; k < R; ++k) acc[x][k] = 0.f;
 #pragma unroll
-    for (int i = 0; i < RT; ++i) {
-        if (i < nrows) {
+    for (int i = 0; i < RT; ++i) {   // rows past the strip: M was read as zeros and P_hat is zero there, no branch needed
 #pragma unroll
-            for (int k = 0; k < R; ++k) {
-                const float pk = lane_bcast(pr[k], i);
+        for (int k = 0; k < R; ++k) {
+            const float pk = lane_bcast(pr[k], i);
 #pragma unroll
-                for (int x = 0; x < V; ++x) acc[x][k] = fmaf(M[i][x], pk, acc[x][k]);
-            }
+            for (int x = 0; x < V; ++x) acc[x][k] = fmaf(M[i][x], pk, acc[x][k]);
         }
     }
     // add the sums of a run of wavefronts (strips of the same column chunk) in LDS, fixed order
