@@ -109,9 +109,9 @@ __device__ __forceinline__ void gram_schmidt_rows(float (&P)[kResRowsPerLane][R]
 // ---- the step, for a workgroup whose tiles use V-wide row accesses ---------------------------------------
 // ITER: several subspace iterations on the resident tile (Appendix G.7): P = M Q, orthogonalise, Q = M^T P_hat
 // repeated a.iters times before the decompression, each round under its own mailbox tag epoch0 + round.
-template <int R, int V, bool UPD, bool ITER>
+// RT: rows of the tile the code is written out for (the strips of the plan are no taller).
+template <int R, int V, bool UPD, bool ITER, int RT>
 __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, float* lds, unsigned epoch0) {
-    constexpr int RT = res_rows_for_rank(R);
     const int lane_id = threadIdx.x & (kWave - 1);
     const int lane = lane_id;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -495,7 +495,7 @@ __device__ __forceinline__ void resident_body(const ResArgs& a, const RTile& t, 
     trace_mark(a, 6);
 }
 
-template <int R, bool UPD, bool ITER>
+template <int R, bool UPD, bool ITER, int RT>
 __global__ __launch_bounds__(kBlock, 2) void k_resident(ResArgs a) {
     __shared__ float lds[kWavesPerBlock * 4 * R * kWave];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -507,9 +507,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_resident(ResArgs a) {
     // all tiles of a workgroup use the same access width; the first slot is never idle
     const RTile t0 = a.tiles[blockIdx.x * kWavesPerBlock];
     const int vec = t0.mat >= 0 ? a.mats[t0.mat].vec : 4;
-    if (vec == 4) resident_body<R, 4, UPD, ITER>(a, t, lds, epoch);
-    else if (vec == 2) resident_body<R, 2, UPD, ITER>(a, t, lds, epoch);
-    else resident_body<R, 1, UPD, ITER>(a, t, lds, epoch);
+    if (vec == 4) resident_body<R, 4, UPD, ITER, RT>(a, t, lds, epoch);
+    else if (vec == 2) resident_body<R, 2, UPD, ITER, RT>(a, t, lds, epoch);
+    else resident_body<R, 1, UPD, ITER, RT>(a, t, lds, epoch);
     // the workgroup that finishes last advances the epoch for the next launch
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -523,32 +523,51 @@ __global__ __launch_bounds__(kBlock, 2) void k_resident(ResArgs a) {
 
 // ---- host side --------------------------------------------------------------------------------------------
 
-template <int R>
-static hipError_t launch_k_resident(const ResArgs& a, int blocks, hipStream_t s, int* max_blocks_per_cu) {
+// The kernels are written out for 24-row tiles and, at rank 1 and 2, for 32-row tiles as well; a plan whose strips
+// are at most 24 rows tall (the ResNet18-shaped set: 23) runs the shorter code, a quarter less work in every phase.
+template <int R, int RT>
+static hipError_t launch_k_resident_rt(const ResArgs& a, int blocks, hipStream_t s, int* max_blocks_per_cu) {
     if (max_blocks_per_cu) {
         // every variant must be co-resident
         int occ[3] = {0, 0, 0};
-        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ[0], k_resident<R, false, false>, kBlock, 0);
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ[0], k_resident<R, false, false, RT>, kBlock, 0);
         if (e != hipSuccess) return e;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ[1], k_resident<R, true, false>, kBlock, 0);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ[1], k_resident<R, true, false, RT>, kBlock, 0);
         if (e != hipSuccess) return e;
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ[2], k_resident<R, false, true>, kBlock, 0);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ[2], k_resident<R, false, true, RT>, kBlock, 0);
         if (e != hipSuccess) return e;
         *max_blocks_per_cu = std::min(occ[0], std::min(occ[1], occ[2]));
         return hipSuccess;
     }
-    if (a.upd.mom) hipLaunchKernelGGL((k_resident<R, true, false>), dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
-    else if (a.iters > 1) hipLaunchKernelGGL((k_resident<R, false, true>), dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
-    else hipLaunchKernelGGL((k_resident<R, false, false>), dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
+    if (a.upd.mom) hipLaunchKernelGGL((k_resident<R, true, false, RT>), dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
+    else if (a.iters > 1) hipLaunchKernelGGL((k_resident<R, false, true, RT>), dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
+    else hipLaunchKernelGGL((k_resident<R, false, false, RT>), dim3((unsigned)blocks), dim3(kBlock), 0, s, a);
     return hipGetLastError();
 }
 
-static hipError_t dispatch_resident(int rank, const ResArgs& a, int blocks, hipStream_t s, int* occ) {
+template <int R>
+static hipError_t launch_k_resident(const ResArgs& a, int blocks, hipStream_t s, int* max_blocks_per_cu, int strip_rows) {
+    if constexpr (res_rows_for_rank(R) > 24) {
+        if (max_blocks_per_cu) {   // the smaller of the two variants' occupancies
+            int o24 = 0, o32 = 0;
+            hipError_t e = launch_k_resident_rt<R, 24>(a, blocks, s, &o24);
+            if (e != hipSuccess) return e;
+            e = launch_k_resident_rt<R, 32>(a, blocks, s, &o32);
+            if (e != hipSuccess) return e;
+            *max_blocks_per_cu = std::min(o24, o32);
+            return hipSuccess;
+        }
+        if (strip_rows > 24) return launch_k_resident_rt<R, 32>(a, blocks, s, nullptr);
+    }
+    return launch_k_resident_rt<R, 24>(a, blocks, s, max_blocks_per_cu);
+}
+
+static hipError_t dispatch_resident(int rank, const ResArgs& a, int blocks, hipStream_t s, int* occ, int strip_rows) {
     switch (rank) {
-        case 1: return launch_k_resident<1>(a, blocks, s, occ);
-        case 2: return launch_k_resident<2>(a, blocks, s, occ);
-        case 3: return launch_k_resident<3>(a, blocks, s, occ);
-        case 4: return launch_k_resident<4>(a, blocks, s, occ);
+        case 1: return launch_k_resident<1>(a, blocks, s, occ, strip_rows);
+        case 2: return launch_k_resident<2>(a, blocks, s, occ, strip_rows);
+        case 3: return launch_k_resident<3>(a, blocks, s, occ, strip_rows);
+        case 4: return launch_k_resident<4>(a, blocks, s, occ, strip_rows);
         default: return hipErrorInvalidValue;
     }
 }
@@ -562,7 +581,7 @@ psgd_status resident_check_device(psgd_plan* plan) {
     if (hipGetDevice(&dev) != hipSuccess) return PSGD_EHIP;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return PSGD_EHIP;
     ResArgs dummy{};
-    if (dispatch_resident(plan->rank, dummy, 0, nullptr, &occ) != hipSuccess) return PSGD_EHIP;
+    if (dispatch_resident(plan->rank, dummy, 0, nullptr, &occ, 0) != hipSuccess) return PSGD_EHIP;
     if (plan->tuning.resident == 2) return PSGD_OK;   // diagnostic: keep the planner's grid whatever the device holds
     build_resident(plan, (int64_t)cus * std::min(occ, kResBlocksPerCU));
     return PSGD_OK;
@@ -607,7 +626,7 @@ psgd_status launch_resident_step(psgd_plan* plan, const void* grad, float* err, 
         hipError_t e = hipEventRecord(static_cast<hipEvent_t>(plan->events[0]), s);
         if (e != hipSuccess) { plan->last_error = hipGetErrorString(e); return PSGD_EHIP; }
     }
-    hipError_t e = dispatch_resident(plan->rank, a, plan->res_blocks, s, nullptr);
+    hipError_t e = dispatch_resident(plan->rank, a, plan->res_blocks, s, nullptr, plan->res_strip_rows);
     if (e != hipSuccess) {
         plan->last_error = std::string("launch k_resident: ") + hipGetErrorString(e);
         return PSGD_EHIP;
