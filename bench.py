@@ -143,7 +143,7 @@ def cpu_baseline(wl, rank, workers, budget_s, compressor="powersgd"):
         spent += time.perf_counter() - t0
         q, errs = res["Q"], res["err"]
         steps += 1
-        if spent >= budget_s or steps >= 50:
+        if spent >= budget_s or steps >= 1000:
             break
     gbs = workers * n_elems * 4 / (spent / steps) / 1e9
     rec = {"value": round(gbs, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
@@ -186,7 +186,7 @@ def cpu_baseline_sparse(wl, rank, workers, budget_s, compressor):
         spent += time.perf_counter() - t0
         errs = res["err"]
         steps += 1
-        if spent >= budget_s or steps >= 50:
+        if spent >= budget_s or steps >= 1000:
             break
     return {"value": round(workers * n_elems * 4 / (spent / steps) / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "ms_per_step": round(1e3 * spent / steps, 3),
