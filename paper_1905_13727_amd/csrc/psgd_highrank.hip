@@ -487,45 +487,35 @@ __global__ __launch_bounds__(kBlock) void k_hr_left(const MatDesc* __restrict__ 
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) acc[g][c][nt] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    // the 16 rows of a step: four loads of M per column group and the lane's P_hat entries.  Rows past the strip read
-    // a real row (the strip's last) whose product is switched off through B = 0.
-    auto load_step = [&](int r0, v4f (&a)[4][NG], float (&b)[4][NT]) {
+    // The 16 rows of a step: four loads of M per column group and the lane's P_hat entries, through descriptors that
+    // end with the strip's last row (rows past it read zeros, a lane without column or rank index is out of range):
+    // no branch surrounds a request, so the waits count exactly what is outstanding.
+    const buf_rsrc eres = make_rsrc(e + (int64_t)r_begin * m, (int64_t)rn * m * 4);
+    const buf_rsrc pres = make_rsrc(p + d.p_off + (int64_t)r_begin * ri, (int64_t)rn * ri * 4);
+    unsigned eo[NG], po[NT];   // element offsets of row kb of a step
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const int col = c0 + 64 * g + 4 * li;
+        eo[g] = (col < m && col < c0 + t.nvec) ? (unsigned)(kb * m + col) : kOutOfRange;
+    }
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int j = 16 * nt + li;
+        po[nt] = j < ri ? (unsigned)(kb * ri + j) : kOutOfRange;
+    }
+    auto load_step = [&](int r_rel, v4f (&a)[4][NG], float (&b)[4][NT]) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            const int row = r0 + 4 * s + kb;
-            const bool ok = row < r_end;
-            const int row_c = ok ? row : r_end - 1;
 #pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                const int col = c0 + 64 * g + 4 * li;
-                a[s][g] = v4f{0.f, 0.f, 0.f, 0.f};
-                if (col < m && col < c0 + t.nvec) {
-                    const v4f* src = reinterpret_cast<const v4f*>(e + (int64_t)row_c * m + col);
-                    a[s][g] = STREAM ? __builtin_nontemporal_load(src) : *src;
-                }
-            }
+            for (int g = 0; g < NG; ++g)
+                a[s][g] = buf_load_v4f_policy<STREAM ? 2 : 0>(
+                    eres, eo[g] == kOutOfRange ? kOutOfRange : (eo[g] + (unsigned)((r_rel + 4 * s) * m)) * 4u);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const int j = 16 * nt + li;
-                b[s][nt] = (ok && j < ri) ? p[d.p_off + (int64_t)row * ri + j] : 0.f;
-            }
+            for (int nt = 0; nt < NT; ++nt)
+                b[s][nt] = buf_load_f32(pres, po[nt] == kOutOfRange ? kOutOfRange : (po[nt] + (unsigned)((r_rel + 4 * s) * ri)) * 4u);
         }
     };
-    // the next step's loads are in flight while the current step is multiplied
-    v4f an[4][NG];
-    float bn[4][NT];
-    if (r_begin < r_end) load_step(r_begin, an, bn);
-    for (int r0 = r_begin; r0 < r_end; r0 += 16) {
-        v4f a[4][NG];
-        float b[4][NT];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-#pragma unroll
-            for (int g = 0; g < NG; ++g) a[s][g] = an[s][g];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) b[s][nt] = bn[s][nt];
-        }
-        if (r0 + 16 < r_end) load_step(r0 + 16, an, bn);
+    auto multiply = [&](const v4f (&a)[4][NG], const float (&b)[4][NT]) {
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -535,6 +525,23 @@ __global__ __launch_bounds__(kBlock) void k_hr_left(const MatDesc* __restrict__ 
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt)
                         acc[g][c][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s][g][c], b[s][nt], acc[g][c][nt], 0, 0, 0);
+    };
+    // the next step's loads are in flight while the current step is multiplied
+    v4f an[4][NG];
+    float bn[4][NT];
+    load_step(0, an, bn);
+    for (int r0 = 0; r0 < rn; r0 += 16) {
+        v4f a[4][NG];
+        float b[4][NT];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+#pragma unroll
+            for (int g = 0; g < NG; ++g) a[s][g] = an[s][g];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) b[s][nt] = bn[s][nt];
+        }
+        load_step(r0 + 16, an, bn);   // past the strip's last row: out of range, nothing is fetched
+        multiply(a, b);
     }
     // acc[g][c][nt][v] = Q[c0 + 64 g + 4 (4 kb + v) + c][16 nt + li] for this strip.  The four strips of the
     // workgroup are added through LDS as (s0 + s1) + (s2 + s3), so that one partial per row block is written.
