@@ -50,8 +50,8 @@ MEASURED_TRAFFIC = {
 # applied to the full set's algorithmic bytes.
 TRANSFORMER_TRAFFIC_RATIO = {
     (4, "k_ef_right"): 3183901020 / 3043491840, (4, "k_left"): 1273799574 / 1217396736, (4, "k_decomp"): 3182413765 / 3043934208,
-    (16, "k_ef_right"): 3183009566 / 3043491840, (16, "k_left"): 1285829804 / 1217396736, (16, "k_decomp"): 3191912143 / 3043934208,
-    (32, "k_ef_right"): 3222841127 / 3043491840, (32, "k_left"): 1305105648 / 1217396736, (32, "k_decomp"): 3200086304 / 3043934208,
+    (16, "k_ef_right"): 3183010845 / 3043491840, (16, "k_left"): 1285812336 / 1217396736, (16, "k_decomp"): 3207978852 / 3043934208,
+    (32, "k_ef_right"): 3222906596 / 3043491840, (32, "k_left"): 1305033872 / 1217396736, (32, "k_decomp"): 3201972705 / 3043934208,
 }
 
 
