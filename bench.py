@@ -49,7 +49,7 @@ MEASURED_TRAFFIC = {
 # profiles/transformer_4layers_bf16_r*_counters.md); here: measured traffic / algorithmic bytes of that subset,
 # applied to the full set's algorithmic bytes.
 TRANSFORMER_TRAFFIC_RATIO = {
-    (4, "k_ef_right"): 3183901020 / 3043491840, (4, "k_left"): 1273799574 / 1217396736, (4, "k_decomp"): 3182413765 / 3043934208,
+    (4, "k_ef_right"): 3170481094 / 3043491840, (4, "k_left"): 1271435096 / 1217396736, (4, "k_decomp"): 3181622066 / 3043934208,
     (16, "k_ef_right"): 3183010845 / 3043491840, (16, "k_left"): 1285812336 / 1217396736, (16, "k_decomp"): 3207978852 / 3043934208,
     (32, "k_ef_right"): 3222906596 / 3043491840, (32, "k_left"): 1305033872 / 1217396736, (32, "k_decomp"): 3201972705 / 3043934208,
 }
@@ -439,8 +439,7 @@ def main():
                    "compressor": args.compressor,
                    "mode": "elementwise sweep + kept entries (two kernels)" if sparse else
                            "resident (one kernel, M kept in registers)" if resident else
-                           ("matrix cores (one kernel per phase)"
-                            if rank > 8 or ((gdt != "f32" or odt != "f32") and tune.get("bf16_valu", 1) == 0)
+                           ("matrix cores (one kernel per phase)" if plan.path() == "matrix cores"
                             else "streaming (one kernel per phase)"),
                    "matrices": int(s.n_matrices), "matrix_elems": int(payload_mat), "vector_elems": int(L),
                    "grad_buffers": len(grads), "update": args.update,

@@ -148,7 +148,9 @@ PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, in
  *                 device holds all row blocks of the launch at once, 0 in two launches, 2 (TEST ONLY) in one
  *                 launch unconditionally: its waits may then time out, see psgd_plan_check
  *   gram_spin     polls before a wait in that launch gives up, 1 .. 2^24 (default 2^18)
- *   bf16_valu     bf16 gradients / output at rank <= 8: 1 (default) streaming kernels, 0 matrix-core kernels
+ *   bf16_valu     bf16 gradients / output at rank <= 8: 1 streaming kernels, 0 matrix-core kernels, -1 (default) the
+ *                 matrix-core kernels at rank >= 4 when the update matrices of all workers exceed 320 MB and every
+ *                 row length is a multiple of 4, the streaming kernels otherwise
  *                 (then every row length must be a multiple of 4, else PSGD_EUNSUPPORTED) */
 PSGD_API psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value);
 
@@ -331,6 +333,15 @@ PSGD_API psgd_status psgd_plan_check(psgd_plan* plan, void* hip_stream, int32_t*
  * Synchronises the device and copies at most
  * `capacity` values of the last step to `out` (host); *n_written = count. */
 PSGD_API psgd_status psgd_plan_read_trace(psgd_plan* plan, uint64_t* out, int64_t capacity, int64_t* n_written);
+
+/* Which kernels psgd_step runs for this plan (Algorithm 1 and the loop of Algorithm 2 are the same on all of
+ * them; the choice is the planner's, from rank, data types, shapes and set size, see psgd_plan_set_tuning):
+ * *path = PSGD_PATH_STREAMING, PSGD_PATH_RESIDENT or PSGD_PATH_MATRIX_CORES.  For a plan that has made no GPU call
+ * yet "resident" is the planner's provisional choice (see psgd_plan_check).  PSGD_EINVAL for NULL arguments. */
+#define PSGD_PATH_STREAMING 0
+#define PSGD_PATH_RESIDENT 1
+#define PSGD_PATH_MATRIX_CORES 2
+PSGD_API psgd_status psgd_plan_path(const psgd_plan* plan, int32_t* path);
 
 /* Static, never NULL. */
 PSGD_API const char* psgd_status_string(psgd_status status);

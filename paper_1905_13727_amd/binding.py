@@ -73,6 +73,8 @@ def load_library(path: Optional[str] = None):
     lib.psgd_random_block_step.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.psgd_random_k_step.restype = C.c_int
     lib.psgd_random_k_step.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.psgd_plan_path.restype = C.c_int
+    lib.psgd_plan_path.argtypes = [vp, C.POINTER(i32)]
     lib.psgd_plan_kept.restype = C.c_int
     lib.psgd_plan_kept.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(i64)]
     lib.psgd_step_static.restype = C.c_int
@@ -194,6 +196,12 @@ class Plan:
     def random_k_step(self, grad, err, indices, vals, out, stream=None):
         self._check(self._lib.psgd_random_k_step(self._h, _ptr(grad), _ptr(err), _ptr(indices), _ptr(vals), _ptr(out),
                                                  _ptr(stream)), "psgd_random_k_step")
+
+    def path(self) -> str:
+        """'streaming', 'resident' or 'matrix cores': the kernels psgd_step runs for this plan."""
+        r = C.c_int32()
+        self._check(self._lib.psgd_plan_path(self._h, C.byref(r)), "psgd_plan_path")
+        return ("streaming", "resident", "matrix cores")[r.value]
 
     def kept(self, tensor: int):
         off, n = C.c_int64(), C.c_int64()

@@ -115,7 +115,8 @@ struct Tuning {
                             // row blocks at once; 0 = always the two launches; 2 = one launch whatever the device holds
                             // (diagnostic: the waits may time out, which psgd_plan_check then reports)
     int64_t gram_spin = 1 << 18;   // polls of one slot in that launch before a wait gives up
-    int64_t bf16_valu = 1;  // bf16 gradients / output at rank <= 8: 1 = the streaming (vector-ALU) kernels, 0 = the matrix-core kernels
+    int64_t bf16_valu = -1; // bf16 gradients / output at rank <= 8: 1 = the streaming (vector-ALU) kernels, 0 = the matrix-core kernels,
+                            // -1 = the matrix-core kernels at rank >= 4 on a set beyond the memory-side cache whose shapes they take
     int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream; 2: as 1 without the check
                             // against the device at upload (diagnostic, with res_max_blocks: lets a test see the waits give up)
     int64_t res_spin = 1 << 21;      // polls before a wait of the resident kernel gives up

@@ -241,9 +241,20 @@ static psgd_status build_hr_tables(psgd_plan* plan) {
 
 psgd_status build_tables(psgd_plan* plan) {
     const Tuning& tu = plan->tuning;
-    // ranks above 8 run on the matrix-core kernels; bf16 data at the lower ranks on either (bf16_valu)
+    // Ranks above 8 run on the matrix-core kernels; bf16 data at the lower ranks on either (bf16_valu).  The planner's
+    // own choice for bf16 data: matrix cores at rank >= 4 on a set beyond the memory-side cache, if its shapes are ones
+    // those kernels take (24-layer transformer-shaped set, ms per step, streaming / matrix cores: rank 2: 5.17 / 5.15,
+    // rank 4: 5.28 / 5.17, rank 8: 6.43 / 5.19).
     const bool bf16 = plan->grad_dtype != PSGD_F32 || plan->out_dtype != PSGD_F32;
-    plan->hr = plan->rank > kValuMaxRank || (bf16 && !tu.bf16_valu);
+    if (tu.bf16_valu < -1 || tu.bf16_valu > 1) return PSGD_EINVAL;
+    bool hr_low = bf16 && tu.bf16_valu == 0;
+    if (bf16 && tu.bf16_valu < 0 && plan->rank >= 4 &&
+        plan->workers * plan->sizes.n_mat_elems * (int64_t)sizeof(float) > kStreamHintBytes) {
+        hr_low = true;
+        for (const MatDesc& d : plan->mats)
+            if (d.m % 4 != 0 || d.m > kHrMaxCols || d.n > kHrMaxRows) hr_low = false;
+    }
+    plan->hr = plan->rank > kValuMaxRank || hr_low;
     if (plan->hr) return build_hr_tables(plan);
     if (plan->out_dtype != PSGD_F32 && tu.k4_nv != 1) return PSGD_EINVAL;   // bf16 output: one column vector per lane
     if (tu.k1_rows < 0 || tu.k3_rows < 0 || tu.k4_rows < 0 || tu.k1_nv < 1 ||
@@ -675,6 +686,12 @@ psgd_status psgd_plan_kept(const psgd_plan* plan, int32_t tensor, int64_t* kept_
     const int32_t mi = plan->tensor_mat[tensor];
     if (kept_off) *kept_off = mi < 0 ? -1 : plan->mats[mi].kept_off;
     if (kept) *kept = mi < 0 ? 0 : plan->mats[mi].kept;
+    return PSGD_OK;
+}
+
+psgd_status psgd_plan_path(const psgd_plan* plan, int32_t* path) {
+    if (!plan || !path) return PSGD_EINVAL;
+    *path = plan->hr ? PSGD_PATH_MATRIX_CORES : (plan->resident_ok ? PSGD_PATH_RESIDENT : PSGD_PATH_STREAMING);
     return PSGD_OK;
 }
 

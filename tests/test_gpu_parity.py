@@ -714,14 +714,15 @@ def test_fused_update_matrix_cores():
 
 # ---- the 24-layer transformer-shaped set at full size, sampled tensors ---------------------------------
 
-@pytest.mark.parametrize("rank", [32, 16, 4])
-def test_transformer_full_size_sampled(rank):
+@pytest.mark.parametrize("rank,path", [(32, "matrix cores"), (16, "matrix cores"), (4, "matrix cores"), (4, "streaming")])
+def test_transformer_full_size_sampled(rank, path):
     """The whole 145-matrix set (1.31 G elements, bf16 gradients and output, fp32 state) runs on the GPU in
     the launch configuration bench.py times.  The method treats every matrix on its own, so the oracle run
     on a sample of the tensors alone (the embedding, one matrix of each other shape from the first and the
     last layer, two vectors) gives exactly what the full-set step must produce for them.  The sampled
     tensors carry the planted-spectrum recipe from the host generator; the rest is noise drawn on the GPU.
-    Five free-running steps at each of the three ranks of the configuration."""
+    Five free-running steps at each of the three ranks of the configuration; rank 4 on the kernels the planner
+    takes for it (matrix cores) and on the streaming kernels."""
     _need_gpu()
     from oracle import powersgd_oracle as O
     from paper_1905_13727_amd import binding as B, workloads as WL
@@ -741,6 +742,9 @@ def test_transformer_full_size_sampled(rank):
     assert (50304, 2048) in first and (2048, 8192) in first and len(sample) >= 8
     dev = torch.device("cuda:0")
     plan = B.Plan(shapes, rank, 1, B.PSGD_BF16, B.PSGD_BF16)
+    if path == "streaming":
+        plan.set_tuning("bf16_valu", 1)
+    assert plan.path() == path
     lay = FlatLayout(plan, shapes)
     s = plan.sizes
     seed = 90 + rank

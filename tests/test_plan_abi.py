@@ -153,3 +153,34 @@ def test_compression_ratios_match_the_paper():
             got = s.payload_elems / s.compressed_elems
             assert abs(got - ratio) <= 0.5
             assert s.compressed_elems == O.compressed_floats(shapes, r)
+
+
+def test_which_kernels_a_plan_runs():
+    """psgd_plan_path: the planner's choice among the streaming, resident and matrix-core kernels, from rank, data
+    types, shapes and set size (no GPU is needed to ask)."""
+    lib = B.load_library()
+    small = [(64, 576), (128, 64), (33,)]
+    big = [(20000, 4096), (4096, 4096), (4096,)]          # 99 M elements: beyond the memory-side cache
+    big_odd = [(20000, 4098), (4096, 4096)]               # a row length that is not a multiple of 4
+    assert B.Plan(small, 2, 1).path() == "resident"
+    assert B.Plan(small, 2, 2).path() == "streaming"
+    assert B.Plan(small, 16, 1).path() == "matrix cores"
+    assert B.Plan(big, 4, 1).path() == "streaming"         # fp32 data at rank <= 8
+    bf = (B.PSGD_BF16, B.PSGD_BF16)
+    assert B.Plan(big, 4, 1, *bf).path() == "matrix cores"  # bf16 data, rank >= 4, a large set
+    assert B.Plan(big, 2, 1, *bf).path() == "streaming"
+    assert B.Plan(small, 4, 1, *bf).path() == "streaming"
+    assert B.Plan(big_odd, 4, 1, *bf).path() == "streaming"
+    p = B.Plan(big, 4, 1, *bf)
+    p.set_tuning("bf16_valu", 1)
+    assert p.path() == "streaming"
+    p.set_tuning("bf16_valu", 0)
+    assert p.path() == "matrix cores"
+    with pytest.raises(B.PsgdError):
+        p.set_tuning("bf16_valu", 2)
+    q = B.Plan(small, 4, 1, *bf)
+    q.set_tuning("bf16_valu", 0)
+    assert q.path() == "matrix cores"
+    import ctypes as C
+    r = C.c_int32()
+    assert lib.psgd_plan_path(None, C.byref(r)) == B.PSGD_EINVAL and lib.psgd_plan_path(p._h, None) == B.PSGD_EINVAL
