@@ -144,10 +144,12 @@ PSGD_API psgd_status psgd_plan_offsets(const psgd_plan* plan, int32_t tensor, in
  *   stream_hints  cache policy of the second and third sweep: -1 (default) by the size of M over all
  *                 workers (non-temporal accesses to M and the error memory above 320 MB), 0 never,
  *                 1 always
- *   gram_fused    tall panels: 1 (default) Gram matrices and factorisation in one launch where the
+ *   gram_fused    orthogonalisation over row blocks: 1 (default) Gram matrices and factorisation in one launch where the
  *                 device holds all row blocks of the launch at once, 0 in two launches, 2 (TEST ONLY) in one
  *                 launch unconditionally: its waits may then time out, see psgd_plan_check
  *   gram_spin     polls before a wait in that launch gives up, 1 .. 2^24 (default 2^18)
+ *   ortho_rows    panels of at most this many rows (0 .. 1024) are orthogonalised by one workgroup with modified
+ *                 Gram-Schmidt in LDS instead of Cholesky-QR over row blocks; default 0: none
  *   bf16_valu     bf16 gradients / output at rank <= 8: 1 streaming kernels, 0 matrix-core kernels, -1 (default) the
  *                 matrix-core kernels at rank >= 4 when the update matrices of all workers exceed 320 MB and every
  *                 row length is a multiple of 4, the streaming kernels otherwise
@@ -188,7 +190,7 @@ PSGD_API psgd_status psgd_decompress(psgd_plan* plan, const float* p, const floa
  * once.  Its sums run in another (fixed) order than the split calls, so the
  * two agree to rounding, not bit for bit; each is reproducible from run to
  * run.  Otherwise psgd_step is exactly the two calls in sequence.  Resident
- * mode, and the one-launch factorisation of tall panels (tuning key
+ * mode, and the one-launch orthogonalisation over row blocks (tuning key
  * gram_fused), keep hand-over words in plan-owned device memory: do not run
  * two calls of the same plan concurrently on different streams.  Both are
  * kernels whose workgroups wait for each other inside one ordinary launch:
@@ -312,8 +314,8 @@ PSGD_API const char* psgd_kernel_name(int32_t index);
 
 /* A plan that has made no GPU call yet: uploads its tables (the plan's one device allocation) and returns.
  * Otherwise waits for hip_stream, then returns PSGD_EHIP if a kernel of this plan whose
- * workgroups wait for each other (resident mode; the one-launch factorisation
- * of tall panels) gave up waiting since the last check, PSGD_OK otherwise.
+ * workgroups wait for each other (resident mode; the one-launch orthogonalisation
+ * over row blocks) gave up waiting since the last check, PSGD_OK otherwise.
  * After PSGD_EHIP the outputs of the steps since the last check are invalid
  * (restore err and q from a copy, or restart them), the plan's hand-over words
  * are reset, and the mode that failed is switched off for this plan: later

@@ -20,9 +20,9 @@ constexpr int kMaxVecPerLaneK3 = 2;  // column vectors a lane owns in the Q = M^
 constexpr int kOrthoBlock = 256;   // threads of the single-workgroup Gram-Schmidt kernel
 constexpr int kValuMaxRank = 8;    // ranks up to this run on the vector-ALU kernels
 constexpr int kPanelFloats = 12288;  // n*r up to this: Gram-Schmidt by one workgroup with the panel in LDS (48 KB)
-constexpr int kGramRows = 256;     // rows per workgroup of the tall-panel Gram / apply kernels
+constexpr int kGramRows = 256;     // rows per workgroup of the Gram / apply kernels (Cholesky-QR over row blocks)
 constexpr int kPreReduceParts = 16; // more partial-P slices than this: a reduction kernel runs before the orthogonalisation
-constexpr int kOrthoMaxRows = 1024; // panels with more rows take the multi-workgroup route
+constexpr int kOrthoMaxRows = 1024; // largest value of the tuning key ortho_rows: panels with more rows always take the multi-workgroup route
 constexpr int kFlatTileElems = 1024;        // baselines: elements of a flattened matrix per workgroup of the elementwise sweep (one 16-byte access per
                                             // lane and array: the smallest slices were the fastest, 8192 -> 1024: 34.7 -> 28.7 us on the ResNet18 set)
 constexpr int kFactorAlignElems = 4;        // P and Q of a matrix start at multiples of 4 floats (vector loads of factor rows)
@@ -39,13 +39,13 @@ struct MatDesc {
     int64_t q_off;      // float offset in packed Q
     int64_t ppart_off;  // float offset in the workspace: partial P, [W * n_cchunk][n][r]
     int64_t qpart_off;  // float offset in the workspace: partial Q, [W * n_rblock][m][r]
-    int64_t gram_off;   // tall panels: offset (in doubles) of the Gram partials, [n_gblock][r*r]
+    int64_t gram_off;   // Cholesky-QR panels: offset (in doubles) of the Gram partials, [n_gblock][r*r]
     int32_t n, m, r;    // rows, columns, effective rank
     int32_t vec;        // elements per vector access along a row (4, 2 or 1)
     int32_t n_cchunk;   // column chunks of the P = M Q kernel (partials to sum)
     int32_t n_rblock;   // row blocks of the Q = M^T P kernel (partials to sum)
     int32_t tensor;     // index in the caller's shape list
-    int32_t n_gblock;   // tall panels: row blocks of the Gram / apply kernels; 0 = panel fits one workgroup's LDS
+    int32_t n_gblock;   // row blocks of the Gram / apply kernels; 0 = panel orthogonalised by one workgroup in LDS (k_ortho)
     int32_t pad_[2];
     int64_t chol_off;   // matrix-core path: offset (in doubles) of this matrix's Cholesky factor, r*r + r values
     int64_t kept_off;   // Random Block / Random K baselines: offset of this matrix's kept values (and indices) in their packed buffers
@@ -111,10 +111,14 @@ struct Tuning {
                                 // memory (and temporal instead of non-temporal stores of Delta'); matrix-core path:
                                 // non-temporal loads of M in sweep 2.
                                 // -1: when M of all workers exceeds kStreamHintBytes; 0: never; 1: always
-    int64_t gram_fused = 1; // tall panels: 1 = Gram matrices and factorisation in one launch when the device holds a matrix's
+    int64_t gram_fused = 1; // Cholesky-QR panels: 1 = Gram matrices and factorisation in one launch when the device holds a matrix's
                             // row blocks at once; 0 = always the two launches; 2 = one launch whatever the device holds
                             // (diagnostic: the waits may time out, which psgd_plan_check then reports)
     int64_t gram_spin = 1 << 18;   // polls of one slot in that launch before a wait gives up
+    int64_t ortho_rows = 0;        // panels of at most this many rows (and kPanelFloats values) are orthogonalised by one workgroup
+                                   // with Gram-Schmidt in LDS (k_ortho), the others by Cholesky-QR over row blocks; 0: none (a
+                                   // launch of its own for the short panels costs more than it saves: ResNet18-shaped set,
+                                   // streaming, rank 2 / 4 / 8: 61.9 / 73.1 / 110.4 us with 1024, 59.6 / 67.0 / 100.9 us with 0)
     int64_t bf16_valu = -1; // bf16 gradients / output at rank <= 8: 1 = the streaming (vector-ALU) kernels, 0 = the matrix-core kernels,
                             // -1 = the matrix-core kernels at rank >= 4 on a set beyond the memory-side cache whose shapes they take
     int64_t resident = 1;   // 1: psgd_step keeps M on chip when the model fits; 0: always stream; 2: as 1 without the check
@@ -170,7 +174,7 @@ struct psgd_plan {
     std::vector<psgd::MatDesc> mats;
     std::vector<psgd::Tile> tiles1, tiles3, tiles4, tilesq;
     std::vector<psgd::Tile> tiles4u;        // third sweep when fused with the update, if its tiles differ (else empty)
-    std::vector<psgd::Tile> tiles_gram;     // row blocks of tall panels (Cholesky-QR)
+    std::vector<psgd::Tile> tiles_gram;     // row blocks of the panels orthogonalised by Cholesky-QR
     std::vector<int64_t> flat_first;        // baselines (Appendix G): running count of the slices of the flattened matrices
     int64_t flat_tiles = 0;                 //   (n_matrices + 1 entries), their total, and the slices of the vector region
     int64_t flat_vec_tiles = 0;
@@ -188,7 +192,7 @@ struct psgd_plan {
     std::vector<psgd::Tile> tilesp;         // 64-element slices of the n x r panels (pre-reduction of partial P)
     bool p_pre_reduce = false;              // some matrix has more than kPreReduceParts partial-P slices
     bool stream_hints = false;              // see Tuning::stream_hints
-    bool gram_fused = false;                // tall panels: one launch (k_gram_chol) instead of two (set at upload)
+    bool gram_fused = false;                // Cholesky-QR panels: one launch (k_gram_chol) instead of two (set at upload)
     int32_t max_n = 0;
     int64_t ws_ppart_floats = 0;            // workspace: partial P region (floats)
     int64_t ws_qpart_floats = 0;            // workspace: partial Q region, starts after partial P

@@ -7,11 +7,12 @@
 //   k_ef_right    M_w = g_w + e_w (stored in e_w's place) fused with the row dot
 //                 products of P_w = M_w Q               (Alg. 2 "Delta_w", Alg. 1 "P <- M Q");
 //                 without the add, one more subspace iteration on a stored M (Appendix G.7)
-//   k_ortho       mean over workers / column chunks, then Gram-Schmidt in LDS, for panels of
-//                 up to 1024 rows                       (Alg. 1 "all reduce mean", "orthogonalize")
-//   k_gram_chol   the same orthonormal factor by Cholesky-QR over many workgroups, for taller
-//                 panels, in one launch; k_gram, k_chol_apply: the same in two launches
-//                                                       (Remark "Orthogonalization is a linear operation")
+//   k_gram_chol   mean over workers / column chunks, then the orthonormal factor Gram-Schmidt
+//                 gives, by Cholesky-QR over many workgroups in one launch; k_gram,
+//                 k_chol_apply: the same in two launches (Alg. 1 "all reduce mean", "orthogonalize";
+//                 Remark "Orthogonalization is a linear operation")
+//   k_ortho       the same by Gram-Schmidt in LDS, one workgroup per matrix, for the panels of at
+//                 most ortho_rows rows (a tuning key; 0 by default: none)
 //   k_left        column sums of Q_w = M_w^T P_hat      (Alg. 1 "Q <- M^T P_hat")
 //   k_q_reduce    mean over workers / row blocks        (Alg. 1 second "all reduce mean"); also
 //                 pre-reduces the partial P when there are many
@@ -258,11 +259,11 @@ __global__ __launch_bounds__(kOrthoBlock) void k_ortho(const MatDesc* __restrict
     for (int64_t idx = tid; idx < nr; idx += kOrthoBlock) dst[idx] = panel[idx];
 }
 
-// ---- tall panels (n*r above the LDS panel): the same orthonormal factor by Cholesky-QR --------------
+// ---- the same orthonormal factor by Cholesky-QR over row blocks (every panel not given to k_ortho) ----
 //
 // Gram-Schmidt yields P_hat = P R^-1 with R upper triangular, positive diagonal (the paper's remark
 // "Orthogonalization is a linear operation"); that R is the Cholesky factor of the Gram matrix
-// P^T P.  For a panel too tall for one workgroup the factor is computed that way, over many
+// P^T P.  The factor is computed that way, over many
 // workgroups: k_gram sums the partials into the mean P (stored in the P buffer) and reduces the
 // Gram matrix of its row block in fp64; k_chol_apply adds the blocks' Gram matrices in a fixed order,
 // factorises (fp64, r <= 8) and solves P_hat R = P row by row.  A pivot <= 1e-30 (the squared norm

@@ -262,7 +262,7 @@ psgd_status build_tables(psgd_plan* plan) {
         tu.k4_nv > kMaxVecPerLaneK3 || tu.res_rows < 0 || tu.res_rows > kResRows || tu.resident < 0 || tu.resident > 2 ||
         tu.res_spin < 1 || tu.res_spin > (int64_t(1) << 30) || tu.res_max_blocks < 0 || tu.res_max_blocks > 65535 ||
         tu.stream_hints < -1 || tu.stream_hints > 1 || tu.xcd_order < -1 || tu.gram_fused < 0 || tu.gram_fused > 2 || tu.gram_spin < 1 ||
-        tu.gram_spin > (1 << 24))
+        tu.gram_spin > (1 << 24) || tu.ortho_rows < 0 || tu.ortho_rows > kOrthoMaxRows)
         return PSGD_EINVAL;
     const size_t nm = plan->mats.size();
     // k_ef_right and k_left address the rows of a wavefront's strip (a quarter of the tile's rows) with 31-bit
@@ -308,7 +308,7 @@ psgd_status build_tables(psgd_plan* plan) {
         d.n_rblock = nrb[i];
         d.ppart_off = pp;
         pp += round_up(W * d.n_cchunk * d.n * d.r, kAlignElems);
-        if ((int64_t)d.n * d.r <= kPanelFloats && d.n <= kOrthoMaxRows) {
+        if ((int64_t)d.n * d.r <= kPanelFloats && d.n <= tu.ortho_rows) {
             d.n_gblock = 0;
             d.gram_off = 0;
             plan->small_mats.push_back((int32_t)i);
@@ -729,6 +729,7 @@ psgd_status psgd_plan_set_tuning(psgd_plan* plan, const char* key, int64_t value
     else if (!strcmp(key, "bf16_valu")) tu.bf16_valu = value;
     else if (!strcmp(key, "gram_fused")) tu.gram_fused = value;
     else if (!strcmp(key, "gram_spin")) tu.gram_spin = value;
+    else if (!strcmp(key, "ortho_rows")) tu.ortho_rows = value;
     else if (!strcmp(key, "res_rows")) tu.res_rows = value;
     else if (!strcmp(key, "res_trace")) tu.res_trace = value;
     else if (!strcmp(key, "res_spin")) tu.res_spin = value;

@@ -222,6 +222,7 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
         CHECK(psgd_plan_set_tuning(plan, "k3_nv", tu->k3_nv) == PSGD_OK);
         CHECK(psgd_plan_set_tuning(plan, "k4_rows", tu->k4_rows) == PSGD_OK);
         CHECK(psgd_plan_set_tuning(plan, "k4_nv", tu->k4_nv) == PSGD_OK);
+        CHECK(psgd_plan_set_tuning(plan, "ortho_rows", tu->ortho_rows) == PSGD_OK);
     }
     check_resident(plan);
     for (int64_t rr : {5, 8, 13, 24, 32}) {
@@ -252,7 +253,7 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
         CHECK(d.ppart_off >= 0 && d.ppart_off + (int64_t)workers * d.n_cchunk * d.n * d.r <= plan->ws_ppart_floats);
         CHECK(d.qpart_off >= plan->ws_ppart_floats &&
               d.qpart_off + (int64_t)workers * d.n_rblock * d.m * d.r <= plan->ws_ppart_floats + plan->ws_qpart_floats);
-        if ((int64_t)d.n * d.r > kPanelFloats || d.n > kOrthoMaxRows) {
+        if ((int64_t)d.n * d.r > kPanelFloats || d.n > plan->tuning.ortho_rows) {
             CHECK(d.n_gblock == (d.n + kGramRows - 1) / kGramRows);
             CHECK(d.gram_off >= 0 && d.gram_off + (int64_t)d.n_gblock * d.r * d.r <= plan->ws_gram_doubles);
         } else {
@@ -272,7 +273,7 @@ static void check_plan(const std::vector<psgd_shape>& shapes, int rank, int work
         }
         for (size_t i = 0; i < plan->mats.size(); ++i) {
             const MatDesc& d = plan->mats[i];
-            if (d.n_gblock == 0) CHECK(small[i] == 1 && rows[i] == 0 && (int64_t)d.n * d.r <= kPanelFloats && d.n <= kOrthoMaxRows);
+            if (d.n_gblock == 0) CHECK(small[i] == 1 && rows[i] == 0 && (int64_t)d.n * d.r <= kPanelFloats && d.n <= plan->tuning.ortho_rows);
             else CHECK(small[i] == 0 && rows[i] == d.n);
         }
     }
@@ -375,8 +376,10 @@ int main() {
     };
     Tuning small;
     small.k1_rows = 8; small.k1_nv = 1; small.k3_rows = 16; small.k3_nv = 1; small.k4_rows = 8; small.k4_nv = 1;
+    small.ortho_rows = kOrthoMaxRows;   // short panels by one workgroup (Gram-Schmidt in LDS)
     Tuning big;
     big.k1_rows = 64; big.k1_nv = 2; big.k3_rows = 300; big.k3_nv = 2; big.k4_rows = 300; big.k4_nv = 2;
+    big.ortho_rows = 64;
     for (auto& s : sets)
         for (int rank : {1, 2, 4, 8})
             for (int W : {1, 3}) {

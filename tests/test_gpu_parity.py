@@ -126,6 +126,8 @@ def test_ragged_shapes_three_workers(rank):
     _need_gpu()
     shapes = [(37, 91), (7,), (50, 650), (130, 1028), (5, 3), (300, 2), (1, 40), (1031,), (3, 4700), (257, 260)]
     _run(_workload(shapes), rank=rank, workers=3, steps=4, seed=rank)
+    # the same with the short panels orthogonalised by one workgroup (Gram-Schmidt in LDS)
+    _run(_workload(shapes), rank=rank, workers=3, steps=3, seed=40 + rank, tuning={"ortho_rows": 1024})
 
 
 @pytest.mark.parametrize("rank,workers", [(1, 1), (3, 2), (4, 1), (8, 2)])
@@ -367,7 +369,7 @@ def test_small_tiles_many_partials():
     sums are exercised."""
     _need_gpu()
     shapes = [(200, 1500), (64, 576), (33,)]
-    tuning = {"k1_rows": 8, "k1_nv": 1, "k3_rows": 16, "k4_rows": 8}
+    tuning = {"k1_rows": 8, "k1_nv": 1, "k3_rows": 16, "k4_rows": 8, "ortho_rows": 64}
     _run(_workload(shapes), rank=3, workers=2, steps=3, seed=5, tuning=tuning)
     tuning = {"k1_rows": 64, "k1_nv": 2, "k3_rows": 300, "k3_nv": 2, "k4_rows": 300, "k4_nv": 2}
     _run(_workload(shapes), rank=4, workers=2, steps=3, seed=6, tuning=tuning)
