@@ -86,12 +86,15 @@ def test_null_pointers_are_rejected_without_a_gpu():
         plan.set_tuning("gram_fused", 3)
     with pytest.raises(B.PsgdError):
         plan.set_tuning("gram_spin", 0)
-    for key, bad in (("resident", 3), ("res_spin", 0), ("res_max_blocks", -1), ("q_reduce_elems", 1), ("k1_mfma", 1)):
+    for key, bad in (("resident", 3), ("res_spin", 0), ("res_max_blocks", -1), ("q_reduce_elems", 1), ("k1_mfma", 1),
+                     ("ortho_rows", -1), ("ortho_rows", 1025)):
         with pytest.raises(B.PsgdError):     # out of range, or a key that no longer exists
             plan.set_tuning(key, bad)
     plan.set_tuning("res_spin", 1 << 10)
     plan.set_tuning("gram_fused", 0)
     plan.set_tuning("gram_spin", 1024)
+    plan.set_tuning("ortho_rows", 1024)
+    plan.set_tuning("ortho_rows", 0)
     with pytest.raises(B.PsgdError):
         plan.set_tuning("xcd_order", -2)
     plan.set_tuning("xcd_order", -1)
