@@ -172,6 +172,32 @@ __device__ __forceinline__ float sum_parts(const float* __restrict__ src, int np
     return s;
 }
 
+// the same for the r <= R values of one panel row at once: the loads of all columns and of several slices are in
+// flight together; per column the slices are added in slice order, as in sum_parts (bit-identical to it)
+template <int R>
+__device__ __forceinline__ void sum_parts_row(const float* __restrict__ src, int r, int nparts, int64_t stride,
+                                              float (&row)[R]) {
+    constexpr int U = R <= 2 ? 8 : (R <= 4 ? 4 : 2);
+#pragma unroll
+    for (int k = 0; k < R; ++k) row[k] = 0.f;
+    int c = 0;
+    for (; c + U <= nparts; c += U) {
+        float v[U][R];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int k = 0; k < R; ++k) v[u][k] = k < r ? src[(int64_t)(c + u) * stride + k] : 0.f;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int k = 0; k < R; ++k) row[k] += v[u][k];
+    }
+    for (; c < nparts; ++c)
+#pragma unroll
+        for (int k = 0; k < R; ++k)
+            if (k < r) row[k] += src[(int64_t)c * stride + k];
+}
+
 __global__ __launch_bounds__(kOrthoBlock) void k_ortho(const MatDesc* __restrict__ mats, const int32_t* __restrict__ which,
                                                        const float* __restrict__ ws, float* __restrict__ p, int workers,
                                                        int pre_reduced) {
@@ -286,13 +312,11 @@ __global__ __launch_bounds__(kBlock) void k_gram(const MatDesc* __restrict__ mat
         for (int b = 0; b < kValuMaxRank; ++b) g[a][b] = 0.0;
     for (int i = t.row0 + tid; i < t.row0 + t.nrows; i += kBlock) {
         float row[kValuMaxRank];
+        sum_parts_row<kValuMaxRank>(ws + d.ppart_off + (int64_t)i * r, r, nparts, nr, row);
 #pragma unroll
         for (int k = 0; k < kValuMaxRank; ++k) {
-            row[k] = 0.f;
-            if (k < r) {
-                row[k] = sum_parts(ws + d.ppart_off + (int64_t)i * r + k, nparts, nr) * inv_w;
-                p[d.p_off + (int64_t)i * r + k] = row[k];
-            }
+            row[k] *= inv_w;
+            if (k < r) p[d.p_off + (int64_t)i * r + k] = row[k];
         }
 #pragma unroll
         for (int a = 0; a < kValuMaxRank; ++a)
@@ -322,6 +346,7 @@ __global__ __launch_bounds__(kBlock) void k_chol_apply(const MatDesc* __restrict
                                                        const double* __restrict__ gram, float* __restrict__ p) {
     constexpr int kMaxSlices = 16;
     __shared__ double part[kMaxSlices][kValuMaxRank * kValuMaxRank];
+    __shared__ double Gs[kValuMaxRank * kValuMaxRank];  // the summed Gram matrix, r x r
     __shared__ double Rm[kValuMaxRank][kValuMaxRank];   // upper triangular factor
     __shared__ double rinv[kValuMaxRank];               // 1 / R_jj, 0 for a zero column
     const Tile t = tiles[blockIdx.x];
@@ -355,6 +380,12 @@ __global__ __launch_bounds__(kBlock) void k_chol_apply(const MatDesc* __restrict
         }
     }
     __syncthreads();
+    if (tid < nent) {   // one thread per entry adds the slices, in slice order
+        double v = 0.0;
+        for (int sl = 0; sl < nslices; ++sl) v += part[sl][tid];
+        Gs[tid] = v;
+    }
+    __syncthreads();
     if (tid == 0) {
         // Every index below is a compile-time constant (loops unrolled to the largest rank, rows and columns
         // past r switched off by predicates), so the matrix lives in registers; R overwrites G's upper triangle.
@@ -362,13 +393,7 @@ __global__ __launch_bounds__(kBlock) void k_chol_apply(const MatDesc* __restrict
 #pragma unroll
         for (int a = 0; a < kValuMaxRank; ++a)
 #pragma unroll
-            for (int b = a; b < kValuMaxRank; ++b)
-            {
-                double v = 0.0;
-                if (b < r)
-                    for (int sl = 0; sl < nslices; ++sl) v += part[sl][a * r + b];
-                G[a][b] = v;
-            }
+            for (int b = a; b < kValuMaxRank; ++b) G[a][b] = b < r ? Gs[a * r + b] : 0.0;
         // Cholesky, row by row of R (upper): R_jj = sqrt(G_jj - sum_k R_kj^2), R_jc = (G_jc - sum_k R_kj R_kc) / R_jj
 #pragma unroll
         for (int j = 0; j < kValuMaxRank; ++j) {
@@ -434,6 +459,7 @@ __global__ __launch_bounds__(kBlock) void k_gram_chol(const MatDesc* __restrict_
     constexpr int E = kValuMaxRank * kValuMaxRank;
     __shared__ double red[kWavesPerBlock][E];
     __shared__ double part[kMaxSlices][E];
+    __shared__ double Gs[E];
     __shared__ double Rm[kValuMaxRank][kValuMaxRank];
     __shared__ double rinv[kValuMaxRank];
     unsigned epoch = 0;
@@ -452,9 +478,11 @@ __global__ __launch_bounds__(kBlock) void k_gram_chol(const MatDesc* __restrict_
     float row[R];
     double g[R][R];
 #pragma unroll
-    for (int k = 0; k < R; ++k) {
-        row[k] = 0.f;
-        if (have && k < r) row[k] = sum_parts(ws + d.ppart_off + (int64_t)i * r + k, nparts, nr) * inv_w;
+    for (int k = 0; k < R; ++k) row[k] = 0.f;
+    if (have) {
+        sum_parts_row<R>(ws + d.ppart_off + (int64_t)i * r, r, nparts, nr, row);
+#pragma unroll
+        for (int k = 0; k < R; ++k) row[k] *= inv_w;
     }
 #pragma unroll
     for (int a = 0; a < R; ++a)
@@ -514,17 +542,18 @@ __global__ __launch_bounds__(kBlock) void k_gram_chol(const MatDesc* __restrict_
         }
     }
     __syncthreads();
+    if (tid < nent) {   // one thread per entry adds the slices, in slice order
+        double v = 0.0;
+        for (int sl = 0; sl < nslices; ++sl) v += part[sl][tid];
+        Gs[tid] = v;
+    }
+    __syncthreads();
     if (tid == 0) {
         double G[R][R];
 #pragma unroll
         for (int a = 0; a < R; ++a)
 #pragma unroll
-            for (int b = a; b < R; ++b) {
-                double v = 0.0;
-                if (b < r)
-                    for (int sl = 0; sl < nslices; ++sl) v += part[sl][a * r + b];
-                G[a][b] = v;
-            }
+            for (int b = a; b < R; ++b) G[a][b] = b < r ? Gs[a * r + b] : 0.0;
         // Cholesky, row by row of R (upper): R_jj = sqrt(G_jj - sum_k R_kj^2), R_jc = (G_jc - sum_k R_kj R_kc) / R_jj
 #pragma unroll
         for (int j = 0; j < R; ++j) {
