@@ -379,7 +379,18 @@ __global__ __launch_bounds__(kBlock) void k_hr_chol(const MatDesc* __restrict__ 
         X[c][c] = rinv[c];
         for (int i = c - 1; i >= 0; --i) {
             double v = 0.0;
-            for (int k = i + 1; k <= c; ++k) v += G[i][k] * X[k][c];
+            int k = i + 1;
+            for (; k + 8 <= c + 1; k += 8) {   // eight products' operands requested together, added in the order of k
+                double gv[8], xv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    gv[u] = G[i][k + u];
+                    xv[u] = X[k + u][c];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v += gv[u] * xv[u];
+            }
+            for (; k <= c; ++k) v += G[i][k] * X[k][c];
             X[i][c] = -v * rinv[i];
         }
     }
