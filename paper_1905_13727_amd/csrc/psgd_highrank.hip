@@ -326,7 +326,8 @@ __global__ __launch_bounds__(kBlock) void k_hr_gram(const MatDesc* __restrict__ 
 // that column of P_hat is zero); what is stored at chol[chol_off ..] is R^-1 (r x r, upper triangular).
 __global__ __launch_bounds__(kBlock) void k_hr_chol(const MatDesc* __restrict__ mats, const double* __restrict__ gram,
                                                     double* __restrict__ chol) {
-    __shared__ double G[kHrMaxRank][kHrMaxRank + 1];
+    __shared__ double G[kHrMaxRank][kHrMaxRank + 1];    // Gram matrix; the trailing part is updated in place
+    __shared__ double Rm[kHrMaxRank][kHrMaxRank + 1];   // its Cholesky factor (upper)
     __shared__ double rinv[kHrMaxRank];
     const MatDesc d = mats[blockIdx.x];
     const int r = d.r, tid = threadIdx.x, nent = r * r;
@@ -345,34 +346,34 @@ __global__ __launch_bounds__(kBlock) void k_hr_chol(const MatDesc* __restrict__ 
         G[ent / r][ent % r] = v;
     }
     __syncthreads();
-    // right-looking Cholesky, row j of R at a time; G's upper triangle is overwritten by R
+    // right-looking Cholesky, row j of R at a time.  Every thread takes the root and the reciprocal of the pivot itself
+    // (same value, same arithmetic) and scales the entries of row j that it needs, so a column costs one barrier; the
+    // trailing update G[a][b] -= R[j][a] R[j][b] (j < a <= b) runs over 16 x 16 blocks of the upper triangle, one
+    // entry per thread.  Row j of G is not written again once its turn has come; R is kept beside it.
+    const int ta = tid >> 4, tb = tid & 15;
     for (int j = 0; j < r; ++j) {
+        const double piv = G[j][j];
+        const bool dead = piv <= 1e-30;
+        const double rjj = dead ? 0.0 : sqrt(piv);
+        const double ri_j = dead ? 0.0 : 1.0 / rjj;   // 0 for a dead column: its row of R is zero
         if (tid == 0) {
-            const double piv = G[j][j];
-            if (piv <= 1e-30) {
-                rinv[j] = 0.0;
-                G[j][j] = 0.0;
-            } else {
-                const double rjj = sqrt(piv);
-                G[j][j] = rjj;
-                rinv[j] = 1.0 / rjj;
-            }
+            rinv[j] = ri_j;
+            Rm[j][j] = rjj;
         }
-        __syncthreads();
-        const double ri_j = rinv[j];
-        for (int c = j + 1 + tid; c < r; c += kBlock) G[j][c] = G[j][c] * ri_j;   // 0 for a dead column
-        __syncthreads();
-        // trailing update: G[a][b] -= R[j][a] R[j][b] for j < a <= b
-        const int rem = r - j - 1;
-        for (int idx = tid; idx < rem * rem; idx += kBlock) {
-            const int a = j + 1 + idx / rem, b = j + 1 + idx % rem;
-            if (b >= a) G[a][b] -= G[j][a] * G[j][b];
+        for (int c = j + 1 + tid; c < r; c += kBlock) Rm[j][c] = G[j][c] * ri_j;
+        for (int a0 = j + 1; a0 < r; a0 += 16) {
+            const int a = a0 + ta;
+            const double ra = a < r ? G[j][a] * ri_j : 0.0;
+            for (int b0 = a0; b0 < r; b0 += 16) {
+                const int b = b0 + tb;
+                if (a < r && b < r && b >= a) G[a][b] -= ra * (G[j][b] * ri_j);
+            }
         }
         __syncthreads();
     }
     // inverse of R by back substitution, one column per thread: R x = e_c.  A dead column (reciprocal 0)
-    // gets x = 0 and, its row of R being zero, takes no part in the others.
-    __shared__ double X[kHrMaxRank][kHrMaxRank + 1];
+    // gets x = 0 and, its row of R being zero, takes no part in the others.  X takes G's place.
+    double (&X)[kHrMaxRank][kHrMaxRank + 1] = G;
     if (tid < r) {
         const int c = tid;
         for (int i = r - 1; i > c; --i) X[i][c] = 0.0;
@@ -384,13 +385,13 @@ __global__ __launch_bounds__(kBlock) void k_hr_chol(const MatDesc* __restrict__ 
                 double gv[8], xv[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    gv[u] = G[i][k + u];
+                    gv[u] = Rm[i][k + u];
                     xv[u] = X[k + u][c];
                 }
 #pragma unroll
                 for (int u = 0; u < 8; ++u) v += gv[u] * xv[u];
             }
-            for (; k <= c; ++k) v += G[i][k] * X[k][c];
+            for (; k <= c; ++k) v += Rm[i][k] * X[k][c];
             X[i][c] = -v * rinv[i];
         }
     }
