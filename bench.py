@@ -49,9 +49,9 @@ MEASURED_TRAFFIC = {
 # profiles/transformer_4layers_bf16_r*_counters.md); here: measured traffic / algorithmic bytes of that subset,
 # applied to the full set's algorithmic bytes.
 TRANSFORMER_TRAFFIC_RATIO = {
-    (4, "k_ef_right"): 3170481094 / 3043491840, (4, "k_left"): 1271435096 / 1217396736, (4, "k_decomp"): 3181622066 / 3043934208,
-    (16, "k_ef_right"): 3183010845 / 3043491840, (16, "k_left"): 1285812336 / 1217396736, (16, "k_decomp"): 3207978852 / 3043934208,
-    (32, "k_ef_right"): 3222906596 / 3043491840, (32, "k_left"): 1305033872 / 1217396736, (32, "k_decomp"): 3201972705 / 3043934208,
+    (4, "k_ef_right"): 3170481503 / 3043491840, (4, "k_left"): 1271433450 / 1217396736, (4, "k_decomp"): 3181641715 / 3043934208,
+    (16, "k_ef_right"): 3183008586 / 3043491840, (16, "k_left"): 1285809725 / 1217396736, (16, "k_decomp"): 3207991556 / 3043934208,
+    (32, "k_ef_right"): 3222822593 / 3043491840, (32, "k_left"): 1305035561 / 1217396736, (32, "k_decomp"): 3201981824 / 3043934208,
 }
 
 
