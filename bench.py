@@ -35,7 +35,7 @@ METRIC = "PowerSGD step gradient GB/s + % HBM peak, ResNet18 shapes r=2"   # the
 
 MEASURED_TRAFFIC = {
     # (workload, rank, workers, kernel slot of kernel_ms): FETCH_SIZE + WRITE_SIZE, scaled, bytes per launch
-    ("resnet18", 2, 1, "k_resident"): 200336903,      # profiles/resident_resnet18_r2.md
+    ("resnet18", 2, 1, "k_resident"): 200345914,      # profiles/resident_resnet18_r2.md
     ("lstm", 4, 1, "k_ef_right"): 391825784,          # profiles/streaming_lstm_r4.md
     ("lstm", 4, 1, "k_left"): 132707849,
     ("lstm", 4, 1, "k_decomp"): 400357535,
